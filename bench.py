@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused SDDMM-SpMM kernel on one MI355X.
+
+A step is one fusedmm_execute call (the whole hot path: schedule lookup, gather,
+VOP/ROP/SOP/MOP/AOP, store, split-row merge) over one synthetic workload whose
+inputs already sit in HBM.  Prints ONE JSON line.
+
+    python bench.py [--workload c2] [--steps K] [--warmup W] [--gpus 1]
+
+Metric: G(edge*dim)/s = nnz * d / seconds per step.  The roofline object prices the
+main kernel's algorithmic bytes (no reuse of Y rows assumed) against the 8 TB/s HBM
+peak; cpu_baseline times the unfused CPU oracle (fp32 build) on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# HBM bytes per main-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# each scaled by the same counter's reading for a copy kernel of known size; see profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, budget_edges_dim: float = 6.0e9):
+    """Time the oracle's fp32 two-phase (unfused) build on a bounded sample of the rows."""
+    import numpy as np
+    import oracle
+    from paper_2011_06391_amd import synth
+
+    g = w.csr
+    work = g.nnz * w.d
+    if work <= budget_edges_dim:
+        sub, rows, sample = g, None, "whole workload"
+    else:
+        frac = budget_edges_dim / work
+        rng = np.random.default_rng(2024)
+        rows = np.sort(rng.choice(g.m, max(1, int(g.m * frac)), replace=False)).astype(np.int64)
+        sub = g.take_rows(rows)
+        sample = f"{len(rows)} random rows of {g.m} ({sub.nnz} of {g.nnz} stored entries), all of Y"
+    X = w.X if rows is None else w.X[rows]
+    times = []
+    for _ in range(3 if sub.nnz * w.d < 2e9 else 1):
+        t0 = time.perf_counter()
+        oracle.unfused(sub.rowptr, sub.colidx, sub.values, X, w.Y, w.pattern, precision="f32", want_abs=False)
+        times.append(time.perf_counter() - t0)
+    t = sorted(times)[len(times) // 2]
+    return {"value": sub.nnz * w.d / t / 1e9, "unit": "G(edge*dim)/s", "cores": synth.num_threads(),
+            "kind": "oracle", "sample": sample, "seconds": t, "precision": "fp32 unfused two-phase"}
+
+
+def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None):
+    import torch
+    from paper_2011_06391_amd import binding, model, synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (torch.cuda.is_available() is False)")
+    binding.load()
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    w = synth.make_workload(workload, d=d)
+    g = w.csr
+    gen_s = time.perf_counter() - t0
+
+    rp = torch.from_numpy(g.rowptr).cuda()
+    ci = torch.from_numpy(g.colidx).cuda()
+    Xd = torch.from_numpy(w.X).cuda()
+    Yd = Xd if w.Y is w.X else torch.from_numpy(w.Y).cuda()
+    vd = None if g.values is None else torch.from_numpy(g.values).cuda()
+    Z = torch.empty((g.m, w.d), dtype=torch.float32, device="cuda")
+    uses_x = w.pattern != "gcn"
+    ops = binding.fusedmm_ops_preset(w.pattern)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plan = binding.Plan(g.m, g.n, rp, ci, options)
+    plan.reserve(w.d)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+
+    def step():
+        plan.execute(ops, Xd if uses_x else None, Yd, Z, vd)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    plan.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms_sum, calls = plan.read_profile()
+    plan.set_profiling(False)
+    assert torch.isfinite(Z[: min(g.m, 4096)]).all().item()
+
+    ms_per_step = elapsed * 1e3 / steps
+    tr = model.traffic(g.m, g.n, g.nnz, w.d, uses_x, vd is not None, w.Y is w.X)
+    kernel_ms = kernel_ms_sum / max(1, calls)
+    achieved = tr.model_bytes / (kernel_ms * 1e-3) / 1e9
+    deg = g.degrees()
+    out = {
+        "metric": "fused SDDMM-SpMM throughput: G(edge*dim)/s + achieved HBM GB/s vs peak, 1 GPU",
+        "value": g.nnz * w.d / (ms_per_step * 1e-3) / 1e9,
+        "unit": "G(edge*dim)/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
+                   "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
+                   "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms,
+                   "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / model.MI355X_HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
+                     "kernel": "fusedmm_fast_kernel", "kernel_ms": kernel_ms,
+                     "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
+                     "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
+    }
+    plan.close()
+    del Z, Xd, Yd, rp, ci
+    torch.cuda.empty_cache()
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", help="c1..c5")
+    ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--small-row-max", type=int, default=0)
+    ap.add_argument("--split-row-min", type=int, default=0)
+    ap.add_argument("--chunk-edges", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    options = None
+    if args.small_row_max or args.split_row_min or args.chunk_edges:
+        options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,
+                   "chunk_edges": args.chunk_edges}
+    out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

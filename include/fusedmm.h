@@ -1,0 +1,175 @@
+/*
+ * fusedmm.h -- C ABI of libfusedmm.so: the fused SDDMM-SpMM kernel (FusedMM,
+ * arXiv 2011.06391) for AMD MI355X (gfx950), hand-written HIP.
+ *
+ *     Z = FusedMM(A, X, Y)                                  (paper Section II)
+ *     z_u = AOP_{v in N(u)} MOP( SOP( ROP( VOP(x_u, y_v) ) ), . )   (Eq. 1,
+ *           Section III-A steps 1-5, Algorithm 1 procedure UpdateU)
+ *
+ * A is an m x n sparse matrix in CSR, X is m x d, Y is n x d, Z is m x d, all
+ * dense matrices row-major fp32 (Table I; Section V-A: single precision).
+ * No edge message is ever written to memory (Section II, "the need for a fused
+ * kernel"); the library's workspace is O(m + nnz/chunk + splits*d).
+ *
+ * Conventions
+ *   - All array arguments named d_* are DEVICE pointers (HIP global memory of
+ *     the current device).  Everything else is a host value or host pointer.
+ *   - 0-based indices.  rowptr: int64, m+1 entries, rowptr[0] == 0,
+ *     rowptr[m] == nnz, non-decreasing.  colidx: int32, nnz entries, each in
+ *     [0, n); order within a row is free; duplicates and self-loops are
+ *     processed as stored (every stored entry is visited exactly once).
+ *   - Leading dimensions (ldx, ldy, ldz) are in ELEMENTS, >= d.
+ *   - d_Y == d_X is allowed.  Z must not overlap X or Y (rows of Y are read by
+ *     other rows' gathers while Z is written).
+ *   - m == 0 and nnz == 0 are valid.  Rows without stored entries get z_u = 0
+ *     (Algorithm 1 initialises z_u to zero); Z is always overwritten.
+ *   - Ownership: the caller owns every buffer it passes and must keep
+ *     d_rowptr / d_colidx alive and unchanged for the life of the plan (the
+ *     plan borrows them).  The plan owns its schedule lists and scratch.
+ *   - Errors: every call returns a fusedmm_status.  No exceptions, no abort.
+ *     On a non-OK status no output has been written by that call.
+ *   - Threading: calls on one plan must not overlap in time (they share the
+ *     plan's scratch).  Different plans are independent.
+ *   - stream arguments are hipStream_t handles passed as void* (NULL = the
+ *     null stream).
+ */
+#ifndef FUSEDMM_H_
+#define FUSEDMM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FUSEDMM_VERSION 100 /* 0.1.0 */
+
+/* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
+ * paper's sweep, Table VI) with 16-byte aligned rows runs the specialised
+ * kernels; any other 1 <= d <= FUSEDMM_MAX_D runs the general kernel. */
+#define FUSEDMM_MAX_D 2048
+
+typedef enum fusedmm_status {
+  FUSEDMM_OK = 0,
+  FUSEDMM_ERR_INVALID_ARG = 1,     /* null pointer, negative size, ld < d, bad rowptr/colidx, missing values */
+  FUSEDMM_ERR_UNSUPPORTED_OPS = 2, /* op tuple outside the supported set */
+  FUSEDMM_ERR_UNSUPPORTED_DIM = 3, /* d < 1 or d > FUSEDMM_MAX_D */
+  FUSEDMM_ERR_ALIAS = 4,           /* Z overlaps X or Y */
+  FUSEDMM_ERR_ALLOC = 5,           /* host or device allocation failed */
+  FUSEDMM_ERR_HIP = 6              /* a HIP runtime call failed */
+} fusedmm_status;
+
+/* Step 1, VOP(x_u, y_v) -> t (Section III-A step 1; Table II binary ops). */
+typedef enum { FUSEDMM_VOP_MUL = 0, FUSEDMM_VOP_SEL2ND = 1, FUSEDMM_VOP_SUB = 2 } fusedmm_vop;
+/* Step 2, ROP(t) -> s (step 2; Table II reductions; NORM of Table III). */
+typedef enum { FUSEDMM_ROP_NOOP = 0, FUSEDMM_ROP_RSUM = 1, FUSEDMM_ROP_SUMSQ = 2, FUSEDMM_ROP_NORM2 = 3 } fusedmm_rop;
+/* Step 3, SOP(s) -> h (step 3).  EDGE_VALUE: h = a_uv (the GCN row of Table III). */
+typedef enum {
+  FUSEDMM_SOP_EDGE_VALUE = 0,
+  FUSEDMM_SOP_SIGMOID = 1,           /* 1/(1+exp(-s)) */
+  FUSEDMM_SOP_ONE_MINUS_SIGMOID = 2, /* 1 - 1/(1+exp(-s)) */
+  FUSEDMM_SOP_INV_1P = 3,            /* 1/(1+s) */
+  FUSEDMM_SOP_SCAL = 4               /* alpha * s */
+} fusedmm_sop;
+/* Step 4, MOP(h, .) -> w (step 4): scale y_v, or scale the VOP output t. */
+typedef enum { FUSEDMM_MOP_MUL_Y = 0, FUSEDMM_MOP_MUL_T = 1 } fusedmm_mop;
+/* Step 5, AOP(z_u, w) (step 5). */
+typedef enum { FUSEDMM_AOP_SUM = 0 } fusedmm_aop;
+
+/* The op selector.  Valid tuples: AOP == SUM and either
+ *   (ROP == NOOP and SOP == EDGE_VALUE)        -- h is the stored edge value, or
+ *   (ROP != NOOP and SOP != EDGE_VALUE)        -- h is a function of the reduction.
+ * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE. */
+typedef struct fusedmm_ops {
+  int32_t vop, rop, sop, mop, aop;
+  float alpha; /* used by FUSEDMM_SOP_SCAL only */
+} fusedmm_ops_t;
+
+/* Application patterns (Table III rows 1-3 and the t-distribution pattern). */
+typedef enum {
+  FUSEDMM_PATTERN_SIGMOID_EMBED = 0,           /* MUL, RSUM, SIGMOID, MUL_Y, SUM */
+  FUSEDMM_PATTERN_ONE_MINUS_SIGMOID_EMBED = 1, /* MUL, RSUM, 1-SIGMOID, MUL_Y, SUM */
+  FUSEDMM_PATTERN_GCN_SUM = 2,                 /* SEL2ND, NOOP, EDGE_VALUE, MUL_Y, SUM  (= SpMM) */
+  FUSEDMM_PATTERN_TDIST = 3,                   /* SUB, SUMSQ, INV_1P, MUL_T, SUM */
+  FUSEDMM_PATTERN_FR = 4                       /* SUB, NORM2, SCAL(alpha), MUL_T, SUM */
+} fusedmm_pattern;
+
+/* Scheduling knobs of the degree-binned plan (the GPU counterpart of the
+ * nnz-balanced 1-D partition, Section III-C).  Zero fields take defaults. */
+typedef struct fusedmm_plan_options {
+  int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront */
+  int32_t split_row_min;   /* rows with  > this many entries get whole workgroups */
+  int32_t chunk_edges;     /* entries per workgroup chunk of a split row */
+  int32_t reserved;
+} fusedmm_plan_options_t;
+
+typedef struct fusedmm_plan fusedmm_plan_t;
+
+/* Library version (FUSEDMM_VERSION of the build). */
+int fusedmm_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* fusedmm_status_string(int status);
+
+/* Fill *out (host) with the op tuple of a pattern; alpha is set to 1. */
+int fusedmm_ops_preset(int pattern, fusedmm_ops_t* out);
+
+/* Build the schedule for one sparsity pattern (Algorithm 1, Part1D, done the
+ * GPU way: rows binned by length, long rows split into chunks).
+ *   out        host: receives the plan
+ *   m, n, nnz  host: matrix shape (m, n < 2^31)
+ *   d_rowptr   device, m+1 int64;  d_colidx  device, nnz int32 (may be NULL if nnz == 0)
+ *   options    host, may be NULL
+ * Reads rowptr back to the host and validates rowptr and colidx; synchronises
+ * the stream; allocates the plan's lists.  Not part of the timed hot path. */
+int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
+                        const int64_t* d_rowptr, const int32_t* d_colidx,
+                        const fusedmm_plan_options_t* options, void* stream);
+
+/* Allocate the partial-sum scratch for feature dimension d up front, so that
+ * later fusedmm_execute calls with dimension <= d never allocate. */
+int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d);
+
+/* Device bytes the plan owns when executing with dimension d. */
+int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out);
+
+/* Schedule statistics (host ints): rows packed per wavefront, rows given one
+ * wavefront, workgroup chunks, rows split over several chunks, partial rows. */
+int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64_t* n_wave_rows,
+                       int64_t* n_chunks, int64_t* n_split_rows, int64_t* n_partials);
+
+/* Z = FusedMM(A, X, Y) with the given ops; asynchronous on `stream`.
+ *   d_values  device, nnz fp32 edge values a_uv; NULL unless SOP == EDGE_VALUE
+ *   d_X       device, m x d (ldx); may be NULL when VOP == SEL2ND
+ *   d_Y       device, n x d (ldy);  d_Z  device, m x d (ldz), overwritten
+ * Does not synchronise.  Does not allocate, except that the first call with a
+ * larger d than any before (and no fusedmm_plan_reserve) grows the scratch. */
+int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
+                    const float* d_values, const float* d_X, int64_t ldx,
+                    const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
+
+/* Test hook: run the same schedule and edge indexing as fusedmm_execute would
+ * for dimension d (row pointers may be of any alignment class: pass
+ * fast_path != 0 to exercise the specialised kernels' indexing, 0 for the
+ * general kernel's) and add 1 to d_counts[e] for every stored entry e visited.
+ * d_counts: device, nnz uint32, zeroed by the caller.  Correct schedules leave
+ * every count equal to 1. */
+int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path,
+                              uint32_t* d_counts, void* stream);
+
+/* Per-kernel timing for benchmarks.  When enabled, fusedmm_execute brackets
+ * its main kernel with HIP events on the launch stream (at most 4096 calls are
+ * retained).  fusedmm_plan_read_profile synchronises those events, returns the
+ * summed main-kernel milliseconds and the number of timed calls, and clears
+ * the record.  All pointers are host pointers. */
+int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled);
+int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, int64_t* calls);
+
+/* Free the plan and everything it owns. */
+int fusedmm_plan_destroy(fusedmm_plan_t* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUSEDMM_H_ */

@@ -1,0 +1,242 @@
+"""ctypes binding of libfusedmm.so -- argument marshalling only.
+
+Function names mirror ``include/fusedmm.h``.  Device arrays are torch tensors
+(PyTorch is used for device memory and streams, nothing else); their
+``data_ptr()`` is handed to the C ABI.  There is no fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfusedmm.so")
+
+FUSEDMM_OK = 0
+FUSEDMM_ERR_INVALID_ARG = 1
+FUSEDMM_ERR_UNSUPPORTED_OPS = 2
+FUSEDMM_ERR_UNSUPPORTED_DIM = 3
+FUSEDMM_ERR_ALIAS = 4
+FUSEDMM_ERR_ALLOC = 5
+FUSEDMM_ERR_HIP = 6
+
+FUSEDMM_MAX_D = 2048
+
+VOP = {"MUL": 0, "SEL2ND": 1, "SUB": 2}
+ROP = {"NOOP": 0, "RSUM": 1, "SUMSQ": 2, "NORM2": 3}
+SOP = {"EDGE_VALUE": 0, "SIGMOID": 1, "ONE_MINUS_SIGMOID": 2, "INV_1P": 3, "SCAL": 4}
+MOP = {"MUL_Y": 0, "MUL_T": 1}
+AOP = {"SUM": 0}
+PATTERN = {"sigmoid": 0, "one_minus_sigmoid": 1, "gcn": 2, "tdist": 3, "fr": 4}
+
+EXPORTS = (
+    "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
+    "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
+    "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
+    "fusedmm_plan_destroy",
+)
+
+
+class fusedmm_ops_t(ctypes.Structure):
+    _fields_ = [("vop", ctypes.c_int32), ("rop", ctypes.c_int32), ("sop", ctypes.c_int32),
+                ("mop", ctypes.c_int32), ("aop", ctypes.c_int32), ("alpha", ctypes.c_float)]
+
+
+class fusedmm_plan_options_t(ctypes.Structure):
+    _fields_ = [("small_row_max", ctypes.c_int32), ("split_row_min", ctypes.c_int32),
+                ("chunk_edges", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class FusedMMError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({fusedmm_status_string(status)})")
+
+
+_lib = None
+
+
+def load():
+    """Load libfusedmm.so (built by paper_2011_06391_amd.build).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2011_06391_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.fusedmm_version.restype = ctypes.c_int
+    lib.fusedmm_version.argtypes = []
+    lib.fusedmm_status_string.restype = ctypes.c_char_p
+    lib.fusedmm_status_string.argtypes = [ctypes.c_int]
+    lib.fusedmm_ops_preset.restype = ctypes.c_int
+    lib.fusedmm_ops_preset.argtypes = [ctypes.c_int, ctypes.POINTER(fusedmm_ops_t)]
+    lib.fusedmm_plan_create.restype = ctypes.c_int
+    lib.fusedmm_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp,
+                                        ctypes.POINTER(fusedmm_plan_options_t), vp]
+    lib.fusedmm_plan_reserve.restype = ctypes.c_int
+    lib.fusedmm_plan_reserve.argtypes = [vp, i32]
+    lib.fusedmm_plan_workspace_bytes.restype = ctypes.c_int
+    lib.fusedmm_plan_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.fusedmm_plan_stats.restype = ctypes.c_int
+    lib.fusedmm_plan_stats.argtypes = [vp] + [ctypes.POINTER(i64)] * 5
+    lib.fusedmm_execute.restype = ctypes.c_int
+    lib.fusedmm_execute.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.fusedmm_debug_edge_visits.restype = ctypes.c_int
+    lib.fusedmm_debug_edge_visits.argtypes = [vp, i32, i32, vp, vp]
+    lib.fusedmm_plan_set_profiling.restype = ctypes.c_int
+    lib.fusedmm_plan_set_profiling.argtypes = [vp, i32]
+    lib.fusedmm_plan_read_profile.restype = ctypes.c_int
+    lib.fusedmm_plan_read_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.fusedmm_plan_destroy.restype = ctypes.c_int
+    lib.fusedmm_plan_destroy.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _dptr(t) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != FUSEDMM_OK:
+        raise FusedMMError(status, where)
+
+
+# ---- thin mirrors of the C entry points ------------------------------------
+
+def fusedmm_version() -> int:
+    return int(load().fusedmm_version())
+
+
+def fusedmm_status_string(status: int) -> str:
+    return load().fusedmm_status_string(int(status)).decode()
+
+
+def fusedmm_ops_preset(pattern) -> fusedmm_ops_t:
+    ops = fusedmm_ops_t()
+    code = PATTERN[pattern] if isinstance(pattern, str) else int(pattern)
+    _check(load().fusedmm_ops_preset(code, ctypes.byref(ops)), "fusedmm_ops_preset")
+    return ops
+
+
+def make_ops(vop: str, rop: str, sop: str, mop: str, aop: str = "SUM", alpha: float = 1.0) -> fusedmm_ops_t:
+    return fusedmm_ops_t(VOP[vop], ROP[rop], SOP[sop], MOP[mop], AOP[aop], alpha)
+
+
+def fusedmm_plan_create(m: int, n: int, nnz: int, d_rowptr, d_colidx, options=None, stream=None) -> ctypes.c_void_p:
+    plan = ctypes.c_void_p()
+    opt = None
+    if options is not None:
+        opt = ctypes.byref(fusedmm_plan_options_t(options.get("small_row_max", 0), options.get("split_row_min", 0),
+                                                  options.get("chunk_edges", 0), 0))
+    st = load().fusedmm_plan_create(ctypes.byref(plan), m, n, nnz, _dptr(d_rowptr), _dptr(d_colidx), opt,
+                                    _stream(stream))
+    _check(st, "fusedmm_plan_create")
+    return plan
+
+
+def fusedmm_plan_reserve(plan, d: int) -> None:
+    _check(load().fusedmm_plan_reserve(plan, d), "fusedmm_plan_reserve")
+
+
+def fusedmm_plan_workspace_bytes(plan, d: int) -> int:
+    out = ctypes.c_size_t()
+    _check(load().fusedmm_plan_workspace_bytes(plan, d, ctypes.byref(out)), "fusedmm_plan_workspace_bytes")
+    return int(out.value)
+
+
+def fusedmm_plan_stats(plan) -> dict:
+    v = [ctypes.c_int64() for _ in range(5)]
+    _check(load().fusedmm_plan_stats(plan, *[ctypes.byref(x) for x in v]), "fusedmm_plan_stats")
+    keys = ("packed_rows", "wave_rows", "chunks", "split_rows", "partials")
+    return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+def fusedmm_execute(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d_Y, ldy: int, d_Z, ldz: int,
+                    stream=None) -> None:
+    st = load().fusedmm_execute(plan, ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
+                                _dptr(d_Z), ldz, _stream(stream))
+    _check(st, "fusedmm_execute")
+
+
+def fusedmm_debug_edge_visits(plan, d: int, fast_path: bool, d_counts, stream=None) -> None:
+    st = load().fusedmm_debug_edge_visits(plan, d, int(fast_path), _dptr(d_counts), _stream(stream))
+    _check(st, "fusedmm_debug_edge_visits")
+
+
+def fusedmm_plan_set_profiling(plan, enabled: bool) -> None:
+    _check(load().fusedmm_plan_set_profiling(plan, int(enabled)), "fusedmm_plan_set_profiling")
+
+
+def fusedmm_plan_read_profile(plan):
+    ms, calls = ctypes.c_double(), ctypes.c_int64()
+    _check(load().fusedmm_plan_read_profile(plan, ctypes.byref(ms), ctypes.byref(calls)), "fusedmm_plan_read_profile")
+    return float(ms.value), int(calls.value)
+
+
+def fusedmm_plan_destroy(plan) -> None:
+    _check(load().fusedmm_plan_destroy(plan), "fusedmm_plan_destroy")
+
+
+# ---- convenience wrapper (still marshalling only) ----------------------------
+
+class Plan:
+    """Owns a fusedmm_plan_t for one CSR pattern held in torch device tensors."""
+
+    def __init__(self, m: int, n: int, rowptr, colidx, options: Optional[dict] = None, stream=None):
+        assert rowptr.is_cuda and rowptr.dtype.is_signed and rowptr.element_size() == 8 and rowptr.is_contiguous()
+        assert colidx.numel() == 0 or (colidx.is_cuda and colidx.element_size() == 4 and colidx.is_contiguous())
+        self.m, self.n, self.nnz = int(m), int(n), int(colidx.numel())
+        self.rowptr, self.colidx = rowptr, colidx  # keep alive: the plan borrows them
+        self._plan = fusedmm_plan_create(self.m, self.n, self.nnz, rowptr, colidx if self.nnz else None, options,
+                                         stream)
+
+    def execute(self, ops, X, Y, Z, values=None, stream=None) -> None:
+        if isinstance(ops, str):
+            ops = fusedmm_ops_preset(ops)
+        d = int(Z.shape[1]) if Z is not None and Z.dim() == 2 else 0
+        for t in (X, Y, Z, values):
+            assert t is None or (t.is_cuda and t.element_size() == 4)
+        ldx = 0 if X is None else X.stride(0)
+        fusedmm_execute(self._plan, ops, d, values, X, ldx, Y, Y.stride(0), Z, Z.stride(0), stream)
+
+    def edge_visits(self, d: int, fast_path: bool, counts, stream=None) -> None:
+        fusedmm_debug_edge_visits(self._plan, d, fast_path, counts, stream)
+
+    def reserve(self, d: int) -> None:
+        fusedmm_plan_reserve(self._plan, d)
+
+    def workspace_bytes(self, d: int) -> int:
+        return fusedmm_plan_workspace_bytes(self._plan, d)
+
+    def stats(self) -> dict:
+        return fusedmm_plan_stats(self._plan)
+
+    def set_profiling(self, enabled: bool) -> None:
+        fusedmm_plan_set_profiling(self._plan, enabled)
+
+    def read_profile(self):
+        return fusedmm_plan_read_profile(self._plan)
+
+    def close(self) -> None:
+        if self._plan is not None:
+            fusedmm_plan_destroy(self._plan)
+            self._plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

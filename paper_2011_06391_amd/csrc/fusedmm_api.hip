@@ -1,0 +1,439 @@
+// Host side of libfusedmm.so: the C ABI of include/fusedmm.h, argument validation,
+// the degree-binned plan (the GPU counterpart of Part1D in Algorithm 1) and dispatch.
+#include "../../include/fusedmm.h"
+#include "fusedmm_internal.h"
+
+#include <algorithm>
+#include <new>
+#include <utility>
+#include <vector>
+
+using namespace fmm;
+
+struct fusedmm_plan {
+  int64_t m = 0, n = 0, nnz = 0;
+  const int64_t* d_rowptr = nullptr;
+  const int32_t* d_colidx = nullptr;
+  int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0;
+  int32_t n_wave = 0, n_packed = 0, n_chunks = 0, n_merges = 0, n_parts = 0;
+  int32_t* d_order = nullptr;
+  ChunkDesc* d_chunks = nullptr;
+  MergeDesc* d_merges = nullptr;
+  float* d_partials = nullptr;
+  int32_t partials_d = 0;  // scratch holds n_parts rows of this many floats
+  bool profiling = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+  size_t events_used = 0;
+};
+
+namespace {
+
+constexpr int32_t kDefaultSmallRowMax = 32;
+constexpr int32_t kDefaultSplitRowMin = 256;
+constexpr int32_t kDefaultChunkEdges = 1024;
+constexpr size_t kMaxProfiledCalls = 4096;
+
+bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
+
+bool ops_valid(const fusedmm_ops_t& o) {
+  if (o.vop < FUSEDMM_VOP_MUL || o.vop > FUSEDMM_VOP_SUB) return false;
+  if (o.rop < FUSEDMM_ROP_NOOP || o.rop > FUSEDMM_ROP_NORM2) return false;
+  if (o.sop < FUSEDMM_SOP_EDGE_VALUE || o.sop > FUSEDMM_SOP_SCAL) return false;
+  if (o.mop < FUSEDMM_MOP_MUL_Y || o.mop > FUSEDMM_MOP_MUL_T) return false;
+  if (o.aop != FUSEDMM_AOP_SUM) return false;
+  return (o.rop == FUSEDMM_ROP_NOOP) == (o.sop == FUSEDMM_SOP_EDGE_VALUE);
+}
+
+// The pattern recogniser: map an op tuple to a specialised kernel, or -1 for the general one.
+int recognise(const fusedmm_ops_t& o) {
+  if (o.vop == FUSEDMM_VOP_MUL && o.rop == FUSEDMM_ROP_RSUM && o.mop == FUSEDMM_MOP_MUL_Y) {
+    if (o.sop == FUSEDMM_SOP_SIGMOID) return PAT_SIGMOID;
+    if (o.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID) return PAT_ONE_MINUS_SIGMOID;
+  }
+  if (o.vop == FUSEDMM_VOP_SEL2ND && o.rop == FUSEDMM_ROP_NOOP && o.sop == FUSEDMM_SOP_EDGE_VALUE) return PAT_GCN;
+  if (o.vop == FUSEDMM_VOP_SUB && o.mop == FUSEDMM_MOP_MUL_T) {
+    if (o.rop == FUSEDMM_ROP_SUMSQ && o.sop == FUSEDMM_SOP_INV_1P) return PAT_TDIST;
+    if (o.rop == FUSEDMM_ROP_NORM2 && o.sop == FUSEDMM_SOP_SCAL) return PAT_FR;
+  }
+  return -1;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int64_t rows_b, int64_t ld_b, int32_t d) {
+  if (!a || !b || rows_a <= 0 || rows_b <= 0) return false;
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  const uintptr_t a1 = a0 + (uintptr_t)((rows_a - 1) * ld_a + d) * sizeof(float);
+  const uintptr_t b1 = b0 + (uintptr_t)((rows_b - 1) * ld_b + d) * sizeof(float);
+  return a0 < b1 && b0 < a1;
+}
+
+void free_plan_device(fusedmm_plan* p) {
+  if (p->d_order) (void)hipFree(p->d_order);
+  if (p->d_chunks) (void)hipFree(p->d_chunks);
+  if (p->d_merges) (void)hipFree(p->d_merges);
+  if (p->d_partials) (void)hipFree(p->d_partials);
+  for (auto& ev : p->events) {
+    (void)hipEventDestroy(ev.first);
+    (void)hipEventDestroy(ev.second);
+  }
+  p->events.clear();
+}
+
+template <class T>
+int upload(T** dst, const std::vector<T>& src, hipStream_t stream) {
+  *dst = nullptr;
+  if (src.empty()) return FUSEDMM_OK;
+  if (hipMalloc(reinterpret_cast<void**>(dst), src.size() * sizeof(T)) != hipSuccess) {
+    (void)hipGetLastError();
+    return FUSEDMM_ERR_ALLOC;
+  }
+  if (hipMemcpyAsync(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, stream) != hipSuccess)
+    return FUSEDMM_ERR_HIP;
+  return FUSEDMM_OK;
+}
+
+int ensure_partials(fusedmm_plan* p, int32_t d) {
+  if (p->n_parts == 0 || d <= p->partials_d) return FUSEDMM_OK;
+  if (p->d_partials) {
+    if (hipDeviceSynchronize() != hipSuccess) return FUSEDMM_ERR_HIP;  // earlier launches may still use it
+    (void)hipFree(p->d_partials);
+    p->d_partials = nullptr;
+    p->partials_d = 0;
+  }
+  if (hipMalloc(reinterpret_cast<void**>(&p->d_partials), (size_t)p->n_parts * d * sizeof(float)) != hipSuccess) {
+    (void)hipGetLastError();
+    return FUSEDMM_ERR_ALLOC;
+  }
+  p->partials_d = d;
+  return FUSEDMM_OK;
+}
+
+void fill_schedule_args(const fusedmm_plan* p, int32_t d, KernelArgs* a) {
+  a->rowptr = p->d_rowptr;
+  a->colidx = p->d_colidx;
+  a->order = p->d_order;
+  a->chunks = p->d_chunks;
+  a->partials = p->d_partials;
+  a->visit_counts = nullptr;
+  a->n_chunks = p->n_chunks;
+  a->n_wave = p->n_wave;
+  a->n_packed = p->n_packed;
+  a->nb_chunk = p->n_chunks;
+  a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int rpb = packed_rows_per_block(d);
+  a->nb_packed = rpb > 0 ? (p->n_packed + rpb - 1) / rpb : 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fusedmm_version(void) { return FUSEDMM_VERSION; }
+
+const char* fusedmm_status_string(int status) {
+  switch (status) {
+    case FUSEDMM_OK: return "ok";
+    case FUSEDMM_ERR_INVALID_ARG: return "invalid argument";
+    case FUSEDMM_ERR_UNSUPPORTED_OPS: return "unsupported op tuple";
+    case FUSEDMM_ERR_UNSUPPORTED_DIM: return "unsupported feature dimension";
+    case FUSEDMM_ERR_ALIAS: return "output overlaps an input";
+    case FUSEDMM_ERR_ALLOC: return "allocation failed";
+    case FUSEDMM_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int fusedmm_ops_preset(int pattern, fusedmm_ops_t* out) {
+  if (!out) return FUSEDMM_ERR_INVALID_ARG;
+  fusedmm_ops_t o;
+  o.aop = FUSEDMM_AOP_SUM;
+  o.alpha = 1.0f;
+  switch (pattern) {
+    case FUSEDMM_PATTERN_SIGMOID_EMBED:
+      o.vop = FUSEDMM_VOP_MUL; o.rop = FUSEDMM_ROP_RSUM; o.sop = FUSEDMM_SOP_SIGMOID; o.mop = FUSEDMM_MOP_MUL_Y; break;
+    case FUSEDMM_PATTERN_ONE_MINUS_SIGMOID_EMBED:
+      o.vop = FUSEDMM_VOP_MUL; o.rop = FUSEDMM_ROP_RSUM; o.sop = FUSEDMM_SOP_ONE_MINUS_SIGMOID; o.mop = FUSEDMM_MOP_MUL_Y; break;
+    case FUSEDMM_PATTERN_GCN_SUM:
+      o.vop = FUSEDMM_VOP_SEL2ND; o.rop = FUSEDMM_ROP_NOOP; o.sop = FUSEDMM_SOP_EDGE_VALUE; o.mop = FUSEDMM_MOP_MUL_Y; break;
+    case FUSEDMM_PATTERN_TDIST:
+      o.vop = FUSEDMM_VOP_SUB; o.rop = FUSEDMM_ROP_SUMSQ; o.sop = FUSEDMM_SOP_INV_1P; o.mop = FUSEDMM_MOP_MUL_T; break;
+    case FUSEDMM_PATTERN_FR:
+      o.vop = FUSEDMM_VOP_SUB; o.rop = FUSEDMM_ROP_NORM2; o.sop = FUSEDMM_SOP_SCAL; o.mop = FUSEDMM_MOP_MUL_T; break;
+    default: return FUSEDMM_ERR_INVALID_ARG;
+  }
+  *out = o;
+  return FUSEDMM_OK;
+}
+
+int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz, const int64_t* d_rowptr,
+                        const int32_t* d_colidx, const fusedmm_plan_options_t* options, void* stream_) {
+  if (!out) return FUSEDMM_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (m < 0 || n < 0 || nnz < 0 || m >= INT32_MAX || n >= INT32_MAX) return FUSEDMM_ERR_INVALID_ARG;
+  if (!d_rowptr || (nnz > 0 && (!d_colidx || n == 0 || m == 0))) return FUSEDMM_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+  int32_t small_max = kDefaultSmallRowMax, split_min = kDefaultSplitRowMin, chunk = kDefaultChunkEdges;
+  if (options) {
+    if (options->small_row_max < 0 || options->split_row_min < 0 || options->chunk_edges < 0) return FUSEDMM_ERR_INVALID_ARG;
+    if (options->small_row_max > 0) small_max = options->small_row_max;
+    if (options->split_row_min > 0) split_min = options->split_row_min;
+    if (options->chunk_edges > 0) chunk = options->chunk_edges;
+  }
+  small_max = std::min(small_max, 1 << 16);
+  split_min = std::min(std::max(split_min, small_max), 1 << 20);
+  chunk = std::min(std::max((chunk + 255) / 256 * 256, 256), 1 << 24);
+
+  // row pointers to the host: O(m) scan, like Part1D
+  std::vector<int64_t> rp;
+  try {
+    rp.resize((size_t)m + 1);
+  } catch (const std::bad_alloc&) {
+    return FUSEDMM_ERR_ALLOC;
+  }
+  if (hipStreamSynchronize(stream) != hipSuccess) return FUSEDMM_ERR_HIP;
+  if (hipMemcpy(rp.data(), d_rowptr, ((size_t)m + 1) * sizeof(int64_t), hipMemcpyDeviceToHost) != hipSuccess)
+    return FUSEDMM_ERR_HIP;
+  if (rp[0] != 0 || rp[m] != nnz) return FUSEDMM_ERR_INVALID_ARG;
+  for (int64_t u = 0; u < m; ++u)
+    if (rp[u + 1] < rp[u]) return FUSEDMM_ERR_INVALID_ARG;
+
+  // column indices must address rows of Y: checked on the device, once
+  if (nnz > 0) {
+    int32_t* d_flag = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t)) != hipSuccess) return FUSEDMM_ERR_ALLOC;
+    int32_t flag = 0;
+    hipError_t e = hipMemcpy(d_flag, &flag, sizeof(flag), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = launch_validate_colidx(d_colidx, nnz, n, d_flag, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e == hipSuccess) e = hipMemcpy(&flag, d_flag, sizeof(flag), hipMemcpyDeviceToHost);
+    (void)hipFree(d_flag);
+    if (e != hipSuccess) return FUSEDMM_ERR_HIP;
+    if (flag != 0) return FUSEDMM_ERR_INVALID_ARG;
+  }
+
+  fusedmm_plan* p = new (std::nothrow) fusedmm_plan();
+  if (!p) return FUSEDMM_ERR_ALLOC;
+  p->m = m; p->n = n; p->nnz = nnz;
+  p->d_rowptr = d_rowptr; p->d_colidx = d_colidx;
+  p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk;
+
+  std::vector<int32_t> order;
+  std::vector<ChunkDesc> chunks;
+  std::vector<MergeDesc> merges;
+  try {
+    // counting sort of the non-split rows by length, longest first, row order kept among equals
+    std::vector<int64_t> bucket((size_t)split_min + 2, 0);
+    int64_t n_long = 0;
+    for (int64_t u = 0; u < m; ++u) {
+      const int64_t deg = rp[u + 1] - rp[u];
+      if (deg > split_min) ++n_long; else ++bucket[(size_t)deg];
+    }
+    // position of the first row of each length when lengths run from split_min down to 0
+    std::vector<int64_t> start((size_t)split_min + 1, 0);
+    int64_t pos = 0;
+    for (int64_t deg = split_min; deg >= 0; --deg) { start[(size_t)deg] = pos; pos += bucket[(size_t)deg]; }
+    order.resize((size_t)(m - n_long));
+    int64_t n_wave = 0;
+    for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
+    int32_t next_part = 0;
+    for (int64_t u = 0; u < m; ++u) {
+      const int64_t deg = rp[u + 1] - rp[u];
+      if (deg <= split_min) {
+        order[(size_t)start[(size_t)deg]++] = (int32_t)u;
+        continue;
+      }
+      const int64_t nc = (deg + chunk - 1) / chunk;
+      int64_t per = (deg + nc - 1) / nc;
+      per = (per + 255) / 256 * 256;  // whole batches of 64 entries for each of the 4 wavefronts
+      const int64_t nc2 = (deg + per - 1) / per;
+      if (nc2 > 1) merges.push_back(MergeDesc{(int32_t)u, next_part, (int32_t)nc2, 0});
+      for (int64_t c = 0; c < nc2; ++c) {
+        ChunkDesc cd;
+        cd.e_begin = rp[u] + c * per;
+        cd.e_count = (int32_t)std::min<int64_t>(per, deg - c * per);
+        cd.row = (int32_t)u;
+        cd.part = nc2 > 1 ? next_part++ : -1;
+        cd.pad = 0;
+        chunks.push_back(cd);
+      }
+    }
+    p->n_wave = (int32_t)n_wave;
+    p->n_packed = (int32_t)((m - n_long) - n_wave);
+    p->n_chunks = (int32_t)chunks.size();
+    p->n_merges = (int32_t)merges.size();
+    p->n_parts = next_part;
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return FUSEDMM_ERR_ALLOC;
+  }
+
+  int st = upload(&p->d_order, order, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_chunks, chunks, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_merges, merges, stream);
+  if (st == FUSEDMM_OK && hipStreamSynchronize(stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+  if (st != FUSEDMM_OK) {
+    free_plan_device(p);
+    delete p;
+    return st;
+  }
+  *out = p;
+  return FUSEDMM_OK;
+}
+
+int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
+  if (!plan) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  return is_fast_dim(d) ? ensure_partials(plan, d) : FUSEDMM_OK;
+}
+
+int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
+  if (!plan || !out) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  size_t b = (size_t)(plan->n_wave + plan->n_packed) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
+             (size_t)plan->n_merges * sizeof(MergeDesc);
+  if (is_fast_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(d, plan->partials_d) * sizeof(float);
+  *out = b;
+  return FUSEDMM_OK;
+}
+
+int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64_t* n_wave_rows, int64_t* n_chunks,
+                       int64_t* n_split_rows, int64_t* n_partials) {
+  if (!plan) return FUSEDMM_ERR_INVALID_ARG;
+  if (n_packed_rows) *n_packed_rows = plan->n_packed;
+  if (n_wave_rows) *n_wave_rows = plan->n_wave;
+  if (n_chunks) *n_chunks = plan->n_chunks;
+  if (n_split_rows) *n_split_rows = plan->n_merges;
+  if (n_partials) *n_partials = plan->n_parts;
+  return FUSEDMM_OK;
+}
+
+int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
+                    int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+  if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (!ops_valid(*ops)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
+  const bool uses_x = ops->vop != FUSEDMM_VOP_SEL2ND;
+  const bool uses_val = ops->sop == FUSEDMM_SOP_EDGE_VALUE;
+  if (plan->m == 0) return FUSEDMM_OK;
+  if (!d_Z || ldz < d) return FUSEDMM_ERR_INVALID_ARG;
+  if (plan->nnz > 0) {
+    if (!d_Y || ldy < d) return FUSEDMM_ERR_INVALID_ARG;
+    if (uses_val && !d_values) return FUSEDMM_ERR_INVALID_ARG;
+  }
+  if (uses_x && (!d_X || ldx < d)) return FUSEDMM_ERR_INVALID_ARG;
+  if (overlaps(d_Z, plan->m, ldz, d_Y, plan->n, ldy, d)) return FUSEDMM_ERR_ALIAS;
+  if (uses_x && overlaps(d_Z, plan->m, ldz, d_X, plan->m, ldx, d)) return FUSEDMM_ERR_ALIAS;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+  const int pattern = recognise(*ops);
+  const bool fast = pattern >= 0 && is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) &&
+                    (plan->nnz == 0 || (aligned16(d_Y) && ldy % 4 == 0)) &&
+                    (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
+
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  if (plan->profiling && plan->events_used < plan->events.size()) {
+    ev0 = plan->events[plan->events_used].first;
+    ev1 = plan->events[plan->events_used].second;
+  }
+
+  hipError_t e = hipSuccess;
+  if (fast) {
+    const int st = ensure_partials(plan, d);
+    if (st != FUSEDMM_OK) return st;
+    KernelArgs a;
+    fill_schedule_args(plan, d, &a);
+    a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
+    a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
+    a.alpha = ops->alpha;
+    if (ev0) (void)hipEventRecord(ev0, stream);
+    e = launch_fast(pattern, d, a, stream);
+    if (ev0) { (void)hipEventRecord(ev1, stream); ++plan->events_used; }
+    // partial rows are stored densely with stride d, whatever the scratch capacity is
+    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, d_Z, ldz, stream);
+  } else {
+    GenericArgs g;
+    g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
+    g.X = d_X; g.Y = d_Y; g.Z = d_Z;
+    g.ldx = ldx; g.ldy = ldy; g.ldz = ldz;
+    g.m = plan->m; g.d = d;
+    g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop;
+    g.alpha = ops->alpha;
+    g.visit_counts = nullptr;
+    if (ev0) (void)hipEventRecord(ev0, stream);
+    e = launch_generic(g, stream);
+    if (ev0) { (void)hipEventRecord(ev1, stream); ++plan->events_used; }
+  }
+  return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+}
+
+int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path, uint32_t* d_counts, void* stream_) {
+  if (!plan) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (fast_path && !is_fast_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (plan->m == 0 || plan->nnz == 0) return FUSEDMM_OK;
+  if (!d_counts) return FUSEDMM_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipError_t e;
+  if (fast_path) {
+    KernelArgs a;
+    fill_schedule_args(plan, d, &a);
+    a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
+    a.ldx = a.ldy = a.ldz = d;
+    a.alpha = 0.f;
+    a.visit_counts = d_counts;
+    e = launch_fast(PAT_VISIT, d, a, stream);
+  } else {
+    GenericArgs g = {};
+    g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;
+    g.m = plan->m; g.d = d;
+    g.visit_counts = d_counts;
+    e = launch_generic(g, stream);
+  }
+  return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+}
+
+int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled) {
+  if (!plan) return FUSEDMM_ERR_INVALID_ARG;
+  plan->profiling = enabled != 0;
+  plan->events_used = 0;
+  if (plan->profiling && plan->events.empty()) {
+    try {
+      plan->events.reserve(kMaxProfiledCalls);
+    } catch (const std::bad_alloc&) {
+      return FUSEDMM_ERR_ALLOC;
+    }
+    for (size_t i = 0; i < kMaxProfiledCalls; ++i) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return FUSEDMM_ERR_HIP;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return FUSEDMM_ERR_HIP; }
+      plan->events.emplace_back(a, b);
+    }
+  }
+  return FUSEDMM_OK;
+}
+
+int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, int64_t* calls) {
+  if (!plan || !main_kernel_ms_sum || !calls) return FUSEDMM_ERR_INVALID_ARG;
+  double sum = 0.0;
+  for (size_t i = 0; i < plan->events_used; ++i) {
+    if (hipEventSynchronize(plan->events[i].second) != hipSuccess) return FUSEDMM_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, plan->events[i].first, plan->events[i].second) != hipSuccess) return FUSEDMM_ERR_HIP;
+    sum += ms;
+  }
+  *main_kernel_ms_sum = sum;
+  *calls = (int64_t)plan->events_used;
+  plan->events_used = 0;
+  return FUSEDMM_OK;
+}
+
+int fusedmm_plan_destroy(fusedmm_plan_t* plan) {
+  if (!plan) return FUSEDMM_OK;
+  free_plan_device(plan);
+  delete plan;
+  return FUSEDMM_OK;
+}
+
+}  // extern "C"

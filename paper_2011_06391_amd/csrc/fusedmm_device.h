@@ -1,0 +1,362 @@
+// Device code of the specialised FusedMM kernels (gfx950, wave64).
+//
+// Work decomposition (one launch covers all three kinds of workgroup):
+//   * packed rows : short rows; a wavefront is cut into S = 64/G lane groups, each
+//                   lane group owns one row (UpdateU of Algorithm 1 per lane group);
+//   * wave rows   : one wavefront per row; its S lane groups take different stored
+//                   entries of the same row and are summed across groups at the end;
+//   * chunks      : long rows; a workgroup of 4 wavefronts takes a contiguous chunk of
+//                   the row's entries, sums the 4 wavefront partials through LDS in a
+//                   fixed order and stores either z_u (single chunk) or a partial row.
+// In every kind a lane group of G lanes holds x_u and the z_u accumulator in VGPRs
+// (the register blocking of Section IV-A), gathers y_v with 16-byte loads that are
+// contiguous across the group, reduces ROP across the group with DPP/swizzle, applies
+// SOP and folds MOP+AOP into FMAs.  z_u is written once with non-temporal stores.
+#pragma once
+#include "fusedmm_internal.h"
+
+namespace fmm {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------
+// cross-lane helpers
+// ---------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// value of lane (lane ^ MASK); MASK a power of two
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+  if constexpr (MASK == 1) return dpp_mov<0xB1>(v);        // quad_perm [1,0,3,2]
+  else if constexpr (MASK == 2) return dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+  else if constexpr (MASK == 8) return dpp_mov<0x128>(v);  // row_ror:8
+  else if constexpr (MASK == 16)
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));  // swap 16
+  else return __shfl_xor(v, MASK);
+}
+
+// Sum over each aligned group of G lanes, result in every lane of the group.
+template <int G>
+__device__ __forceinline__ float group_allreduce(float v) {
+  static_assert(G == 8 || G == 16 || G == 32 || G == 64, "lane group size");
+  v += dpp_mov<0xB1>(v);                      // lanes ^1
+  v += dpp_mov<0x4E>(v);                      // lanes ^2   -> quad sums
+  v += dpp_mov<0x141>(v);                     // row_half_mirror -> sums of 8
+  if constexpr (G >= 16) v += dpp_mov<0x140>(v);  // row_mirror -> sums of 16
+  if constexpr (G >= 32) v += lane_xor<16>(v);
+  if constexpr (G >= 64) v += lane_xor<32>(v);
+  return v;
+}
+
+// Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
+template <int G>
+__device__ __forceinline__ float cross_group_allreduce(float v) {
+  if constexpr (G <= 8) v += lane_xor<8>(v);
+  if constexpr (G <= 16) v += lane_xor<16>(v);
+  if constexpr (G <= 32) v += lane_xor<32>(v);
+  return v;
+}
+
+__device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+
+// ---------------------------------------------------------------------------------------
+// per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
+// ---------------------------------------------------------------------------------------
+template <int P>
+struct PatTraits {
+  static constexpr bool uses_x = (P != PAT_GCN && P != PAT_VISIT);
+  static constexpr bool uses_val = (P == PAT_GCN);
+  static constexpr bool loads_y = (P != PAT_VISIT);
+};
+
+template <int P, int G, int V, bool CHECK>
+__device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V], float aval, float alpha,
+                                            bool valid, v4f (&z)[V]) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  if constexpr (P == PAT_GCN) {
+    // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP+AOP: z += h * y
+    float h = aval;
+    if (CHECK && !valid) h = 0.f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) z[i] += h * y[i];
+  } else if constexpr (P == PAT_SIGMOID || P == PAT_ONE_MINUS_SIGMOID) {
+    float p = 0.f;  // VOP = MUL and this lane's share of ROP = RSUM
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      p = __builtin_fmaf(x[i].x, y[i].x, p);
+      p = __builtin_fmaf(x[i].y, y[i].y, p);
+      p = __builtin_fmaf(x[i].z, y[i].z, p);
+      p = __builtin_fmaf(x[i].w, y[i].w, p);
+    }
+    const float s = group_allreduce<G>(p);
+    // SOP: sigma(s) = 1/(1+2^(-s log2 e)); 1-sigma(s) = sigma(-s).  2^big = inf -> h = 0, no NaN.
+    const float e = __builtin_amdgcn_exp2f(P == PAT_SIGMOID ? -s * kLog2e : s * kLog2e);
+    float h = __builtin_amdgcn_rcpf(1.0f + e);
+    if (CHECK && !valid) h = 0.f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) z[i] += h * y[i];  // MOP = MUL with y_v, AOP = SUM
+  } else if constexpr (P == PAT_TDIST || P == PAT_FR) {
+    v4f t[V];
+    float p = 0.f;  // VOP = SUB, ROP = sum of squares
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      t[i] = x[i] - y[i];
+      p = __builtin_fmaf(t[i].x, t[i].x, p);
+      p = __builtin_fmaf(t[i].y, t[i].y, p);
+      p = __builtin_fmaf(t[i].z, t[i].z, p);
+      p = __builtin_fmaf(t[i].w, t[i].w, p);
+    }
+    const float s = group_allreduce<G>(p);
+    float h = (P == PAT_TDIST) ? __builtin_amdgcn_rcpf(1.0f + s) : alpha * __builtin_amdgcn_sqrtf(s);
+    if (CHECK && !valid) h = 0.f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) z[i] += h * t[i];  // MOP = MUL with the VOP output
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// One wavefront accumulates the stored entries [e0, e1) of a single row.  The S lane groups
+// take entries round-robin inside batches of 64; z holds this group's partial sum.
+// ---------------------------------------------------------------------------------------
+template <int P, int D, int G, int U>
+__device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
+                                                const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int lane) {
+  constexpr int V = D / (4 * G);
+  constexpr int S = 64 / G;
+  static_assert(S * U <= 64 && 64 % (S * U) == 0, "unroll must tile a batch of 64 entries");
+  using T = PatTraits<P>;
+  const int slot = lane / G;
+  const int g = lane % G;
+  const float* ybase = a.Y + 4 * g;
+
+  for (int64_t base = e0; base < e1; base += 64) {
+    const int cnt = (int)((e1 - base) < 64 ? (e1 - base) : 64);  // wave-uniform
+    int colb = 0;
+    float valb = 0.f;
+    if (lane < cnt) {
+      colb = a.colidx[base + lane];
+      if constexpr (T::uses_val) valb = a.values[base + lane];
+    }
+    for (int k0 = 0; k0 < cnt; k0 += S * U) {
+      int c[U];
+      float av[U];
+      v4f y[U][V];
+      if (k0 + S * U <= cnt) {
+        // every lane group has a stored entry in each of the U steps
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = k0 + u * S + slot;
+          c[u] = __shfl(colb, j);
+          av[u] = T::uses_val ? __shfl(valb, j) : 0.f;
+        }
+        if constexpr (T::loads_y) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const float* yr = ybase + (int64_t)c[u] * a.ldy;
+#pragma unroll
+            for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * G * i);
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a.alpha, true, z);
+        } else {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            if (g == 0) atomicAdd(a.visit_counts + (base + k0 + u * S + slot), 1u);
+        }
+      } else {
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = k0 + u * S + slot;
+          ok[u] = j < cnt;
+          c[u] = __shfl(colb, j & 63);
+          av[u] = T::uses_val ? __shfl(valb, j & 63) : 0.f;
+        }
+        if constexpr (T::loads_y) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (ok[u]) {
+              const float* yr = ybase + (int64_t)c[u] * a.ldy;
+#pragma unroll
+              for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * G * i);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
+        } else {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            if (ok[u] && g == 0) atomicAdd(a.visit_counts + (base + k0 + u * S + slot), 1u);
+        }
+      }
+    }
+  }
+}
+
+template <int D, int G>
+__device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
+  const float* xr = a.X + row * a.ldx + 4 * g;
+#pragma unroll
+  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4(xr + 4 * G * i);
+}
+
+template <int V>
+__device__ __forceinline__ void zero(v4f (&z)[V]) {
+#pragma unroll
+  for (int i = 0; i < V; ++i) z[i] = v4f{0.f, 0.f, 0.f, 0.f};
+}
+
+template <int D, int G>
+__device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / (4 * G)]) {
+#pragma unroll
+  for (int i = 0; i < D / (4 * G); ++i)
+    __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * g + 4 * G * i));
+}
+
+// ---------------------------------------------------------------------------------------
+// The fused kernel.  GW/UW: lane-group size and unroll of the wave-row and chunk paths;
+// GP/UP: of the packed path.
+// ---------------------------------------------------------------------------------------
+template <int P, int D, int GW, int UW, int GP, int UP>
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
+  using T = PatTraits<P>;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int b = blockIdx.x;
+
+  if (b < a.nb_chunk) {
+    // ---- long rows: one chunk per workgroup -------------------------------------------
+    constexpr int V = D / (4 * GW);
+    __shared__ v4f stage[kWavesPerBlock][D / 4];
+    const ChunkDesc ch = a.chunks[b];
+    const int per = ((ch.e_count + kWavesPerBlock * 64 - 1) / (kWavesPerBlock * 64)) * 64;
+    const int lo = wave * per < ch.e_count ? wave * per : ch.e_count;
+    const int hi = (wave + 1) * per < ch.e_count ? (wave + 1) * per : ch.e_count;
+    const int g = lane % GW;
+    v4f x[V], z[V];
+    zero(z);
+    if constexpr (T::uses_x) load_x<D, GW>(a, ch.row, g, x); else zero(x);
+    wave_accumulate<P, D, GW, UW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
+    if constexpr (T::loads_y) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        z[i].x = cross_group_allreduce<GW>(z[i].x);
+        z[i].y = cross_group_allreduce<GW>(z[i].y);
+        z[i].z = cross_group_allreduce<GW>(z[i].z);
+        z[i].w = cross_group_allreduce<GW>(z[i].w);
+      }
+      if (lane < GW) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) stage[wave][g + GW * i] = z[i];
+      }
+      __syncthreads();
+      if (threadIdx.x < D / 4) {
+        v4f s = stage[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) s += stage[w][threadIdx.x];
+        float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * D;
+        __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * threadIdx.x));
+      }
+    }
+  } else if (b < a.nb_chunk + a.nb_wave) {
+    // ---- one row per wavefront ---------------------------------------------------------
+    constexpr int V = D / (4 * GW);
+    const int idx = (b - a.nb_chunk) * kWavesPerBlock + wave;
+    if (idx >= a.n_wave) return;
+    const int row = __builtin_amdgcn_readfirstlane(a.order[idx]);
+    const int64_t e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
+    const int g = lane % GW;
+    v4f x[V], z[V];
+    zero(z);
+    if constexpr (T::uses_x) load_x<D, GW>(a, row, g, x); else zero(x);
+    wave_accumulate<P, D, GW, UW>(a, e0, e1, x, z, lane);
+    if constexpr (T::loads_y) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        z[i].x = cross_group_allreduce<GW>(z[i].x);
+        z[i].y = cross_group_allreduce<GW>(z[i].y);
+        z[i].z = cross_group_allreduce<GW>(z[i].z);
+        z[i].w = cross_group_allreduce<GW>(z[i].w);
+      }
+      if (lane < GW) store_row<D, GW>(a.Z + (int64_t)row * a.ldz, g, z);
+    }
+  } else {
+    // ---- packed short rows: one row per lane group -------------------------------------
+    constexpr int V = D / (4 * GP);
+    constexpr int S = 64 / GP;
+    static_assert(GP % UP == 0, "packed unroll must divide the lane-group size");
+    const int slot = lane / GP;
+    const int g = lane % GP;
+    const int idx = ((b - a.nb_chunk - a.nb_wave) * kWavesPerBlock + wave) * S + slot;
+    const bool has_row = idx < a.n_packed;
+    int64_t row = 0, e0 = 0;
+    int deg = 0;
+    if (has_row) {
+      row = a.order[a.n_wave + idx];
+      e0 = a.rowptr[row];
+      deg = (int)(a.rowptr[row + 1] - e0);
+    }
+    v4f x[V], z[V];
+    zero(z);
+    zero(x);
+    if constexpr (T::uses_x) {
+      if (deg > 0) load_x<D, GP>(a, row, g, x);
+    }
+    int maxdeg = deg;  // wave-uniform upper bound of the trip count
+    if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
+    if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
+    if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
+    maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
+    const float* ybase = a.Y + 4 * g;
+
+    for (int bb = 0; bb < maxdeg; bb += GP) {
+      int colb = 0;
+      float valb = 0.f;
+      if (bb + g < deg) {
+        colb = a.colidx[e0 + bb + g];
+        if constexpr (T::uses_val) valb = a.values[e0 + bb + g];
+      }
+      const int steps = (maxdeg - bb) < GP ? (maxdeg - bb) : GP;
+      for (int k = 0; k < steps; k += UP) {
+        bool ok[UP];
+        int c[UP];
+        float av[UP];
+        v4f y[UP][V];
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+          ok[u] = (bb + k + u) < deg;
+          c[u] = __shfl(colb, slot * GP + k + u);
+          av[u] = T::uses_val ? __shfl(valb, slot * GP + k + u) : 0.f;
+        }
+        if constexpr (T::loads_y) {
+#pragma unroll
+          for (int u = 0; u < UP; ++u) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (ok[u]) {
+              const float* yr = ybase + (int64_t)c[u] * a.ldy;
+#pragma unroll
+              for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * GP * i);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
+        } else {
+#pragma unroll
+          for (int u = 0; u < UP; ++u)
+            if (ok[u] && g == 0) atomicAdd(a.visit_counts + (e0 + bb + k + u), 1u);
+        }
+      }
+    }
+    if constexpr (T::loads_y) {
+      if (has_row) store_row<D, GP>(a.Z + row * a.ldz, g, z);
+    }
+  }
+}
+
+}  // namespace fmm

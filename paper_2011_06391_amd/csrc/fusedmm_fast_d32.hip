@@ -1,0 +1,8 @@
+// Specialised FusedMM kernels for d = 32: lane groups of 8 lanes (unroll 8) for wave rows and
+// chunks, lane groups of 8 lanes (unroll 4) for packed short rows.
+#define FMM_D 32
+#define FMM_GW 8
+#define FMM_UW 8
+#define FMM_GP 8
+#define FMM_UP 4
+#include "fusedmm_fast_impl.h"

@@ -1,0 +1,33 @@
+// Instantiates the specialised kernel for one feature dimension and defines its launcher.
+// Included by fusedmm_fast_d*.hip with FMM_D / FMM_GW / FMM_UW / FMM_GP / FMM_UP set.
+#include "fusedmm_device.h"
+
+namespace fmm {
+
+#define FMM_CAT2(a, b) a##b
+#define FMM_CAT(a, b) FMM_CAT2(a, b)
+
+template <int P>
+static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
+  const int64_t blocks = (int64_t)a.nb_chunk + a.nb_wave + a.nb_packed;
+  if (blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP>), dim3((unsigned)blocks),
+                     dim3(kBlockThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+int FMM_CAT(packed_rows_per_block_d, FMM_D)() { return kWavesPerBlock * (64 / FMM_GP); }
+
+hipError_t FMM_CAT(launch_fast_d, FMM_D)(int pattern, const KernelArgs& a, hipStream_t stream) {
+  switch (pattern) {
+    case PAT_SIGMOID: return launch_one<PAT_SIGMOID>(a, stream);
+    case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID>(a, stream);
+    case PAT_GCN: return launch_one<PAT_GCN>(a, stream);
+    case PAT_TDIST: return launch_one<PAT_TDIST>(a, stream);
+    case PAT_FR: return launch_one<PAT_FR>(a, stream);
+    case PAT_VISIT: return launch_one<PAT_VISIT>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace fmm

@@ -1,0 +1,152 @@
+// General FusedMM kernel (any 1 <= d <= 2048, any supported op tuple, any alignment),
+// the split-row merge kernel, the colidx validator and the (pattern, d) dispatcher.
+#include "fusedmm_internal.h"
+#include "../../include/fusedmm.h"
+
+namespace fmm {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_allreduce(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+__device__ __forceinline__ float vop_apply(int vop, float x, float y) {
+  return vop == FUSEDMM_VOP_MUL ? x * y : (vop == FUSEDMM_VOP_SEL2ND ? y : x - y);
+}
+
+// Algorithm 1, UpdateU, one wavefront per row: lane l owns elements l, l+64, l+128, ...
+// of z_u in registers.  The five steps run per stored entry in the paper's order; the
+// row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
+constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
+
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (row >= a.m) return;
+  const int64_t e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
+  const int d = a.d;
+  if (a.visit_counts) {
+    for (int64_t e = e0 + lane; e < e1; e += 64) atomicAdd(a.visit_counts + e, 1u);
+    return;
+  }
+  const bool uses_x = a.vop != FUSEDMM_VOP_SEL2ND;
+  const float* xr = uses_x ? a.X + row * a.ldx : nullptr;
+  float acc[kGenericAcc];
+#pragma unroll
+  for (int i = 0; i < kGenericAcc; ++i) acc[i] = 0.f;
+
+  for (int64_t e = e0; e < e1; ++e) {
+    const float* yr = a.Y + (int64_t)a.colidx[e] * a.ldy;
+    float h;
+    if (a.rop == FUSEDMM_ROP_NOOP) {
+      h = a.values[e];  // SOP = EDGE_VALUE
+    } else {
+      float p = 0.f;
+      for (int k = lane; k < d; k += 64) {
+        const float t = vop_apply(a.vop, uses_x ? xr[k] : 0.f, yr[k]);  // VOP
+        p += (a.rop == FUSEDMM_ROP_RSUM) ? t : t * t;                    // ROP (per-lane share)
+      }
+      float s = wave_allreduce(p);
+      if (a.rop == FUSEDMM_ROP_NORM2) s = sqrtf(s);
+      switch (a.sop) {  // SOP
+        case FUSEDMM_SOP_SIGMOID: h = 1.0f / (1.0f + expf(-s)); break;
+        case FUSEDMM_SOP_ONE_MINUS_SIGMOID: h = 1.0f / (1.0f + expf(s)); break;
+        case FUSEDMM_SOP_INV_1P: h = 1.0f / (1.0f + s); break;
+        default: h = a.alpha * s; break;  // SCAL
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kGenericAcc; ++i) {
+      const int k = lane + 64 * i;
+      if (k < d) {
+        const float y = yr[k];
+        const float operand = (a.mop == FUSEDMM_MOP_MUL_Y) ? y : vop_apply(a.vop, uses_x ? xr[k] : 0.f, y);
+        acc[i] += h * operand;  // MOP + AOP
+      }
+    }
+  }
+  float* zr = a.Z + row * a.ldz;
+#pragma unroll
+  for (int i = 0; i < kGenericAcc; ++i) {
+    const int k = lane + 64 * i;
+    if (k < d) zr[k] = acc[i];
+  }
+}
+
+hipError_t launch_generic(const GenericArgs& a, hipStream_t stream) {
+  if (a.m <= 0) return hipSuccess;
+  const int64_t blocks = (a.m + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(fusedmm_generic_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+// z_u = sum of the row's partial rows, in chunk order (fixed order => run-to-run deterministic).
+__global__ __launch_bounds__(128) void fusedmm_merge_kernel(const MergeDesc* merges, const float* partials, int32_t d,
+                                                           float* Z, int64_t ldz) {
+  const MergeDesc md = merges[blockIdx.x];
+  const float* src = partials + (int64_t)md.first_part * d;
+  float* dst = Z + (int64_t)md.row * ldz;
+  for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
+    v4f s = *reinterpret_cast<const v4f*>(src + 4 * c);
+    for (int p = 1; p < md.n_parts; ++p) s += *reinterpret_cast<const v4f*>(src + (int64_t)p * d + 4 * c);
+    __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * c));
+  }
+}
+
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, float* Z,
+                        int64_t ldz, hipStream_t stream) {
+  if (n_merges <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)n_merges), dim3(128), 0, stream, merges, partials, d, Z, ldz);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void validate_colidx_kernel(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag) {
+  bool bad = false;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t c = colidx[i];
+    bad |= (c < 0) || ((int64_t)c >= n);
+  }
+  if (bad) atomicOr(flag, 1);
+}
+
+hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag, hipStream_t stream) {
+  if (nnz <= 0) return hipSuccess;
+  int64_t blocks = (nnz + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(validate_colidx_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, colidx, nnz, n, flag);
+  return hipGetLastError();
+}
+
+// ---- dispatcher over the per-dimension translation units --------------------------------
+#define FMM_DECL(D)                                                                   \
+  hipError_t launch_fast_d##D(int pattern, const KernelArgs& a, hipStream_t stream); \
+  int packed_rows_per_block_d##D();
+FMM_DECL(32) FMM_DECL(64) FMM_DECL(128) FMM_DECL(256) FMM_DECL(512)
+#undef FMM_DECL
+
+int packed_rows_per_block(int d) {
+  switch (d) {
+    case 32: return packed_rows_per_block_d32();
+    case 64: return packed_rows_per_block_d64();
+    case 128: return packed_rows_per_block_d128();
+    case 256: return packed_rows_per_block_d256();
+    case 512: return packed_rows_per_block_d512();
+    default: return 0;
+  }
+}
+
+hipError_t launch_fast(int pattern, int d, const KernelArgs& a, hipStream_t stream) {
+  switch (d) {
+    case 32: return launch_fast_d32(pattern, a, stream);
+    case 64: return launch_fast_d64(pattern, a, stream);
+    case 128: return launch_fast_d128(pattern, a, stream);
+    case 256: return launch_fast_d256(pattern, a, stream);
+    case 512: return launch_fast_d512(pattern, a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace fmm

@@ -1,0 +1,66 @@
+"""The C-ABI library loads and exports every symbol include/fusedmm.h declares.
+Only host-side calls (no GPU work) are made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2011_06391_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fusedmm.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fusedmm_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2011_06391_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_header_declares_the_documented_entry_points():
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"libfusedmm.so lacks {name}"
+        assert isinstance(getattr(lib, name), ctypes._CFuncPtr)
+
+
+def test_host_only_calls(lib):
+    assert binding.fusedmm_version() == 100
+    assert binding.fusedmm_status_string(0) == "ok"
+    assert "alias" in binding.fusedmm_status_string(binding.FUSEDMM_ERR_ALIAS) or "overlap" in binding.fusedmm_status_string(binding.FUSEDMM_ERR_ALIAS)
+    assert binding.fusedmm_status_string(12345) == "unknown status"
+    o = binding.fusedmm_ops_preset("tdist")
+    assert (o.vop, o.rop, o.sop, o.mop, o.aop) == (binding.VOP["SUB"], binding.ROP["SUMSQ"], binding.SOP["INV_1P"],
+                                                   binding.MOP["MUL_T"], 0)
+    o = binding.fusedmm_ops_preset("gcn")
+    assert (o.vop, o.rop, o.sop, o.mop) == (1, 0, 0, 0)
+    with pytest.raises(binding.FusedMMError):
+        binding.fusedmm_ops_preset(99)
+    # null arguments are reported, not dereferenced
+    assert lib.fusedmm_ops_preset(0, None) == binding.FUSEDMM_ERR_INVALID_ARG
+    assert lib.fusedmm_plan_create(None, 0, 0, 0, None, None, None, None) == binding.FUSEDMM_ERR_INVALID_ARG
+    assert lib.fusedmm_execute(None, None, 32, None, None, 0, None, 0, None, 0, None) == binding.FUSEDMM_ERR_INVALID_ARG
+    assert lib.fusedmm_plan_destroy(None) == binding.FUSEDMM_OK
+
+
+def test_enum_values_match_header():
+    text = open(HEADER).read()
+    for table, prefix in ((binding.VOP, "FUSEDMM_VOP_"), (binding.ROP, "FUSEDMM_ROP_"), (binding.SOP, "FUSEDMM_SOP_"),
+                          (binding.MOP, "FUSEDMM_MOP_")):
+        for name, val in table.items():
+            m = re.search(prefix + name + r"\s*=\s*(\d+)", text)
+            assert m and int(m.group(1)) == val, (prefix + name)
+    assert int(re.search(r"#define FUSEDMM_MAX_D (\d+)", text).group(1)) == binding.FUSEDMM_MAX_D

@@ -1,0 +1,339 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Tolerance (stated by the benchmark spec): max |Z_gpu - Z_ref| / sum|terms| <= 1e-4 per output
+entry in fp32; entries whose terms are all zero (empty rows) must be exactly 0.
+Which stored entries are visited must be exact: checked bitwise with integer data
+and with the edge-visit hook.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import random_csr
+from paper_2011_06391_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+FAST_DIMS = (32, 64, 128, 256, 512)
+PATTERNS = ("sigmoid", "one_minus_sigmoid", "gcn", "tdist", "fr")
+ALPHA = 0.37
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (torch.cuda.is_available() is False)")
+    from paper_2011_06391_amd import binding
+    binding.load()  # raises if libfusedmm.so is missing: there is no fallback
+    return binding
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_gpu(B, rowptr, colidx, vals, X, Y, pattern_or_ops, m, n, alpha=1.0, options=None, Z_fill=np.nan):
+    d = Y.shape[1]
+    rp, ci = dev(rowptr), dev(colidx)
+    plan = B.Plan(m, n, rp, ci, options)
+    Xd, Yd, vd = dev(X), (dev(Y) if Y is not X else None), dev(vals)
+    if Yd is None:
+        Yd = Xd
+    Z = torch.full((m, d), Z_fill, dtype=torch.float32, device="cuda")  # must be overwritten everywhere
+    ops = B.fusedmm_ops_preset(pattern_or_ops) if isinstance(pattern_or_ops, str) else pattern_or_ops
+    ops.alpha = alpha
+    plan.execute(ops, Xd, Yd, Z, vd)
+    torch.cuda.synchronize()
+    out = Z.cpu().numpy()
+    stats = plan.stats()
+    plan.close()
+    return out, stats
+
+
+def check(Zg, Zr, S, what=""):
+    err, am, viol = oracle.compare(Zg, Zr, S)
+    assert viol == 0, f"{what}: {viol} entries with no terms are not exactly zero"
+    assert err <= TOL, f"{what}: max rel err {err:.3e} at flat index {am}"
+    return err
+
+
+def skewed_csr(rng, m, n, long_rows):
+    """Mostly short rows, a few long ones (several chunks, ragged tails), some empty."""
+    degs = rng.integers(0, 40, m)
+    degs[rng.random(m) < 0.2] = 0
+    for r, L in long_rows.items():
+        degs[r] = L
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(degs)
+    colidx = rng.integers(0, n, rowptr[-1]).astype(np.int32)  # duplicates allowed, unsorted
+    return rowptr, colidx
+
+
+@pytest.mark.parametrize("d", FAST_DIMS)
+@pytest.mark.parametrize("pattern", PATTERNS)
+def test_fast_kernels_all_bins(B, pattern, d):
+    """Every specialised (pattern, d) instance over packed rows, wave rows, single-chunk
+    rows and rows split over several chunks, with ragged tails and empty rows."""
+    rng = np.random.default_rng(1000 + d)
+    m, n = 301, 517
+    long_rows = {3: 64, 4: 65, 10: 127, 11: 257, 57: 700, 200: 1024, 201: 1025, 299: 3001, 300: 5000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows)
+    X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    vals = rng.uniform(0.05, 1.0, len(colidx)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
+    for options in (None, {"small_row_max": 8, "split_row_min": 96, "chunk_edges": 512}):
+        Zg, stats = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA, options=options)
+        check(Zg, Zr, S, f"{pattern} d={d} options={options}")
+        assert stats["packed_rows"] > 0 and stats["wave_rows"] > 0 and stats["chunks"] > 0 and stats["split_rows"] > 0
+
+
+@pytest.mark.parametrize("d", (1, 3, 4, 33, 100, 130, 2048))
+@pytest.mark.parametrize("pattern", PATTERNS)
+def test_general_kernel_odd_dims(B, pattern, d):
+    rng = np.random.default_rng(7 + d)
+    m, n = 37, 53
+    rowptr, colidx = random_csr(rng, m, n, 0.25, empty_rows=(0, 5, m - 1), duplicates=True, sort_cols=False)
+    X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    vals = rng.uniform(0.05, 1.0, len(colidx)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
+    Zg, _ = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA)
+    check(Zg, Zr, S, f"{pattern} d={d}")
+
+
+# op tuples outside the five presets: (binding names) -> (oracle names)
+OTHER_TUPLES = [
+    (("MUL", "RSUM", "SCAL", "MUL_Y"), ("MUL", "RSUM", "SCAL", "MUL_Y")),
+    (("SUB", "SUMSQ", "SIGMOID", "MUL_Y"), ("SUB", "SUMSQ", "SIGMOID", "MUL_Y")),
+    (("MUL", "NORM2", "INV_1P", "MUL_T"), ("MUL", "NORM", "INV1P", "MUL_T")),
+    (("SEL2ND", "RSUM", "ONE_MINUS_SIGMOID", "MUL_Y"), ("SEL2ND", "RSUM", "ONE_MINUS_SIGMOID", "MUL_Y")),
+]
+
+
+@pytest.mark.parametrize("d", (20, 128))
+@pytest.mark.parametrize("tuples", OTHER_TUPLES)
+def test_general_kernel_other_op_tuples(B, tuples, d):
+    gpu_names, oracle_names = tuples
+    rng = np.random.default_rng(99)
+    m, n = 40, 60
+    rowptr, colidx = random_csr(rng, m, n, 0.2, empty_rows=(2,))
+    X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, None, X, Y, oracle_names, alpha=ALPHA)
+    Zg, _ = run_gpu(B, rowptr, colidx, None, X, Y, B.make_ops(*gpu_names), m, n, alpha=ALPHA)
+    check(Zg, Zr, S, f"{gpu_names} d={d}")
+
+
+def test_leading_dimensions_and_rectangular(B):
+    """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
+    rng = np.random.default_rng(5)
+    m, n, d = 150, 400, 64
+    rowptr, colidx = skewed_csr(rng, m, n, {7: 600})
+    Xb = rng.uniform(-0.5, 0.5, (m, d + 16)).astype(np.float32)
+    Yb = rng.uniform(-0.5, 0.5, (n, d + 32)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, None, Xb[:, :d], Yb[:, :d], "tdist")
+    rp, ci = dev(rowptr), dev(colidx)
+    plan = B.Plan(m, n, rp, ci)
+    Xd, Yd = dev(Xb), dev(Yb)
+    Zb = torch.full((m, d + 8), 7.0, dtype=torch.float32, device="cuda")
+    plan.execute("tdist", Xd[:, :d], Yd[:, :d], Zb[:, :d])
+    torch.cuda.synchronize()
+    out = Zb.cpu().numpy()
+    check(out[:, :d], Zr, S, "strided")
+    assert (out[:, d:] == 7.0).all()
+    # an unaligned view (offset by one float) must take the general kernel and still be right
+    Zr2, S2, _ = oracle.unfused(rowptr, colidx, None, Xb[:, 1:d + 1], Yb[:, 1:d + 1], "tdist")
+    Zc = torch.full((m, d), np.nan, dtype=torch.float32, device="cuda")
+    plan.execute("tdist", Xd[:, 1:d + 1], Yd[:, 1:d + 1], Zc)
+    torch.cuda.synchronize()
+    check(Zc.cpu().numpy(), Zr2, S2, "unaligned")
+    plan.close()
+
+
+@pytest.mark.parametrize("d", (32, 128, 512, 48))
+def test_edges_visited_exactly_once_integer_data(B, d):
+    """GCN pattern, unit edge values, small-integer features: every fp32 partial sum is an
+    exact integer in any order, so the GPU result must equal the oracle bit for bit.  A
+    missed or doubled stored entry cannot hide behind a tolerance."""
+    g = synth.rmat(12, (1 << 11) * 16, seed=31)
+    X = synth.fill_int((g.m, d), 41, -8, 8)
+    vals = np.ones(g.nnz, dtype=np.float32)
+    assert g.degrees().max() * 8 < 2 ** 24
+    Zr, _, _ = oracle.unfused(g.rowptr, g.colidx, vals, None, X, "gcn")
+    for options in (None, {"small_row_max": 4, "split_row_min": 64, "chunk_edges": 256}):
+        Zg, _ = run_gpu(B, g.rowptr, g.colidx, vals, None, X, "gcn", g.m, g.n, options=options)
+        assert np.array_equal(Zg.astype(np.float64), Zr)
+
+
+@pytest.mark.parametrize("d", FAST_DIMS)
+def test_edge_visit_hook_fast_and_general(B, d):
+    g = synth.rmat(13, (1 << 12) * 16, seed=32)
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    for options in (None, {"small_row_max": 3, "split_row_min": 70, "chunk_edges": 256}):
+        plan = B.Plan(g.m, g.n, rp, ci, options)
+        for fast in (True, False):
+            counts = torch.zeros(g.nnz, dtype=torch.int32, device="cuda")
+            plan.edge_visits(d, fast, counts)
+            torch.cuda.synchronize()
+            c = counts.cpu().numpy()
+            assert c.min() == 1 and c.max() == 1, f"d={d} fast={fast}: visit counts in [{c.min()}, {c.max()}]"
+        plan.close()
+
+
+def test_empty_inputs(B):
+    d = 64
+    # all rows empty
+    rowptr = np.zeros(11, dtype=np.int64)
+    colidx = np.zeros(0, dtype=np.int32)
+    X = np.ones((10, d), dtype=np.float32)
+    for pattern in PATTERNS:
+        vals = np.zeros(0, dtype=np.float32)
+        Zg, _ = run_gpu(B, rowptr, colidx, vals, X, X, pattern, 10, 10)
+        assert (Zg == 0).all()
+    # m == 0
+    rp = dev(np.zeros(1, dtype=np.int64))
+    plan = B.Plan(0, 5, rp, torch.zeros(0, dtype=torch.int32, device="cuda"))
+    Z = torch.zeros((0, d), dtype=torch.float32, device="cuda")
+    Y = torch.zeros((5, d), dtype=torch.float32, device="cuda")
+    plan.execute("sigmoid", Z, Y, Z)  # nothing to do, must succeed
+    plan.close()
+    # one row, one entry; one hub row between empty rows
+    rowptr = np.array([0, 0, 1500, 1500, 1501], dtype=np.int64)
+    rng = np.random.default_rng(3)
+    colidx = rng.integers(0, 4, 1501).astype(np.int32)
+    X = rng.uniform(-0.5, 0.5, (4, d)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, None, X, X, "sigmoid")
+    Zg, _ = run_gpu(B, rowptr, colidx, None, X, X, "sigmoid", 4, 4)
+    check(Zg, Zr, S, "hub between empty rows")
+    assert (Zg[0] == 0).all() and (Zg[2] == 0).all()
+
+
+def test_sigmoid_saturation_no_nan(B):
+    d = 32
+    rowptr = np.array([0, 2], dtype=np.int64)
+    colidx = np.array([0, 1], dtype=np.int32)
+    X = np.full((1, d), 30.0, dtype=np.float32)
+    Y = np.stack([np.full(d, 30.0), np.full(d, -30.0)]).astype(np.float32)
+    for pattern in ("sigmoid", "one_minus_sigmoid"):
+        Zr, S, _ = oracle.unfused(rowptr, colidx, None, X, Y, pattern)
+        Zg, _ = run_gpu(B, rowptr, colidx, None, X, Y, pattern, 1, 2)
+        assert np.isfinite(Zg).all()
+        check(Zg, Zr, S, pattern)
+
+
+def test_run_to_run_determinism(B):
+    w = synth.make_workload("c1")
+    g = w.csr
+    rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(w.X)
+    plan = B.Plan(g.m, g.n, rp, ci, {"small_row_max": 4, "split_row_min": 8, "chunk_edges": 256})
+    outs = []
+    for _ in range(3):
+        Z = torch.empty((g.m, w.d), dtype=torch.float32, device="cuda")
+        plan.execute(w.pattern, Xd, Xd, Z)
+        torch.cuda.synchronize()
+        outs.append(Z.cpu().numpy())
+    plan.close()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_status_codes(B):
+    g = synth.rmat(8, 1024, seed=2)
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    d = 32
+    X = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
+    Z = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
+    plan = B.Plan(g.m, g.n, rp, ci)
+    ops = B.fusedmm_ops_preset("sigmoid")
+
+    def status(fn):
+        with pytest.raises(B.FusedMMError) as ei:
+            fn()
+        return ei.value.status
+
+    assert status(lambda: B.fusedmm_execute(plan._plan, ops, 0, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_DIM
+    assert status(lambda: B.fusedmm_execute(plan._plan, ops, 4096, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_DIM
+    assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, X, d - 1, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
+    assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, None, d, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
+    assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, X, d, X, d, X, d)) == B.FUSEDMM_ERR_ALIAS
+    gcn = B.fusedmm_ops_preset("gcn")
+    assert status(lambda: B.fusedmm_execute(plan._plan, gcn, d, None, None, 0, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
+    bad = B.make_ops("MUL", "NOOP", "SIGMOID", "MUL_Y")  # vector-valued h is not supported
+    assert status(lambda: B.fusedmm_execute(plan._plan, bad, d, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_OPS
+    assert (Z == 0).all().item()  # nothing was written by the failed calls
+    plan.close()
+    # bad structure is refused at plan creation, before any kernel could index out of bounds
+    bad_ci = ci.clone()
+    bad_ci[5] = g.n
+    assert status(lambda: B.Plan(g.m, g.n, rp, bad_ci)) == B.FUSEDMM_ERR_INVALID_ARG
+    bad_rp = rp.clone()
+    bad_rp[3] = bad_rp[4] + 1
+    assert status(lambda: B.Plan(g.m, g.n, bad_rp, ci)) == B.FUSEDMM_ERR_INVALID_ARG
+    assert status(lambda: B.Plan(g.m, g.n, rp, ci[:-1])) == B.FUSEDMM_ERR_INVALID_ARG
+
+
+def test_workspace_is_not_per_edge_message(B):
+    """The library never materialises messages: workspace = O(m + chunks + partials*d)."""
+    w = synth.make_workload("c2")
+    g = w.csr
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    plan = B.Plan(g.m, g.n, rp, ci)
+    s = plan.stats()
+    ws = plan.workspace_bytes(w.d)
+    assert ws <= 4 * g.m + 24 * s["chunks"] + 16 * s["split_rows"] + 4 * w.d * s["partials"]
+    assert ws < 0.02 * 4 * g.nnz * w.d  # far below the nnz x d message tensor
+    assert s["packed_rows"] + s["wave_rows"] + s["chunks"] - s["partials"] + s["split_rows"] == g.m
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ("c1", "c2"))
+def test_workload_full_elementwise(B, name):
+    w = synth.make_workload(name)
+    g = w.csr
+    Zr, S, _ = oracle.unfused(g.rowptr, g.colidx, g.values, w.X, w.Y, w.pattern)
+    Zg, stats = run_gpu(B, g.rowptr, g.colidx, g.values, w.X, w.Y, w.pattern, g.m, g.n)
+    err = check(Zg, Zr, S, name)
+    print(f"{name}: nnz={g.nnz} max rel err {err:.2e} plan {stats}")
+
+
+@pytest.mark.parametrize("name", ("c3", "c4", "c5"))
+def test_workload_full_size_sampled_rows(B, name):
+    """Full-size run in the launch configuration bench.py uses; the oracle recomputes a
+    sample of rows (the longest rows, random rows, empty rows) one by one from the same
+    inputs -- a rectangular slice of A against the whole of Y.  Plus the edge-visit hook
+    over the whole graph."""
+    w = synth.make_workload(name)
+    g = w.csr
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    plan = B.Plan(g.m, g.n, rp, ci)
+    Xd = dev(w.X)
+    Yd = Xd if w.Y is w.X else dev(w.Y)
+    vd = dev(g.values)
+    Z = torch.full((g.m, w.d), np.nan, dtype=torch.float32, device="cuda")
+    plan.execute(w.pattern, None if w.pattern == "gcn" else Xd, Yd, Z, vd)
+    torch.cuda.synchronize()
+    deg = g.degrees()
+    rng = np.random.default_rng(17)
+    hubs = np.argsort(-deg)[:6]
+    rand = rng.choice(g.m, 1500, replace=False)
+    empty = np.nonzero(deg == 0)[0][:50]
+    mid = np.nonzero((deg > 200) & (deg < 3000))[0][:200]
+    rows = np.unique(np.concatenate([hubs, rand, empty, mid])).astype(np.int64)
+    sub = g.take_rows(rows)
+    Zr, S, _ = oracle.unfused(sub.rowptr, sub.colidx, sub.values, w.X[rows], w.Y, w.pattern)
+    Zg = Z[torch.from_numpy(rows).cuda()].cpu().numpy()
+    err = check(Zg, Zr, S, name)
+    # properties that hold at any size: every entry finite, empty rows exactly zero
+    assert torch.isfinite(Z).all().item()
+    ez = torch.from_numpy(np.nonzero(deg == 0)[0]).cuda()
+    if len(ez) > 0:
+        assert (Z[ez] == 0).all().item()
+    del Z
+    counts = torch.zeros(g.nnz, dtype=torch.int32, device="cuda")
+    plan.edge_visits(w.d, True, counts)
+    torch.cuda.synchronize()
+    assert counts.min().item() == 1 and counts.max().item() == 1
+    print(f"{name}: nnz={g.nnz} sampled rows {len(rows)} max rel err {err:.2e} plan {plan.stats()}")
+    plan.close()
