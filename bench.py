@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def cpu_baseline(w, budget_edges_dim: float = 6.0e9):
+def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
     """Time the oracle's fp32 two-phase (unfused) build on a bounded sample of the rows."""
     import numpy as np
     import oracle
@@ -46,16 +46,17 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e9):
         sample = f"{len(rows)} random rows of {g.m} ({sub.nnz} of {g.nnz} stored entries), all of Y"
     X = w.X if rows is None else w.X[rows]
     times = []
-    for _ in range(3 if sub.nnz * w.d < 2e9 else 1):
+    reps = int(min(25, max(1, 2.0e10 // max(1, sub.nnz * w.d))))  # small workloads are repeated; median reported
+    for _ in range(reps):
         t0 = time.perf_counter()
         oracle.unfused(sub.rowptr, sub.colidx, sub.values, X, w.Y, w.pattern, precision="f32", want_abs=False)
         times.append(time.perf_counter() - t0)
     t = sorted(times)[len(times) // 2]
     return {"value": sub.nnz * w.d / t / 1e9, "unit": "G(edge*dim)/s", "cores": synth.num_threads(),
-            "kind": "oracle", "sample": sample, "seconds": t, "precision": "fp32 unfused two-phase"}
+            "kind": "oracle", "sample": sample, "seconds": t, "repetitions": reps, "precision": "fp32 unfused two-phase"}
 
 
-def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None):
+def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -124,6 +125,15 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                      "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
                      "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
     }
+    if copy_mib > 0:
+        # one launch of the plain copy kernel with known traffic, for calibrating profiler counters
+        src = torch.ones(copy_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        binding.fusedmm_debug_copy(dst, src, copy_mib << 20)
+        torch.cuda.synchronize()
+        assert (dst[-4:] == 1).all().item()
+        out["config"]["copy_calibration_bytes_each_way"] = copy_mib << 20
+        del src, dst
     plan.close()
     del Z, Xd, Yd, rp, ci
     torch.cuda.empty_cache()
@@ -140,6 +150,8 @@ def main():
     ap.add_argument("--workload", default="c2", help="c1..c5")
     ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also launch the plain copy kernel once over this many MiB (profiler calibration)")
     ap.add_argument("--small-row-max", type=int, default=0)
     ap.add_argument("--split-row-min", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
@@ -150,7 +162,8 @@ def main():
     if args.small_row_max or args.split_row_min or args.chunk_edges:
         options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,
                    "chunk_edges": args.chunk_edges}
-    out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d)
+    out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
+              args.copy_calibration_mib)
     print(json.dumps(out))
 
 

@@ -166,6 +166,12 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
 int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled);
 int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, int64_t* calls);
 
+/* Measurement aid: a plain grid-stride copy kernel, dst[i] = src[i] for `bytes` bytes
+ * (device pointers, 16-byte aligned, bytes a multiple of 16, non-overlapping),
+ * asynchronous on `stream`.  Profilers' memory counters are calibrated against its
+ * known traffic (bytes read + bytes written). */
+int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
 /* Free the plan and everything it owns. */
 int fusedmm_plan_destroy(fusedmm_plan_t* plan);
 

@@ -35,7 +35,7 @@ EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
-    "fusedmm_plan_destroy",
+    "fusedmm_plan_destroy", "fusedmm_debug_copy",
 )
 
 
@@ -92,6 +92,8 @@ def load():
     lib.fusedmm_plan_set_profiling.argtypes = [vp, i32]
     lib.fusedmm_plan_read_profile.restype = ctypes.c_int
     lib.fusedmm_plan_read_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.fusedmm_debug_copy.restype = ctypes.c_int
+    lib.fusedmm_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_plan_destroy.restype = ctypes.c_int
     lib.fusedmm_plan_destroy.argtypes = [vp]
     _lib = lib
@@ -184,6 +186,10 @@ def fusedmm_plan_read_profile(plan):
     ms, calls = ctypes.c_double(), ctypes.c_int64()
     _check(load().fusedmm_plan_read_profile(plan, ctypes.byref(ms), ctypes.byref(calls)), "fusedmm_plan_read_profile")
     return float(ms.value), int(calls.value)
+
+
+def fusedmm_debug_copy(d_dst, d_src, nbytes: int, stream=None) -> None:
+    _check(load().fusedmm_debug_copy(_dptr(d_dst), _dptr(d_src), nbytes, _stream(stream)), "fusedmm_debug_copy")
 
 
 def fusedmm_plan_destroy(plan) -> None:

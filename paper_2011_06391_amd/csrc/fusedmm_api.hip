@@ -429,6 +429,14 @@ int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, 
   return FUSEDMM_OK;
 }
 
+int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream_) {
+  if (bytes == 0) return FUSEDMM_OK;
+  if (!d_dst || !d_src || bytes % 16 != 0 || !aligned16(d_dst) || !aligned16(d_src)) return FUSEDMM_ERR_INVALID_ARG;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(d_dst), b = reinterpret_cast<uintptr_t>(d_src);
+  if (a < b + bytes && b < a + bytes) return FUSEDMM_ERR_ALIAS;
+  return launch_copy(d_dst, d_src, bytes, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+}
+
 int fusedmm_plan_destroy(fusedmm_plan_t* plan) {
   if (!plan) return FUSEDMM_OK;
   free_plan_device(plan);

@@ -120,6 +120,22 @@ hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n,
   return hipGetLastError();
 }
 
+// Plain streaming copy, 16 bytes per thread per step (counter calibration).
+__global__ __launch_bounds__(256) void fusedmm_copy_kernel(v4f* dst, const v4f* src, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(fusedmm_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<v4f*>(dst),
+                     static_cast<const v4f*>(src), n16);
+  return hipGetLastError();
+}
+
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
   hipError_t launch_fast_d##D(int pattern, const KernelArgs& a, hipStream_t stream); \

@@ -77,4 +77,6 @@ hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* 
 // flag[0] |= 1 if any colidx entry is outside [0, n).
 hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag, hipStream_t stream);
 
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
 }  // namespace fmm
