@@ -80,6 +80,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    options = dict(options or {})
+    options.setdefault("feature_dim_hint", w.d)
     plan = binding.Plan(g.m, g.n, rp, ci, options)
     plan.reserve(w.d)
     torch.cuda.synchronize()
@@ -155,13 +157,16 @@ def main():
     ap.add_argument("--small-row-max", type=int, default=0)
     ap.add_argument("--split-row-min", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
+    ap.add_argument("--column-classes", type=int, default=0)
+    ap.add_argument("--tile-row-min", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
     options = None
-    if args.small_row_max or args.split_row_min or args.chunk_edges:
+    if args.small_row_max or args.split_row_min or args.chunk_edges or args.column_classes or args.tile_row_min:
         options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,
-                   "chunk_edges": args.chunk_edges}
+                   "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
+                   "tile_row_min": args.tile_row_min}
     out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
               args.copy_calibration_mib)
     print(json.dumps(out))

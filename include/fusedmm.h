@@ -101,7 +101,15 @@ typedef struct fusedmm_plan_options {
   int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront */
   int32_t split_row_min;   /* rows with  > this many entries get whole workgroups */
   int32_t chunk_edges;     /* entries per workgroup chunk of a split row */
-  int32_t reserved;
+  int32_t column_classes;  /* long rows are cut by column range into this many classes, each class
+                              processed by one XCD so that its slice of Y stays in that XCD's L2;
+                              0 = automatic (off for small Y, else 16 or 32), 1 = off; rounded up
+                              to a multiple of 8, at most 512.
+                              Needs column indices sorted within the long rows, else it is skipped. */
+  int32_t tile_row_min;    /* rows with >= this many entries are cut by column class; 0 = 8 per class */
+  int32_t feature_dim_hint;/* feature dimension the plan will mostly run with, used by the automatic
+                              choice of column_classes; 0 = 128 */
+  int32_t reserved[2];
 } fusedmm_plan_options_t;
 
 typedef struct fusedmm_plan fusedmm_plan_t;
@@ -134,10 +142,13 @@ int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d);
 /* Device bytes the plan owns when executing with dimension d. */
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out);
 
-/* Schedule statistics (host ints): rows packed per wavefront, rows given one
- * wavefront, workgroup chunks, rows split over several chunks, partial rows. */
+/* Schedule statistics (host ints, any pointer may be NULL): rows packed per
+ * wavefront, rows given one wavefront, workgroup chunks of untiled long rows,
+ * rows merged from partial rows, partial rows, rows cut by column class, their
+ * segments, number of column classes in use (1 = no tiling). */
 int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64_t* n_wave_rows,
-                       int64_t* n_chunks, int64_t* n_split_rows, int64_t* n_partials);
+                       int64_t* n_chunks, int64_t* n_split_rows, int64_t* n_partials,
+                       int64_t* n_tiled_rows, int64_t* n_tile_segments, int64_t* n_column_classes);
 
 /* Z = FusedMM(A, X, Y) with the given ops; asynchronous on `stream`.
  *   d_values  device, nnz fp32 edge values a_uv; NULL unless SOP == EDGE_VALUE

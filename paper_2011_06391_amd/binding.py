@@ -46,7 +46,9 @@ class fusedmm_ops_t(ctypes.Structure):
 
 class fusedmm_plan_options_t(ctypes.Structure):
     _fields_ = [("small_row_max", ctypes.c_int32), ("split_row_min", ctypes.c_int32),
-                ("chunk_edges", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("chunk_edges", ctypes.c_int32), ("column_classes", ctypes.c_int32),
+                ("tile_row_min", ctypes.c_int32), ("feature_dim_hint", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 class FusedMMError(RuntimeError):
@@ -83,7 +85,7 @@ def load():
     lib.fusedmm_plan_workspace_bytes.restype = ctypes.c_int
     lib.fusedmm_plan_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.fusedmm_plan_stats.restype = ctypes.c_int
-    lib.fusedmm_plan_stats.argtypes = [vp] + [ctypes.POINTER(i64)] * 5
+    lib.fusedmm_plan_stats.argtypes = [vp] + [ctypes.POINTER(i64)] * 8
     lib.fusedmm_execute.restype = ctypes.c_int
     lib.fusedmm_execute.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.fusedmm_debug_edge_visits.restype = ctypes.c_int
@@ -142,7 +144,8 @@ def fusedmm_plan_create(m: int, n: int, nnz: int, d_rowptr, d_colidx, options=No
     opt = None
     if options is not None:
         opt = ctypes.byref(fusedmm_plan_options_t(options.get("small_row_max", 0), options.get("split_row_min", 0),
-                                                  options.get("chunk_edges", 0), 0))
+                                                  options.get("chunk_edges", 0), options.get("column_classes", 0),
+                                                  options.get("tile_row_min", 0), options.get("feature_dim_hint", 0)))
     st = load().fusedmm_plan_create(ctypes.byref(plan), m, n, nnz, _dptr(d_rowptr), _dptr(d_colidx), opt,
                                     _stream(stream))
     _check(st, "fusedmm_plan_create")
@@ -160,9 +163,10 @@ def fusedmm_plan_workspace_bytes(plan, d: int) -> int:
 
 
 def fusedmm_plan_stats(plan) -> dict:
-    v = [ctypes.c_int64() for _ in range(5)]
+    v = [ctypes.c_int64() for _ in range(8)]
     _check(load().fusedmm_plan_stats(plan, *[ctypes.byref(x) for x in v]), "fusedmm_plan_stats")
-    keys = ("packed_rows", "wave_rows", "chunks", "split_rows", "partials")
+    keys = ("packed_rows", "wave_rows", "chunks", "split_rows", "partials", "tiled_rows", "tile_segments",
+            "column_classes")
     return {k: int(x.value) for k, x in zip(keys, v)}
 
 

@@ -16,8 +16,11 @@ struct fusedmm_plan {
   const int32_t* d_colidx = nullptr;
   int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0;
   int32_t n_wave = 0, n_packed = 0, n_chunks = 0, n_merges = 0, n_parts = 0;
+  int32_t n_items = 0, n_tile_descs = 0, n_tiled_rows = 0, n_classes = 1;
   int32_t* d_order = nullptr;
   ChunkDesc* d_chunks = nullptr;
+  BlockItem* d_items = nullptr;
+  ChunkDesc* d_tile_descs = nullptr;
   MergeDesc* d_merges = nullptr;
   float* d_partials = nullptr;
   int32_t partials_d = 0;  // scratch holds n_parts rows of this many floats
@@ -31,6 +34,13 @@ namespace {
 constexpr int32_t kDefaultSmallRowMax = 32;
 constexpr int32_t kDefaultSplitRowMin = 256;
 constexpr int32_t kDefaultChunkEdges = 1024;
+// Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
+// dimension) is well beyond what the eight 4 MB L2s keep resident anyway (>= 96 MiB); 16 classes
+// up to 2M rows, 32 beyond; rows need >= 8 entries per class to be worth a partial row per class.
+constexpr int64_t kTilingMinYBytes = 96ll << 20;
+constexpr int64_t kTilingManyRows = 2ll << 20;
+constexpr int32_t kMaxColumnClasses = 512;
+constexpr int32_t kDefaultTileEdgesPerClass = 8;
 constexpr size_t kMaxProfiledCalls = 4096;
 
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
@@ -72,6 +82,8 @@ void free_plan_device(fusedmm_plan* p) {
   if (p->d_order) (void)hipFree(p->d_order);
   if (p->d_chunks) (void)hipFree(p->d_chunks);
   if (p->d_merges) (void)hipFree(p->d_merges);
+  if (p->d_items) (void)hipFree(p->d_items);
+  if (p->d_tile_descs) (void)hipFree(p->d_tile_descs);
   if (p->d_partials) (void)hipFree(p->d_partials);
   for (auto& ev : p->events) {
     (void)hipEventDestroy(ev.first);
@@ -114,6 +126,9 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, KernelArgs* a) {
   a->colidx = p->d_colidx;
   a->order = p->d_order;
   a->chunks = p->d_chunks;
+  a->items = p->d_items;
+  a->tile_descs = p->d_tile_descs;
+  a->nb_tiled = p->n_items;
   a->partials = p->d_partials;
   a->visit_counts = nullptr;
   a->n_chunks = p->n_chunks;
@@ -181,6 +196,19 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     if (options->split_row_min > 0) split_min = options->split_row_min;
     if (options->chunk_edges > 0) chunk = options->chunk_edges;
   }
+  int32_t n_classes = 0, tile_min = 0, d_hint = 128;
+  if (options) {
+    if (options->column_classes < 0 || options->tile_row_min < 0 || options->feature_dim_hint < 0) return FUSEDMM_ERR_INVALID_ARG;
+    n_classes = options->column_classes;
+    tile_min = options->tile_row_min;
+    if (options->feature_dim_hint > 0) d_hint = options->feature_dim_hint;
+  }
+  if (n_classes == 0) {
+    const int64_t y_bytes = n * (int64_t)d_hint * (int64_t)sizeof(float);
+    n_classes = y_bytes < kTilingMinYBytes ? 1 : (n < kTilingManyRows ? 16 : 32);
+  }
+  if (n_classes > 1) n_classes = std::min((n_classes + kNumXcd - 1) / kNumXcd * kNumXcd, kMaxColumnClasses);
+  if (tile_min <= 0) tile_min = kDefaultTileEdgesPerClass * n_classes;
   small_max = std::min(small_max, 1 << 16);
   split_min = std::min(std::max(split_min, small_max), 1 << 20);
   chunk = std::min(std::max((chunk + 255) / 256 * 256, 256), 1 << 24);
@@ -220,58 +248,165 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk;
 
   std::vector<int32_t> order;
-  std::vector<ChunkDesc> chunks;
+  std::vector<ChunkDesc> chunks, tile_descs;
   std::vector<MergeDesc> merges;
+  std::vector<BlockItem> items;
+  int st = FUSEDMM_OK;
   try {
-    // counting sort of the non-split rows by length, longest first, row order kept among equals
+    // ---- which rows are cut into column-class tiles ------------------------------------
+    std::vector<int32_t> tiled_rows;
+    std::vector<int32_t> bounds;  // per tiled row: n_classes + 1 offsets into the row
+    const int64_t class_width = n_classes > 1 ? (n + n_classes - 1) / n_classes : n;
+    if (n_classes > 1 && nnz > 0) {
+      for (int64_t u = 0; u < m; ++u)
+        if (rp[u + 1] - rp[u] >= tile_min) tiled_rows.push_back((int32_t)u);
+      if (!tiled_rows.empty()) {
+        int32_t *d_rows = nullptr, *d_bounds = nullptr, *d_flag = nullptr;
+        const size_t nb = tiled_rows.size() * (size_t)(n_classes + 1);
+        bounds.resize(nb);
+        int32_t flag = 0;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_rows), tiled_rows.size() * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_bounds), nb * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t));
+        if (e != hipSuccess) {
+          (void)hipGetLastError();
+          st = FUSEDMM_ERR_ALLOC;
+        } else {
+          e = hipMemcpy(d_rows, tiled_rows.data(), tiled_rows.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+          if (e == hipSuccess) e = hipMemcpy(d_flag, &flag, sizeof(flag), hipMemcpyHostToDevice);
+          if (e == hipSuccess)
+            e = launch_tile_bounds(d_rowptr, d_colidx, d_rows, (int32_t)tiled_rows.size(), n_classes, class_width,
+                                   d_bounds, d_flag, stream);
+          if (e == hipSuccess) e = hipStreamSynchronize(stream);
+          if (e == hipSuccess) e = hipMemcpy(bounds.data(), d_bounds, nb * sizeof(int32_t), hipMemcpyDeviceToHost);
+          if (e == hipSuccess) e = hipMemcpy(&flag, d_flag, sizeof(flag), hipMemcpyDeviceToHost);
+          if (e != hipSuccess) st = FUSEDMM_ERR_HIP;
+        }
+        if (d_rows) (void)hipFree(d_rows);
+        if (d_bounds) (void)hipFree(d_bounds);
+        if (d_flag) (void)hipFree(d_flag);
+        if (st != FUSEDMM_OK) { delete p; return st; }
+        if (flag != 0) tiled_rows.clear();  // some long row has unsorted columns: no tiling for this pattern
+      }
+    }
+    const bool tiling = !tiled_rows.empty();
+    const int64_t tiled_from = tiling ? tile_min : INT64_MAX;
+
+    // ---- counting sort of the short rows by length, longest first, row order kept among equals
     std::vector<int64_t> bucket((size_t)split_min + 2, 0);
     int64_t n_long = 0;
     for (int64_t u = 0; u < m; ++u) {
       const int64_t deg = rp[u + 1] - rp[u];
-      if (deg > split_min) ++n_long; else ++bucket[(size_t)deg];
+      if (deg > split_min || deg >= tiled_from) ++n_long; else ++bucket[(size_t)deg];
     }
-    // position of the first row of each length when lengths run from split_min down to 0
     std::vector<int64_t> start((size_t)split_min + 1, 0);
     int64_t pos = 0;
     for (int64_t deg = split_min; deg >= 0; --deg) { start[(size_t)deg] = pos; pos += bucket[(size_t)deg]; }
     order.resize((size_t)(m - n_long));
     int64_t n_wave = 0;
     for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
+
+    // cut [e_begin, e_begin + count) of `row` into workgroup chunks; returns the number of chunks
     int32_t next_part = 0;
-    for (int64_t u = 0; u < m; ++u) {
-      const int64_t deg = rp[u + 1] - rp[u];
-      if (deg <= split_min) {
-        order[(size_t)start[(size_t)deg]++] = (int32_t)u;
-        continue;
-      }
-      const int64_t nc = (deg + chunk - 1) / chunk;
-      int64_t per = (deg + nc - 1) / nc;
+    auto chunk_up = [&](int64_t row, int64_t e_begin, int64_t count, bool always_partial, std::vector<ChunkDesc>& dst) {
+      const int64_t nc = (count + chunk - 1) / chunk;
+      int64_t per = (count + nc - 1) / nc;
       per = (per + 255) / 256 * 256;  // whole batches of 64 entries for each of the 4 wavefronts
-      const int64_t nc2 = (deg + per - 1) / per;
-      if (nc2 > 1) merges.push_back(MergeDesc{(int32_t)u, next_part, (int32_t)nc2, 0});
+      const int64_t nc2 = (count + per - 1) / per;
       for (int64_t c = 0; c < nc2; ++c) {
         ChunkDesc cd;
-        cd.e_begin = rp[u] + c * per;
-        cd.e_count = (int32_t)std::min<int64_t>(per, deg - c * per);
-        cd.row = (int32_t)u;
-        cd.part = nc2 > 1 ? next_part++ : -1;
+        cd.e_begin = e_begin + c * per;
+        cd.e_count = (int32_t)std::min<int64_t>(per, count - c * per);
+        cd.row = (int32_t)row;
+        cd.part = (nc2 > 1 || always_partial) ? next_part++ : -1;
         cd.pad = 0;
-        chunks.push_back(cd);
+        dst.push_back(cd);
+      }
+      return (int32_t)nc2;
+    };
+
+    // per class: segments for whole workgroups, for single wavefronts, for lane groups
+    std::vector<std::vector<ChunkDesc>> cls_chunk((size_t)(tiling ? n_classes : 0)), cls_wave(cls_chunk.size()),
+        cls_packed(cls_chunk.size());
+    size_t ti = 0;
+    for (int64_t u = 0; u < m; ++u) {
+      const int64_t deg = rp[u + 1] - rp[u];
+      if (deg >= tiled_from) {
+        const int32_t* bnd = bounds.data() + ti * (size_t)(n_classes + 1);
+        ++ti;
+        const int32_t first_part = next_part;
+        for (int32_t c = 0; c < n_classes; ++c) {
+          const int64_t cnt = (int64_t)bnd[c + 1] - bnd[c];
+          if (cnt <= 0) continue;
+          const int64_t e_begin = rp[u] + bnd[c];
+          if (cnt > split_min) {
+            chunk_up(u, e_begin, cnt, true, cls_chunk[(size_t)c]);
+          } else {
+            ChunkDesc cd{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
+            (cnt > small_max ? cls_wave : cls_packed)[(size_t)c].push_back(cd);
+          }
+        }
+        merges.push_back(MergeDesc{(int32_t)u, first_part, next_part - first_part, 0});
+        ++p->n_tiled_rows;
+      } else if (deg <= split_min) {
+        order[(size_t)start[(size_t)deg]++] = (int32_t)u;
+      } else {
+        const int32_t first_part = next_part;
+        const int32_t nc = chunk_up(u, rp[u], deg, false, chunks);
+        if (nc > 1) merges.push_back(MergeDesc{(int32_t)u, first_part, nc, 0});
       }
     }
+
+    // ---- lay the tiles out class by class and deal the classes to the XCDs -------------
+    if (tiling) {
+      std::vector<std::vector<BlockItem>> xcd_items(kNumXcd);
+      auto by_len_desc = [](const ChunkDesc& a, const ChunkDesc& b) { return a.e_count > b.e_count; };
+      for (int32_t c = 0; c < n_classes; ++c) {
+        auto& lst = xcd_items[(size_t)(c % kNumXcd)];
+        std::stable_sort(cls_wave[(size_t)c].begin(), cls_wave[(size_t)c].end(), by_len_desc);
+        std::stable_sort(cls_packed[(size_t)c].begin(), cls_packed[(size_t)c].end(), by_len_desc);
+        for (const ChunkDesc& cd : cls_chunk[(size_t)c]) {
+          lst.push_back(BlockItem{kItemChunk, (int32_t)tile_descs.size(), 1, 0});
+          tile_descs.push_back(cd);
+        }
+        const auto& wv = cls_wave[(size_t)c];
+        for (size_t k = 0; k < wv.size(); k += kWavesPerBlock) {
+          const int32_t cnt = (int32_t)std::min<size_t>(kWavesPerBlock, wv.size() - k);
+          lst.push_back(BlockItem{kItemWave, (int32_t)tile_descs.size(), cnt, 0});
+          tile_descs.insert(tile_descs.end(), wv.begin() + (long)k, wv.begin() + (long)k + cnt);
+        }
+        const auto& pk = cls_packed[(size_t)c];
+        for (size_t k = 0; k < pk.size(); k += kPackedSegsPerItem) {
+          const int32_t cnt = (int32_t)std::min<size_t>(kPackedSegsPerItem, pk.size() - k);
+          lst.push_back(BlockItem{kItemPacked, (int32_t)tile_descs.size(), cnt, 0});
+          tile_descs.insert(tile_descs.end(), pk.begin() + (long)k, pk.begin() + (long)k + cnt);
+        }
+      }
+      size_t longest = 0;
+      for (const auto& lst : xcd_items) longest = std::max(longest, lst.size());
+      items.assign(longest * kNumXcd, BlockItem{kItemNone, 0, 0, 0});
+      for (int k = 0; k < kNumXcd; ++k)
+        for (size_t j = 0; j < xcd_items[(size_t)k].size(); ++j) items[j * kNumXcd + (size_t)k] = xcd_items[(size_t)k][j];
+      p->n_classes = n_classes;
+    }
+    if (tile_descs.size() >= (size_t)INT32_MAX || items.size() >= (size_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
     p->n_wave = (int32_t)n_wave;
     p->n_packed = (int32_t)((m - n_long) - n_wave);
     p->n_chunks = (int32_t)chunks.size();
     p->n_merges = (int32_t)merges.size();
     p->n_parts = next_part;
+    p->n_items = (int32_t)items.size();
+    p->n_tile_descs = (int32_t)tile_descs.size();
   } catch (const std::bad_alloc&) {
     delete p;
     return FUSEDMM_ERR_ALLOC;
   }
 
-  int st = upload(&p->d_order, order, stream);
+  st = upload(&p->d_order, order, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_chunks, chunks, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_merges, merges, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_items, items, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_tile_descs, tile_descs, stream);
   if (st == FUSEDMM_OK && hipStreamSynchronize(stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
   if (st != FUSEDMM_OK) {
     free_plan_device(p);
@@ -292,20 +427,25 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
   if (!plan || !out) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   size_t b = (size_t)(plan->n_wave + plan->n_packed) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
-             (size_t)plan->n_merges * sizeof(MergeDesc);
+             (size_t)plan->n_merges * sizeof(MergeDesc) + (size_t)plan->n_items * sizeof(BlockItem) +
+             (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
   if (is_fast_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(d, plan->partials_d) * sizeof(float);
   *out = b;
   return FUSEDMM_OK;
 }
 
 int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64_t* n_wave_rows, int64_t* n_chunks,
-                       int64_t* n_split_rows, int64_t* n_partials) {
+                       int64_t* n_split_rows, int64_t* n_partials, int64_t* n_tiled_rows, int64_t* n_tile_segments,
+                       int64_t* n_column_classes) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (n_packed_rows) *n_packed_rows = plan->n_packed;
   if (n_wave_rows) *n_wave_rows = plan->n_wave;
   if (n_chunks) *n_chunks = plan->n_chunks;
   if (n_split_rows) *n_split_rows = plan->n_merges;
   if (n_partials) *n_partials = plan->n_parts;
+  if (n_tiled_rows) *n_tiled_rows = plan->n_tiled_rows;
+  if (n_tile_segments) *n_tile_segments = plan->n_tile_descs;
+  if (n_column_classes) *n_column_classes = plan->n_classes;
   return FUSEDMM_OK;
 }
 

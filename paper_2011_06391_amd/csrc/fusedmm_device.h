@@ -62,6 +62,28 @@ __device__ __forceinline__ float cross_group_allreduce(float v) {
 
 __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
 
+// Loads of data that is read once (column indices, edge values, x_u).  A non-temporal hint
+// on them was measured: -1 % kernel time on the two largest workloads, +3..10 % on the two
+// where X aliases Y (x_u is then also somebody's y_v), so it is off.
+#ifndef FMM_STREAM_HINT
+#define FMM_STREAM_HINT 0
+#endif
+template <class T>
+__device__ __forceinline__ T ld_stream(const T* p) {
+#if FMM_STREAM_HINT
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+__device__ __forceinline__ v4f ld4_stream(const float* p) {
+#if FMM_STREAM_HINT
+  return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+#else
+  return *reinterpret_cast<const v4f*>(p);
+#endif
+}
+
 // ---------------------------------------------------------------------------------------
 // per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
 // ---------------------------------------------------------------------------------------
@@ -137,8 +159,8 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
     int colb = 0;
     float valb = 0.f;
     if (lane < cnt) {
-      colb = a.colidx[base + lane];
-      if constexpr (T::uses_val) valb = a.values[base + lane];
+      colb = ld_stream(a.colidx + base + lane);
+      if constexpr (T::uses_val) valb = ld_stream(a.values + base + lane);
     }
     for (int k0 = 0; k0 < cnt; k0 += S * U) {
       int c[U];
@@ -202,7 +224,7 @@ template <int D, int G>
 __device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
   const float* xr = a.X + row * a.ldx + 4 * g;
 #pragma unroll
-  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4(xr + 4 * G * i);
+  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4_stream(xr + 4 * G * i);
 }
 
 template <int V>
@@ -219,8 +241,19 @@ __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / 
 }
 
 // ---------------------------------------------------------------------------------------
-// The fused kernel.  GW/UW: lane-group size and unroll of the wave-row and chunk paths;
+// The fused kernel.  GW/UW: lane-group size and unroll of the wave and chunk paths;
 // GP/UP: of the packed path.
+//
+// A workgroup first decodes what it has been given (uniform across the workgroup):
+//   tiled region   blockIdx <  nb_tiled : a BlockItem written by the plan.  Long rows are cut
+//                  by column class (a contiguous range of column ids) into tiles; block b runs
+//                  on XCD b % 8, and the plan puts all tiles of class c on XCD c % 8, class
+//                  after class, so each XCD's L2 only ever holds its own slices of Y.
+//   chunk region   one ChunkDesc per workgroup (long rows that are not tiled)
+//   wave region    4 rows, one per wavefront
+//   packed region  4*S short rows, one per lane group
+// and then runs one of three bodies: chunk, wave segments, packed segments.  A segment is
+// a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
 template <int P, int D, int GW, int UW, int GP, int UP>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
@@ -228,12 +261,28 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int b = blockIdx.x;
+  __shared__ v4f stage[kWavesPerBlock][D / 4];
 
-  if (b < a.nb_chunk) {
-    // ---- long rows: one chunk per workgroup -------------------------------------------
+  int kind, first, count;
+  bool from_desc;  // segments come from descriptors (tiles) rather than from order[] + rowptr[]
+  if (b < a.nb_tiled) {
+    const BlockItem it = a.items[b];
+    kind = it.kind; first = it.first; count = it.count; from_desc = true;
+  } else if (b < a.nb_tiled + a.nb_chunk) {
+    kind = kItemChunk; first = b - a.nb_tiled; count = 1; from_desc = false;
+  } else if (b < a.nb_tiled + a.nb_chunk + a.nb_wave) {
+    kind = kItemWave; first = (b - a.nb_tiled - a.nb_chunk) * kWavesPerBlock;
+    count = a.n_wave - first < kWavesPerBlock ? a.n_wave - first : kWavesPerBlock; from_desc = false;
+  } else {
+    constexpr int kRows = kWavesPerBlock * (64 / GP);
+    kind = kItemPacked; first = (b - a.nb_tiled - a.nb_chunk - a.nb_wave) * kRows;
+    count = a.n_packed - first < kRows ? a.n_packed - first : kRows; from_desc = false;
+  }
+
+  if (kind == kItemChunk) {
+    // ---- a workgroup on one run of entries of a long row -------------------------------
     constexpr int V = D / (4 * GW);
-    __shared__ v4f stage[kWavesPerBlock][D / 4];
-    const ChunkDesc ch = a.chunks[b];
+    const ChunkDesc ch = from_desc ? a.tile_descs[first] : a.chunks[first];
     const int per = ((ch.e_count + kWavesPerBlock * 64 - 1) / (kWavesPerBlock * 64)) * 64;
     const int lo = wave * per < ch.e_count ? wave * per : ch.e_count;
     const int hi = (wave + 1) * per < ch.e_count ? (wave + 1) * per : ch.e_count;
@@ -263,13 +312,22 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * threadIdx.x));
       }
     }
-  } else if (b < a.nb_chunk + a.nb_wave) {
-    // ---- one row per wavefront ---------------------------------------------------------
+  } else if (kind == kItemWave) {
+    // ---- one segment per wavefront -----------------------------------------------------
     constexpr int V = D / (4 * GW);
-    const int idx = (b - a.nb_chunk) * kWavesPerBlock + wave;
-    if (idx >= a.n_wave) return;
-    const int row = __builtin_amdgcn_readfirstlane(a.order[idx]);
-    const int64_t e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
+    if (wave >= count) return;
+    int row;
+    int64_t e0, e1;
+    float* dst;
+    if (from_desc) {
+      const ChunkDesc td = a.tile_descs[first + wave];
+      row = td.row; e0 = td.e_begin; e1 = td.e_begin + td.e_count;
+      dst = a.partials + (int64_t)td.part * D;
+    } else {
+      row = __builtin_amdgcn_readfirstlane(a.order[first + wave]);
+      e0 = a.rowptr[row]; e1 = a.rowptr[row + 1];
+      dst = a.Z + (int64_t)row * a.ldz;
+    }
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
@@ -283,80 +341,91 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         z[i].z = cross_group_allreduce<GW>(z[i].z);
         z[i].w = cross_group_allreduce<GW>(z[i].w);
       }
-      if (lane < GW) store_row<D, GW>(a.Z + (int64_t)row * a.ldz, g, z);
+      if (lane < GW) store_row<D, GW>(dst, g, z);
     }
-  } else {
-    // ---- packed short rows: one row per lane group -------------------------------------
+  } else if (kind == kItemPacked) {
+    // ---- one short segment per lane group ----------------------------------------------
     constexpr int V = D / (4 * GP);
     constexpr int S = 64 / GP;
     static_assert(GP % UP == 0, "packed unroll must divide the lane-group size");
     const int slot = lane / GP;
     const int g = lane % GP;
-    const int idx = ((b - a.nb_chunk - a.nb_wave) * kWavesPerBlock + wave) * S + slot;
-    const bool has_row = idx < a.n_packed;
-    int64_t row = 0, e0 = 0;
-    int deg = 0;
-    if (has_row) {
-      row = a.order[a.n_wave + idx];
-      e0 = a.rowptr[row];
-      deg = (int)(a.rowptr[row + 1] - e0);
-    }
-    v4f x[V], z[V];
-    zero(z);
-    zero(x);
-    if constexpr (T::uses_x) {
-      if (deg > 0) load_x<D, GP>(a, row, g, x);
-    }
-    int maxdeg = deg;  // wave-uniform upper bound of the trip count
-    if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
-    if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
-    if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
-    maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
     const float* ybase = a.Y + 4 * g;
-
-    for (int bb = 0; bb < maxdeg; bb += GP) {
-      int colb = 0;
-      float valb = 0.f;
-      if (bb + g < deg) {
-        colb = a.colidx[e0 + bb + g];
-        if constexpr (T::uses_val) valb = a.values[e0 + bb + g];
-      }
-      const int steps = (maxdeg - bb) < GP ? (maxdeg - bb) : GP;
-      for (int k = 0; k < steps; k += UP) {
-        bool ok[UP];
-        int c[UP];
-        float av[UP];
-        v4f y[UP][V];
-#pragma unroll
-        for (int u = 0; u < UP; ++u) {
-          ok[u] = (bb + k + u) < deg;
-          c[u] = __shfl(colb, slot * GP + k + u);
-          av[u] = T::uses_val ? __shfl(valb, slot * GP + k + u) : 0.f;
+    for (int round = 0; round < count; round += kWavesPerBlock * S) {
+      const int idx = round + wave * S + slot;
+      const bool has_seg = idx < count;
+      int64_t row = 0, e0 = 0;
+      int deg = 0;
+      float* dst = nullptr;
+      if (has_seg) {
+        if (from_desc) {
+          const ChunkDesc td = a.tile_descs[first + idx];
+          row = td.row; e0 = td.e_begin; deg = td.e_count;
+          dst = a.partials + (int64_t)td.part * D;
+        } else {
+          row = a.order[a.n_wave + first + idx];
+          e0 = a.rowptr[row];
+          deg = (int)(a.rowptr[row + 1] - e0);
+          dst = a.Z + row * a.ldz;
         }
-        if constexpr (T::loads_y) {
+      }
+      v4f x[V], z[V];
+      zero(z);
+      zero(x);
+      if constexpr (T::uses_x) {
+        if (deg > 0) load_x<D, GP>(a, row, g, x);
+      }
+      int maxdeg = deg;  // wave-uniform upper bound of the trip count
+      if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
+      if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
+      if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
+      maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
+
+      for (int bb = 0; bb < maxdeg; bb += GP) {
+        int colb = 0;
+        float valb = 0.f;
+        if (bb + g < deg) {
+          colb = ld_stream(a.colidx + e0 + bb + g);
+          if constexpr (T::uses_val) valb = ld_stream(a.values + e0 + bb + g);
+        }
+        const int steps = (maxdeg - bb) < GP ? (maxdeg - bb) : GP;
+        for (int k = 0; k < steps; k += UP) {
+          bool ok[UP];
+          int c[UP];
+          float av[UP];
+          v4f y[UP][V];
 #pragma unroll
           for (int u = 0; u < UP; ++u) {
-#pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) {
-              const float* yr = ybase + (int64_t)c[u] * a.ldy;
-#pragma unroll
-              for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * GP * i);
-            }
+            ok[u] = (bb + k + u) < deg;
+            c[u] = __shfl(colb, slot * GP + k + u);
+            av[u] = T::uses_val ? __shfl(valb, slot * GP + k + u) : 0.f;
           }
+          if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
-        } else {
+            for (int u = 0; u < UP; ++u) {
 #pragma unroll
-          for (int u = 0; u < UP; ++u)
-            if (ok[u] && g == 0) atomicAdd(a.visit_counts + (e0 + bb + k + u), 1u);
+              for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+              if (ok[u]) {
+                const float* yr = ybase + (int64_t)c[u] * a.ldy;
+#pragma unroll
+                for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * GP * i);
+              }
+            }
+#pragma unroll
+            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
+          } else {
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+              if (ok[u] && g == 0) atomicAdd(a.visit_counts + (e0 + bb + k + u), 1u);
+          }
         }
       }
-    }
-    if constexpr (T::loads_y) {
-      if (has_row) store_row<D, GP>(a.Z + row * a.ldz, g, z);
+      if constexpr (T::loads_y) {
+        if (has_seg) store_row<D, GP>(dst, g, z);
+      }
     }
   }
+  // kind == kItemNone: padding at the end of an XCD's list, nothing to do
 }
 
 }  // namespace fmm

@@ -83,23 +83,38 @@ hipError_t launch_generic(const GenericArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// z_u = sum of the row's partial rows, in chunk order (fixed order => run-to-run deterministic).
-__global__ __launch_bounds__(128) void fusedmm_merge_kernel(const MergeDesc* merges, const float* partials, int32_t d,
-                                                           float* Z, int64_t ldz) {
-  const MergeDesc md = merges[blockIdx.x];
-  const float* src = partials + (int64_t)md.first_part * d;
-  float* dst = Z + (int64_t)md.row * ldz;
-  for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
-    v4f s = *reinterpret_cast<const v4f*>(src + 4 * c);
-    for (int p = 1; p < md.n_parts; ++p) s += *reinterpret_cast<const v4f*>(src + (int64_t)p * d + 4 * c);
-    __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * c));
+// z_u = sum of the row's partial rows, in slot order (fixed order => run-to-run deterministic).
+// A workgroup covers 256 / (d/4) rows; a thread owns one 16-byte column of one row and keeps
+// eight partial-row loads in flight.
+__global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
+                                                           const float* partials, int32_t d, float* Z, int64_t ldz) {
+  const int cols = d >> 2;
+  const int rows_per_block = 256 / cols;
+  const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
+  const int64_t mi = (int64_t)blockIdx.x * rows_per_block + r;
+  if (r >= rows_per_block || mi >= n_merges) return;
+  const MergeDesc md = merges[mi];
+  const float* src = partials + (int64_t)md.first_part * d + 4 * c;
+  v4f s = {0.f, 0.f, 0.f, 0.f};
+  int p = 0;
+  for (; p + 8 <= md.n_parts; p += 8) {
+    v4f t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)(p + k) * d));
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += t[k];
   }
+  for (; p < md.n_parts; ++p) s += __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * d));
+  __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(Z + (int64_t)md.row * ldz + 4 * c));
 }
 
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, float* Z,
                         int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
-  hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)n_merges), dim3(128), 0, stream, merges, partials, d, Z, ldz);
+  const int rows_per_block = 256 / (d >> 2);
+  const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
+  hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
+                     Z, ldz);
   return hipGetLastError();
 }
 
@@ -117,6 +132,40 @@ hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n,
   int64_t blocks = (nnz + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(validate_colidx_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, colidx, nnz, n, flag);
+  return hipGetLastError();
+}
+
+// One wavefront per tiled row: is the row sorted by column, and where does each column class start?
+__global__ __launch_bounds__(kBlockThreads) void tile_bounds_kernel(const int64_t* rowptr, const int32_t* colidx,
+                                                                    const int32_t* rows, int32_t n_rows, int32_t n_classes,
+                                                                    int64_t class_width, int32_t* bounds, int32_t* unsorted) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (w >= n_rows) return;
+  const int32_t row = rows[w];
+  const int64_t e0 = rowptr[row];
+  const int64_t len = rowptr[row + 1] - e0;
+  bool bad = false;
+  for (int64_t i = lane; i + 1 < len; i += 64) bad |= colidx[e0 + i] > colidx[e0 + i + 1];
+  if (bad) atomicOr(unsorted, 1);
+  for (int c = lane; c <= n_classes; c += 64) {
+    const int64_t target = (int64_t)c * class_width;  // first column id of class c
+    int64_t lo = 0, hi = len;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)colidx[e0 + mid] < target) lo = mid + 1; else hi = mid;
+    }
+    bounds[w * (n_classes + 1) + c] = (int32_t)lo;
+  }
+}
+
+hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, int32_t n_rows,
+                              int32_t n_classes, int64_t class_width, int32_t* bounds, int32_t* unsorted,
+                              hipStream_t stream) {
+  if (n_rows <= 0) return hipSuccess;
+  const int blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(tile_bounds_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, rowptr, colidx, rows,
+                     n_rows, n_classes, class_width, bounds, unsorted);
   return hipGetLastError();
 }
 

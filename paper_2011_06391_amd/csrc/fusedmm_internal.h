@@ -21,6 +21,19 @@ struct ChunkDesc {
   int32_t pad;
 };
 
+// What a workgroup of the tiled region does: kind, index of its first descriptor in
+// tile_descs[], and how many descriptors (1 for a chunk, <= 4 wave segments, <= 32 packed
+// segments).  Items are stored interleaved by XCD: items[j * 8 + k] is the j-th item of XCD k.
+enum : int { kItemNone = 0, kItemChunk = 1, kItemWave = 2, kItemPacked = 3 };
+constexpr int kNumXcd = 8;
+constexpr int kPackedSegsPerItem = 32;
+struct BlockItem {
+  int32_t kind;
+  int32_t first;
+  int32_t count;
+  int32_t pad;
+};
+
 // A row split over several chunks: z_u = partial[first] + ... + partial[first+count-1].
 struct MergeDesc {
   int32_t row;
@@ -38,15 +51,24 @@ struct KernelArgs {
   float* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
-  // schedule: blockIdx in [0, nb_chunk) -> chunks; [nb_chunk, nb_chunk+nb_wave) -> one row
-  // per wavefront from order[0 .. n_wave); then packed rows from order[n_wave .. n_wave+n_packed).
+  // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
+  // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed).
   const int32_t* order;
   const ChunkDesc* chunks;
+  const BlockItem* items;       // tiled region, nb_tiled entries
+  const ChunkDesc* tile_descs;  // segments of tiled rows; part is always a partial row
   float* partials;
   uint32_t* visit_counts;
   int32_t n_chunks, n_wave, n_packed;
-  int32_t nb_chunk, nb_wave, nb_packed;
+  int32_t nb_tiled, nb_chunk, nb_wave, nb_packed;
 };
+
+// Column-class boundaries of the tiled rows: bounds[i * (n_classes + 1) + c] = offset within row
+// rows[i] of the first stored entry whose column is >= c * class_width (c = 0..n_classes);
+// unsorted[0] is set if any of those rows has decreasing column indices.
+hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, int32_t n_rows,
+                              int32_t n_classes, int64_t class_width, int32_t* bounds, int32_t* unsorted,
+                              hipStream_t stream);
 
 // Rows per workgroup in the packed range for dimension d (host needs it for the grid).
 int packed_rows_per_block(int d);

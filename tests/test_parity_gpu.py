@@ -59,7 +59,7 @@ def check(Zg, Zr, S, what=""):
     return err
 
 
-def skewed_csr(rng, m, n, long_rows):
+def skewed_csr(rng, m, n, long_rows, sort_cols=False):
     """Mostly short rows, a few long ones (several chunks, ragged tails), some empty."""
     degs = rng.integers(0, 40, m)
     degs[rng.random(m) < 0.2] = 0
@@ -68,7 +68,13 @@ def skewed_csr(rng, m, n, long_rows):
     rowptr = np.zeros(m + 1, dtype=np.int64)
     rowptr[1:] = np.cumsum(degs)
     colidx = rng.integers(0, n, rowptr[-1]).astype(np.int32)  # duplicates allowed, unsorted
+    if sort_cols:
+        for u in range(m):
+            colidx[rowptr[u]:rowptr[u + 1]].sort()
     return rowptr, colidx
+
+
+TILED = {"small_row_max": 8, "split_row_min": 96, "chunk_edges": 256, "column_classes": 16, "tile_row_min": 120}
 
 
 @pytest.mark.parametrize("d", FAST_DIMS)
@@ -88,6 +94,32 @@ def test_fast_kernels_all_bins(B, pattern, d):
         Zg, stats = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA, options=options)
         check(Zg, Zr, S, f"{pattern} d={d} options={options}")
         assert stats["packed_rows"] > 0 and stats["wave_rows"] > 0 and stats["chunks"] > 0 and stats["split_rows"] > 0
+        assert stats["tiled_rows"] == 0  # these rows are unsorted: column-class tiling must not engage
+
+
+@pytest.mark.parametrize("d", FAST_DIMS)
+@pytest.mark.parametrize("pattern", PATTERNS)
+def test_fast_kernels_column_class_tiles(B, pattern, d):
+    """Long sorted rows cut by column class: tiles of every size (workgroup chunks, wavefront
+    segments, packed segments, empty classes), merged from partial rows."""
+    rng = np.random.default_rng(2000 + d)
+    m, n = 301, 4000
+    long_rows = {3: 64, 4: 119, 5: 120, 10: 127, 11: 257, 57: 700, 200: 1024, 201: 1025, 299: 3001, 300: 9000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    # one long row living in a single class, one skipping most classes
+    e = rowptr[57]
+    colidx[e:e + 700] = np.sort(rng.integers(0, 250, 700))
+    e = rowptr[11]
+    colidx[e:e + 257] = np.sort(np.concatenate([rng.integers(0, 10, 130), rng.integers(3990, 4000, 127)]))
+    X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    vals = rng.uniform(0.05, 1.0, len(colidx)).astype(np.float32)
+    Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
+    for options in (TILED, dict(TILED, column_classes=64, tile_row_min=64, small_row_max=2, split_row_min=40)):
+        Zg, stats = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA, options=options)
+        check(Zg, Zr, S, f"{pattern} d={d} options={options}")
+        assert stats["tiled_rows"] >= 7 and stats["tile_segments"] > stats["tiled_rows"]
+        assert stats["column_classes"] == options["column_classes"]
 
 
 @pytest.mark.parametrize("d", (1, 3, 4, 33, 100, 130, 2048))
@@ -163,16 +195,19 @@ def test_edges_visited_exactly_once_integer_data(B, d):
     vals = np.ones(g.nnz, dtype=np.float32)
     assert g.degrees().max() * 8 < 2 ** 24
     Zr, _, _ = oracle.unfused(g.rowptr, g.colidx, vals, None, X, "gcn")
-    for options in (None, {"small_row_max": 4, "split_row_min": 64, "chunk_edges": 256}):
-        Zg, _ = run_gpu(B, g.rowptr, g.colidx, vals, None, X, "gcn", g.m, g.n, options=options)
+    for options in (None, {"small_row_max": 4, "split_row_min": 64, "chunk_edges": 256},
+                    {"column_classes": 8, "tile_row_min": 40}, {"column_classes": 40, "tile_row_min": 100}):
+        Zg, stats = run_gpu(B, g.rowptr, g.colidx, vals, None, X, "gcn", g.m, g.n, options=options)
         assert np.array_equal(Zg.astype(np.float64), Zr)
+        assert (stats["tiled_rows"] > 0) == (options is not None and "column_classes" in options)
 
 
 @pytest.mark.parametrize("d", FAST_DIMS)
 def test_edge_visit_hook_fast_and_general(B, d):
     g = synth.rmat(13, (1 << 12) * 16, seed=32)
     rp, ci = dev(g.rowptr), dev(g.colidx)
-    for options in (None, {"small_row_max": 3, "split_row_min": 70, "chunk_edges": 256}):
+    for options in (None, {"small_row_max": 3, "split_row_min": 70, "chunk_edges": 256},
+                    {"column_classes": 16, "tile_row_min": 64}, {"column_classes": 128, "tile_row_min": 256}):
         plan = B.Plan(g.m, g.n, rp, ci, options)
         for fast in (True, False):
             counts = torch.zeros(g.nnz, dtype=torch.int32, device="cuda")
@@ -228,7 +263,9 @@ def test_run_to_run_determinism(B):
     w = synth.make_workload("c1")
     g = w.csr
     rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(w.X)
-    plan = B.Plan(g.m, g.n, rp, ci, {"small_row_max": 4, "split_row_min": 8, "chunk_edges": 256})
+    plan = B.Plan(g.m, g.n, rp, ci, {"small_row_max": 4, "split_row_min": 8, "chunk_edges": 256,
+                                     "column_classes": 8, "tile_row_min": 12})
+    assert plan.stats()["tiled_rows"] > 0
     outs = []
     for _ in range(3):
         Z = torch.empty((g.m, w.d), dtype=torch.float32, device="cuda")
@@ -282,9 +319,11 @@ def test_workspace_is_not_per_edge_message(B):
     plan = B.Plan(g.m, g.n, rp, ci)
     s = plan.stats()
     ws = plan.workspace_bytes(w.d)
-    assert ws <= 4 * g.m + 24 * s["chunks"] + 16 * s["split_rows"] + 4 * w.d * s["partials"]
+    assert ws <= 4 * g.m + 24 * (s["chunks"] + s["tile_segments"]) + 16 * s["split_rows"] + 4 * w.d * s["partials"] \
+        + 16 * (s["tile_segments"] + 8)
     assert ws < 0.02 * 4 * g.nnz * w.d  # far below the nnz x d message tensor
-    assert s["packed_rows"] + s["wave_rows"] + s["chunks"] - s["partials"] + s["split_rows"] == g.m
+    if s["tiled_rows"] == 0:
+        assert s["packed_rows"] + s["wave_rows"] + s["chunks"] - s["partials"] + s["split_rows"] == g.m
     plan.close()
 
 
@@ -307,7 +346,8 @@ def test_workload_full_size_sampled_rows(B, name):
     w = synth.make_workload(name)
     g = w.csr
     rp, ci = dev(g.rowptr), dev(g.colidx)
-    plan = B.Plan(g.m, g.n, rp, ci)
+    plan = B.Plan(g.m, g.n, rp, ci, {"feature_dim_hint": w.d})  # as bench.py creates it
+    assert plan.stats()["tiled_rows"] > 0  # the large workloads run with column-class tiling
     Xd = dev(w.X)
     Yd = Xd if w.Y is w.X else dev(w.Y)
     vd = dev(g.values)
