@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 
 # HBM bytes per main-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+# They belong to the kernel build and default plan the profiles were taken with.
+MEASURED_TRAFFIC_BYTES = {"c2": 515150739, "c3": 26024466260, "c4": 7020485731, "c5": 86471334738}
 
 
 def cpu_baseline(w, budget_edges_dim: float = 6.0e10):

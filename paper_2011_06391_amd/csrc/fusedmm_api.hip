@@ -306,28 +306,50 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     int64_t n_wave = 0;
     for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
 
-    // cut [e_begin, e_begin + count) of `row` into workgroup chunks; returns the number of chunks
-    int32_t next_part = 0;
-    auto chunk_up = [&](int64_t row, int64_t e_begin, int64_t count, bool always_partial, std::vector<ChunkDesc>& dst) {
+    // length of a workgroup chunk when `count` entries are cut into chunks of at most chunk_edges:
+    // equal shares, rounded up to whole batches of 64 entries for each of the 4 wavefronts
+    auto chunk_len = [&](int64_t count) {
       const int64_t nc = (count + chunk - 1) / chunk;
-      int64_t per = (count + nc - 1) / nc;
-      per = (per + 255) / 256 * 256;  // whole batches of 64 entries for each of the 4 wavefronts
-      const int64_t nc2 = (count + per - 1) / per;
-      for (int64_t c = 0; c < nc2; ++c) {
-        ChunkDesc cd;
-        cd.e_begin = e_begin + c * per;
-        cd.e_count = (int32_t)std::min<int64_t>(per, count - c * per);
-        cd.row = (int32_t)row;
-        cd.part = (nc2 > 1 || always_partial) ? next_part++ : -1;
-        cd.pad = 0;
-        dst.push_back(cd);
-      }
-      return (int32_t)nc2;
+      return ((count + nc - 1) / nc + 255) / 256 * 256;
     };
 
-    // per class: segments for whole workgroups, for single wavefronts, for lane groups
-    std::vector<std::vector<ChunkDesc>> cls_chunk((size_t)(tiling ? n_classes : 0)), cls_wave(cls_chunk.size()),
-        cls_packed(cls_chunk.size());
+    // ---- pass 1 over the tiles: per class, the number of chunk descriptors and of shorter
+    // segments of each length (all segments of a class are laid out longest first) -----------
+    const size_t ncls = tiling ? (size_t)n_classes : 0;
+    const size_t hw = (size_t)split_min + 1;
+    std::vector<int64_t> cls_nchunk(ncls, 0), cls_hist(ncls * hw, 0);
+    for (size_t ti = 0; tiling && ti < tiled_rows.size(); ++ti) {
+      const int32_t* bnd = bounds.data() + ti * (size_t)(n_classes + 1);
+      for (size_t c = 0; c < ncls; ++c) {
+        const int64_t cnt = (int64_t)bnd[c + 1] - bnd[c];
+        if (cnt <= 0) continue;
+        if (cnt > split_min) {
+          const int64_t per = chunk_len(cnt);
+          cls_nchunk[c] += (cnt + per - 1) / per;
+        } else {
+          ++cls_hist[c * hw + (size_t)cnt];
+        }
+      }
+    }
+    // descriptor layout: class by class, [chunks][wavefront segments][lane-group segments]
+    std::vector<int64_t> cls_base(ncls + 1, 0), cls_nwave(ncls, 0), cls_nshort(ncls, 0), cls_chunk_cursor(ncls, 0);
+    for (size_t c = 0; c < ncls; ++c) {
+      int64_t at = cls_base[c] + cls_nchunk[c];
+      cls_chunk_cursor[c] = cls_base[c];
+      for (int64_t len = split_min; len >= 1; --len) {
+        const int64_t h = cls_hist[c * hw + (size_t)len];
+        cls_hist[c * hw + (size_t)len] = at;  // from now on: where the next segment of this length goes
+        at += h;
+        (len > small_max ? cls_nwave : cls_nshort)[c] += h;
+      }
+      cls_base[c + 1] = at;
+    }
+    if (ncls > 0 && cls_base[ncls] >= (int64_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
+    tile_descs.resize(ncls > 0 ? (size_t)cls_base[ncls] : 0);
+
+    // ---- pass 2: rows in order; partial-row slots are handed out here, so the merge order of a
+    // row is fixed by (class, chunk) and does not depend on how the descriptors were arranged ---
+    int32_t next_part = 0;
     size_t ti = 0;
     for (int64_t u = 0; u < m; ++u) {
       const int64_t deg = rp[u + 1] - rp[u];
@@ -335,15 +357,17 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
         const int32_t* bnd = bounds.data() + ti * (size_t)(n_classes + 1);
         ++ti;
         const int32_t first_part = next_part;
-        for (int32_t c = 0; c < n_classes; ++c) {
+        for (size_t c = 0; c < ncls; ++c) {
           const int64_t cnt = (int64_t)bnd[c + 1] - bnd[c];
           if (cnt <= 0) continue;
           const int64_t e_begin = rp[u] + bnd[c];
           if (cnt > split_min) {
-            chunk_up(u, e_begin, cnt, true, cls_chunk[(size_t)c]);
+            const int64_t per = chunk_len(cnt);
+            for (int64_t off = 0; off < cnt; off += per)
+              tile_descs[(size_t)cls_chunk_cursor[c]++] =
+                  ChunkDesc{e_begin + off, (int32_t)std::min<int64_t>(per, cnt - off), (int32_t)u, next_part++, 0};
           } else {
-            ChunkDesc cd{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
-            (cnt > small_max ? cls_wave : cls_packed)[(size_t)c].push_back(cd);
+            tile_descs[(size_t)cls_hist[c * hw + (size_t)cnt]++] = ChunkDesc{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
           }
         }
         merges.push_back(MergeDesc{(int32_t)u, first_part, next_part - first_part, 0});
@@ -351,35 +375,31 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
       } else if (deg <= split_min) {
         order[(size_t)start[(size_t)deg]++] = (int32_t)u;
       } else {
-        const int32_t first_part = next_part;
-        const int32_t nc = chunk_up(u, rp[u], deg, false, chunks);
-        if (nc > 1) merges.push_back(MergeDesc{(int32_t)u, first_part, nc, 0});
+        const int64_t per = chunk_len(deg);
+        const int32_t nc = (int32_t)((deg + per - 1) / per);
+        if (nc > 1) merges.push_back(MergeDesc{(int32_t)u, next_part, nc, 0});
+        for (int64_t off = 0; off < deg; off += per)
+          chunks.push_back(ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(per, deg - off), (int32_t)u,
+                                     nc > 1 ? next_part++ : -1, 0});
       }
     }
 
-    // ---- lay the tiles out class by class and deal the classes to the XCDs -------------
+    // ---- deal the classes to the XCDs: class c runs on XCD c % 8, one class after the other ----
     if (tiling) {
       std::vector<std::vector<BlockItem>> xcd_items(kNumXcd);
-      auto by_len_desc = [](const ChunkDesc& a, const ChunkDesc& b) { return a.e_count > b.e_count; };
-      for (int32_t c = 0; c < n_classes; ++c) {
-        auto& lst = xcd_items[(size_t)(c % kNumXcd)];
-        std::stable_sort(cls_wave[(size_t)c].begin(), cls_wave[(size_t)c].end(), by_len_desc);
-        std::stable_sort(cls_packed[(size_t)c].begin(), cls_packed[(size_t)c].end(), by_len_desc);
-        for (const ChunkDesc& cd : cls_chunk[(size_t)c]) {
-          lst.push_back(BlockItem{kItemChunk, (int32_t)tile_descs.size(), 1, 0});
-          tile_descs.push_back(cd);
+      for (size_t c = 0; c < ncls; ++c) {
+        auto& lst = xcd_items[c % kNumXcd];
+        int64_t at = cls_base[c];
+        for (int64_t k = 0; k < cls_nchunk[c]; ++k) lst.push_back(BlockItem{kItemChunk, (int32_t)(at++), 1, 0});
+        for (int64_t k = 0; k < cls_nwave[c]; k += kWavesPerBlock) {
+          const int32_t cnt = (int32_t)std::min<int64_t>(kWavesPerBlock, cls_nwave[c] - k);
+          lst.push_back(BlockItem{kItemWave, (int32_t)at, cnt, 0});
+          at += cnt;
         }
-        const auto& wv = cls_wave[(size_t)c];
-        for (size_t k = 0; k < wv.size(); k += kWavesPerBlock) {
-          const int32_t cnt = (int32_t)std::min<size_t>(kWavesPerBlock, wv.size() - k);
-          lst.push_back(BlockItem{kItemWave, (int32_t)tile_descs.size(), cnt, 0});
-          tile_descs.insert(tile_descs.end(), wv.begin() + (long)k, wv.begin() + (long)k + cnt);
-        }
-        const auto& pk = cls_packed[(size_t)c];
-        for (size_t k = 0; k < pk.size(); k += kPackedSegsPerItem) {
-          const int32_t cnt = (int32_t)std::min<size_t>(kPackedSegsPerItem, pk.size() - k);
-          lst.push_back(BlockItem{kItemPacked, (int32_t)tile_descs.size(), cnt, 0});
-          tile_descs.insert(tile_descs.end(), pk.begin() + (long)k, pk.begin() + (long)k + cnt);
+        for (int64_t k = 0; k < cls_nshort[c]; k += kPackedSegsPerItem) {
+          const int32_t cnt = (int32_t)std::min<int64_t>(kPackedSegsPerItem, cls_nshort[c] - k);
+          lst.push_back(BlockItem{kItemPacked, (int32_t)at, cnt, 0});
+          at += cnt;
         }
       }
       size_t longest = 0;
