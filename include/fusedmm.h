@@ -101,12 +101,14 @@ typedef struct fusedmm_plan_options {
   int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront */
   int32_t split_row_min;   /* rows with  > this many entries get whole workgroups */
   int32_t chunk_edges;     /* entries per workgroup chunk of a split row */
-  int32_t column_classes;  /* long rows are cut by column range into this many classes, each class
-                              processed by one XCD so that its slice of Y stays in that XCD's L2;
-                              0 = automatic (off for small Y, else 16 or 32), 1 = off; rounded up
-                              to a multiple of 8, at most 512.
-                              Needs column indices sorted within the long rows, else it is skipped. */
-  int32_t tile_row_min;    /* rows with >= this many entries are cut by column class; 0 = 8 per class */
+  int32_t column_classes;  /* long rows are cut by contiguous column ranges ("classes") into tiles and
+                              all tiles of a class run on one XCD, so that its slice of Y stays in that
+                              XCD's L2.  This is the finest number of classes (8, 16, 32, ... up to 512,
+                              rounded up); shorter rows use nested coarser levels down to 8 classes.
+                              0 = automatic (off while Y is small), 1 = off.  Needs column indices sorted
+                              within the long rows, else it is skipped. */
+  int32_t tile_row_min;    /* rows with >= this many entries are cut into 8 classes, with twice as many
+                              into 16, and so on; 0 = 128 (16 entries per class) */
   int32_t feature_dim_hint;/* feature dimension the plan will mostly run with, used by the automatic
                               choice of column_classes; 0 = 128 */
   int32_t reserved[2];

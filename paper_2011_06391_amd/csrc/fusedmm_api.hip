@@ -35,12 +35,14 @@ constexpr int32_t kDefaultSmallRowMax = 32;
 constexpr int32_t kDefaultSplitRowMin = 256;
 constexpr int32_t kDefaultChunkEdges = 1024;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
-// dimension) is well beyond what the eight 4 MB L2s keep resident anyway (>= 96 MiB); 16 classes
-// up to 2M rows, 32 beyond; rows need >= 8 entries per class to be worth a partial row per class.
+// dimension) is well beyond what the eight 4 MB L2s keep resident anyway (>= 96 MiB); the finest
+// level keeps a class slice of Y at >= 4 MiB and stops at 64 classes; a row needs 16 entries per
+// class on average for a partial row per class to be worth it.
 constexpr int64_t kTilingMinYBytes = 96ll << 20;
-constexpr int64_t kTilingManyRows = 2ll << 20;
+constexpr int64_t kTilingMinSliceBytes = 4ll << 20;
+constexpr int32_t kAutoMaxColumnClasses = 64;
 constexpr int32_t kMaxColumnClasses = 512;
-constexpr int32_t kDefaultTileEdgesPerClass = 8;
+constexpr int32_t kDefaultTileEdgesPerClass = 16;
 constexpr size_t kMaxProfiledCalls = 4096;
 
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
@@ -204,11 +206,22 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     if (options->feature_dim_hint > 0) d_hint = options->feature_dim_hint;
   }
   if (n_classes == 0) {
+    // automatic: off while Y (n rows of the hinted dimension) is small; else the finest level keeps
+    // a class slice of Y at >= 4 MiB (finer slices than an L2 holds gain nothing), at most 64 classes
     const int64_t y_bytes = n * (int64_t)d_hint * (int64_t)sizeof(float);
-    n_classes = y_bytes < kTilingMinYBytes ? 1 : (n < kTilingManyRows ? 16 : 32);
+    n_classes = 1;
+    if (y_bytes >= kTilingMinYBytes) {
+      n_classes = kNumXcd;
+      while (n_classes < kAutoMaxColumnClasses && y_bytes / (2 * n_classes) >= kTilingMinSliceBytes) n_classes *= 2;
+    }
   }
-  if (n_classes > 1) n_classes = std::min((n_classes + kNumXcd - 1) / kNumXcd * kNumXcd, kMaxColumnClasses);
-  if (tile_min <= 0) tile_min = kDefaultTileEdgesPerClass * n_classes;
+  if (n_classes > 1) {  // levels are nested: 8, 16, 32, ... classes
+    int32_t c = kNumXcd;
+    while (c < n_classes && c < kMaxColumnClasses) c *= 2;
+    n_classes = c;
+  }
+  if (tile_min <= 0) tile_min = kDefaultTileEdgesPerClass * kNumXcd;
+  const int64_t tile_edges_per_class = std::max<int64_t>(1, tile_min / kNumXcd);
   small_max = std::min(small_max, 1 << 16);
   split_min = std::min(std::max(split_min, small_max), 1 << 20);
   chunk = std::min(std::max((chunk + 255) / 256 * 256, 256), 1 << 24);
@@ -253,36 +266,56 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   std::vector<BlockItem> items;
   int st = FUSEDMM_OK;
   try {
-    // ---- which rows are cut into column-class tiles ------------------------------------
-    std::vector<int32_t> tiled_rows;
-    std::vector<int32_t> bounds;  // per tiled row: n_classes + 1 offsets into the row
-    const int64_t class_width = n_classes > 1 ? (n + n_classes - 1) / n_classes : n;
+    // ---- which rows are cut into column-class tiles, and how finely ---------------------
+    // Level of a row = number of classes it is cut into: the largest of 8, 16, ..., n_classes
+    // that leaves it tile_edges_per_class entries per class on average.  Classes are nested
+    // contiguous column ranges: a class of level L is n_classes / L finest classes.
+    std::vector<int32_t> tiled_rows, tiled_level;
+    std::vector<int64_t> bnd_off;  // per tiled row: where its level + 1 boundaries start in bounds[]
+    std::vector<int32_t> bounds;
+    const int64_t class_width = n_classes > 1 ? (n + n_classes - 1) / n_classes : n;  // of the finest classes
     if (n_classes > 1 && nnz > 0) {
-      for (int64_t u = 0; u < m; ++u)
-        if (rp[u + 1] - rp[u] >= tile_min) tiled_rows.push_back((int32_t)u);
+      int64_t nb = 0;
+      for (int64_t u = 0; u < m; ++u) {
+        const int64_t deg = rp[u + 1] - rp[u];
+        if (deg < tile_min) continue;
+        int32_t level = kNumXcd;
+        while (level < n_classes && deg >= tile_edges_per_class * 2 * level) level *= 2;
+        tiled_rows.push_back((int32_t)u);
+        tiled_level.push_back(level);
+        bnd_off.push_back(nb);
+        nb += level + 1;
+      }
       if (!tiled_rows.empty()) {
-        int32_t *d_rows = nullptr, *d_bounds = nullptr, *d_flag = nullptr;
-        const size_t nb = tiled_rows.size() * (size_t)(n_classes + 1);
-        bounds.resize(nb);
+        int32_t *d_rows = nullptr, *d_level = nullptr, *d_bounds = nullptr, *d_flag = nullptr;
+        int64_t* d_off = nullptr;
+        const size_t nt = tiled_rows.size();
+        bounds.resize((size_t)nb);
         int32_t flag = 0;
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_rows), tiled_rows.size() * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_bounds), nb * sizeof(int32_t));
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_rows), nt * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_level), nt * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_off), nt * sizeof(int64_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_bounds), (size_t)nb * sizeof(int32_t));
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t));
         if (e != hipSuccess) {
           (void)hipGetLastError();
           st = FUSEDMM_ERR_ALLOC;
         } else {
-          e = hipMemcpy(d_rows, tiled_rows.data(), tiled_rows.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+          e = hipMemcpy(d_rows, tiled_rows.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice);
+          if (e == hipSuccess) e = hipMemcpy(d_level, tiled_level.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice);
+          if (e == hipSuccess) e = hipMemcpy(d_off, bnd_off.data(), nt * sizeof(int64_t), hipMemcpyHostToDevice);
           if (e == hipSuccess) e = hipMemcpy(d_flag, &flag, sizeof(flag), hipMemcpyHostToDevice);
           if (e == hipSuccess)
-            e = launch_tile_bounds(d_rowptr, d_colidx, d_rows, (int32_t)tiled_rows.size(), n_classes, class_width,
+            e = launch_tile_bounds(d_rowptr, d_colidx, d_rows, d_level, d_off, (int32_t)nt, n_classes, class_width,
                                    d_bounds, d_flag, stream);
           if (e == hipSuccess) e = hipStreamSynchronize(stream);
-          if (e == hipSuccess) e = hipMemcpy(bounds.data(), d_bounds, nb * sizeof(int32_t), hipMemcpyDeviceToHost);
+          if (e == hipSuccess) e = hipMemcpy(bounds.data(), d_bounds, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToHost);
           if (e == hipSuccess) e = hipMemcpy(&flag, d_flag, sizeof(flag), hipMemcpyDeviceToHost);
           if (e != hipSuccess) st = FUSEDMM_ERR_HIP;
         }
         if (d_rows) (void)hipFree(d_rows);
+        if (d_level) (void)hipFree(d_level);
+        if (d_off) (void)hipFree(d_off);
         if (d_bounds) (void)hipFree(d_bounds);
         if (d_flag) (void)hipFree(d_flag);
         if (st != FUSEDMM_OK) { delete p; return st; }
@@ -319,10 +352,12 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     const size_t hw = (size_t)split_min + 1;
     std::vector<int64_t> cls_nchunk(ncls, 0), cls_hist(ncls * hw, 0);
     for (size_t ti = 0; tiling && ti < tiled_rows.size(); ++ti) {
-      const int32_t* bnd = bounds.data() + ti * (size_t)(n_classes + 1);
-      for (size_t c = 0; c < ncls; ++c) {
-        const int64_t cnt = (int64_t)bnd[c + 1] - bnd[c];
+      const int32_t* bnd = bounds.data() + bnd_off[ti];
+      const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
+      for (size_t t = 0; t < level; ++t) {
+        const int64_t cnt = (int64_t)bnd[t + 1] - bnd[t];
         if (cnt <= 0) continue;
+        const size_t c = t * stride;  // the tile is filed under the first finest class it covers
         if (cnt > split_min) {
           const int64_t per = chunk_len(cnt);
           cls_nchunk[c] += (cnt + per - 1) / per;
@@ -354,13 +389,15 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     for (int64_t u = 0; u < m; ++u) {
       const int64_t deg = rp[u + 1] - rp[u];
       if (deg >= tiled_from) {
-        const int32_t* bnd = bounds.data() + ti * (size_t)(n_classes + 1);
+        const int32_t* bnd = bounds.data() + bnd_off[ti];
+        const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
         ++ti;
         const int32_t first_part = next_part;
-        for (size_t c = 0; c < ncls; ++c) {
-          const int64_t cnt = (int64_t)bnd[c + 1] - bnd[c];
+        for (size_t t = 0; t < level; ++t) {
+          const int64_t cnt = (int64_t)bnd[t + 1] - bnd[t];
           if (cnt <= 0) continue;
-          const int64_t e_begin = rp[u] + bnd[c];
+          const size_t c = t * stride;
+          const int64_t e_begin = rp[u] + bnd[t];
           if (cnt > split_min) {
             const int64_t per = chunk_len(cnt);
             for (int64_t off = 0; off < cnt; off += per)
@@ -384,11 +421,12 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
       }
     }
 
-    // ---- deal the classes to the XCDs: class c runs on XCD c % 8, one class after the other ----
+    // ---- deal the classes to the XCDs: XCD k owns the k-th eighth of the column range and works
+    // through its finest classes in order; coarser tiles sit where their first finest class is ----
     if (tiling) {
       std::vector<std::vector<BlockItem>> xcd_items(kNumXcd);
       for (size_t c = 0; c < ncls; ++c) {
-        auto& lst = xcd_items[c % kNumXcd];
+        auto& lst = xcd_items[c / (ncls / kNumXcd)];
         int64_t at = cls_base[c];
         for (int64_t k = 0; k < cls_nchunk[c]; ++k) lst.push_back(BlockItem{kItemChunk, (int32_t)(at++), 1, 0});
         for (int64_t k = 0; k < cls_nwave[c]; k += kWavesPerBlock) {

@@ -135,37 +135,43 @@ hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n,
   return hipGetLastError();
 }
 
-// One wavefront per tiled row: is the row sorted by column, and where does each column class start?
+// One wavefront per tiled row: is the row sorted by column, and where does each of its column
+// classes start?  A row of level L has L classes, each n_classes / L finest classes wide.
 __global__ __launch_bounds__(kBlockThreads) void tile_bounds_kernel(const int64_t* rowptr, const int32_t* colidx,
-                                                                    const int32_t* rows, int32_t n_rows, int32_t n_classes,
-                                                                    int64_t class_width, int32_t* bounds, int32_t* unsorted) {
+                                                                    const int32_t* rows, const int32_t* level,
+                                                                    const int64_t* out_off, int32_t n_rows,
+                                                                    int32_t n_classes, int64_t class_width,
+                                                                    int32_t* bounds, int32_t* unsorted) {
   const int lane = threadIdx.x & 63;
   const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   if (w >= n_rows) return;
   const int32_t row = rows[w];
+  const int32_t L = level[w];
+  const int64_t width = class_width * (n_classes / L);
   const int64_t e0 = rowptr[row];
   const int64_t len = rowptr[row + 1] - e0;
   bool bad = false;
   for (int64_t i = lane; i + 1 < len; i += 64) bad |= colidx[e0 + i] > colidx[e0 + i + 1];
   if (bad) atomicOr(unsorted, 1);
-  for (int c = lane; c <= n_classes; c += 64) {
-    const int64_t target = (int64_t)c * class_width;  // first column id of class c
+  int32_t* out = bounds + out_off[w];
+  for (int c = lane; c <= L; c += 64) {
+    const int64_t target = (int64_t)c * width;  // first column id of class c
     int64_t lo = 0, hi = len;
     while (lo < hi) {
       const int64_t mid = (lo + hi) >> 1;
       if ((int64_t)colidx[e0 + mid] < target) lo = mid + 1; else hi = mid;
     }
-    bounds[w * (n_classes + 1) + c] = (int32_t)lo;
+    out[c] = (int32_t)lo;
   }
 }
 
-hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, int32_t n_rows,
-                              int32_t n_classes, int64_t class_width, int32_t* bounds, int32_t* unsorted,
-                              hipStream_t stream) {
+hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, const int32_t* level,
+                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, int64_t class_width,
+                              int32_t* bounds, int32_t* unsorted, hipStream_t stream) {
   if (n_rows <= 0) return hipSuccess;
   const int blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
   hipLaunchKernelGGL(tile_bounds_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, rowptr, colidx, rows,
-                     n_rows, n_classes, class_width, bounds, unsorted);
+                     level, out_off, n_rows, n_classes, class_width, bounds, unsorted);
   return hipGetLastError();
 }
 

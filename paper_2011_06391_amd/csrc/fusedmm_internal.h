@@ -63,12 +63,13 @@ struct KernelArgs {
   int32_t nb_tiled, nb_chunk, nb_wave, nb_packed;
 };
 
-// Column-class boundaries of the tiled rows: bounds[i * (n_classes + 1) + c] = offset within row
-// rows[i] of the first stored entry whose column is >= c * class_width (c = 0..n_classes);
+// Column-class boundaries of the tiled rows.  Row rows[i] is cut into level[i] classes, each
+// n_classes / level[i] finest classes (class_width columns) wide; bounds[out_off[i] + c] = offset
+// within the row of the first stored entry whose column is in class c or later (c = 0..level[i]).
 // unsorted[0] is set if any of those rows has decreasing column indices.
-hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, int32_t n_rows,
-                              int32_t n_classes, int64_t class_width, int32_t* bounds, int32_t* unsorted,
-                              hipStream_t stream);
+hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, const int32_t* level,
+                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, int64_t class_width,
+                              int32_t* bounds, int32_t* unsorted, hipStream_t stream);
 
 // Rows per workgroup in the packed range for dimension d (host needs it for the grid).
 int packed_rows_per_block(int d);
