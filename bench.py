@@ -128,6 +128,40 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                      "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
                      "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
     }
+    # Context figures, measured after and outside the timed region (never part of `value`):
+    # the same step replayed from a HIP graph (launch overhead removed), and the streaming
+    # bandwidth of a plain copy kernel on this machine (read + write bytes per second).
+    context = {}
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        context["ms_per_step_hip_graph"] = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
+    except Exception as exc:  # context only: never let it break the benchmark line
+        context["hip_graph_error"] = repr(exc)[:200]
+    try:
+        nbytes = 1 << 30
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        binding.fusedmm_debug_copy(dst, src, nbytes)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            binding.fusedmm_debug_copy(dst, src, nbytes)
+        e1.record()
+        torch.cuda.synchronize()
+        context["copy_kernel_GBs_read_plus_write"] = 5 * 2 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+    except Exception as exc:
+        context["copy_error"] = repr(exc)[:200]
+    out["config"]["context"] = context
     if copy_mib > 0:
         # one launch of the plain copy kernel with known traffic, for calibrating profiler counters
         src = torch.ones(copy_mib << 18, dtype=torch.float32, device="cuda")
