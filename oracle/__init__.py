@@ -23,10 +23,11 @@ _SRC = os.path.join(_HERE, "fusedmm_oracle.c")
 _LIBS = {"f64": os.path.join(_HERE, "liboracle_f64.so"), "f32": os.path.join(_HERE, "liboracle_f32.so")}
 _loaded = {}
 
-VOP = {"MUL": 0, "SEL2ND": 1, "SUB": 2}
-ROP = {"NOOP": 0, "RSUM": 1, "SUMSQ": 2, "NORM": 3}
-SOP = {"EDGE_VALUE": 0, "SIGMOID": 1, "ONE_MINUS_SIGMOID": 2, "INV1P": 3, "SCAL": 4}
-MOP = {"MUL_Y": 0, "MUL_T": 1}
+VOP = {"MUL": 0, "SEL2ND": 1, "SUB": 2, "ADD": 3}
+ROP = {"NOOP": 0, "RSUM": 1, "SUMSQ": 2, "NORM": 3, "RMUL": 4}
+SOP = {"EDGE_VALUE": 0, "SIGMOID": 1, "ONE_MINUS_SIGMOID": 2, "INV1P": 3, "SCAL": 4, "NOOP": 5}
+MOP = {"MUL_Y": 0, "MUL_T": 1, "SEL2ND": 2}
+AOP = {"ASUM": 0, "AMAX": 1, "AMIN": 2}
 
 # (VOP, ROP, SOP, MOP) of the application patterns; AOP is always ASUM.
 # Table III rows 1-3 and the t-distribution pattern of the author notes.
@@ -73,6 +74,8 @@ def _codes(ops):
     if isinstance(ops, str):
         ops = PATTERNS[ops]
     v, r, s, mo = ops
+    if v == "ADD" or r == "RMUL" or s == "NOOP" or mo == "SEL2ND" or (r == "NOOP") != (s == "EDGE_VALUE"):
+        raise ValueError(f"{ops}: outside the scalar-message patterns; use unfused_general")
     return VOP[v], ROP[r], SOP[s], MOP[mo]
 
 
@@ -108,6 +111,38 @@ def unfused(rowptr, colidx, values, X, Y, ops, alpha: float = 1.0, precision: st
     if rc != 0:
         raise ValueError(f"oracle spmm failed ({rc})")
     return Z, S, H[:nnz]
+
+
+def unfused_general(rowptr, colidx, values, X, Y, ops, aop: str = "ASUM", alpha: float = 1.0):
+    """The general five-step path (all operations of Table II), two phases, fp64.
+
+    ``ops`` = (VOP, ROP, SOP, MOP) names, ``aop`` in ASUM / AMAX / AMIN.  Returns (Z, S, H);
+    H is nnz scalars, or nnz x d when the message is a vector (ROP is NOOP and SOP is not
+    EDGE_VALUE).  S is sum|w| for ASUM and max|w| for AMAX / AMIN.
+    """
+    rowptr, colidx, values, X, Y = _prep(rowptr, colidx, values, X, Y)
+    v, r, s_, mo = ops
+    vop, rop, sop, mop, aopc = VOP[v], ROP[r], SOP[s_], MOP[mo], AOP[aop]
+    m = len(rowptr) - 1
+    d = Y.shape[1]
+    nnz = int(rowptr[-1])
+    lib = _lib("f64")
+    vec = int(lib.fmm_oracle_h_is_vector_f64(ctypes.c_int(rop), ctypes.c_int(sop)))
+    H = np.empty(max(1, nnz) * (d if vec else 1), dtype=np.float64)
+    Z = np.empty((m, d), dtype=np.float64)
+    S = np.empty((m, d), dtype=np.float64)
+    ldx = 0 if X is None else X.shape[1]
+    i64, dbl, ci = ctypes.c_int64, ctypes.c_double, ctypes.c_int
+    rc = lib.fmm_oracle_sddmm_general_f64(i64(m), i64(d), _ptr(rowptr), _ptr(colidx), _ptr(values), _ptr(X), i64(ldx),
+                                          _ptr(Y), i64(d), ci(vop), ci(rop), ci(sop), dbl(alpha), _ptr(H))
+    if rc != 0:
+        raise ValueError(f"oracle general sddmm failed ({rc})")
+    rc = lib.fmm_oracle_spmm_general_f64(i64(m), i64(d), _ptr(rowptr), _ptr(colidx), _ptr(X), i64(ldx), _ptr(Y), i64(d),
+                                         ci(vop), ci(mop), ci(aopc), ci(vec), _ptr(H), _ptr(Z), _ptr(S))
+    if rc != 0:
+        raise ValueError(f"oracle general spmm failed ({rc})")
+    H = H[:nnz * d].reshape(nnz, d) if vec else H[:nnz]
+    return Z, S, H
 
 
 def message_tensor(rowptr, colidx, values, X, Y, ops, alpha: float = 1.0):

@@ -216,3 +216,109 @@ int FN(fmm_oracle_update_u_all)(int64_t m, int64_t d, const int64_t* rowptr, con
   free(t); free(w);
   return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * The general five-step path (Section III-A, Table II): every standard operation the paper
+ * lists for the five steps, including the ones outside the three application patterns:
+ *   VOP  ADD (x + y)                                   Table II "ADD"
+ *   ROP  RMUL (product of the elements)                Table II "RMUL"
+ *   SOP  NOOP (h = s, or h = t when there was no ROP)  Section III-A: a step may be skipped
+ *   SOP  on a VECTOR: when ROP is a no-op, SOP is applied to every element of t and the edge
+ *        message h is a length-d vector (Algorithm 1: "directly use z if ROP is a NOOP";
+ *        Fig. 3: messages can be vectors); MOP is then element-wise h (.) operand
+ *   MOP  SEL2ND (w = y_v, the second operand)          Table II "SEL2ND ... VOP, MOP"
+ *   AOP  AMAX / AMIN                                   Table II "AMAX" (AMIN: its mirror image)
+ * Reading for AMAX/AMIN: Algorithm 1 sets z_u to 0 before the loop and AOP combines z_u with
+ * every message, so the result is max(0, max_v w) (resp. min(0, min_v w)); a row without
+ * entries yields 0.
+ * H holds one real per stored entry when h is a scalar and d reals per stored entry when it
+ * is a vector: the unfused pipeline's sparse tensor.
+ * S (comparison denominator) is the sum of |w| for ASUM and the largest |w| for AMAX/AMIN.
+ * ------------------------------------------------------------------------------------------ */
+enum { O_VOP_ADD = 3 };
+enum { O_ROP_RMUL = 4 };
+enum { O_SOP_NOOP = 5 };
+enum { O_MOP_SEL2ND = 2 };
+enum { O_AOP_SUM = 0, O_AOP_MAX = 1, O_AOP_MIN = 2 };
+
+static inline real g_vop(int vop, real x, real y) {
+  switch (vop) {
+    case O_VOP_MUL: return x * y;
+    case O_VOP_SEL2ND: return y;
+    case O_VOP_SUB: return x - y;
+    default: return x + y; /* O_VOP_ADD */
+  }
+}
+
+static inline real g_sop(int sop, real s, real a_uv, real alpha) {
+  switch (sop) {
+    case O_SOP_EDGE_VALUE: return a_uv;
+    case O_SOP_SIGMOID: return (real)(1.0 / (1.0 + exp(-(double)s)));
+    case O_SOP_ONE_MINUS_SIGMOID: return (real)(1.0 - 1.0 / (1.0 + exp(-(double)s)));
+    case O_SOP_INV1P: return (real)1 / ((real)1 + s);
+    case O_SOP_SCAL: return alpha * s;
+    default: return s; /* O_SOP_NOOP */
+  }
+}
+
+/* 1 when the message h is a vector (no reduction and SOP acts on t), 0 when it is a scalar */
+int FN(fmm_oracle_h_is_vector)(int rop, int sop) { return rop == O_ROP_NOOP && sop != O_SOP_EDGE_VALUE; }
+
+/* Phase 1 of the general path: H[e] (scalar h) or H[e*d .. e*d+d) (vector h). */
+int FN(fmm_oracle_sddmm_general)(int64_t m, int64_t d, const int64_t* rowptr, const int32_t* colidx,
+                                 const float* values, const float* X, int64_t ldx, const float* Y, int64_t ldy,
+                                 int vop, int rop, int sop, double alpha, real* H) {
+  if (sop == O_SOP_EDGE_VALUE && !values && rowptr[m] > 0) return -1;
+  if (vop != O_VOP_SEL2ND && !X && rowptr[m] > 0) return -3;
+  const int vec = FN(fmm_oracle_h_is_vector)(rop, sop);
+  for (int64_t u = 0; u < m; ++u) {
+    for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+      const float* yv = Y + (int64_t)colidx[e] * ldy;
+      if (vec) {
+        for (int64_t k = 0; k < d; ++k) {
+          real t = g_vop(vop, X ? (real)X[u * ldx + k] : 0, (real)yv[k]);
+          H[e * d + k] = g_sop(sop, t, 0, (real)alpha);
+        }
+      } else {
+        real s = 0;
+        if (rop == O_ROP_RMUL) s = 1;
+        for (int64_t k = 0; k < d && rop != O_ROP_NOOP; ++k) {
+          real t = g_vop(vop, X ? (real)X[u * ldx + k] : 0, (real)yv[k]);
+          if (rop == O_ROP_RSUM) s += t;
+          else if (rop == O_ROP_RMUL) s *= t;
+          else s += t * t;
+        }
+        if (rop == O_ROP_NORM) s = (real)sqrt((double)s);
+        H[e] = g_sop(sop, s, values ? (real)values[e] : 0, (real)alpha);
+      }
+    }
+  }
+  return 0;
+}
+
+/* Phase 2 of the general path: MOP then AOP over the materialised H. */
+int FN(fmm_oracle_spmm_general)(int64_t m, int64_t d, const int64_t* rowptr, const int32_t* colidx,
+                                const float* X, int64_t ldx, const float* Y, int64_t ldy,
+                                int vop, int mop, int aop, int h_is_vector, const real* H, real* Z, real* S) {
+  for (int64_t u = 0; u < m; ++u) {
+    for (int64_t k = 0; k < d; ++k) { Z[u * d + k] = 0; if (S) S[u * d + k] = 0; }
+    for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e) {
+      const float* yv = Y + (int64_t)colidx[e] * ldy;
+      for (int64_t k = 0; k < d; ++k) {
+        const real h = h_is_vector ? H[e * d + k] : H[e];
+        real w;
+        if (mop == O_MOP_SEL2ND) w = (real)yv[k];
+        else if (mop == O_MOP_MUL_Y) w = h * (real)yv[k];
+        else w = h * g_vop(vop, X ? (real)X[u * ldx + k] : 0, (real)yv[k]);
+        real* z = &Z[u * d + k];
+        const real aw = (real)fabs((double)w);
+        if (aop == O_AOP_SUM) { *z += w; if (S) S[u * d + k] += aw; }
+        else {
+          if (aop == O_AOP_MAX) { if (w > *z) *z = w; } else { if (w < *z) *z = w; }
+          if (S && aw > S[u * d + k]) S[u * d + k] = aw;
+        }
+      }
+    }
+  }
+  return 0;
+}

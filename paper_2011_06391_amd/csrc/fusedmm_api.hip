@@ -35,10 +35,10 @@ constexpr int32_t kDefaultSmallRowMax = 32;
 constexpr int32_t kDefaultSplitRowMin = 256;
 constexpr int32_t kDefaultChunkEdges = 1024;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
-// dimension) is well beyond what the eight 4 MB L2s keep resident anyway (>= 96 MiB); the finest
+// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB); the finest
 // level keeps a class slice of Y at >= 4 MiB and stops at 64 classes; a row needs 16 entries per
 // class on average for a partial row per class to be worth it.
-constexpr int64_t kTilingMinYBytes = 96ll << 20;
+constexpr int64_t kTilingMinYBytes = 48ll << 20;
 constexpr int64_t kTilingMinSliceBytes = 4ll << 20;
 constexpr int32_t kAutoMaxColumnClasses = 64;
 constexpr int32_t kMaxColumnClasses = 512;
