@@ -61,26 +61,33 @@ typedef enum fusedmm_status {
 } fusedmm_status;
 
 /* Step 1, VOP(x_u, y_v) -> t (Section III-A step 1; Table II binary ops). */
-typedef enum { FUSEDMM_VOP_MUL = 0, FUSEDMM_VOP_SEL2ND = 1, FUSEDMM_VOP_SUB = 2 } fusedmm_vop;
-/* Step 2, ROP(t) -> s (step 2; Table II reductions; NORM of Table III). */
-typedef enum { FUSEDMM_ROP_NOOP = 0, FUSEDMM_ROP_RSUM = 1, FUSEDMM_ROP_SUMSQ = 2, FUSEDMM_ROP_NORM2 = 3 } fusedmm_rop;
-/* Step 3, SOP(s) -> h (step 3).  EDGE_VALUE: h = a_uv (the GCN row of Table III). */
+typedef enum { FUSEDMM_VOP_MUL = 0, FUSEDMM_VOP_SEL2ND = 1, FUSEDMM_VOP_SUB = 2, FUSEDMM_VOP_ADD = 3 } fusedmm_vop;
+/* Step 2, ROP(t) -> s (step 2; Table II reductions; NORM of Table III).  RMUL: product of the elements. */
+typedef enum {
+  FUSEDMM_ROP_NOOP = 0, FUSEDMM_ROP_RSUM = 1, FUSEDMM_ROP_SUMSQ = 2, FUSEDMM_ROP_NORM2 = 3, FUSEDMM_ROP_RMUL = 4
+} fusedmm_rop;
+/* Step 3, SOP -> h (step 3).  EDGE_VALUE: h = a_uv (the GCN row of Table III).  After a reduction
+ * SOP acts on the scalar s; when ROP is NOOP (and SOP is not EDGE_VALUE) it acts on every element
+ * of t and the message h is a vector (Algorithm 1: "directly use z if ROP is a NOOP"). */
 typedef enum {
   FUSEDMM_SOP_EDGE_VALUE = 0,
   FUSEDMM_SOP_SIGMOID = 1,           /* 1/(1+exp(-s)) */
   FUSEDMM_SOP_ONE_MINUS_SIGMOID = 2, /* 1 - 1/(1+exp(-s)) */
   FUSEDMM_SOP_INV_1P = 3,            /* 1/(1+s) */
-  FUSEDMM_SOP_SCAL = 4               /* alpha * s */
+  FUSEDMM_SOP_SCAL = 4,              /* alpha * s */
+  FUSEDMM_SOP_NOOP = 5               /* h = s (or h = t) */
 } fusedmm_sop;
-/* Step 4, MOP(h, .) -> w (step 4): scale y_v, or scale the VOP output t. */
-typedef enum { FUSEDMM_MOP_MUL_Y = 0, FUSEDMM_MOP_MUL_T = 1 } fusedmm_mop;
-/* Step 5, AOP(z_u, w) (step 5). */
-typedef enum { FUSEDMM_AOP_SUM = 0 } fusedmm_aop;
+/* Step 4, MOP(h, .) -> w (step 4): h (.) y_v, h (.) t with t the VOP output, or y_v itself (SEL2ND). */
+typedef enum { FUSEDMM_MOP_MUL_Y = 0, FUSEDMM_MOP_MUL_T = 1, FUSEDMM_MOP_SEL2ND = 2 } fusedmm_mop;
+/* Step 5, AOP(z_u, w) (step 5; Table II ASUM, AMAX).  z_u starts at 0 (Algorithm 1), so MAX yields
+ * max(0, max_v w) and MIN yields min(0, min_v w); rows without entries give 0. */
+typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2 } fusedmm_aop;
 
-/* The op selector.  Valid tuples: AOP == SUM and either
- *   (ROP == NOOP and SOP == EDGE_VALUE)        -- h is the stored edge value, or
- *   (ROP != NOOP and SOP != EDGE_VALUE)        -- h is a function of the reduction.
- * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE. */
+/* The op selector.  Every combination of the values above is valid except that
+ * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
+ * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
+ * The five application patterns below run the specialised kernels (d in {32,...,512}); every
+ * other tuple runs the general kernel (one wavefront per row, any d up to FUSEDMM_MAX_D). */
 typedef struct fusedmm_ops {
   int32_t vop, rop, sop, mop, aop;
   float alpha; /* used by FUSEDMM_SOP_SCAL only */

@@ -48,16 +48,17 @@ constexpr size_t kMaxProfiledCalls = 4096;
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
 
 bool ops_valid(const fusedmm_ops_t& o) {
-  if (o.vop < FUSEDMM_VOP_MUL || o.vop > FUSEDMM_VOP_SUB) return false;
-  if (o.rop < FUSEDMM_ROP_NOOP || o.rop > FUSEDMM_ROP_NORM2) return false;
-  if (o.sop < FUSEDMM_SOP_EDGE_VALUE || o.sop > FUSEDMM_SOP_SCAL) return false;
-  if (o.mop < FUSEDMM_MOP_MUL_Y || o.mop > FUSEDMM_MOP_MUL_T) return false;
-  if (o.aop != FUSEDMM_AOP_SUM) return false;
-  return (o.rop == FUSEDMM_ROP_NOOP) == (o.sop == FUSEDMM_SOP_EDGE_VALUE);
+  if (o.vop < FUSEDMM_VOP_MUL || o.vop > FUSEDMM_VOP_ADD) return false;
+  if (o.rop < FUSEDMM_ROP_NOOP || o.rop > FUSEDMM_ROP_RMUL) return false;
+  if (o.sop < FUSEDMM_SOP_EDGE_VALUE || o.sop > FUSEDMM_SOP_NOOP) return false;
+  if (o.mop < FUSEDMM_MOP_MUL_Y || o.mop > FUSEDMM_MOP_SEL2ND) return false;
+  if (o.aop < FUSEDMM_AOP_SUM || o.aop > FUSEDMM_AOP_MIN) return false;
+  return o.sop != FUSEDMM_SOP_EDGE_VALUE || o.rop == FUSEDMM_ROP_NOOP;
 }
 
 // The pattern recogniser: map an op tuple to a specialised kernel, or -1 for the general one.
 int recognise(const fusedmm_ops_t& o) {
+  if (o.aop != FUSEDMM_AOP_SUM) return -1;
   if (o.vop == FUSEDMM_VOP_MUL && o.rop == FUSEDMM_ROP_RSUM && o.mop == FUSEDMM_MOP_MUL_Y) {
     if (o.sop == FUSEDMM_SOP_SIGMOID) return PAT_SIGMOID;
     if (o.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID) return PAT_ONE_MINUS_SIGMOID;
@@ -556,7 +557,7 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     g.X = d_X; g.Y = d_Y; g.Z = d_Z;
     g.ldx = ldx; g.ldy = ldy; g.ldz = ldz;
     g.m = plan->m; g.d = d;
-    g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop;
+    g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
     g.alpha = ops->alpha;
     g.visit_counts = nullptr;
     if (ev0) (void)hipEventRecord(ev0, stream);

@@ -13,13 +13,37 @@ __device__ __forceinline__ float wave_allreduce(float v) {
   return v;
 }
 
+__device__ __forceinline__ float wave_allreduce_mul(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v *= __shfl_xor(v, off);
+  return v;
+}
+
 __device__ __forceinline__ float vop_apply(int vop, float x, float y) {
-  return vop == FUSEDMM_VOP_MUL ? x * y : (vop == FUSEDMM_VOP_SEL2ND ? y : x - y);
+  switch (vop) {
+    case FUSEDMM_VOP_MUL: return x * y;
+    case FUSEDMM_VOP_SEL2ND: return y;
+    case FUSEDMM_VOP_SUB: return x - y;
+    default: return x + y;  // ADD
+  }
+}
+
+__device__ __forceinline__ float sop_apply(int sop, float s, float alpha) {
+  switch (sop) {
+    case FUSEDMM_SOP_SIGMOID: return 1.0f / (1.0f + expf(-s));
+    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return 1.0f / (1.0f + expf(s));
+    case FUSEDMM_SOP_INV_1P: return 1.0f / (1.0f + s);
+    case FUSEDMM_SOP_SCAL: return alpha * s;
+    default: return s;  // NOOP
+  }
 }
 
 // Algorithm 1, UpdateU, one wavefront per row: lane l owns elements l, l+64, l+128, ...
 // of z_u in registers.  The five steps run per stored entry in the paper's order; the
 // row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
+// Covers every op of Table II: scalar messages (after a reduction, or the edge value) and
+// vector messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation
+// from a zero-initialised z_u.
 constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
 
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgs a) {
@@ -33,38 +57,43 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
     return;
   }
   const bool uses_x = a.vop != FUSEDMM_VOP_SEL2ND;
+  const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
   const float* xr = uses_x ? a.X + row * a.ldx : nullptr;
   float acc[kGenericAcc];
 #pragma unroll
-  for (int i = 0; i < kGenericAcc; ++i) acc[i] = 0.f;
+  for (int i = 0; i < kGenericAcc; ++i) acc[i] = 0.f;  // z_u <- 0
 
   for (int64_t e = e0; e < e1; ++e) {
     const float* yr = a.Y + (int64_t)a.colidx[e] * a.ldy;
-    float h;
-    if (a.rop == FUSEDMM_ROP_NOOP) {
-      h = a.values[e];  // SOP = EDGE_VALUE
-    } else {
-      float p = 0.f;
+    float h = 0.f;
+    if (a.sop == FUSEDMM_SOP_EDGE_VALUE) {
+      h = a.values[e];
+    } else if (a.rop != FUSEDMM_ROP_NOOP) {
+      float p = (a.rop == FUSEDMM_ROP_RMUL) ? 1.f : 0.f;
       for (int k = lane; k < d; k += 64) {
         const float t = vop_apply(a.vop, uses_x ? xr[k] : 0.f, yr[k]);  // VOP
-        p += (a.rop == FUSEDMM_ROP_RSUM) ? t : t * t;                    // ROP (per-lane share)
+        if (a.rop == FUSEDMM_ROP_RSUM) p += t;                            // ROP (per-lane share)
+        else if (a.rop == FUSEDMM_ROP_RMUL) p *= t;
+        else p += t * t;
       }
-      float s = wave_allreduce(p);
+      float s = (a.rop == FUSEDMM_ROP_RMUL) ? wave_allreduce_mul(p) : wave_allreduce(p);
       if (a.rop == FUSEDMM_ROP_NORM2) s = sqrtf(s);
-      switch (a.sop) {  // SOP
-        case FUSEDMM_SOP_SIGMOID: h = 1.0f / (1.0f + expf(-s)); break;
-        case FUSEDMM_SOP_ONE_MINUS_SIGMOID: h = 1.0f / (1.0f + expf(s)); break;
-        case FUSEDMM_SOP_INV_1P: h = 1.0f / (1.0f + s); break;
-        default: h = a.alpha * s; break;  // SCAL
-      }
+      h = sop_apply(a.sop, s, a.alpha);  // SOP on the scalar
     }
 #pragma unroll
     for (int i = 0; i < kGenericAcc; ++i) {
       const int k = lane + 64 * i;
       if (k < d) {
         const float y = yr[k];
-        const float operand = (a.mop == FUSEDMM_MOP_MUL_Y) ? y : vop_apply(a.vop, uses_x ? xr[k] : 0.f, y);
-        acc[i] += h * operand;  // MOP + AOP
+        const float t = vop_apply(a.vop, uses_x ? xr[k] : 0.f, y);
+        const float hk = scalar_h ? h : sop_apply(a.sop, t, a.alpha);  // SOP on the element
+        float w;                                                         // MOP
+        if (a.mop == FUSEDMM_MOP_SEL2ND) w = y;
+        else if (a.mop == FUSEDMM_MOP_MUL_Y) w = hk * y;
+        else w = hk * t;
+        if (a.aop == FUSEDMM_AOP_SUM) acc[i] += w;                       // AOP
+        else if (a.aop == FUSEDMM_AOP_MAX) acc[i] = fmaxf(acc[i], w);
+        else acc[i] = fminf(acc[i], w);
       }
     }
   }

@@ -88,7 +88,7 @@ struct GenericArgs {
   int64_t ldx, ldy, ldz;
   int64_t m;
   int32_t d;
-  int32_t vop, rop, sop, mop;
+  int32_t vop, rop, sop, mop, aop;
   float alpha;
   uint32_t* visit_counts;  // non-null: count visits instead of computing
 };

@@ -159,6 +159,40 @@ def test_general_kernel_other_op_tuples(B, tuples, d):
     check(Zg, Zr, S, f"{gpu_names} d={d}")
 
 
+# the general five-step path: (binding names, AOP) -> (oracle names, AOP)
+GENERAL_TUPLES = [
+    ((("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MAX"), (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMAX")),
+    ((("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MIN"), (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMIN")),
+    ((("MUL", "NOOP", "SIGMOID", "MUL_Y"), "SUM"), (("MUL", "NOOP", "SIGMOID", "MUL_Y"), "ASUM")),
+    ((("MUL", "NOOP", "SIGMOID", "MUL_Y"), "MAX"), (("MUL", "NOOP", "SIGMOID", "MUL_Y"), "AMAX")),
+    ((("ADD", "RMUL", "NOOP", "MUL_T"), "SUM"), (("ADD", "RMUL", "NOOP", "MUL_T"), "ASUM")),
+    ((("SUB", "NOOP", "NOOP", "MUL_T"), "MIN"), (("SUB", "NOOP", "NOOP", "MUL_T"), "AMIN")),
+    ((("MUL", "RSUM", "SIGMOID", "SEL2ND"), "SUM"), (("MUL", "RSUM", "SIGMOID", "SEL2ND"), "ASUM")),
+    ((("ADD", "NORM2", "SCAL", "MUL_Y"), "MAX"), (("ADD", "NORM", "SCAL", "MUL_Y"), "AMAX")),
+    ((("MUL", "NOOP", "INV_1P", "MUL_Y"), "SUM"), (("MUL", "NOOP", "INV1P", "MUL_Y"), "ASUM")),  # |x y| < 0.81: away from the pole of 1/(1+t)
+    # AOP other than SUM on a tuple that has a specialised kernel must take the general path
+    ((("MUL", "RSUM", "SIGMOID", "MUL_Y"), "MAX"), (("MUL", "RSUM", "SIGMOID", "MUL_Y"), "AMAX")),
+]
+
+
+@pytest.mark.parametrize("d", (5, 64, 128, 200))
+@pytest.mark.parametrize("tuples", GENERAL_TUPLES)
+def test_general_five_step_path(B, tuples, d):
+    (gpu_names, gpu_aop), (oracle_names, oracle_aop) = tuples
+    rng = np.random.default_rng(4242 + d)
+    m, n = 45, 70
+    rowptr, colidx = random_csr(rng, m, n, 0.2, empty_rows=(2, 30))
+    X = rng.uniform(-0.9, 0.9, (m, d)).astype(np.float32) if "RMUL" not in gpu_names else \
+        rng.uniform(0.4, 0.6, (m, d)).astype(np.float32)   # keeps the product of d factors in range
+    Y = rng.uniform(-0.9, 0.9, (n, d)).astype(np.float32) if "RMUL" not in gpu_names else \
+        rng.uniform(0.4, 0.6, (n, d)).astype(np.float32)
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, oracle_names, oracle_aop, alpha=ALPHA)
+    Zg, _ = run_gpu(B, rowptr, colidx, vals, X, Y, B.make_ops(*gpu_names, aop=gpu_aop), m, n, alpha=ALPHA)
+    check(Zg, Zr, S, f"{gpu_names} {gpu_aop} d={d}")
+    assert (Zg[[2, 30]] == 0).all()
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
@@ -328,7 +362,10 @@ def test_status_codes(B):
     assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, X, d, X, d, X, d)) == B.FUSEDMM_ERR_ALIAS
     gcn = B.fusedmm_ops_preset("gcn")
     assert status(lambda: B.fusedmm_execute(plan._plan, gcn, d, None, None, 0, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
-    bad = B.make_ops("MUL", "NOOP", "SIGMOID", "MUL_Y")  # vector-valued h is not supported
+    bad = B.make_ops("MUL", "RSUM", "EDGE_VALUE", "MUL_Y")  # the edge value is not the result of a reduction
+    assert status(lambda: B.fusedmm_execute(plan._plan, bad, d, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_OPS
+    bad = B.fusedmm_ops_preset("sigmoid")
+    bad.aop = 7
     assert status(lambda: B.fusedmm_execute(plan._plan, bad, d, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_OPS
     assert (Z == 0).all().item()  # nothing was written by the failed calls
     plan.close()
