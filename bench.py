@@ -94,13 +94,19 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    plan.set_profiling(True)
-    torch.cuda.synchronize()
+    # the timed region: exactly `steps` executes, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # the same `steps` executes again, now with HIP events recorded around the main kernel on
+    # the launch stream (the two event records per step cost ~4 us of stream time, which is why
+    # they are kept out of the region that defines `value`; the kernel's own duration is the same)
+    plan.set_profiling(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
     kernel_ms_sum, calls = plan.read_profile()
     plan.set_profiling(False)
     assert torch.isfinite(Z[: min(g.m, 4096)]).all().item()
@@ -125,6 +131,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                      "frac": achieved / model.MI355X_HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
                      "kernel": "fusedmm_fast_kernel", "kernel_ms": kernel_ms,
+                     "kernel_timing": "HIP events around the main kernel on the launch stream, same K executes repeated "
+                                      "right after the timed region",
                      "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
                      "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
     }
@@ -182,8 +190,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="c1..c5")
     ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
     ap.add_argument("--no-cpu-baseline", action="store_true")
