@@ -57,7 +57,8 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
             "kind": "oracle", "sample": sample, "seconds": t, "repetitions": reps, "precision": "fp32 unfused two-phase"}
 
 
-def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0):
+def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0,
+        autotune: bool = False):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -83,7 +84,11 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     t0 = time.perf_counter()
     options = dict(options or {})
     options.setdefault("feature_dim_hint", w.d)
-    plan = binding.Plan(g.m, g.n, rp, ci, options)
+    if autotune:
+        plan = binding.Plan.tuned(g.m, g.n, rp, ci, ops, Xd if uses_x else None, Yd, Z, vd)
+        options = plan.tuned_options
+    else:
+        plan = binding.Plan(g.m, g.n, rp, ci, options)
     plan.reserve(w.d)
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3
@@ -125,7 +130,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
-                   "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms,
+                   "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms, "plan_options": options, "autotuned": autotune,
                    "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / model.MI355X_HBM_PEAK_GBS,
@@ -200,6 +205,7 @@ def main():
     ap.add_argument("--small-row-max", type=int, default=0)
     ap.add_argument("--split-row-min", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
+    ap.add_argument("--autotune", action="store_true", help="choose the schedule with fusedmm_plan_create_tuned")
     ap.add_argument("--column-classes", type=int, default=0)
     ap.add_argument("--tile-row-min", type=int, default=0)
     args = ap.parse_args()
@@ -211,7 +217,7 @@ def main():
                    "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
                    "tile_row_min": args.tile_row_min}
     out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
-              args.copy_calibration_mib)
+              args.copy_calibration_mib, args.autotune)
     print(json.dumps(out))
 
 

@@ -144,6 +144,20 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
                         const int64_t* d_rowptr, const int32_t* d_colidx,
                         const fusedmm_plan_options_t* options, void* stream);
 
+/* Build the schedule by measurement (the counterpart of the paper's autotuned kernels,
+ * Section IV-B: parameters chosen per machine by timing candidates).  Creates a plan for each of
+ * a small set of candidate schedules (column-class tiling off / 8..64 classes / two minimum row
+ * lengths), times three fusedmm_execute calls of each with the given operands on `stream`,
+ * keeps the fastest and destroys the others.  Arguments as for fusedmm_plan_create and
+ * fusedmm_execute; d_Z is overwritten.  `chosen` (host, may be NULL) receives the winning options,
+ * `best_ms` (host, may be NULL) its time per execute.  Synchronises the stream; not for the hot path. */
+int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
+                              const int64_t* d_rowptr, const int32_t* d_colidx,
+                              const fusedmm_ops_t* ops, int32_t d, const float* d_values,
+                              const float* d_X, int64_t ldx, const float* d_Y, int64_t ldy,
+                              float* d_Z, int64_t ldz, void* stream,
+                              fusedmm_plan_options_t* chosen, float* best_ms);
+
 /* Allocate the partial-sum scratch for feature dimension d up front, so that
  * later fusedmm_execute calls with dimension <= d never allocate. */
 int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d);

@@ -35,7 +35,7 @@ EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
-    "fusedmm_plan_destroy", "fusedmm_debug_copy",
+    "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned",
 )
 
 
@@ -80,6 +80,10 @@ def load():
     lib.fusedmm_plan_create.restype = ctypes.c_int
     lib.fusedmm_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp,
                                         ctypes.POINTER(fusedmm_plan_options_t), vp]
+    lib.fusedmm_plan_create_tuned.restype = ctypes.c_int
+    lib.fusedmm_plan_create_tuned.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp, ctypes.POINTER(fusedmm_ops_t),
+                                              i32, vp, vp, i64, vp, i64, vp, i64, vp,
+                                              ctypes.POINTER(fusedmm_plan_options_t), ctypes.POINTER(ctypes.c_float)]
     lib.fusedmm_plan_reserve.restype = ctypes.c_int
     lib.fusedmm_plan_reserve.argtypes = [vp, i32]
     lib.fusedmm_plan_workspace_bytes.restype = ctypes.c_int
@@ -152,6 +156,19 @@ def fusedmm_plan_create(m: int, n: int, nnz: int, d_rowptr, d_colidx, options=No
     return plan
 
 
+def fusedmm_plan_create_tuned(m: int, n: int, nnz: int, d_rowptr, d_colidx, ops: fusedmm_ops_t, d: int, d_values, d_X,
+                              ldx: int, d_Y, ldy: int, d_Z, ldz: int, stream=None):
+    """Returns (plan, chosen options as a dict, milliseconds per execute of the winner)."""
+    plan, chosen, ms = ctypes.c_void_p(), fusedmm_plan_options_t(), ctypes.c_float()
+    st = load().fusedmm_plan_create_tuned(ctypes.byref(plan), m, n, nnz, _dptr(d_rowptr), _dptr(d_colidx),
+                                          ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
+                                          _dptr(d_Z), ldz, _stream(stream), ctypes.byref(chosen), ctypes.byref(ms))
+    _check(st, "fusedmm_plan_create_tuned")
+    opts = {"column_classes": chosen.column_classes, "tile_row_min": chosen.tile_row_min,
+            "feature_dim_hint": chosen.feature_dim_hint}
+    return plan, opts, float(ms.value)
+
+
 def fusedmm_plan_reserve(plan, d: int) -> None:
     _check(load().fusedmm_plan_reserve(plan, d), "fusedmm_plan_reserve")
 
@@ -204,6 +221,20 @@ def fusedmm_plan_destroy(plan) -> None:
 
 class Plan:
     """Owns a fusedmm_plan_t for one CSR pattern held in torch device tensors."""
+
+    @classmethod
+    def tuned(cls, m: int, n: int, rowptr, colidx, ops, X, Y, Z, values=None, stream=None):
+        """Plan chosen by timing candidate schedules with these operands (fusedmm_plan_create_tuned)."""
+        if isinstance(ops, str):
+            ops = fusedmm_ops_preset(ops)
+        self = cls.__new__(cls)
+        self.m, self.n, self.nnz = int(m), int(n), int(colidx.numel())
+        self.rowptr, self.colidx = rowptr, colidx
+        ldx = 0 if X is None else X.stride(0)
+        self._plan, self.tuned_options, self.tuned_ms = fusedmm_plan_create_tuned(
+            self.m, self.n, self.nnz, rowptr, colidx if self.nnz else None, ops, int(Z.shape[1]), values, X, ldx,
+            Y, Y.stride(0), Z, Z.stride(0), stream)
+        return self
 
     def __init__(self, m: int, n: int, rowptr, colidx, options: Optional[dict] = None, stream=None):
         assert rowptr.is_cuda and rowptr.dtype.is_signed and rowptr.element_size() == 8 and rowptr.is_contiguous()

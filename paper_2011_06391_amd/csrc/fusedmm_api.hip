@@ -628,6 +628,65 @@ int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, 
   return FUSEDMM_OK;
 }
 
+int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz, const int64_t* d_rowptr,
+                              const int32_t* d_colidx, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
+                              const float* d_X, int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz,
+                              void* stream_, fusedmm_plan_options_t* chosen, float* best_ms) {
+  if (!out || !ops) return FUSEDMM_ERR_INVALID_ARG;
+  *out = nullptr;
+  // candidate schedules: no column-class tiling, and nested tiling with 8..64 finest classes at
+  // two minimum row lengths; everything else at its default
+  static const int32_t kCandidates[][2] = {{1, 0}, {8, 64}, {8, 128}, {16, 128}, {32, 128}, {64, 128}, {16, 256}, {64, 256}};
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess) return FUSEDMM_ERR_HIP;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FUSEDMM_ERR_HIP; }
+  fusedmm_plan_t* best = nullptr;
+  float best_time = 0.f;
+  fusedmm_plan_options_t best_opt = {};
+  int st = FUSEDMM_OK;
+  for (const auto& cand : kCandidates) {
+    fusedmm_plan_options_t opt = {};
+    opt.column_classes = cand[0];
+    opt.tile_row_min = cand[1];
+    opt.feature_dim_hint = d;
+    fusedmm_plan_t* p = nullptr;
+    st = fusedmm_plan_create(&p, m, n, nnz, d_rowptr, d_colidx, &opt, stream_);
+    if (st != FUSEDMM_OK) break;
+    if (cand[0] > 1 && p->n_tiled_rows == 0) {  // tiling did not engage (short or unsorted rows): same as {1, 0}
+      (void)fusedmm_plan_destroy(p);
+      continue;
+    }
+    constexpr int kWarm = 2, kTimed = 3;
+    for (int it = 0; it < kWarm + kTimed && st == FUSEDMM_OK; ++it) {
+      if (it == kWarm && hipEventRecord(e0, stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+      if (st == FUSEDMM_OK) st = fusedmm_execute(p, ops, d, d_values, d_X, ldx, d_Y, ldy, d_Z, ldz, stream_);
+    }
+    float ms = 0.f;
+    if (st == FUSEDMM_OK && (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                             hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+      st = FUSEDMM_ERR_HIP;
+    if (st != FUSEDMM_OK) { (void)fusedmm_plan_destroy(p); break; }
+    ms /= kTimed;
+    if (!best || ms < best_time) {
+      if (best) (void)fusedmm_plan_destroy(best);
+      best = p; best_time = ms; best_opt = opt;
+    } else {
+      (void)fusedmm_plan_destroy(p);
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (st != FUSEDMM_OK) {
+    if (best) (void)fusedmm_plan_destroy(best);
+    return st;
+  }
+  *out = best;
+  if (chosen) *chosen = best_opt;
+  if (best_ms) *best_ms = best_time;
+  return FUSEDMM_OK;
+}
+
 int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream_) {
   if (bytes == 0) return FUSEDMM_OK;
   if (!d_dst || !d_src || bytes % 16 != 0 || !aligned16(d_dst) || !aligned16(d_src)) return FUSEDMM_ERR_INVALID_ARG;

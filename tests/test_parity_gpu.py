@@ -341,6 +341,28 @@ def test_execute_can_be_captured_in_a_hip_graph(B):
     plan.close()
 
 
+def test_tuned_plan_is_a_valid_plan(B):
+    """fusedmm_plan_create_tuned picks one of the candidate schedules by timing; whichever it
+    picks, results must match the oracle and every stored entry must be visited once."""
+    g = synth.rmat(14, (1 << 13) * 16, seed=77)
+    d = 128
+    X = synth.fill_uniform((g.m, d), 78, -0.5, 0.5)
+    rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(X)
+    Z = torch.empty((g.m, d), dtype=torch.float32, device="cuda")
+    plan = B.Plan.tuned(g.m, g.n, rp, ci, "one_minus_sigmoid", Xd, Xd, Z)
+    assert plan.tuned_ms > 0 and plan.tuned_options["column_classes"] in (1, 8, 16, 32, 64)
+    Z.fill_(float("nan"))
+    plan.execute("one_minus_sigmoid", Xd, Xd, Z)
+    torch.cuda.synchronize()
+    Zr, S, _ = oracle.unfused(g.rowptr, g.colidx, None, X, X, "one_minus_sigmoid")
+    check(Z.cpu().numpy(), Zr, S, f"tuned {plan.tuned_options}")
+    counts = torch.zeros(g.nnz, dtype=torch.int32, device="cuda")
+    plan.edge_visits(d, True, counts)
+    torch.cuda.synchronize()
+    assert counts.min().item() == 1 and counts.max().item() == 1
+    plan.close()
+
+
 def test_status_codes(B):
     g = synth.rmat(8, 1024, seed=2)
     rp, ci = dev(g.rowptr), dev(g.colidx)
