@@ -192,13 +192,16 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path,
                               uint32_t* d_counts, void* stream);
 
-/* Per-kernel timing for benchmarks.  When enabled, fusedmm_execute brackets
- * its main kernel with HIP events on the launch stream (at most 4096 calls are
- * retained).  fusedmm_plan_read_profile synchronises those events, returns the
- * summed main-kernel milliseconds and the number of timed calls, and clears
- * the record.  All pointers are host pointers. */
+/* Per-kernel timing for benchmarks.  When enabled, fusedmm_execute records three HIP events on
+ * the launch stream: one before its main kernel, one right after it and one more right after that
+ * (at most 4096 calls are retained).  fusedmm_plan_read_profile synchronises those events and
+ * returns the summed before->after milliseconds (main kernel + the cost of the bracket itself),
+ * the summed after->after2 milliseconds (the cost of an empty bracket: subtract it to get the
+ * kernel's own duration, which matters for kernels of a few tens of microseconds) and the number
+ * of timed calls, then clears the record.  All pointers are host pointers. */
 int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled);
-int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, int64_t* calls);
+int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, double* empty_bracket_ms_sum,
+                              int64_t* calls);
 
 /* Measurement aid: a plain grid-stride copy kernel, dst[i] = src[i] for `bytes` bytes
  * (device pointers, 16-byte aligned, bytes a multiple of 16, non-overlapping),

@@ -97,7 +97,8 @@ def load():
     lib.fusedmm_plan_set_profiling.restype = ctypes.c_int
     lib.fusedmm_plan_set_profiling.argtypes = [vp, i32]
     lib.fusedmm_plan_read_profile.restype = ctypes.c_int
-    lib.fusedmm_plan_read_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.fusedmm_plan_read_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                              ctypes.POINTER(i64)]
     lib.fusedmm_debug_copy.restype = ctypes.c_int
     lib.fusedmm_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_plan_destroy.restype = ctypes.c_int
@@ -204,9 +205,11 @@ def fusedmm_plan_set_profiling(plan, enabled: bool) -> None:
 
 
 def fusedmm_plan_read_profile(plan):
-    ms, calls = ctypes.c_double(), ctypes.c_int64()
-    _check(load().fusedmm_plan_read_profile(plan, ctypes.byref(ms), ctypes.byref(calls)), "fusedmm_plan_read_profile")
-    return float(ms.value), int(calls.value)
+    """(main kernel ms sum incl. bracket cost, empty-bracket ms sum, calls)."""
+    ms, empty, calls = ctypes.c_double(), ctypes.c_double(), ctypes.c_int64()
+    _check(load().fusedmm_plan_read_profile(plan, ctypes.byref(ms), ctypes.byref(empty), ctypes.byref(calls)),
+           "fusedmm_plan_read_profile")
+    return float(ms.value), float(empty.value), int(calls.value)
 
 
 def fusedmm_debug_copy(d_dst, d_src, nbytes: int, stream=None) -> None:

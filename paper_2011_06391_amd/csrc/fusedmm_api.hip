@@ -25,7 +25,8 @@ struct fusedmm_plan {
   float* d_partials = nullptr;
   int32_t partials_d = 0;  // scratch holds n_parts rows of this many floats
   bool profiling = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+  struct EventTriple { hipEvent_t before, after, after2; };
+  std::vector<EventTriple> events;  // main kernel between before/after; nothing between after/after2
   size_t events_used = 0;
 };
 
@@ -89,8 +90,9 @@ void free_plan_device(fusedmm_plan* p) {
   if (p->d_tile_descs) (void)hipFree(p->d_tile_descs);
   if (p->d_partials) (void)hipFree(p->d_partials);
   for (auto& ev : p->events) {
-    (void)hipEventDestroy(ev.first);
-    (void)hipEventDestroy(ev.second);
+    (void)hipEventDestroy(ev.before);
+    (void)hipEventDestroy(ev.after);
+    (void)hipEventDestroy(ev.after2);
   }
   p->events.clear();
 }
@@ -531,10 +533,11 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
                     (plan->nnz == 0 || (aligned16(d_Y) && ldy % 4 == 0)) &&
                     (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
 
-  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
   if (plan->profiling && plan->events_used < plan->events.size()) {
-    ev0 = plan->events[plan->events_used].first;
-    ev1 = plan->events[plan->events_used].second;
+    ev0 = plan->events[plan->events_used].before;
+    ev1 = plan->events[plan->events_used].after;
+    ev2 = plan->events[plan->events_used].after2;
   }
 
   hipError_t e = hipSuccess;
@@ -548,7 +551,7 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     a.alpha = ops->alpha;
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_fast(pattern, d, a, stream);
-    if (ev0) { (void)hipEventRecord(ev1, stream); ++plan->events_used; }
+    if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored densely with stride d, whatever the scratch capacity is
     if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, d_Z, ldz, stream);
   } else {
@@ -562,7 +565,7 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     g.visit_counts = nullptr;
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_generic(g, stream);
-    if (ev0) { (void)hipEventRecord(ev1, stream); ++plan->events_used; }
+    if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
   }
   return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }
@@ -604,25 +607,31 @@ int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled) {
       return FUSEDMM_ERR_ALLOC;
     }
     for (size_t i = 0; i < kMaxProfiledCalls; ++i) {
-      hipEvent_t a, b;
+      hipEvent_t a, b, c;
       if (hipEventCreate(&a) != hipSuccess) return FUSEDMM_ERR_HIP;
       if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return FUSEDMM_ERR_HIP; }
-      plan->events.emplace_back(a, b);
+      if (hipEventCreate(&c) != hipSuccess) { (void)hipEventDestroy(a); (void)hipEventDestroy(b); return FUSEDMM_ERR_HIP; }
+      plan->events.push_back(fusedmm_plan::EventTriple{a, b, c});
     }
   }
   return FUSEDMM_OK;
 }
 
-int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, int64_t* calls) {
-  if (!plan || !main_kernel_ms_sum || !calls) return FUSEDMM_ERR_INVALID_ARG;
-  double sum = 0.0;
+int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, double* empty_bracket_ms_sum,
+                              int64_t* calls) {
+  if (!plan || !main_kernel_ms_sum || !empty_bracket_ms_sum || !calls) return FUSEDMM_ERR_INVALID_ARG;
+  double sum = 0.0, empty = 0.0;
   for (size_t i = 0; i < plan->events_used; ++i) {
-    if (hipEventSynchronize(plan->events[i].second) != hipSuccess) return FUSEDMM_ERR_HIP;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, plan->events[i].first, plan->events[i].second) != hipSuccess) return FUSEDMM_ERR_HIP;
+    const auto& ev = plan->events[i];
+    if (hipEventSynchronize(ev.after2) != hipSuccess) return FUSEDMM_ERR_HIP;
+    float ms = 0.f, ms0 = 0.f;
+    if (hipEventElapsedTime(&ms, ev.before, ev.after) != hipSuccess) return FUSEDMM_ERR_HIP;
+    if (hipEventElapsedTime(&ms0, ev.after, ev.after2) != hipSuccess) return FUSEDMM_ERR_HIP;
     sum += ms;
+    empty += ms0;
   }
   *main_kernel_ms_sum = sum;
+  *empty_bracket_ms_sum = empty;
   *calls = (int64_t)plan->events_used;
   plan->events_used = 0;
   return FUSEDMM_OK;
