@@ -528,8 +528,11 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
   if (uses_x && overlaps(d_Z, plan->m, ldz, d_X, plan->m, ldx, d)) return FUSEDMM_ERR_ALIAS;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-  const int pattern = recognise(*ops);
-  const bool fast = pattern >= 0 && is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) &&
+  // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
+  // structure with the ops decided at run time; odd shapes fall back to the general kernel
+  const int recognised = recognise(*ops);
+  const int pattern = recognised >= 0 ? recognised : PAT_RUNTIME;
+  const bool fast = is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) &&
                     (plan->nnz == 0 || (aligned16(d_Y) && ldy % 4 == 0)) &&
                     (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
 
@@ -549,11 +552,12 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
+    a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop; a.aop = ops->aop;
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_fast(pattern, d, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored densely with stride d, whatever the scratch capacity is
-    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, d_Z, ldz, stream);
+    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, d_Z, ldz, stream);
   } else {
     GenericArgs g;
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
@@ -584,6 +588,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
+    a.vop = a.rop = a.sop = a.mop = a.aop = 0;
     a.visit_counts = d_counts;
     e = launch_fast(PAT_VISIT, d, a, stream);
   } else {

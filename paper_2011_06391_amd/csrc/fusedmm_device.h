@@ -14,6 +14,7 @@
 // SOP and folds MOP+AOP into FMAs.  z_u is written once with non-temporal stores.
 #pragma once
 #include "fusedmm_internal.h"
+#include "../../include/fusedmm.h"
 
 namespace fmm {
 
@@ -51,6 +52,23 @@ __device__ __forceinline__ float group_allreduce(float v) {
   return v;
 }
 
+// Product over each aligned group of G lanes (ROP = RMUL), result in every lane of the group.
+template <int G>
+__device__ __forceinline__ float group_allreduce_mul(float v) {
+  v *= dpp_mov<0xB1>(v);
+  v *= dpp_mov<0x4E>(v);
+  v *= dpp_mov<0x141>(v);
+  if constexpr (G >= 16) v *= dpp_mov<0x140>(v);
+  if constexpr (G >= 32) v *= lane_xor<16>(v);
+  if constexpr (G >= 64) v *= lane_xor<32>(v);
+  return v;
+}
+
+// AOP on two floats: SUM, MAX or MIN (aop is wave-uniform).
+__device__ __forceinline__ float aop_apply(int aop, float z, float w) {
+  return aop == FUSEDMM_AOP_SUM ? z + w : (aop == FUSEDMM_AOP_MAX ? fmaxf(z, w) : fminf(z, w));
+}
+
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
 __device__ __forceinline__ float cross_group_allreduce(float v) {
@@ -58,6 +76,33 @@ __device__ __forceinline__ float cross_group_allreduce(float v) {
   if constexpr (G <= 16) v += lane_xor<16>(v);
   if constexpr (G <= 32) v += lane_xor<32>(v);
   return v;
+}
+
+// The same across-group combination with a run-time AOP.
+template <int G>
+__device__ __forceinline__ float cross_group_allreduce_aop(int aop, float v) {
+  if constexpr (G <= 8) v = aop_apply(aop, v, lane_xor<8>(v));
+  if constexpr (G <= 16) v = aop_apply(aop, v, lane_xor<16>(v));
+  if constexpr (G <= 32) v = aop_apply(aop, v, lane_xor<32>(v));
+  return v;
+}
+
+template <int P, int G, int V>
+__device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V]) {
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    if constexpr (P == PAT_RUNTIME) {
+      z[i].x = cross_group_allreduce_aop<G>(a.aop, z[i].x);
+      z[i].y = cross_group_allreduce_aop<G>(a.aop, z[i].y);
+      z[i].z = cross_group_allreduce_aop<G>(a.aop, z[i].z);
+      z[i].w = cross_group_allreduce_aop<G>(a.aop, z[i].w);
+    } else {
+      z[i].x = cross_group_allreduce<G>(z[i].x);
+      z[i].y = cross_group_allreduce<G>(z[i].y);
+      z[i].z = cross_group_allreduce<G>(z[i].z);
+      z[i].w = cross_group_allreduce<G>(z[i].w);
+    }
+  }
 }
 
 __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
@@ -93,11 +138,89 @@ struct PatTraits {
   static constexpr bool uses_val = (P == PAT_GCN);
   static constexpr bool loads_y = (P != PAT_VISIT);
 };
+// whether x_u / the edge values are read: fixed per pattern, a (uniform) run-time fact for PAT_RUNTIME
+template <int P>
+__device__ __forceinline__ bool reads_x(const KernelArgs& a) {
+  if constexpr (P == PAT_RUNTIME) return a.vop != FUSEDMM_VOP_SEL2ND; else return PatTraits<P>::uses_x;
+}
+template <int P>
+__device__ __forceinline__ bool reads_values(const KernelArgs& a) {
+  if constexpr (P == PAT_RUNTIME) return a.sop == FUSEDMM_SOP_EDGE_VALUE; else return PatTraits<P>::uses_val;
+}
+
+__device__ __forceinline__ float rt_vop(int vop, float x, float y) {
+  switch (vop) {
+    case FUSEDMM_VOP_MUL: return x * y;
+    case FUSEDMM_VOP_SEL2ND: return y;
+    case FUSEDMM_VOP_SUB: return x - y;
+    default: return x + y;
+  }
+}
+__device__ __forceinline__ float rt_sop(int sop, float s, float alpha) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  switch (sop) {
+    case FUSEDMM_SOP_SIGMOID: return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-s * kLog2e));
+    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * kLog2e));
+    case FUSEDMM_SOP_INV_1P: return __builtin_amdgcn_rcpf(1.0f + s);
+    case FUSEDMM_SOP_SCAL: return alpha * s;
+    default: return s;
+  }
+}
 
 template <int P, int G, int V, bool CHECK>
-__device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V], float aval, float alpha,
+__device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V], float aval, const KernelArgs& a,
                                             bool valid, v4f (&z)[V]) {
   constexpr float kLog2e = 1.4426950408889634f;
+  const float alpha = a.alpha;
+  if constexpr (P == PAT_RUNTIME) {
+    // every op of the selector, decided by wave-uniform branches: the five steps in order
+    v4f t[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {  // VOP
+      t[i].x = rt_vop(a.vop, x[i].x, y[i].x);
+      t[i].y = rt_vop(a.vop, x[i].y, y[i].y);
+      t[i].z = rt_vop(a.vop, x[i].z, y[i].z);
+      t[i].w = rt_vop(a.vop, x[i].w, y[i].w);
+    }
+    const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
+    float h = aval;
+    if (a.sop != FUSEDMM_SOP_EDGE_VALUE && a.rop != FUSEDMM_ROP_NOOP) {  // ROP, then SOP on the scalar
+      float s;
+      if (a.rop == FUSEDMM_ROP_RMUL) {
+        float p = 1.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) p *= t[i].x * t[i].y * t[i].z * t[i].w;
+        s = group_allreduce_mul<G>(p);
+      } else {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          if (a.rop == FUSEDMM_ROP_RSUM) p += (t[i].x + t[i].y) + (t[i].z + t[i].w);
+          else p += (t[i].x * t[i].x + t[i].y * t[i].y) + (t[i].z * t[i].z + t[i].w * t[i].w);
+        }
+        s = group_allreduce<G>(p);
+        if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
+      }
+      h = rt_sop(a.sop, s, alpha);
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      v4f hv;  // SOP on each element when the message is a vector
+      if (scalar_h) {
+        hv = v4f{h, h, h, h};
+      } else {
+        hv.x = rt_sop(a.sop, t[i].x, alpha); hv.y = rt_sop(a.sop, t[i].y, alpha);
+        hv.z = rt_sop(a.sop, t[i].z, alpha); hv.w = rt_sop(a.sop, t[i].w, alpha);
+      }
+      v4f w = a.mop == FUSEDMM_MOP_SEL2ND ? y[i] : (a.mop == FUSEDMM_MOP_MUL_Y ? hv * y[i] : hv * t[i]);  // MOP
+      if (CHECK && !valid) w = v4f{0.f, 0.f, 0.f, 0.f};  // 0 is neutral for SUM and, from a zero start, for MAX and MIN
+      z[i].x = aop_apply(a.aop, z[i].x, w.x);  // AOP
+      z[i].y = aop_apply(a.aop, z[i].y, w.y);
+      z[i].z = aop_apply(a.aop, z[i].z, w.z);
+      z[i].w = aop_apply(a.aop, z[i].w, w.w);
+    }
+    return;
+  }
   if constexpr (P == PAT_GCN) {
     // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP+AOP: z += h * y
     float h = aval;
@@ -153,6 +276,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   const int slot = lane / G;
   const int g = lane % G;
   const float* ybase = a.Y + 4 * g;
+  const bool use_val = reads_values<P>(a);
 
   for (int64_t base = e0; base < e1; base += 64) {
     const int cnt = (int)((e1 - base) < 64 ? (e1 - base) : 64);  // wave-uniform
@@ -160,7 +284,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
     float valb = 0.f;
     if (lane < cnt) {
       colb = ld_stream(a.colidx + base + lane);
-      if constexpr (T::uses_val) valb = ld_stream(a.values + base + lane);
+      if (use_val) valb = ld_stream(a.values + base + lane);
     }
     for (int k0 = 0; k0 < cnt; k0 += S * U) {
       int c[U];
@@ -172,7 +296,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         for (int u = 0; u < U; ++u) {
           const int j = k0 + u * S + slot;
           c[u] = __shfl(colb, j);
-          av[u] = T::uses_val ? __shfl(valb, j) : 0.f;
+          av[u] = use_val ? __shfl(valb, j) : 0.f;
         }
         if constexpr (T::loads_y) {
 #pragma unroll
@@ -182,7 +306,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
             for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * G * i);
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a.alpha, true, z);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -195,7 +319,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           const int j = k0 + u * S + slot;
           ok[u] = j < cnt;
           c[u] = __shfl(colb, j & 63);
-          av[u] = T::uses_val ? __shfl(valb, j & 63) : 0.f;
+          av[u] = use_val ? __shfl(valb, j & 63) : 0.f;
         }
         if constexpr (T::loads_y) {
 #pragma unroll
@@ -209,7 +333,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
             }
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -289,16 +413,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if constexpr (T::uses_x) load_x<D, GW>(a, ch.row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW>(a, ch.row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
-#pragma unroll
-      for (int i = 0; i < V; ++i) {
-        z[i].x = cross_group_allreduce<GW>(z[i].x);
-        z[i].y = cross_group_allreduce<GW>(z[i].y);
-        z[i].z = cross_group_allreduce<GW>(z[i].z);
-        z[i].w = cross_group_allreduce<GW>(z[i].w);
-      }
+      combine_groups<P, GW, V>(a, z);
       if (lane < GW) {
 #pragma unroll
         for (int i = 0; i < V; ++i) stage[wave][g + GW * i] = z[i];
@@ -307,7 +425,15 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       if (threadIdx.x < D / 4) {
         v4f s = stage[0][threadIdx.x];
 #pragma unroll
-        for (int w = 1; w < kWavesPerBlock; ++w) s += stage[w][threadIdx.x];
+        for (int w = 1; w < kWavesPerBlock; ++w) {
+          const v4f o = stage[w][threadIdx.x];
+          if constexpr (P == PAT_RUNTIME) {
+            s.x = aop_apply(a.aop, s.x, o.x); s.y = aop_apply(a.aop, s.y, o.y);
+            s.z = aop_apply(a.aop, s.z, o.z); s.w = aop_apply(a.aop, s.w, o.w);
+          } else {
+            s += o;
+          }
+        }
         float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * D;
         __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * threadIdx.x));
       }
@@ -331,16 +457,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if constexpr (T::uses_x) load_x<D, GW>(a, row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW>(a, row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
-#pragma unroll
-      for (int i = 0; i < V; ++i) {
-        z[i].x = cross_group_allreduce<GW>(z[i].x);
-        z[i].y = cross_group_allreduce<GW>(z[i].y);
-        z[i].z = cross_group_allreduce<GW>(z[i].z);
-        z[i].w = cross_group_allreduce<GW>(z[i].w);
-      }
+      combine_groups<P, GW, V>(a, z);
       if (lane < GW) store_row<D, GW>(dst, g, z);
     }
   } else if (kind == kItemPacked) {
@@ -351,6 +471,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int slot = lane / GP;
     const int g = lane % GP;
     const float* ybase = a.Y + 4 * g;
+    const bool use_val = reads_values<P>(a);
     for (int round = 0; round < count; round += kWavesPerBlock * S) {
       const int idx = round + wave * S + slot;
       const bool has_seg = idx < count;
@@ -372,7 +493,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       v4f x[V], z[V];
       zero(z);
       zero(x);
-      if constexpr (T::uses_x) {
+      if (reads_x<P>(a)) {
         if (deg > 0) load_x<D, GP>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
@@ -386,7 +507,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         float valb = 0.f;
         if (bb + g < deg) {
           colb = ld_stream(a.colidx + e0 + bb + g);
-          if constexpr (T::uses_val) valb = ld_stream(a.values + e0 + bb + g);
+          if (use_val) valb = ld_stream(a.values + e0 + bb + g);
         }
         const int steps = (maxdeg - bb) < GP ? (maxdeg - bb) : GP;
         for (int k = 0; k < steps; k += UP) {
@@ -398,7 +519,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
           for (int u = 0; u < UP; ++u) {
             ok[u] = (bb + k + u) < deg;
             c[u] = __shfl(colb, slot * GP + k + u);
-            av[u] = T::uses_val ? __shfl(valb, slot * GP + k + u) : 0.f;
+            av[u] = use_val ? __shfl(valb, slot * GP + k + u) : 0.f;
           }
           if constexpr (T::loads_y) {
 #pragma unroll
@@ -412,7 +533,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
               }
             }
 #pragma unroll
-            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a.alpha, ok[u], z);
+            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a, ok[u], z);
           } else {
 #pragma unroll
             for (int u = 0; u < UP; ++u)

@@ -26,6 +26,7 @@ hipError_t FMM_CAT(launch_fast_d, FMM_D)(int pattern, const KernelArgs& a, hipSt
     case PAT_TDIST: return launch_one<PAT_TDIST>(a, stream);
     case PAT_FR: return launch_one<PAT_FR>(a, stream);
     case PAT_VISIT: return launch_one<PAT_VISIT>(a, stream);
+    case PAT_RUNTIME: return launch_one<PAT_RUNTIME>(a, stream);
     default: return hipErrorInvalidValue;
   }
 }

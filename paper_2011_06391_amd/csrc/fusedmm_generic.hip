@@ -115,8 +115,15 @@ hipError_t launch_generic(const GenericArgs& a, hipStream_t stream) {
 // z_u = sum of the row's partial rows, in slot order (fixed order => run-to-run deterministic).
 // A workgroup covers 256 / (d/4) rows; a thread owns one 16-byte column of one row and keeps
 // eight partial-row loads in flight.
+__device__ __forceinline__ v4f merge_two(int aop, v4f s, v4f t) {
+  if (aop == FUSEDMM_AOP_SUM) return s + t;
+  if (aop == FUSEDMM_AOP_MAX) return v4f{fmaxf(s.x, t.x), fmaxf(s.y, t.y), fmaxf(s.z, t.z), fmaxf(s.w, t.w)};
+  return v4f{fminf(s.x, t.x), fminf(s.y, t.y), fminf(s.z, t.z), fminf(s.w, t.w)};
+}
+
 __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
-                                                           const float* partials, int32_t d, float* Z, int64_t ldz) {
+                                                           const float* partials, int32_t d, int32_t aop, float* Z,
+                                                           int64_t ldz) {
   const int cols = d >> 2;
   const int rows_per_block = 256 / cols;
   const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
@@ -131,19 +138,20 @@ __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* mer
 #pragma unroll
     for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)(p + k) * d));
 #pragma unroll
-    for (int k = 0; k < 8; ++k) s += t[k];
+    for (int k = 0; k < 8; ++k) s = merge_two(aop, s, t[k]);
   }
-  for (; p < md.n_parts; ++p) s += __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * d));
+  for (; p < md.n_parts; ++p)
+    s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * d)));
   __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(Z + (int64_t)md.row * ldz + 4 * c));
 }
 
-hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, float* Z,
-                        int64_t ldz, hipStream_t stream) {
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
+                        float* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
   const int rows_per_block = 256 / (d >> 2);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
-                     Z, ldz);
+                     aop, Z, ldz);
   return hipGetLastError();
 }
 

@@ -6,7 +6,8 @@
 namespace fmm {
 
 // Pattern ids of the specialised kernels (host dispatch -> template instance).
-enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5 };
+// PAT_RUNTIME: the same kernel structure with the five ops read from KernelArgs at run time (any valid tuple).
+enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6 };
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
@@ -51,6 +52,7 @@ struct KernelArgs {
   float* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
+  int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
   // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed).
   const int32_t* order;
@@ -94,7 +96,8 @@ struct GenericArgs {
 };
 hipError_t launch_generic(const GenericArgs& a, hipStream_t stream);
 
-hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d,
+// aop: FUSEDMM_AOP_SUM / MAX / MIN, how partial rows are combined
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
                         float* Z, int64_t ldz, hipStream_t stream);
 
 // flag[0] |= 1 if any colidx entry is outside [0, n).

@@ -193,6 +193,28 @@ def test_general_five_step_path(B, tuples, d):
     assert (Zg[[2, 30]] == 0).all()
 
 
+@pytest.mark.parametrize("d", (32, 128, 512))
+@pytest.mark.parametrize("tuples", GENERAL_TUPLES + [((t[0], "SUM"), (t[1], "ASUM")) for t in OTHER_TUPLES])
+def test_runtime_ops_fast_kernel_all_bins(B, tuples, d):
+    """Op tuples without a specialised instance run the same fast kernel with run-time ops: packed
+    rows, wave rows, chunks, column-class tiles and the SUM / MAX / MIN merge of partial rows."""
+    (gpu_names, gpu_aop), (oracle_names, oracle_aop) = tuples
+    rng = np.random.default_rng(777 + d)
+    m, n = 211, 1500
+    long_rows = {3: 64, 5: 120, 11: 257, 57: 700, 100: 1025, 210: 4000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    lo, hi = (0.48, 0.52) if "RMUL" in gpu_names else (-0.9, 0.9)
+    X = rng.uniform(lo, hi, (m, d)).astype(np.float32)
+    Y = rng.uniform(lo, hi, (n, d)).astype(np.float32)
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, oracle_names, oracle_aop, alpha=ALPHA)
+    for options in ({"column_classes": 1}, TILED):
+        Zg, stats = run_gpu(B, rowptr, colidx, vals, X, Y, B.make_ops(*gpu_names, aop=gpu_aop), m, n, alpha=ALPHA,
+                            options=options)
+        check(Zg, Zr, S, f"{gpu_names} {gpu_aop} d={d} {options}")
+        assert (stats["tiled_rows"] > 0) == (options is TILED)
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
