@@ -222,6 +222,13 @@ def fusedmm_plan_destroy(plan) -> None:
 
 # ---- convenience wrapper (still marshalling only) ----------------------------
 
+def _check_csr(rowptr, colidx) -> None:
+    if not (rowptr.is_cuda and str(rowptr.dtype) == "torch.int64" and rowptr.is_contiguous()):
+        raise TypeError("rowptr must be a contiguous CUDA int64 tensor")
+    if colidx.numel() and not (colidx.is_cuda and str(colidx.dtype) == "torch.int32" and colidx.is_contiguous()):
+        raise TypeError("colidx must be a contiguous CUDA int32 tensor")
+
+
 class Plan:
     """Owns a fusedmm_plan_t for one CSR pattern held in torch device tensors."""
 
@@ -230,6 +237,7 @@ class Plan:
         """Plan chosen by timing candidate schedules with these operands (fusedmm_plan_create_tuned)."""
         if isinstance(ops, str):
             ops = fusedmm_ops_preset(ops)
+        _check_csr(rowptr, colidx)
         self = cls.__new__(cls)
         self.m, self.n, self.nnz = int(m), int(n), int(colidx.numel())
         self.rowptr, self.colidx = rowptr, colidx
@@ -240,8 +248,7 @@ class Plan:
         return self
 
     def __init__(self, m: int, n: int, rowptr, colidx, options: Optional[dict] = None, stream=None):
-        assert rowptr.is_cuda and rowptr.dtype.is_signed and rowptr.element_size() == 8 and rowptr.is_contiguous()
-        assert colidx.numel() == 0 or (colidx.is_cuda and colidx.element_size() == 4 and colidx.is_contiguous())
+        _check_csr(rowptr, colidx)
         self.m, self.n, self.nnz = int(m), int(n), int(colidx.numel())
         self.rowptr, self.colidx = rowptr, colidx  # keep alive: the plan borrows them
         self._plan = fusedmm_plan_create(self.m, self.n, self.nnz, rowptr, colidx if self.nnz else None, options,
@@ -252,7 +259,8 @@ class Plan:
             ops = fusedmm_ops_preset(ops)
         d = int(Z.shape[1]) if Z is not None and Z.dim() == 2 else 0
         for t in (X, Y, Z, values):
-            assert t is None or (t.is_cuda and t.element_size() == 4)
+            if t is not None and not (t.is_cuda and str(t.dtype) == "torch.float32" and (t.dim() < 2 or t.stride(-1) == 1)):
+                raise TypeError("operands must be CUDA float32 tensors with unit stride along the feature dimension")
         ldx = 0 if X is None else X.stride(0)
         fusedmm_execute(self._plan, ops, d, values, X, ldx, Y, Y.stride(0), Z, Z.stride(0), stream)
 
