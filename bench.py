@@ -179,6 +179,22 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         del src, dst
     except Exception as exc:
         context["copy_error"] = repr(exc)[:200]
+    try:
+        # the gather ceiling of this graph and schedule: the GCN pattern with unit edge values is the
+        # same stream of row gathers with one FMA per element and no ROP / SOP
+        ones = torch.ones(max(1, g.nnz), dtype=torch.float32, device="cuda")
+        gcn = binding.fusedmm_ops_preset("gcn")
+        for _ in range(3):
+            plan.execute(gcn, None, Yd, Z, ones)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            plan.execute(gcn, None, Yd, Z, ones)
+        torch.cuda.synchronize()
+        context["ms_per_step_pure_gather_same_schedule"] = (time.perf_counter() - t0) * 1e3 / steps
+        del ones
+    except Exception as exc:
+        context["gather_error"] = repr(exc)[:200]
     out["config"]["context"] = context
     if copy_mib > 0:
         # one launch of the plain copy kernel with known traffic, for calibrating profiler counters

@@ -1,0 +1,109 @@
+"""Seeded random differential tests: random shapes, degree mixes, schedules (every plan option),
+patterns and op tuples against the oracle.  Each case is small, but between them they hit the
+thresholds from both sides (rows exactly at small_row_max / split_row_min / tile_row_min, chunk
+lengths at multiples of 64 and 256, more column classes than columns, classes without entries)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+PATTERNS = ("sigmoid", "one_minus_sigmoid", "gcn", "tdist", "fr")
+# (binding names, binding AOP, oracle names, oracle AOP)
+TUPLES = [
+    (("MUL", "RSUM", "SCAL", "MUL_T"), "SUM", ("MUL", "RSUM", "SCAL", "MUL_T"), "ASUM"),
+    (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MAX", ("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMAX"),
+    (("SUB", "NOOP", "SIGMOID", "MUL_T"), "MIN", ("SUB", "NOOP", "SIGMOID", "MUL_T"), "AMIN"),
+    (("ADD", "SUMSQ", "INV_1P", "SEL2ND"), "MAX", ("ADD", "SUMSQ", "INV1P", "SEL2ND"), "AMAX"),
+]
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2011_06391_amd import binding
+    binding.load()
+    return binding
+
+
+def make_case(seed):
+    rng = np.random.default_rng(seed)
+    m = int(rng.integers(1, 400))
+    n = int(rng.integers(1, 3000))
+    opts = {
+        "small_row_max": int(rng.choice([1, 2, 7, 16, 32, 33])),
+        "split_row_min": int(rng.choice([16, 63, 64, 65, 256])),
+        "chunk_edges": int(rng.choice([256, 512, 1024])),
+        "column_classes": int(rng.choice([1, 8, 16, 64, 512])),
+        "tile_row_min": int(rng.choice([8, 17, 64, 128])),
+    }
+    specials = [0, 1, opts["small_row_max"], opts["small_row_max"] + 1, opts["split_row_min"], opts["split_row_min"] + 1,
+                opts["tile_row_min"] - 1, opts["tile_row_min"], 63, 64, 65, 255, 256, 257, 511, 512, 513, 1024, 1025, 2500]
+    degs = np.where(rng.random(m) < 0.3, rng.choice(specials, m), rng.integers(0, 40, m))
+    degs = np.where(rng.random(m) < 0.15, 0, degs).astype(np.int64)
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(degs)
+    nnz = int(rowptr[-1])
+    if rng.random() < 0.5:  # columns concentrated in a narrow band: most classes stay empty
+        lo = int(rng.integers(0, n))
+        colidx = (lo + rng.integers(0, max(1, n // 7), nnz)) % n
+    else:
+        colidx = rng.integers(0, n, nnz)
+    colidx = colidx.astype(np.int32)
+    sorted_cols = rng.random() < 0.8
+    if sorted_cols:
+        for u in range(m):
+            colidx[rowptr[u]:rowptr[u + 1]].sort()
+    d = int(rng.choice([32, 64, 128, 256, 512]))
+    share = rng.random() < 0.3 and m <= n
+    ld = d + int(rng.choice([0, 0, 4, 12]))
+    Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
+    Xb = Yb[:m] if share else rng.uniform(-0.7, 0.7, (m, ld)).astype(np.float32)
+    vals = rng.uniform(-1, 1, max(1, nnz)).astype(np.float32)[:nnz]
+    return m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FUSEDMM_RANDOM_CASES", "60"))))
+def test_random_case(B, seed):
+    m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts = make_case(1000 + seed)
+    rng = np.random.default_rng(seed)
+    X, Y = np.ascontiguousarray(Xb[:, :d]), np.ascontiguousarray(Yb[:, :d])
+    if seed % 3 == 2:
+        gnames, gaop, onames, oaop = TUPLES[(seed // 3) % len(TUPLES)]
+        Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, onames, oaop, alpha=0.21)
+        ops = B.make_ops(*gnames, aop=gaop, alpha=0.21)
+        what = f"{gnames}/{gaop}"
+    else:
+        pattern = PATTERNS[int(rng.integers(0, len(PATTERNS)))]
+        Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=0.21)
+        ops = B.fusedmm_ops_preset(pattern)
+        ops.alpha = 0.21
+        what = pattern
+    rp = torch.from_numpy(rowptr).cuda()
+    ci = torch.from_numpy(colidx).cuda()
+    Yd = torch.from_numpy(Yb).cuda()
+    Xd = Yd[:m] if share else torch.from_numpy(Xb).cuda()
+    vd = torch.from_numpy(vals).cuda()
+    Zb = torch.full((m, Yb.shape[1]), np.nan, dtype=torch.float32, device="cuda")
+    plan = B.Plan(m, n, rp, ci, opts)
+    plan.execute(ops, Xd[:, :d], Yd[:, :d], Zb[:, :d], vd)
+    torch.cuda.synchronize()
+    out = Zb.cpu().numpy()
+    err, am, viol = oracle.compare(out[:, :d], Zr, S)
+    info = f"seed {seed} {what} m={m} n={n} d={d} nnz={len(colidx)} opts={opts} stats={plan.stats()}"
+    assert viol == 0, info
+    assert err <= TOL, f"{info}: max rel err {err:.3e} at {am}"
+    assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
+    counts = torch.zeros(max(1, len(colidx)), dtype=torch.int32, device="cuda")
+    plan.edge_visits(d, True, counts)
+    torch.cuda.synchronize()
+    if len(colidx):
+        c = counts[:len(colidx)].cpu().numpy()
+        assert c.min() == 1 and c.max() == 1, info
+    plan.close()
