@@ -75,7 +75,7 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
 
 
 def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0,
-        autotune: bool = False):
+        autotune: bool = False, y_bf16: bool = False):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -110,8 +110,17 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3
 
+    Yb = None
+    if y_bf16:  # optional storage mode, never the default: Y rounded once to bfloat16, arithmetic stays fp32
+        Yb = torch.empty((g.n, w.d), dtype=torch.int16, device="cuda")
+        binding.fusedmm_to_bf16(Yb, Yd, g.n * w.d)
+        torch.cuda.synchronize()
+
     def step():
-        plan.execute(ops, Xd if uses_x else None, Yd, Z, vd)
+        if Yb is not None:
+            plan.execute_bf16y(ops, Xd if uses_x else None, Yb, Z, vd)
+        else:
+            plan.execute(ops, Xd if uses_x else None, Yd, Z, vd)
 
     for _ in range(warmup):
         step()
@@ -139,7 +148,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     Z_sample = Z[torch.from_numpy(sample_rows).cuda()].cpu().numpy()  # rows of the timed result, checked on the CPU leg
 
     ms_per_step = elapsed * 1e3 / steps
-    tr = model.traffic(g.m, g.n, g.nnz, w.d, uses_x, vd is not None, w.Y is w.X)
+    tr = model.traffic(g.m, g.n, g.nnz, w.d, uses_x, vd is not None, w.Y is w.X, y_bytes=2 if y_bf16 else 4)
     kernel_ms = (kernel_ms_sum - empty_ms_sum) / max(1, calls)  # bracket cost measured by an empty bracket per call
     if kernel_ms <= 0.0:  # a kernel of a few microseconds can vanish in the bracket's own jitter
         kernel_ms = kernel_ms_sum / max(1, calls)
@@ -150,14 +159,14 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "unit": "G(edge*dim)/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32 (Y stored as bf16)" if y_bf16 else "f32", "data": "synthetic",
         "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
                    "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms, "plan_options": options, "autotuned": autotune,
                    "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / model.MI355X_HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
+                     "traffic": None if (y_bf16 or autotune or d) else MEASURED_TRAFFIC_BYTES.get(workload),
                      "kernel": "fusedmm_fast_kernel", "kernel_ms": kernel_ms,
                      "kernel_timing": "HIP events around the main kernel on the launch stream, same K executes repeated "
                                       "right after the timed region; an empty event bracket per call is subtracted",
@@ -245,7 +254,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     torch.cuda.empty_cache()
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
-        out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample)
+        if not y_bf16:  # the oracle would have to be fed the rounded Y; tests/test_bf16_storage_gpu.py does that
+            out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample)
     return out
 
 
@@ -263,6 +273,8 @@ def main():
     ap.add_argument("--split-row-min", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
     ap.add_argument("--autotune", action="store_true", help="choose the schedule with fusedmm_plan_create_tuned")
+    ap.add_argument("--y-bf16", action="store_true",
+                    help="optional storage mode: gather Y from a bfloat16 copy (not the headline configuration)")
     ap.add_argument("--column-classes", type=int, default=0)
     ap.add_argument("--tile-row-min", type=int, default=0)
     args = ap.parse_args()
@@ -274,7 +286,7 @@ def main():
                    "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
                    "tile_row_min": args.tile_row_min}
     out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
-              args.copy_calibration_mib, args.autotune)
+              args.copy_calibration_mib, args.autotune, args.y_bf16)
     print(json.dumps(out))
 
 

@@ -183,6 +183,20 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                     const float* d_values, const float* d_X, int64_t ldx,
                     const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
 
+/* The same operation with Y stored as bfloat16 (the upper 16 bits of each fp32 value): the
+ * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
+ * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
+ * 8-byte aligned: ldy % 4 == 0).  Only d in {32, 64, 128, 256, 512} with aligned operands
+ * (FUSEDMM_ERR_UNSUPPORTED_DIM / FUSEDMM_ERR_INVALID_ARG otherwise).  The result equals
+ * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back. */
+int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
+                          const float* d_values, const float* d_X, int64_t ldx,
+                          const uint16_t* d_Y_bf16, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
+
+/* d_dst[i] = bfloat16(d_src[i]) for i < count, round to nearest even (device pointers,
+ * asynchronous on `stream`): the storage format fusedmm_execute_bf16y reads. */
+int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* stream);
+
 /* Test hook: run the same schedule and edge indexing as fusedmm_execute would
  * for dimension d (row pointers may be of any alignment class: pass
  * fast_path != 0 to exercise the specialised kernels' indexing, 0 for the

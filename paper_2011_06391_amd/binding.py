@@ -35,7 +35,8 @@ EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
-    "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned",
+    "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
+    "fusedmm_to_bf16",
 )
 
 
@@ -92,6 +93,10 @@ def load():
     lib.fusedmm_plan_stats.argtypes = [vp] + [ctypes.POINTER(i64)] * 8
     lib.fusedmm_execute.restype = ctypes.c_int
     lib.fusedmm_execute.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.fusedmm_execute_bf16y.restype = ctypes.c_int
+    lib.fusedmm_execute_bf16y.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.fusedmm_to_bf16.restype = ctypes.c_int
+    lib.fusedmm_to_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_debug_edge_visits.restype = ctypes.c_int
     lib.fusedmm_debug_edge_visits.argtypes = [vp, i32, i32, vp, vp]
     lib.fusedmm_plan_set_profiling.restype = ctypes.c_int
@@ -195,6 +200,17 @@ def fusedmm_execute(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d
     _check(st, "fusedmm_execute")
 
 
+def fusedmm_execute_bf16y(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d_Y_bf16, ldy: int, d_Z, ldz: int,
+                          stream=None) -> None:
+    st = load().fusedmm_execute_bf16y(plan, ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y_bf16), ldy,
+                                      _dptr(d_Z), ldz, _stream(stream))
+    _check(st, "fusedmm_execute_bf16y")
+
+
+def fusedmm_to_bf16(d_dst, d_src, count: int, stream=None) -> None:
+    _check(load().fusedmm_to_bf16(_dptr(d_dst), _dptr(d_src), count, _stream(stream)), "fusedmm_to_bf16")
+
+
 def fusedmm_debug_edge_visits(plan, d: int, fast_path: bool, d_counts, stream=None) -> None:
     st = load().fusedmm_debug_edge_visits(plan, d, int(fast_path), _dptr(d_counts), _stream(stream))
     _check(st, "fusedmm_debug_edge_visits")
@@ -263,6 +279,16 @@ class Plan:
                 raise TypeError("operands must be CUDA float32 tensors with unit stride along the feature dimension")
         ldx = 0 if X is None else X.stride(0)
         fusedmm_execute(self._plan, ops, d, values, X, ldx, Y, Y.stride(0), Z, Z.stride(0), stream)
+
+    def execute_bf16y(self, ops, X, Y_bf16, Z, values=None, stream=None) -> None:
+        """Y_bf16: CUDA tensor of 2-byte elements (torch.bfloat16, int16 or uint16 bits), n x d."""
+        if isinstance(ops, str):
+            ops = fusedmm_ops_preset(ops)
+        if not (Y_bf16.is_cuda and Y_bf16.element_size() == 2 and Y_bf16.stride(-1) == 1):
+            raise TypeError("Y_bf16 must be a CUDA tensor of 2-byte elements with unit stride along the feature dimension")
+        ldx = 0 if X is None else X.stride(0)
+        fusedmm_execute_bf16y(self._plan, ops, int(Z.shape[1]), values, X, ldx, Y_bf16, Y_bf16.stride(0), Z, Z.stride(0),
+                              stream)
 
     def edge_visits(self, d: int, fast_path: bool, counts, stream=None) -> None:
         fusedmm_debug_edge_visits(self._plan, d, fast_path, counts, stream)

@@ -510,8 +510,12 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
   return FUSEDMM_OK;
 }
 
-int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
-                    int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+namespace {
+
+// Shared body of fusedmm_execute and fusedmm_execute_bf16y.  y_bf16: d_Y points at bfloat16 rows
+// (2 bytes per element, ldy in elements); only the fast instances exist for that storage.
+int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
+                 int64_t ldx, const void* d_Y, bool y_bf16, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
   if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   if (!ops_valid(*ops)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
@@ -524,7 +528,14 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     if (uses_val && !d_values) return FUSEDMM_ERR_INVALID_ARG;
   }
   if (uses_x && (!d_X || ldx < d)) return FUSEDMM_ERR_INVALID_ARG;
-  if (overlaps(d_Z, plan->m, ldz, d_Y, plan->n, ldy, d)) return FUSEDMM_ERR_ALIAS;
+  // Z against Y: compare byte ranges (a bfloat16 row is half as long)
+  {
+    const uintptr_t z0 = reinterpret_cast<uintptr_t>(d_Z);
+    const uintptr_t z1 = z0 + (uintptr_t)((plan->m - 1) * ldz + d) * sizeof(float);
+    const uintptr_t y0 = reinterpret_cast<uintptr_t>(d_Y);
+    const uintptr_t y1 = y0 + (uintptr_t)((plan->n > 0 ? plan->n - 1 : 0) * ldy + d) * (y_bf16 ? 2u : 4u);
+    if (d_Y && plan->n > 0 && z0 < y1 && y0 < z1) return FUSEDMM_ERR_ALIAS;
+  }
   if (uses_x && overlaps(d_Z, plan->m, ldz, d_X, plan->m, ldx, d)) return FUSEDMM_ERR_ALIAS;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
@@ -532,9 +543,11 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
   // structure with the ops decided at run time; odd shapes fall back to the general kernel
   const int recognised = recognise(*ops);
   const int pattern = recognised >= 0 ? recognised : PAT_RUNTIME;
-  const bool fast = is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) &&
-                    (plan->nnz == 0 || (aligned16(d_Y) && ldy % 4 == 0)) &&
+  const bool y_ok = plan->nnz == 0 || (y_bf16 ? ((reinterpret_cast<uintptr_t>(d_Y) & 7u) == 0 && ldy % 4 == 0)
+                                              : (aligned16(d_Y) && ldy % 4 == 0));
+  const bool fast = is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
                     (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
+  if (y_bf16 && !fast) return is_fast_dim(d) ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
   if (plan->profiling && plan->events_used < plan->events.size()) {
@@ -554,14 +567,14 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     a.alpha = ops->alpha;
     a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop; a.aop = ops->aop;
     if (ev0) (void)hipEventRecord(ev0, stream);
-    e = launch_fast(pattern, d, a, stream);
+    e = launch_fast(pattern, d, y_bf16, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored densely with stride d, whatever the scratch capacity is
     if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, d_Z, ldz, stream);
   } else {
     GenericArgs g;
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
-    g.X = d_X; g.Y = d_Y; g.Z = d_Z;
+    g.X = d_X; g.Y = static_cast<const float*>(d_Y); g.Z = d_Z;
     g.ldx = ldx; g.ldy = ldy; g.ldz = ldz;
     g.m = plan->m; g.d = d;
     g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
@@ -572,6 +585,25 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, c
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
   }
   return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+}
+
+}  // namespace
+
+int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
+                    int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, false, ldy, d_Z, ldz, stream_);
+}
+
+int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
+                          const float* d_X, int64_t ldx, const uint16_t* d_Y_bf16, int64_t ldy, float* d_Z, int64_t ldz,
+                          void* stream_) {
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y_bf16, true, ldy, d_Z, ldz, stream_);
+}
+
+int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* stream_) {
+  if (count == 0) return FUSEDMM_OK;
+  if (!d_dst || !d_src) return FUSEDMM_ERR_INVALID_ARG;
+  return launch_to_bf16(d_dst, d_src, count, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }
 
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path, uint32_t* d_counts, void* stream_) {
@@ -590,7 +622,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = 0;
     a.visit_counts = d_counts;
-    e = launch_fast(PAT_VISIT, d, a, stream);
+    e = launch_fast(PAT_VISIT, d, false, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;

@@ -107,6 +107,21 @@ __device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V])
 
 __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
 
+// Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YB = false: Y is fp32, one
+// 16-byte load.  YB = true: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
+// load widened by shifts; the arithmetic stays fp32.
+template <bool YB>
+__device__ __forceinline__ v4f gather4(const void* Y, int64_t col, int64_t ldy, int piece) {
+  if constexpr (YB) {
+    typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+    const v2u raw = *reinterpret_cast<const v2u*>(static_cast<const uint16_t*>(Y) + col * ldy + 4 * piece);
+    return v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
+               __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
+  } else {
+    return ld4(static_cast<const float*>(Y) + col * ldy + 4 * piece);
+  }
+}
+
 // Loads of data that is read once (column indices, edge values, x_u).  A non-temporal hint
 // on them was measured: -1 % kernel time on the two largest workloads, +3..10 % on the two
 // where X aliases Y (x_u is then also somebody's y_v), so it is off.
@@ -266,7 +281,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 // One wavefront accumulates the stored entries [e0, e1) of a single row.  The S lane groups
 // take entries round-robin inside batches of 64; z holds this group's partial sum.
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int G, int U>
+template <int P, int D, int G, int U, bool YB>
 __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
                                                 const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int lane) {
   constexpr int V = D / (4 * G);
@@ -275,7 +290,6 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   using T = PatTraits<P>;
   const int slot = lane / G;
   const int g = lane % G;
-  const float* ybase = a.Y + 4 * g;
   const bool use_val = reads_values<P>(a);
 
   for (int64_t base = e0; base < e1; base += 64) {
@@ -301,9 +315,8 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         if constexpr (T::loads_y) {
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            const float* yr = ybase + (int64_t)c[u] * a.ldy;
 #pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * G * i);
+            for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + G * i);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z);
@@ -327,9 +340,8 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
             if (ok[u]) {
-              const float* yr = ybase + (int64_t)c[u] * a.ldy;
 #pragma unroll
-              for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * G * i);
+              for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + G * i);
             }
           }
 #pragma unroll
@@ -379,7 +391,7 @@ __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / 
 // and then runs one of three bodies: chunk, wave segments, packed segments.  A segment is
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int GW, int UW, int GP, int UP>
+template <int P, int D, int GW, int UW, int GP, int UP, bool YB>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   using T = PatTraits<P>;
   const int lane = threadIdx.x & 63;
@@ -414,7 +426,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     v4f x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW>(a, ch.row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
+    wave_accumulate<P, D, GW, UW, YB>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if (lane < GW) {
@@ -458,7 +470,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     v4f x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW>(a, row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW>(a, e0, e1, x, z, lane);
+    wave_accumulate<P, D, GW, UW, YB>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if (lane < GW) store_row<D, GW>(dst, g, z);
@@ -470,7 +482,6 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     static_assert(GP % UP == 0, "packed unroll must divide the lane-group size");
     const int slot = lane / GP;
     const int g = lane % GP;
-    const float* ybase = a.Y + 4 * g;
     const bool use_val = reads_values<P>(a);
     for (int round = 0; round < count; round += kWavesPerBlock * S) {
       const int idx = round + wave * S + slot;
@@ -527,9 +538,8 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
 #pragma unroll
               for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
               if (ok[u]) {
-                const float* yr = ybase + (int64_t)c[u] * a.ldy;
 #pragma unroll
-                for (int i = 0; i < V; ++i) y[u][i] = ld4(yr + 4 * GP * i);
+                for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + GP * i);
               }
             }
 #pragma unroll

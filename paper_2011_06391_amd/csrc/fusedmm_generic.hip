@@ -230,7 +230,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
-  hipError_t launch_fast_d##D(int pattern, const KernelArgs& a, hipStream_t stream); \
+  hipError_t launch_fast_d##D(int pattern, bool y_bf16, const KernelArgs& a, hipStream_t stream); \
   int packed_rows_per_block_d##D();
 FMM_DECL(32) FMM_DECL(64) FMM_DECL(128) FMM_DECL(256) FMM_DECL(512)
 #undef FMM_DECL
@@ -246,15 +246,34 @@ int packed_rows_per_block(int d) {
   }
 }
 
-hipError_t launch_fast(int pattern, int d, const KernelArgs& a, hipStream_t stream) {
+hipError_t launch_fast(int pattern, int d, bool y_bf16, const KernelArgs& a, hipStream_t stream) {
   switch (d) {
-    case 32: return launch_fast_d32(pattern, a, stream);
-    case 64: return launch_fast_d64(pattern, a, stream);
-    case 128: return launch_fast_d128(pattern, a, stream);
-    case 256: return launch_fast_d256(pattern, a, stream);
-    case 512: return launch_fast_d512(pattern, a, stream);
+    case 32: return launch_fast_d32(pattern, y_bf16, a, stream);
+    case 64: return launch_fast_d64(pattern, y_bf16, a, stream);
+    case 128: return launch_fast_d128(pattern, y_bf16, a, stream);
+    case 256: return launch_fast_d256(pattern, y_bf16, a, stream);
+    case 512: return launch_fast_d512(pattern, y_bf16, a, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+// fp32 -> bfloat16, round to nearest even on the discarded 16 bits; a NaN keeps a set mantissa bit.
+__global__ __launch_bounds__(256) void to_bf16_kernel(uint16_t* dst, const float* src, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, src[i]);
+    uint32_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) r = (u >> 16) | 0x0040u;  // NaN
+    else r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    dst[i] = (uint16_t)r;
+  }
+}
+
+hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(to_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dst, src, count);
+  return hipGetLastError();
 }
 
 }  // namespace fmm
