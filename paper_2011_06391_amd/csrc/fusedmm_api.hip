@@ -32,8 +32,8 @@ struct fusedmm_plan {
 
 namespace {
 
-constexpr int32_t kDefaultSmallRowMax = 32;
-constexpr int32_t kDefaultSplitRowMin = 256;
+constexpr int32_t kDefaultSmallRowMax = 64;
+constexpr int32_t kDefaultSplitRowMin = 512;
 constexpr int32_t kDefaultChunkEdges = 1024;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
 // dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB); the finest
