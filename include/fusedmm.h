@@ -105,9 +105,9 @@ typedef enum {
 /* Scheduling knobs of the degree-binned plan (the GPU counterpart of the
  * nnz-balanced 1-D partition, Section III-C).  Zero fields take defaults. */
 typedef struct fusedmm_plan_options {
-  int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront */
-  int32_t split_row_min;   /* rows with  > this many entries get whole workgroups */
-  int32_t chunk_edges;     /* entries per workgroup chunk of a split row */
+  int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront (default 64) */
+  int32_t split_row_min;   /* rows with  > this many entries get whole workgroups (default 512) */
+  int32_t chunk_edges;     /* entries per workgroup chunk of a split row (default 1024) */
   int32_t column_classes;  /* long rows are cut by contiguous column ranges ("classes") into tiles and
                               all tiles of a class run on one XCD, so that its slice of Y stays in that
                               XCD's L2.  This is the finest number of classes (8, 16, 32, ... up to 512,
