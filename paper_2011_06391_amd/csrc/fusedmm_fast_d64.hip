@@ -1,10 +1,10 @@
-// Specialised FusedMM kernels for d = 64: lane groups of 16 lanes (unroll 8) for wave rows and
+// Specialised FusedMM kernels for d = 64: lane groups of 16 lanes (unroll 4) for wave rows and
 // chunks, lane groups of 8 lanes (unroll 4) for packed short rows.  The four tuning
 // values can be overridden on the compiler command line when sweeping.
 #define FMM_D 64
 #ifndef FMM_GW
 #define FMM_GW 16
-#define FMM_UW 8
+#define FMM_UW 4
 #define FMM_GP 8
 #define FMM_UP 4
 #endif
