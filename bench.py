@@ -154,6 +154,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     if kernel_ms <= 0.0:  # a kernel of a few microseconds can vanish in the bracket's own jitter
         kernel_ms = kernel_ms_sum / max(1, calls)
     achieved = tr.model_bytes / (kernel_ms * 1e-3) / 1e9
+    traffic_bytes = None if (y_bf16 or autotune or d or custom_plan) else MEASURED_TRAFFIC_BYTES.get(workload)
     out = {
         "metric": "fused SDDMM-SpMM throughput: G(edge*dim)/s + achieved HBM GB/s vs peak, 1 GPU",
         "value": g.nnz * w.d / (ms_per_step * 1e-3) / 1e9,
@@ -167,7 +168,10 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                    "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / model.MI355X_HBM_PEAK_GBS,
-                     "traffic": None if (y_bf16 or autotune or d or custom_plan) else MEASURED_TRAFFIC_BYTES.get(workload),
+                     "traffic": traffic_bytes,
+                     "traffic_GBs": None if traffic_bytes is None else traffic_bytes / (kernel_ms * 1e-3) / 1e9,
+                     "traffic_frac_of_peak": None if traffic_bytes is None
+                     else traffic_bytes / (kernel_ms * 1e-3) / 1e9 / model.MI355X_HBM_PEAK_GBS,
                      "kernel": "fusedmm_fast_kernel", "kernel_ms": kernel_ms,
                      "kernel_timing": "HIP events around the main kernel on the launch stream, same K executes repeated "
                                       "right after the timed region; an empty event bracket per call is subtracted",
