@@ -27,7 +27,7 @@ VOP = {"MUL": 0, "SEL2ND": 1, "SUB": 2, "ADD": 3}
 ROP = {"NOOP": 0, "RSUM": 1, "SUMSQ": 2, "NORM": 3, "RMUL": 4}
 SOP = {"EDGE_VALUE": 0, "SIGMOID": 1, "ONE_MINUS_SIGMOID": 2, "INV1P": 3, "SCAL": 4, "NOOP": 5}
 MOP = {"MUL_Y": 0, "MUL_T": 1, "SEL2ND": 2}
-AOP = {"ASUM": 0, "AMAX": 1, "AMIN": 2}
+AOP = {"ASUM": 0, "AMAX": 1, "AMIN": 2, "AMEAN": 3}
 
 # (VOP, ROP, SOP, MOP) of the application patterns; AOP is always ASUM.
 # Table III rows 1-3 and the t-distribution pattern of the author notes.
@@ -116,9 +116,9 @@ def unfused(rowptr, colidx, values, X, Y, ops, alpha: float = 1.0, precision: st
 def unfused_general(rowptr, colidx, values, X, Y, ops, aop: str = "ASUM", alpha: float = 1.0):
     """The general five-step path (all operations of Table II), two phases, fp64.
 
-    ``ops`` = (VOP, ROP, SOP, MOP) names, ``aop`` in ASUM / AMAX / AMIN.  Returns (Z, S, H);
+    ``ops`` = (VOP, ROP, SOP, MOP) names, ``aop`` in ASUM / AMAX / AMIN / AMEAN.  Returns (Z, S, H);
     H is nnz scalars, or nnz x d when the message is a vector (ROP is NOOP and SOP is not
-    EDGE_VALUE).  S is sum|w| for ASUM and max|w| for AMAX / AMIN.
+    EDGE_VALUE).  S is sum|w| for ASUM, max|w| for AMAX / AMIN and mean|w| for AMEAN.
     """
     rowptr, colidx, values, X, Y = _prep(rowptr, colidx, values, X, Y)
     v, r, s_, mo = ops

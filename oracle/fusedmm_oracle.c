@@ -228,18 +228,22 @@ int FN(fmm_oracle_update_u_all)(int64_t m, int64_t d, const int64_t* rowptr, con
  *        Fig. 3: messages can be vectors); MOP is then element-wise h (.) operand
  *   MOP  SEL2ND (w = y_v, the second operand)          Table II "SEL2ND ... VOP, MOP"
  *   AOP  AMAX / AMIN                                   Table II "AMAX" (AMIN: its mirror image)
+ *   AOP  AMEAN                                         Section III-B, GCN paragraph: mean pooling
  * Reading for AMAX/AMIN: Algorithm 1 sets z_u to 0 before the loop and AOP combines z_u with
  * every message, so the result is max(0, max_v w) (resp. min(0, min_v w)); a row without
  * entries yields 0.
+ * Reading for AMEAN: the messages of a row are summed as with ASUM and the sum is divided by
+ * the number of stored entries of the row; a row without entries yields 0.
  * H holds one real per stored entry when h is a scalar and d reals per stored entry when it
  * is a vector: the unfused pipeline's sparse tensor.
- * S (comparison denominator) is the sum of |w| for ASUM and the largest |w| for AMAX/AMIN.
+ * S (comparison denominator) is the sum of |w| for ASUM, the largest |w| for AMAX/AMIN and
+ * the mean of |w| for AMEAN.
  * ------------------------------------------------------------------------------------------ */
 enum { O_VOP_ADD = 3 };
 enum { O_ROP_RMUL = 4 };
 enum { O_SOP_NOOP = 5 };
 enum { O_MOP_SEL2ND = 2 };
-enum { O_AOP_SUM = 0, O_AOP_MAX = 1, O_AOP_MIN = 2 };
+enum { O_AOP_SUM = 0, O_AOP_MAX = 1, O_AOP_MIN = 2, O_AOP_MEAN = 3 };
 
 static inline real g_vop(int vop, real x, real y) {
   switch (vop) {
@@ -312,12 +316,16 @@ int FN(fmm_oracle_spmm_general)(int64_t m, int64_t d, const int64_t* rowptr, con
         else w = h * g_vop(vop, X ? (real)X[u * ldx + k] : 0, (real)yv[k]);
         real* z = &Z[u * d + k];
         const real aw = (real)fabs((double)w);
-        if (aop == O_AOP_SUM) { *z += w; if (S) S[u * d + k] += aw; }
+        if (aop == O_AOP_SUM || aop == O_AOP_MEAN) { *z += w; if (S) S[u * d + k] += aw; }
         else {
           if (aop == O_AOP_MAX) { if (w > *z) *z = w; } else { if (w < *z) *z = w; }
           if (S && aw > S[u * d + k]) S[u * d + k] = aw;
         }
       }
+    }
+    const int64_t deg = rowptr[u + 1] - rowptr[u];
+    if (aop == O_AOP_MEAN && deg > 0) {
+      for (int64_t k = 0; k < d; ++k) { Z[u * d + k] /= (real)deg; if (S) S[u * d + k] /= (real)deg; }
     }
   }
   return 0;

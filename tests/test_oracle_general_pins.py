@@ -116,3 +116,46 @@ def test_scalar_pattern_wrapper_rejects_general_ops(problem):
         oracle.unfused(rowptr, colidx, None, X, Y, ("ADD", "RSUM", "SIGMOID", "MUL_Y"))
     with pytest.raises(ValueError):
         oracle.unfused(rowptr, colidx, None, X, Y, ("MUL", "NOOP", "SIGMOID", "MUL_Y"))
+
+
+def test_mean_pooling_is_the_row_normalised_product(problem):
+    """SEL2ND, NOOP, EDGE_VALUE, MUL, AMEAN with unit edge values: z_u is the mean of the
+    neighbours' feature rows, i.e. D^-1 A Y through scipy's sparse product; a row without
+    stored entries gives 0 (Section III-B: GCN variants pool by mean instead of sum)."""
+    import scipy.sparse as sp
+    m, n, d, rowptr, colidx, X, Y, vals = problem
+    ones = np.ones(len(colidx), dtype=np.float32)
+    A = sp.csr_matrix((ones.astype(np.float64), colidx, rowptr), shape=(m, n))
+    deg = np.diff(rowptr)
+    inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0)
+    ref = sp.diags(inv) @ (A @ Y.astype(np.float64))
+    Z, S, _ = oracle.unfused_general(rowptr, colidx, ones, None, Y, ("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMEAN")
+    np.testing.assert_allclose(Z, ref, rtol=1e-13, atol=1e-15)
+    assert (Z[[0, 11]] == 0).all() and (S[[0, 11]] == 0).all()
+    np.testing.assert_allclose(S, sp.diags(inv) @ (A @ np.abs(Y.astype(np.float64))), rtol=1e-13, atol=1e-15)
+
+
+def test_mean_of_identical_messages_is_the_message(rng):
+    """If every neighbour carries the same feature row c, the mean is c whatever the degree:
+    a missing or misplaced division by the row length cannot pass."""
+    m, n, d = 12, 40, 5
+    rowptr, colidx = random_csr(rng, m, n, 0.4, empty_rows=(3,))
+    c = rng.uniform(-2, 2, d).astype(np.float32)
+    Y = np.tile(c, (n, 1))
+    Z, _, _ = oracle.unfused_general(rowptr, colidx, None, None, Y, ("SEL2ND", "NOOP", "NOOP", "SEL2ND"), "AMEAN")
+    deg = np.diff(rowptr)
+    assert len(set(deg[deg > 0])) > 3
+    np.testing.assert_allclose(Z[deg > 0], np.tile(c.astype(np.float64), ((deg > 0).sum(), 1)), rtol=1e-14)
+    assert (Z[3] == 0).all()
+
+
+def test_mean_is_sum_over_degree_for_a_nonlinear_tuple(problem):
+    """AMEAN of the sigmoid-embedding messages equals the pinned ASUM result divided by the
+    row lengths (dense numpy reference for the sum)."""
+    m, n, d, rowptr, colidx, X, Y, vals = problem
+    A = dense_mask(rowptr, colidx, m, n)
+    X64, Y64 = X.astype(np.float64), Y.astype(np.float64)
+    ref_sum = (A * sigmoid(X64 @ Y64.T)) @ Y64
+    deg = np.diff(rowptr)
+    Z, _, _ = oracle.unfused_general(rowptr, colidx, None, X, Y, ("MUL", "RSUM", "SIGMOID", "MUL_Y"), "AMEAN")
+    np.testing.assert_allclose(Z[deg > 0], ref_sum[deg > 0] / deg[deg > 0, None], rtol=1e-12, atol=1e-14)
