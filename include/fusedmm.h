@@ -80,8 +80,9 @@ typedef enum {
 /* Step 4, MOP(h, .) -> w (step 4): h (.) y_v, h (.) t with t the VOP output, or y_v itself (SEL2ND). */
 typedef enum { FUSEDMM_MOP_MUL_Y = 0, FUSEDMM_MOP_MUL_T = 1, FUSEDMM_MOP_SEL2ND = 2 } fusedmm_mop;
 /* Step 5, AOP(z_u, w) (step 5; Table II ASUM, AMAX).  z_u starts at 0 (Algorithm 1), so MAX yields
- * max(0, max_v w) and MIN yields min(0, min_v w); rows without entries give 0. */
-typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2 } fusedmm_aop;
+ * max(0, max_v w) and MIN yields min(0, min_v w); rows without entries give 0.  MEAN (the mean
+ * pooling of Section III-B's GCN variants) is the SUM divided by the row's number of stored entries. */
+typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FUSEDMM_AOP_MEAN = 3 } fusedmm_aop;
 
 /* The op selector.  Every combination of the values above is valid except that
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).

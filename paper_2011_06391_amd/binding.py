@@ -28,7 +28,7 @@ VOP = {"MUL": 0, "SEL2ND": 1, "SUB": 2, "ADD": 3}
 ROP = {"NOOP": 0, "RSUM": 1, "SUMSQ": 2, "NORM2": 3, "RMUL": 4}
 SOP = {"EDGE_VALUE": 0, "SIGMOID": 1, "ONE_MINUS_SIGMOID": 2, "INV_1P": 3, "SCAL": 4, "NOOP": 5}
 MOP = {"MUL_Y": 0, "MUL_T": 1, "SEL2ND": 2}
-AOP = {"SUM": 0, "MAX": 1, "MIN": 2}
+AOP = {"SUM": 0, "MAX": 1, "MIN": 2, "MEAN": 3}
 PATTERN = {"sigmoid": 0, "one_minus_sigmoid": 1, "gcn": 2, "tdist": 3, "fr": 4}
 
 EXPORTS = (

@@ -53,7 +53,7 @@ bool ops_valid(const fusedmm_ops_t& o) {
   if (o.rop < FUSEDMM_ROP_NOOP || o.rop > FUSEDMM_ROP_RMUL) return false;
   if (o.sop < FUSEDMM_SOP_EDGE_VALUE || o.sop > FUSEDMM_SOP_NOOP) return false;
   if (o.mop < FUSEDMM_MOP_MUL_Y || o.mop > FUSEDMM_MOP_SEL2ND) return false;
-  if (o.aop < FUSEDMM_AOP_SUM || o.aop > FUSEDMM_AOP_MIN) return false;
+  if (o.aop < FUSEDMM_AOP_SUM || o.aop > FUSEDMM_AOP_MEAN) return false;
   return o.sop != FUSEDMM_SOP_EDGE_VALUE || o.rop == FUSEDMM_ROP_NOOP;
 }
 
@@ -565,12 +565,14 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
-    a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop; a.aop = ops->aop;
+    a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop;
+    a.mean = ops->aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
+    a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_fast(pattern, d, y_bf16, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored densely with stride d, whatever the scratch capacity is
-    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, d_Z, ldz, stream);
+    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
   } else {
     GenericArgs g;
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
@@ -620,7 +622,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
-    a.vop = a.rop = a.sop = a.mop = a.aop = 0;
+    a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.visit_counts = d_counts;
     e = launch_fast(PAT_VISIT, d, false, a, stream);
   } else {

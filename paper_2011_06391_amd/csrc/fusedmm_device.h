@@ -369,6 +369,12 @@ __device__ __forceinline__ void zero(v4f (&z)[V]) {
   for (int i = 0; i < V; ++i) z[i] = v4f{0.f, 0.f, 0.f, 0.f};
 }
 
+template <int V>
+__device__ __forceinline__ void scale(v4f (&z)[V], float f) {
+#pragma unroll
+  for (int i = 0; i < V; ++i) z[i] *= f;
+}
+
 template <int D, int G>
 __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / (4 * G)]) {
 #pragma unroll
@@ -446,6 +452,9 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
             s += o;
           }
         }
+        if constexpr (P == PAT_RUNTIME) {
+          if (a.mean && ch.part < 0) s *= 1.0f / (float)ch.e_count;  // the chunk is the whole row
+        }
         float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * D;
         __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * threadIdx.x));
       }
@@ -473,6 +482,9 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     wave_accumulate<P, D, GW, UW, YB>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
+      if constexpr (P == PAT_RUNTIME) {
+        if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
+      }
       if (lane < GW) store_row<D, GW>(dst, g, z);
     }
   } else if (kind == kItemPacked) {
@@ -552,6 +564,9 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         }
       }
       if constexpr (T::loads_y) {
+        if constexpr (P == PAT_RUNTIME) {
+          if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
+        }
         if (has_seg) store_row<D, GP>(dst, g, z);
       }
     }

@@ -43,7 +43,7 @@ __device__ __forceinline__ float sop_apply(int sop, float s, float alpha) {
 // row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
 // Covers every op of Table II: scalar messages (after a reduction, or the edge value) and
 // vector messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation
-// from a zero-initialised z_u.
+// from a zero-initialised z_u, and MEAN (the sum divided by the row length).
 constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
 
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgs a) {
@@ -91,17 +91,18 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
         if (a.mop == FUSEDMM_MOP_SEL2ND) w = y;
         else if (a.mop == FUSEDMM_MOP_MUL_Y) w = hk * y;
         else w = hk * t;
-        if (a.aop == FUSEDMM_AOP_SUM) acc[i] += w;                       // AOP
+        if (a.aop == FUSEDMM_AOP_SUM || a.aop == FUSEDMM_AOP_MEAN) acc[i] += w;  // AOP
         else if (a.aop == FUSEDMM_AOP_MAX) acc[i] = fmaxf(acc[i], w);
         else acc[i] = fminf(acc[i], w);
       }
     }
   }
   float* zr = a.Z + row * a.ldz;
+  const float post = (a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? 1.0f / (float)(e1 - e0) : 1.0f;  // mean pooling
 #pragma unroll
   for (int i = 0; i < kGenericAcc; ++i) {
     const int k = lane + 64 * i;
-    if (k < d) zr[k] = acc[i];
+    if (k < d) zr[k] = acc[i] * post;
   }
 }
 
@@ -116,14 +117,14 @@ hipError_t launch_generic(const GenericArgs& a, hipStream_t stream) {
 // A workgroup covers 256 / (d/4) rows; a thread owns one 16-byte column of one row and keeps
 // eight partial-row loads in flight.
 __device__ __forceinline__ v4f merge_two(int aop, v4f s, v4f t) {
-  if (aop == FUSEDMM_AOP_SUM) return s + t;
+  if (aop == FUSEDMM_AOP_SUM || aop == FUSEDMM_AOP_MEAN) return s + t;
   if (aop == FUSEDMM_AOP_MAX) return v4f{fmaxf(s.x, t.x), fmaxf(s.y, t.y), fmaxf(s.z, t.z), fmaxf(s.w, t.w)};
   return v4f{fminf(s.x, t.x), fminf(s.y, t.y), fminf(s.z, t.z), fminf(s.w, t.w)};
 }
 
 __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
-                                                           const float* partials, int32_t d, int32_t aop, float* Z,
-                                                           int64_t ldz) {
+                                                           const float* partials, int32_t d, int32_t aop,
+                                                           const int64_t* rowptr, float* Z, int64_t ldz) {
   const int cols = d >> 2;
   const int rows_per_block = 256 / cols;
   const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
@@ -142,16 +143,17 @@ __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* mer
   }
   for (; p < md.n_parts; ++p)
     s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * d)));
+  if (aop == FUSEDMM_AOP_MEAN) s *= 1.0f / (float)(rowptr[md.row + 1] - rowptr[md.row]);  // split rows are never empty
   __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(Z + (int64_t)md.row * ldz + 4 * c));
 }
 
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
-                        float* Z, int64_t ldz, hipStream_t stream) {
+                        const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
   const int rows_per_block = 256 / (d >> 2);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
-                     aop, Z, ldz);
+                     aop, rowptr, Z, ldz);
   return hipGetLastError();
 }
 

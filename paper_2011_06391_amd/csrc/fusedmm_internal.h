@@ -52,7 +52,8 @@ struct KernelArgs {
   float* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
-  int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only
+  int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only; aop is SUM, MAX or MIN here
+  int32_t mean;                     // PAT_RUNTIME: a row stored whole is divided by its length (mean pooling)
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
   // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed).
   const int32_t* order;
@@ -100,9 +101,10 @@ struct GenericArgs {
 };
 hipError_t launch_generic(const GenericArgs& a, hipStream_t stream);
 
-// aop: FUSEDMM_AOP_SUM / MAX / MIN, how partial rows are combined
+// aop: FUSEDMM_AOP_SUM / MAX / MIN, how partial rows are combined; FUSEDMM_AOP_MEAN: summed, then
+// divided by the row's length taken from rowptr
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
-                        float* Z, int64_t ldz, hipStream_t stream);
+                        const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
 
 // flag[0] |= 1 if any colidx entry is outside [0, n).
 hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag, hipStream_t stream);

@@ -20,6 +20,8 @@ TUPLES = [
     (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MAX", ("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMAX"),
     (("SUB", "NOOP", "SIGMOID", "MUL_T"), "MIN", ("SUB", "NOOP", "SIGMOID", "MUL_T"), "AMIN"),
     (("ADD", "SUMSQ", "INV_1P", "SEL2ND"), "MAX", ("ADD", "SUMSQ", "INV1P", "SEL2ND"), "AMAX"),
+    (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MEAN", ("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMEAN"),
+    (("MUL", "RSUM", "SIGMOID", "MUL_Y"), "MEAN", ("MUL", "RSUM", "SIGMOID", "MUL_Y"), "AMEAN"),
 ]
 
 
