@@ -202,3 +202,52 @@ def compare(Z_test: np.ndarray, Z_ref: np.ndarray, S: np.ndarray):
         return float("inf"), int(np.argmax(~np.isfinite(Zt))), viol
     am = int(np.argmax(rel))
     return float(rel.flat[am]), am, viol
+
+
+# --------------------------------------------------------------------------- #
+# minibatch embedding epoch (the end-to-end experiment of Section V, Table VIII)
+# --------------------------------------------------------------------------- #
+
+def embedding_epoch(rowptr, colidx, X0, batch_rows: int, negatives, lr: float):
+    """One epoch of minibatch graph embedding built from two FusedMM calls per batch.
+
+    The paper's end-to-end experiment (Section V, Table VIII: d = 128, batches of 256 vertices)
+    trains an embedding with the sigmoid pattern of Table III but does not print the update
+    rule; minibatching is left to the application (Section III-C).  The reading taken here, for
+    batch B_i = rows [i*batch_rows, (i+1)*batch_rows) of the square adjacency matrix, in order:
+
+        Zpos = FusedMM(A[B_i, :], X[B_i], X)   with (MUL, RSUM, 1-SIGMOID, MUL, ASUM)
+        Zneg = FusedMM(N_i,       X[B_i], X)   with (MUL, RSUM,   SIGMOID, MUL, ASUM)
+        X[B_i] <- X[B_i] + lr * (Zpos - Zneg)
+
+    where N_i is the |B_i| x n pattern whose every row holds the batch's negative samples
+    ``negatives[i]`` (shared by the rows of a batch).  This is one ascent step, with respect to
+    the batch's own rows, on  sum_{v in N(u)} log sigma(x_u.x_v) + sum_{w in neg} log(1 - sigma(x_u.x_w)).
+    The embedding is stored in fp32 (the paper's storage type): both FusedMM calls of a batch read
+    the matrix as the batches before it left it, the update is computed in double and rounded to
+    fp32 once per batch.  Returns (X, S): the embedding after the epoch (float32) and, per
+    element, lr * (sum of |terms| of both calls), the scale its rounding error is measured on.
+    """
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    negatives = np.ascontiguousarray(negatives, dtype=np.int32)
+    X = np.array(X0, dtype=np.float32, copy=True)
+    n, d = X.shape
+    assert len(rowptr) == n + 1, "square adjacency matrix expected"
+    n_batches = (n + batch_rows - 1) // batch_rows
+    assert negatives.shape[0] == n_batches
+    s = negatives.shape[1]
+    S = np.zeros((n, d), dtype=np.float64)
+    for i in range(n_batches):
+        b0, b1 = i * batch_rows, min(n, (i + 1) * batch_rows)
+        rows = b1 - b0
+        rp = rowptr[b0:b1 + 1] - rowptr[b0]
+        ci = colidx[rowptr[b0]:rowptr[b1]]
+        Xb = X[b0:b1].copy()
+        Zpos, Spos, _ = unfused(rp, ci, None, Xb, X, "one_minus_sigmoid")
+        nrp = np.arange(rows + 1, dtype=np.int64) * s
+        nci = np.tile(negatives[i], rows)
+        Zneg, Sneg, _ = unfused(nrp, nci, None, Xb, X, "sigmoid")
+        X[b0:b1] = (Xb.astype(np.float64) + lr * (Zpos - Zneg)).astype(np.float32)
+        S[b0:b1] = lr * (Spos + Sneg)
+    return X, S
