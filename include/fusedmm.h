@@ -227,6 +227,40 @@ int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* strea
 /* Free the plan and everything it owns. */
 int fusedmm_plan_destroy(fusedmm_plan_t* plan);
 
+/* ---------------------------------------------------------------------------------------------
+ * Minibatch embedding epoch: the end-to-end training experiment of Section V (Table VIII: d = 128,
+ * batches of 256 vertices, sigmoid embedding pattern of Table III).  A minibatch is a rectangular
+ * slice A[B, :] of the adjacency matrix (Section III, Fig. 2); forming the batches is the
+ * application's job (Section III-C), which is what this layer does.  The paper does not print the
+ * update rule; the one implemented, for batch i = rows [i*batch_rows, min(n, (i+1)*batch_rows)) of
+ * a square n x n pattern, batches in order, X being both operand matrices:
+ *     Zpos = FusedMM(A[B_i, :], X[B_i], X)  with (MUL, RSUM, 1-SIGMOID, MUL, SUM)
+ *     Zneg = FusedMM(N_i,       X[B_i], X)  with (MUL, RSUM,   SIGMOID, MUL, SUM)
+ *     X[B_i] <- X[B_i] + lr * (Zpos - Zneg)
+ * N_i is the |B_i| x n pattern whose every row holds the n_negative sample columns of batch i.
+ * Both calls of a batch read X as the earlier batches left it; the rows of the batch are written
+ * after both have finished (stream order), so results do not depend on scheduling.
+ *
+ * create : d_rowptr (n+1 int64, device), d_colidx (nnz int32, device) as for fusedmm_plan_create and
+ *          borrowed for the life of the handle; d_negatives: device, n_batches * n_negative int32,
+ *          batch-major, read once here (copied), may be NULL when n_negative == 0.  Builds two plans
+ *          per batch; synchronises the stream.  Samples outside [0, n) -> FUSEDMM_ERR_INVALID_ARG.
+ * reserve: allocates the two batch_rows x d result buffers and the plans' scratch for dimension d,
+ *          so that fusedmm_minibatch_epoch allocates nothing afterwards (e.g. under stream capture).
+ * epoch  : one pass over all batches, asynchronous on `stream`, in place on d_X (n rows, leading
+ *          dimension ldx >= d).  Any 1 <= d <= FUSEDMM_MAX_D; d in {32,...,512} with 16-byte aligned
+ *          rows runs the specialised kernels.  Overlapping epochs on one handle must be on one stream.
+ * info   : number of batches and of kernel launches one epoch issues (host pointers, may be NULL).
+ * Errors as elsewhere: a status is returned and nothing is launched for the failing batch. */
+typedef struct fusedmm_minibatch fusedmm_minibatch_t;
+int fusedmm_minibatch_create(fusedmm_minibatch_t** out, int64_t n, int64_t nnz, const int64_t* d_rowptr,
+                             const int32_t* d_colidx, int32_t batch_rows, int32_t n_negative,
+                             const int32_t* d_negatives, void* stream);
+int fusedmm_minibatch_reserve(fusedmm_minibatch_t* mb, int32_t d);
+int fusedmm_minibatch_epoch(fusedmm_minibatch_t* mb, int32_t d, float lr, float* d_X, int64_t ldx, void* stream);
+int fusedmm_minibatch_info(const fusedmm_minibatch_t* mb, int32_t* n_batches, int64_t* launches_per_epoch);
+int fusedmm_minibatch_destroy(fusedmm_minibatch_t* mb);
+
 #ifdef __cplusplus
 }
 #endif

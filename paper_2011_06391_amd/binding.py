@@ -36,7 +36,8 @@ EXPORTS = (
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
     "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
-    "fusedmm_to_bf16",
+    "fusedmm_to_bf16", "fusedmm_minibatch_create", "fusedmm_minibatch_reserve", "fusedmm_minibatch_epoch",
+    "fusedmm_minibatch_info", "fusedmm_minibatch_destroy",
 )
 
 
@@ -108,6 +109,16 @@ def load():
     lib.fusedmm_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_plan_destroy.restype = ctypes.c_int
     lib.fusedmm_plan_destroy.argtypes = [vp]
+    lib.fusedmm_minibatch_create.restype = ctypes.c_int
+    lib.fusedmm_minibatch_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, vp, i32, i32, vp, vp]
+    lib.fusedmm_minibatch_reserve.restype = ctypes.c_int
+    lib.fusedmm_minibatch_reserve.argtypes = [vp, i32]
+    lib.fusedmm_minibatch_epoch.restype = ctypes.c_int
+    lib.fusedmm_minibatch_epoch.argtypes = [vp, i32, ctypes.c_float, vp, i64, vp]
+    lib.fusedmm_minibatch_info.restype = ctypes.c_int
+    lib.fusedmm_minibatch_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i64)]
+    lib.fusedmm_minibatch_destroy.restype = ctypes.c_int
+    lib.fusedmm_minibatch_destroy.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -236,6 +247,33 @@ def fusedmm_plan_destroy(plan) -> None:
     _check(load().fusedmm_plan_destroy(plan), "fusedmm_plan_destroy")
 
 
+def fusedmm_minibatch_create(n: int, nnz: int, d_rowptr, d_colidx, batch_rows: int, n_negative: int, d_negatives,
+                             stream=None) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    _check(load().fusedmm_minibatch_create(ctypes.byref(h), n, nnz, _dptr(d_rowptr), _dptr(d_colidx), batch_rows,
+                                           n_negative, _dptr(d_negatives), _stream(stream)), "fusedmm_minibatch_create")
+    return h
+
+
+def fusedmm_minibatch_reserve(mb, d: int) -> None:
+    _check(load().fusedmm_minibatch_reserve(mb, d), "fusedmm_minibatch_reserve")
+
+
+def fusedmm_minibatch_epoch(mb, d: int, lr: float, d_X, ldx: int, stream=None) -> None:
+    _check(load().fusedmm_minibatch_epoch(mb, d, ctypes.c_float(lr), _dptr(d_X), ldx, _stream(stream)),
+           "fusedmm_minibatch_epoch")
+
+
+def fusedmm_minibatch_info(mb):
+    nb, launches = ctypes.c_int32(), ctypes.c_int64()
+    _check(load().fusedmm_minibatch_info(mb, ctypes.byref(nb), ctypes.byref(launches)), "fusedmm_minibatch_info")
+    return {"n_batches": nb.value, "launches_per_epoch": launches.value}
+
+
+def fusedmm_minibatch_destroy(mb) -> None:
+    _check(load().fusedmm_minibatch_destroy(mb), "fusedmm_minibatch_destroy")
+
+
 # ---- convenience wrapper (still marshalling only) ----------------------------
 
 def _check_csr(rowptr, colidx) -> None:
@@ -312,6 +350,48 @@ class Plan:
         if self._plan is not None:
             fusedmm_plan_destroy(self._plan)
             self._plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Minibatch:
+    """Owns a fusedmm_minibatch_t: the per-batch plans of one graph for embedding epochs."""
+
+    def __init__(self, n: int, rowptr, colidx, batch_rows: int, negatives=None, stream=None):
+        _check_csr(rowptr, colidx)
+        self.n, self.nnz = int(n), int(colidx.numel())
+        self.rowptr, self.colidx = rowptr, colidx  # keep alive: the plans borrow them
+        n_negative = 0
+        if negatives is not None:
+            if not (negatives.is_cuda and str(negatives.dtype) == "torch.int32" and negatives.is_contiguous()
+                    and negatives.dim() == 2):
+                raise TypeError("negatives must be a contiguous CUDA int32 tensor of shape (n_batches, n_negative)")
+            if negatives.shape[0] != (self.n + batch_rows - 1) // batch_rows:
+                raise ValueError("negatives needs one row per batch")
+            n_negative = int(negatives.shape[1])
+        self._mb = fusedmm_minibatch_create(self.n, self.nnz, rowptr, colidx if self.nnz else None, int(batch_rows),
+                                            n_negative, negatives if n_negative else None, stream)
+
+    def reserve(self, d: int) -> None:
+        fusedmm_minibatch_reserve(self._mb, d)
+
+    def epoch(self, X, lr: float, stream=None) -> None:
+        if not (X.is_cuda and str(X.dtype) == "torch.float32" and X.dim() == 2 and X.stride(1) == 1
+                and X.shape[0] == self.n):
+            raise TypeError("X must be a CUDA float32 tensor of n rows with unit stride along the feature dimension")
+        fusedmm_minibatch_epoch(self._mb, int(X.shape[1]), float(lr), X, X.stride(0), stream)
+
+    def info(self) -> dict:
+        return fusedmm_minibatch_info(self._mb)
+
+    def close(self) -> None:
+        if self._mb is not None:
+            fusedmm_minibatch_destroy(self._mb)
+            self._mb = None
 
     def __del__(self):
         try:

@@ -18,6 +18,7 @@ LIB = os.path.join(HERE, "libfusedmm.so")
 SOURCES = [
     "fusedmm_api.hip",
     "fusedmm_generic.hip",
+    "fusedmm_minibatch.hip",
     "fusedmm_fast_d32.hip",
     "fusedmm_fast_d64.hip",
     "fusedmm_fast_d128.hip",
