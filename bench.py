@@ -272,12 +272,100 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     return out
 
 
+def run_epoch(workload: str, steps: int, warmup: int, with_cpu: bool):
+    """Secondary workloads e1 / e2: one step = one minibatch embedding epoch (fusedmm_minibatch_epoch):
+    per batch of 256 vertices two FusedMM executes on a rectangular slice and one update of its rows."""
+    import numpy as np
+    import torch
+    from paper_2011_06391_amd import binding, model, synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (torch.cuda.is_available() is False)")
+    binding.load()
+    w = synth.make_epoch_workload(workload)
+    g, d = w.csr, w.d
+    rp, ci = torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda()
+    neg = torch.from_numpy(w.negatives).cuda()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    mb = binding.Minibatch(g.m, rp, ci, w.batch_rows, neg)
+    mb.reserve(d)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    info = mb.info()
+    X = torch.from_numpy(w.X0).cuda()
+    for _ in range(warmup):
+        mb.epoch(X, w.lr)
+    X.copy_(torch.from_numpy(w.X0).cuda())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        mb.epoch(X, w.lr)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / steps
+    assert torch.isfinite(X).all().item()
+    entries = g.nnz + g.m * w.n_negative          # stored entries processed per epoch, both calls
+    pos = model.traffic(g.m, g.n, g.nnz, d, True, False, True)
+    negt = model.traffic(g.m, g.n, g.m * w.n_negative, d, True, False, True)
+    alg_bytes = pos.model_bytes + negt.model_bytes + 4 * g.m * d * 4   # + the update: read Zpos, Zneg, X, write X
+    achieved = alg_bytes / (ms_per_step * 1e-3) / 1e9
+    context = {}
+    try:   # the same epoch replayed from a HIP graph (launch overhead of the host removed)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            mb.epoch(X, w.lr)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        context["ms_per_epoch_hip_graph"] = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
+    except Exception as exc:
+        context["hip_graph_error"] = repr(exc)[:200]
+    # parity of one epoch from the initial embedding (checked on the CPU leg)
+    X.copy_(torch.from_numpy(w.X0).cuda())
+    mb.epoch(X, w.lr)
+    torch.cuda.synchronize()
+    X1 = X.cpu().numpy()
+    mb.close()
+    out = {
+        "metric": "fused SDDMM-SpMM throughput: G(edge*dim)/s + achieved HBM GB/s vs peak, 1 GPU",
+        "value": entries * d / (ms_per_step * 1e-3) / 1e9, "unit": "G(edge*dim)/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": workload, "description": w.description, "step": "one minibatch embedding epoch",
+                   "n": g.m, "nnz": g.nnz, "d": d, "batch_rows": w.batch_rows, "n_negative": w.n_negative,
+                   "n_batches": info["n_batches"], "launches_per_epoch": info["launches_per_epoch"],
+                   "entries_per_epoch": entries, "plan_ms": plan_ms, "context": context},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / model.MI355X_HBM_PEAK_GBS, "traffic": None,
+                     "note": "whole epoch (all launches), not one kernel: launches of 256 rows are latency-bound",
+                     "algorithmic_bytes": alg_bytes},
+    }
+    if with_cpu:
+        import oracle
+        t0 = time.perf_counter()
+        Xr, S = oracle.embedding_epoch(g.rowptr, g.colidx, w.X0, w.batch_rows, w.negatives, w.lr)
+        cpu_s = time.perf_counter() - t0
+        bound = 1e-4 * S + 2.0 ** -22 * np.abs(Xr)
+        excess = float((np.abs(X1.astype(np.float64) - Xr.astype(np.float64)) - bound).max())
+        out["cpu_baseline"] = {"value": entries * d / cpu_s / 1e9, "unit": "G(edge*dim)/s",
+                               "cores": synth.num_threads(), "kind": "oracle",
+                               "sample": "one whole epoch of the same workload, fp64 two-phase oracle", "seconds": cpu_s,
+                               "parity_of_one_epoch": {"max_excess_over_bound": excess, "ok": excess <= 0.0,
+                                                       "rule": "|X_gpu - X_oracle| <= 1e-4 * lr * sum|terms| + 2^-22 |X|"}}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="c2", help="c1..c5")
+    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2); e1, e2: minibatch embedding epochs (secondary)")
     ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
@@ -296,6 +384,11 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if args.workload.lower() in ("e1", "e2"):
+        steps = args.steps if args.steps != 200 else 50
+        warmup = args.warmup if args.warmup != 200 else 5
+        print(json.dumps(run_epoch(args.workload.lower(), steps, warmup, not args.no_cpu_baseline)))
+        return
     options = None
     if args.small_row_max or args.split_row_min or args.chunk_edges or args.column_classes or args.tile_row_min:
         options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,

@@ -250,3 +250,42 @@ def make_workload(name: str, d: Optional[int] = None, relabel: bool = True) -> W
         return Workload(name, "one_minus_sigmoid", dd, g, X, Y,
                         "R-MAT scale 22, 2^26 pairs symmetrised, X!=Y U[-0.5,0.5)")
     raise ValueError(f"unknown workload {name!r}")
+
+
+# --------------------------------------------------------------------------- #
+# minibatch embedding epochs (inputs of the end-to-end training experiment)
+# --------------------------------------------------------------------------- #
+
+@dataclass
+class EpochWorkload:
+    name: str
+    d: int
+    batch_rows: int
+    n_negative: int
+    lr: float
+    csr: CSR
+    X0: np.ndarray
+    negatives: np.ndarray   # (n_batches, n_negative) int32, shared by the rows of a batch
+    description: str
+
+
+EPOCH_WORKLOADS = ("e1", "e2")
+
+
+def make_epoch_workload(name: str) -> EpochWorkload:
+    """Synthetic stand-ins with the sizes of the two citation graphs the paper trains on
+    (2 708 vertices / 5 278 edges and 19 717 / 44 324; maximum degree about 170): Chung-Lu
+    patterns with a power-law tail, d = 128, batches of 256 vertices, 5 negative samples per
+    batch, embedding U[-0.5, 0.5)."""
+    name = name.lower()
+    spec = {"e1": (2708, 5278, 0.5, 1101, 2101, 3101), "e2": (19717, 44324, 4.0, 1102, 2102, 3102)}
+    if name not in spec:
+        raise ValueError(f"unknown epoch workload {name!r}")
+    n, pairs, i0, gseed, xseed, nseed = spec[name]
+    d, batch_rows, s = 128, 256, 5
+    g = chung_lu(n, pairs, i0, gseed)
+    X0 = fill_uniform((n, d), xseed, -0.5, 0.5)
+    nb = (n + batch_rows - 1) // batch_rows
+    negatives = fill_int((nb, s), nseed, 0, n - 1).astype(np.int32)
+    return EpochWorkload(name, d, batch_rows, s, 0.02, g, X0, negatives,
+                         f"Chung-Lu n={n}, {pairs} pairs symmetrised, d={d}, batch {batch_rows}, {s} negatives per batch")

@@ -118,3 +118,20 @@ def test_take_rows_slice():
     assert s.m == 4 and s.n == g.n
     for i, r in enumerate(rows):
         assert np.array_equal(s.colidx[s.rowptr[i]:s.rowptr[i + 1]], g.colidx[g.rowptr[r]:g.rowptr[r + 1]])
+
+
+def test_epoch_workloads():
+    """Stand-ins for the two citation graphs of the end-to-end experiment: sizes, symmetry, determinism."""
+    import scipy.sparse as sp
+    for name, n, pairs in (("e1", 2708, 5278), ("e2", 19717, 44324)):
+        w = synth.make_epoch_workload(name)
+        g = w.csr
+        assert (g.m, g.n, w.d, w.batch_rows) == (n, n, 128, 256)
+        assert 1.8 * pairs < g.nnz <= 2 * pairs and 60 <= g.degrees().max() <= 400
+        A = sp.csr_matrix((np.ones(g.nnz), g.colidx, g.rowptr), shape=(n, n))
+        assert A.max() == 1 and (A != A.T).nnz == 0 and A.diagonal().sum() == 0
+        assert w.negatives.shape == ((n + 255) // 256, 5) and w.negatives.dtype == np.int32
+        assert w.negatives.min() >= 0 and w.negatives.max() < n
+        w2 = synth.make_epoch_workload(name)
+        assert np.array_equal(w.negatives, w2.negatives) and np.array_equal(w.X0, w2.X0)
+        assert np.array_equal(g.colidx, w2.csr.colidx)
