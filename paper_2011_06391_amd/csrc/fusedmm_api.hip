@@ -545,7 +545,8 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   const int pattern = recognised >= 0 ? recognised : PAT_RUNTIME;
   const bool y_ok = plan->nnz == 0 || (y_bf16 ? ((reinterpret_cast<uintptr_t>(d_Y) & 7u) == 0 && ldy % 4 == 0)
                                               : (aligned16(d_Y) && ldy % 4 == 0));
-  const bool fast = is_fast_dim(d) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
+  // the fast kernels address a row of Y by a 32-bit pitch in bytes
+  const bool fast = is_fast_dim(d) && ldy < (int64_t(1) << 29) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
                     (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
   if (y_bf16 && !fast) return is_fast_dim(d) ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 

@@ -110,15 +110,21 @@ __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<co
 // Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YB = false: Y is fp32, one
 // 16-byte load.  YB = true: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
 // load widened by shifts; the arithmetic stays fp32.
+// The address is one 32 x 32 -> 64-bit multiply-add: column index (validated, non-negative) times
+// the row pitch in bytes (below 2^32, checked by the host) plus the lane's own base.  Spelled with
+// 64-bit operands the same address costs three quarter-rate multiplies per gathered row, which made
+// the gather loop bound by vector ALU issue rather than by memory.
 template <bool YB>
-__device__ __forceinline__ v4f gather4(const void* Y, int64_t col, int64_t ldy, int piece) {
+__device__ __forceinline__ v4f gather4(const void* Y, int col, int64_t ldy, int piece) {
+  const uint32_t pitch = (uint32_t)ldy * (YB ? 2u : 4u);
+  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YB ? 8u : 16u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
   if constexpr (YB) {
     typedef unsigned int v2u __attribute__((ext_vector_type(2)));
-    const v2u raw = *reinterpret_cast<const v2u*>(static_cast<const uint16_t*>(Y) + col * ldy + 4 * piece);
+    const v2u raw = *reinterpret_cast<const v2u*>(p);
     return v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
                __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
   } else {
-    return ld4(static_cast<const float*>(Y) + col * ldy + 4 * piece);
+    return *reinterpret_cast<const v4f*>(p);
   }
 }
 
