@@ -75,7 +75,7 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
 
 
 def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0,
-        autotune: bool = False, y_bf16: bool = False, with_context: bool = True):
+        autotune: bool = False, y_storage: str = "f32", with_context: bool = True):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -112,14 +112,17 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     plan_ms = (time.perf_counter() - t0) * 1e3
 
     Yb = None
-    if y_bf16:  # optional storage mode, never the default: Y rounded once to bfloat16, arithmetic stays fp32
+    y_bf16 = y_storage != "f32"  # any 2-byte storage of Y
+    if y_bf16:  # optional storage mode, never the default: Y rounded once to bfloat16 / half, arithmetic stays fp32
         Yb = torch.empty((g.n, w.d), dtype=torch.int16, device="cuda")
-        binding.fusedmm_to_bf16(Yb, Yd, g.n * w.d)
+        (binding.fusedmm_to_bf16 if y_storage == "bf16" else binding.fusedmm_to_f16)(Yb, Yd, g.n * w.d)
         torch.cuda.synchronize()
 
     def step():
-        if Yb is not None:
+        if Yb is not None and y_storage == "bf16":
             plan.execute_bf16y(ops, Xd if uses_x else None, Yb, Z, vd)
+        elif Yb is not None:
+            plan.execute_f16y(ops, Xd if uses_x else None, Yb, Z, vd)
         else:
             plan.execute(ops, Xd if uses_x else None, Yd, Z, vd)
 
@@ -161,7 +164,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "unit": "G(edge*dim)/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (Y stored as bf16)" if y_bf16 else "f32", "data": "synthetic",
+        "dtype": f"f32 (Y stored as {y_storage})" if y_bf16 else "f32", "data": "synthetic",
         "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
                    "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms, "plan_options": options, "autotuned": autotune,
@@ -267,7 +270,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     torch.cuda.empty_cache()
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
-        if not y_bf16:  # the oracle would have to be fed the rounded Y; tests/test_bf16_storage_gpu.py does that
+        if not y_bf16:  # the oracle would have to be fed the rounded Y; tests/test_reduced_storage_gpu.py does that
             out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample)
     return out
 
@@ -377,6 +380,8 @@ def main():
     ap.add_argument("--split-row-min", type=int, default=0)
     ap.add_argument("--chunk-edges", type=int, default=0)
     ap.add_argument("--autotune", action="store_true", help="choose the schedule with fusedmm_plan_create_tuned")
+    ap.add_argument("--y-f16", action="store_true",
+                    help="optional storage mode: gather Y from an IEEE half copy (not the headline configuration)")
     ap.add_argument("--y-bf16", action="store_true",
                     help="optional storage mode: gather Y from a bfloat16 copy (not the headline configuration)")
     ap.add_argument("--column-classes", type=int, default=0)
@@ -395,7 +400,8 @@ def main():
                    "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
                    "tile_row_min": args.tile_row_min}
     out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
-              args.copy_calibration_mib, args.autotune, args.y_bf16, not args.no_context)
+              args.copy_calibration_mib, args.autotune, "bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32"),
+              not args.no_context)
     print(json.dumps(out))
 
 

@@ -198,6 +198,15 @@ int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_
  * asynchronous on `stream`): the storage format fusedmm_execute_bf16y reads. */
 int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* stream);
 
+/* The same again with Y stored in IEEE half precision (binary16: 11 significant bits instead of
+ * bfloat16's 8, range up to 65504): same layout, alignment and error rules as fusedmm_execute_bf16y;
+ * fusedmm_to_f16 converts with round to nearest even (values beyond the half range become infinity).
+ * The result equals fusedmm_execute on the fp32 matrix whose entries are the half values widened back. */
+int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
+                         const float* d_values, const float* d_X, int64_t ldx,
+                         const uint16_t* d_Y_f16, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
+int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream);
+
 /* Test hook: run the same schedule and edge indexing as fusedmm_execute would
  * for dimension d (row pointers may be of any alignment class: pass
  * fast_path != 0 to exercise the specialised kernels' indexing, 0 for the

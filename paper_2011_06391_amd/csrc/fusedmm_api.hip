@@ -512,10 +512,11 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
 
 namespace {
 
-// Shared body of fusedmm_execute and fusedmm_execute_bf16y.  y_bf16: d_Y points at bfloat16 rows
-// (2 bytes per element, ldy in elements); only the fast instances exist for that storage.
+// Shared body of fusedmm_execute, fusedmm_execute_bf16y and fusedmm_execute_f16y.  y_format other than
+// kYF32: d_Y points at rows of 2-byte elements (ldy in elements); only the fast instances exist for those.
 int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
-                 int64_t ldx, const void* d_Y, bool y_bf16, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+                 int64_t ldx, const void* d_Y, int y_format, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+  const bool y_bf16 = y_format != kYF32;  // any 2-byte storage
   if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   if (!ops_valid(*ops)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
@@ -570,7 +571,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     a.mean = ops->aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
     a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;
     if (ev0) (void)hipEventRecord(ev0, stream);
-    e = launch_fast(pattern, d, y_bf16, a, stream);
+    e = launch_fast(pattern, d, y_format, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored densely with stride d, whatever the scratch capacity is
     if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
@@ -594,13 +595,24 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
 int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
                     int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
-  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, false, ldy, d_Z, ldz, stream_);
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, kYF32, ldy, d_Z, ldz, stream_);
 }
 
 int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
                           const float* d_X, int64_t ldx, const uint16_t* d_Y_bf16, int64_t ldy, float* d_Z, int64_t ldz,
                           void* stream_) {
-  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y_bf16, true, ldy, d_Z, ldz, stream_);
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y_bf16, kYBf16, ldy, d_Z, ldz, stream_);
+}
+
+int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
+                         const float* d_X, int64_t ldx, const uint16_t* d_Y_f16, int64_t ldy, float* d_Z, int64_t ldz,
+                         void* stream_) {
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y_f16, kYF16, ldy, d_Z, ldz, stream_);
+}
+
+int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream_) {
+  if (count > 0 && (!d_dst || !d_src)) return FUSEDMM_ERR_INVALID_ARG;
+  return launch_to_f16(d_dst, d_src, count, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }
 
 int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* stream_) {
@@ -625,7 +637,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.visit_counts = d_counts;
-    e = launch_fast(PAT_VISIT, d, false, a, stream);
+    e = launch_fast(PAT_VISIT, d, kYF32, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;

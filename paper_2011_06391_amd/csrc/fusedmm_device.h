@@ -107,22 +107,25 @@ __device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V])
 
 __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
 
-// Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YB = false: Y is fp32, one
-// 16-byte load.  YB = true: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
-// load widened by shifts; the arithmetic stays fp32.
+// Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YF = kYF32: Y is fp32, one
+// 16-byte load.  YF = kYBf16: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
+// load widened by shifts.  YF = kYF16: IEEE half precision, one 8-byte load and four conversions.
+// The arithmetic stays fp32 in every case.
 // The address is one 32 x 32 -> 64-bit multiply-add: column index (validated, non-negative) times
-// the row pitch in bytes (below 2^32, checked by the host) plus the lane's own base.  Spelled with
-// 64-bit operands the same address costs three quarter-rate multiplies per gathered row, which made
-// the gather loop bound by vector ALU issue rather than by memory.
-template <bool YB>
+// the row pitch in bytes (below 2^32, checked by the host) plus the lane's own base.
+template <int YF>
 __device__ __forceinline__ v4f gather4(const void* Y, int col, int64_t ldy, int piece) {
-  const uint32_t pitch = (uint32_t)ldy * (YB ? 2u : 4u);
-  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YB ? 8u : 16u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
-  if constexpr (YB) {
+  const uint32_t pitch = (uint32_t)ldy * (YF == kYF32 ? 4u : 2u);
+  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YF == kYF32 ? 16u : 8u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+  if constexpr (YF == kYBf16) {
     typedef unsigned int v2u __attribute__((ext_vector_type(2)));
     const v2u raw = *reinterpret_cast<const v2u*>(p);
     return v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
                __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
+  } else if constexpr (YF == kYF16) {
+    typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+    const v4h raw = *reinterpret_cast<const v4h*>(p);
+    return v4f{(float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w};
   } else {
     return *reinterpret_cast<const v4f*>(p);
   }
@@ -287,7 +290,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 // One wavefront accumulates the stored entries [e0, e1) of a single row.  The S lane groups
 // take entries round-robin inside batches of 64; z holds this group's partial sum.
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int G, int U, bool YB>
+template <int P, int D, int G, int U, int YF>
 __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
                                                 const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int lane) {
   constexpr int V = D / (4 * G);
@@ -322,7 +325,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 #pragma unroll
           for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + G * i);
+            for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + G * i);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z);
@@ -347,7 +350,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
             for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
             if (ok[u]) {
 #pragma unroll
-              for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + G * i);
+              for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + G * i);
             }
           }
 #pragma unroll
@@ -403,7 +406,7 @@ __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / 
 // and then runs one of three bodies: chunk, wave segments, packed segments.  A segment is
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int GW, int UW, int GP, int UP, bool YB>
+template <int P, int D, int GW, int UW, int GP, int UP, int YF>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   using T = PatTraits<P>;
   const int lane = threadIdx.x & 63;
@@ -438,7 +441,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     v4f x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW>(a, ch.row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YB>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
+    wave_accumulate<P, D, GW, UW, YF>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if (lane < GW) {
@@ -485,7 +488,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     v4f x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW>(a, row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YB>(a, e0, e1, x, z, lane);
+    wave_accumulate<P, D, GW, UW, YF>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if constexpr (P == PAT_RUNTIME) {
@@ -557,7 +560,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
               for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
               if (ok[u]) {
 #pragma unroll
-                for (int i = 0; i < V; ++i) y[u][i] = gather4<YB>(a.Y, c[u], a.ldy, g + GP * i);
+                for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + GP * i);
               }
             }
 #pragma unroll

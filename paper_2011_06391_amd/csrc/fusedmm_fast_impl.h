@@ -7,37 +7,38 @@ namespace fmm {
 #define FMM_CAT2(a, b) a##b
 #define FMM_CAT(a, b) FMM_CAT2(a, b)
 
-template <int P, bool YB>
+template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
   const int64_t blocks = (int64_t)a.nb_tiled + a.nb_chunk + a.nb_wave + a.nb_packed;
   if (blocks <= 0) return hipSuccess;
-  hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP, YB>), dim3((unsigned)blocks),
+  hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP, YF>), dim3((unsigned)blocks),
                      dim3(kBlockThreads), 0, stream, a);
   return hipGetLastError();
 }
 
 int FMM_CAT(packed_rows_per_block_d, FMM_D)() { return kWavesPerBlock * (64 / FMM_GP); }
 
-hipError_t FMM_CAT(launch_fast_d, FMM_D)(int pattern, bool y_bf16, const KernelArgs& a, hipStream_t stream) {
-  if (y_bf16) {
-    switch (pattern) {
-      case PAT_SIGMOID: return launch_one<PAT_SIGMOID, true>(a, stream);
-      case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, true>(a, stream);
-      case PAT_GCN: return launch_one<PAT_GCN, true>(a, stream);
-      case PAT_TDIST: return launch_one<PAT_TDIST, true>(a, stream);
-      case PAT_FR: return launch_one<PAT_FR, true>(a, stream);
-      case PAT_RUNTIME: return launch_one<PAT_RUNTIME, true>(a, stream);
-      default: return hipErrorInvalidValue;
-    }
-  }
+template <int YF>
+static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t stream) {
   switch (pattern) {
-    case PAT_SIGMOID: return launch_one<PAT_SIGMOID, false>(a, stream);
-    case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, false>(a, stream);
-    case PAT_GCN: return launch_one<PAT_GCN, false>(a, stream);
-    case PAT_TDIST: return launch_one<PAT_TDIST, false>(a, stream);
-    case PAT_FR: return launch_one<PAT_FR, false>(a, stream);
-    case PAT_VISIT: return launch_one<PAT_VISIT, false>(a, stream);
-    case PAT_RUNTIME: return launch_one<PAT_RUNTIME, false>(a, stream);
+    case PAT_SIGMOID: return launch_one<PAT_SIGMOID, YF>(a, stream);
+    case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, YF>(a, stream);
+    case PAT_GCN: return launch_one<PAT_GCN, YF>(a, stream);
+    case PAT_TDIST: return launch_one<PAT_TDIST, YF>(a, stream);
+    case PAT_FR: return launch_one<PAT_FR, YF>(a, stream);
+    case PAT_RUNTIME: return launch_one<PAT_RUNTIME, YF>(a, stream);
+    case PAT_VISIT:  // the edge-visit instance reads no Y: one form is enough
+      if constexpr (YF == kYF32) return launch_one<PAT_VISIT, kYF32>(a, stream);
+      return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t FMM_CAT(launch_fast_d, FMM_D)(int pattern, int y_format, const KernelArgs& a, hipStream_t stream) {
+  switch (y_format) {
+    case kYF32: return launch_format<kYF32>(pattern, a, stream);
+    case kYBf16: return launch_format<kYBf16>(pattern, a, stream);
+    case kYF16: return launch_format<kYF16>(pattern, a, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -232,7 +232,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
-  hipError_t launch_fast_d##D(int pattern, bool y_bf16, const KernelArgs& a, hipStream_t stream); \
+  hipError_t launch_fast_d##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
   int packed_rows_per_block_d##D();
 FMM_DECL(32) FMM_DECL(64) FMM_DECL(128) FMM_DECL(256) FMM_DECL(512)
 #undef FMM_DECL
@@ -248,13 +248,13 @@ int packed_rows_per_block(int d) {
   }
 }
 
-hipError_t launch_fast(int pattern, int d, bool y_bf16, const KernelArgs& a, hipStream_t stream) {
+hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream) {
   switch (d) {
-    case 32: return launch_fast_d32(pattern, y_bf16, a, stream);
-    case 64: return launch_fast_d64(pattern, y_bf16, a, stream);
-    case 128: return launch_fast_d128(pattern, y_bf16, a, stream);
-    case 256: return launch_fast_d256(pattern, y_bf16, a, stream);
-    case 512: return launch_fast_d512(pattern, y_bf16, a, stream);
+    case 32: return launch_fast_d32(pattern, y_format, a, stream);
+    case 64: return launch_fast_d64(pattern, y_format, a, stream);
+    case 128: return launch_fast_d128(pattern, y_format, a, stream);
+    case 256: return launch_fast_d256(pattern, y_format, a, stream);
+    case 512: return launch_fast_d512(pattern, y_format, a, stream);
     default: return hipErrorInvalidValue;
   }
 }
@@ -268,6 +268,20 @@ __global__ __launch_bounds__(256) void to_bf16_kernel(uint16_t* dst, const float
     else r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     dst[i] = (uint16_t)r;
   }
+}
+
+// fp32 -> IEEE half, round to nearest even (the hardware conversion); overflow gives infinity.
+__global__ __launch_bounds__(256) void to_f16_kernel(uint16_t* dst, const float* src, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = __builtin_bit_cast(uint16_t, (_Float16)src[i]);
+}
+
+hipError_t launch_to_f16(uint16_t* dst, const float* src, size_t count, hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dst, src, count);
+  return hipGetLastError();
 }
 
 hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStream_t stream) {

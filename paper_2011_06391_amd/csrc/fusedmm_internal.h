@@ -48,7 +48,7 @@ struct KernelArgs {
   const int32_t* colidx;
   const float* values;
   const float* X;
-  const void* Y;  // fp32, or bfloat16 when the launch says so; ldy counts elements of that type
+  const void* Y;  // fp32, or bfloat16 / half when the launch says so; ldy counts elements of that type
   float* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
@@ -77,12 +77,17 @@ hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, cons
 // Rows per workgroup in the packed range for dimension d (host needs it for the grid).
 int packed_rows_per_block(int d);
 
-// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512.  y_bf16: a.Y holds
-// bfloat16 (only the five sum patterns and the run-time-ops instance exist in that form).
-hipError_t launch_fast(int pattern, int d, bool y_bf16, const KernelArgs& a, hipStream_t stream);
+// Storage formats of Y the specialised kernels read (arithmetic is fp32 in all of them).
+enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2 };
+
+// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512.  y_format other than
+// kYF32: a.Y holds 2-byte elements (the five sum patterns and the run-time-ops instance exist in that form).
+hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream);
 
 // dst[i] = bfloat16(src[i]), round to nearest even; NaN stays NaN.
 hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStream_t stream);
+// dst[i] = half(src[i]), round to nearest even.
+hipError_t launch_to_f16(uint16_t* dst, const float* src, size_t count, hipStream_t stream);
 
 // General kernel: any 1 <= d <= 2048, any op tuple, any alignment; one wavefront per row.
 struct GenericArgs {

@@ -1,6 +1,7 @@
-"""Y stored as bfloat16 (fusedmm_execute_bf16y): the GPU must compute, in fp32 arithmetic, the same
-function of the ROUNDED inputs as the oracle does in fp64.  The rounding itself (fusedmm_to_bf16) is
-checked bit for bit against a round-to-nearest-even written independently in numpy."""
+"""Y stored as bfloat16 or IEEE half (fusedmm_execute_bf16y / fusedmm_execute_f16y): the GPU must
+compute, in fp32 arithmetic, the same function of the ROUNDED inputs as the oracle does in fp64.  The
+rounding itself (fusedmm_to_bf16 / fusedmm_to_f16) is checked bit for bit against a round-to-nearest-even
+written independently in numpy (bfloat16) and against numpy's own float16 conversion (half)."""
 import numpy as np
 import pytest
 
@@ -56,6 +57,73 @@ def test_rounding_kernel_bit_exact(B):
     assert np.isnan(widen(out.cpu().numpy().view(np.uint16)))[0]
 
 
+def test_half_rounding_kernel_bit_exact(B):
+    rng = np.random.default_rng(2)
+    a = np.concatenate([(rng.normal(size=100000) * 10.0 ** rng.integers(-9, 6, 100000)).astype(np.float32),
+                        np.array([0.0, -0.0, 1.0, 65504.0, 65519.9, 65520.0, 1e6, -1e6, 6.0e-8, 5.96e-8, 2.9e-8, 3.1e-8,
+                                  np.inf, -np.inf], np.float32),
+                        # exact ties between neighbouring halves around 1.0 (spacing 2^-10)
+                        np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -(1.0 + 2.0 ** -11)], np.float32)]).astype(np.float32)
+    src = torch.from_numpy(a).cuda()
+    dst = torch.zeros(len(a), dtype=torch.int16, device="cuda")
+    B.fusedmm_to_f16(dst, src, len(a))
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy().view(np.uint16)
+    with np.errstate(over="ignore"):
+        want = a.astype(np.float16).view(np.uint16)   # IEEE round to nearest even, subnormals kept, overflow to inf
+    np.testing.assert_array_equal(got, want)
+    assert got.view(np.float16)[-3:].tolist() == [1.0, 1.001953125, -1.0]
+    nan = torch.tensor([float("nan")], device="cuda")
+    out = torch.zeros(1, dtype=torch.int16, device="cuda")
+    B.fusedmm_to_f16(out, nan, 1)
+    assert np.isnan(out.cpu().numpy().view(np.float16))[0]
+
+
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512))
+@pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "general"))
+def test_half_storage_parity(B, pattern, d):
+    rng = np.random.default_rng(41 + d)
+    g = synth.rmat(11, (1 << 10) * 24, seed=190 + d)
+    m = n = g.m
+    X = rng.uniform(-0.6, 0.6, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.6, 0.6, (n, d)).astype(np.float32)
+    Y[5, :4] = [1e-7, -3e-8, 6.2e-5, 70000.0]      # half subnormals and an overflow to infinity ...
+    vals = rng.uniform(-1, 1, g.nnz).astype(np.float32)
+    with np.errstate(over="ignore"):
+        bits = Y.astype(np.float16).view(np.uint16)
+    Yr = bits.view(np.float16).astype(np.float32)    # what the GPU will see
+    assert np.isinf(Yr[5, 3])
+    Yr[5, 3] = Y[5, 3] = 0.25                       # ... checked above as a conversion; keep the parity data finite
+    bits = Yr.astype(np.float16).view(np.uint16)
+    assert np.abs(Yr - Y).max() < 0.6 * 2 ** -11
+    if pattern == "general":
+        names, oaop, gaop = ("SUB", "NOOP", "SIGMOID", "MUL_Y"), "AMEAN", "MEAN"
+        Zr, S, _ = oracle.unfused_general(g.rowptr, g.colidx, vals, X, Yr, names, oaop, alpha=0.3)
+        ops = B.make_ops(*names, aop=gaop, alpha=0.3)
+    else:
+        Zr, S, _ = oracle.unfused(g.rowptr, g.colidx, vals, X, Yr, pattern, alpha=0.3)
+        ops = B.fusedmm_ops_preset(pattern)
+        ops.alpha = 0.3
+    rp, ci = torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda()
+    Xd, Yd, vd = torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), torch.from_numpy(vals).cuda()
+    Yh = torch.zeros((n, d), dtype=torch.int16, device="cuda")
+    B.fusedmm_to_f16(Yh, Yd, n * d)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(Yh.cpu().numpy().view(np.uint16), bits)
+    for options in ({"column_classes": 1}, {"column_classes": 16, "tile_row_min": 64, "split_row_min": 128}):
+        plan = B.Plan(m, n, rp, ci, options)
+        Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+        plan.execute_f16y(ops, None if pattern == "gcn" else Xd, Yh, Z, vd)
+        torch.cuda.synchronize()
+        err, am, viol = oracle.compare(Z.cpu().numpy(), Zr, S)
+        assert viol == 0 and err <= TOL, f"{pattern} d={d} {options}: err {err:.3e} at {am}, viol {viol}"
+        Z32 = torch.empty_like(Z)
+        plan.execute(ops, None if pattern == "gcn" else Xd, torch.from_numpy(Yr).cuda(), Z32, vd)
+        torch.cuda.synchronize()
+        assert torch.equal(Z, Z32)        # same numbers as the fp32 entry point on the widened matrix
+        plan.close()
+
+
 @pytest.mark.parametrize("d", (32, 64, 128, 256, 512))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "fr", "general"))
 def test_bf16_storage_parity(B, pattern, d):
@@ -106,7 +174,8 @@ def test_bf16_argument_checks(B):
         X = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
         Yb = torch.zeros((g.n, ld), dtype=torch.int16, device="cuda")
         Z = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
-        with pytest.raises(B.FusedMMError) as ei:
-            B.fusedmm_execute_bf16y(plan._plan, ops, d, None, X, d, Yb, ld, Z, d)
-        assert ei.value.status == expect
+        for entry in (B.fusedmm_execute_bf16y, B.fusedmm_execute_f16y):
+            with pytest.raises(B.FusedMMError) as ei:
+                entry(plan._plan, ops, d, None, X, d, Yb, ld, Z, d)
+            assert ei.value.status == expect
     plan.close()
