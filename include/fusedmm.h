@@ -207,6 +207,14 @@ int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t
                          const uint16_t* d_Y_f16, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
 int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream);
 
+/* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
+ * values are fp64 and so is every step's arithmetic.  Runs the general kernel (one wavefront per
+ * row, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the specialised schedule is
+ * fp32 only.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened. */
+int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
+                        const double* d_values, const double* d_X, int64_t ldx,
+                        const double* d_Y, int64_t ldy, double* d_Z, int64_t ldz, void* stream);
+
 /* Test hook: run the same schedule and edge indexing as fusedmm_execute would
  * for dimension d (row pointers may be of any alignment class: pass
  * fast_path != 0 to exercise the specialised kernels' indexing, 0 for the

@@ -36,7 +36,8 @@ EXPORTS = (
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
     "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
-    "fusedmm_to_bf16", "fusedmm_execute_f16y", "fusedmm_to_f16", "fusedmm_minibatch_create", "fusedmm_minibatch_reserve", "fusedmm_minibatch_epoch",
+    "fusedmm_to_bf16", "fusedmm_execute_f16y", "fusedmm_to_f16", "fusedmm_execute_f64",
+    "fusedmm_minibatch_create", "fusedmm_minibatch_reserve", "fusedmm_minibatch_epoch",
     "fusedmm_minibatch_info", "fusedmm_minibatch_destroy",
 )
 
@@ -102,6 +103,8 @@ def load():
     lib.fusedmm_execute_f16y.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.fusedmm_to_f16.restype = ctypes.c_int
     lib.fusedmm_to_f16.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.fusedmm_execute_f64.restype = ctypes.c_int
+    lib.fusedmm_execute_f64.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.fusedmm_debug_edge_visits.restype = ctypes.c_int
     lib.fusedmm_debug_edge_visits.argtypes = [vp, i32, i32, vp, vp]
     lib.fusedmm_plan_set_profiling.restype = ctypes.c_int
@@ -233,6 +236,13 @@ def fusedmm_execute_f16y(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: i
     _check(st, "fusedmm_execute_f16y")
 
 
+def fusedmm_execute_f64(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d_Y, ldy: int, d_Z, ldz: int,
+                        stream=None) -> None:
+    st = load().fusedmm_execute_f64(plan, ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
+                                    _dptr(d_Z), ldz, _stream(stream))
+    _check(st, "fusedmm_execute_f64")
+
+
 def fusedmm_to_f16(d_dst, d_src, count: int, stream=None) -> None:
     _check(load().fusedmm_to_f16(_dptr(d_dst), _dptr(d_src), count, _stream(stream)), "fusedmm_to_f16")
 
@@ -342,6 +352,15 @@ class Plan:
         ldx = 0 if X is None else X.stride(0)
         fusedmm_execute_bf16y(self._plan, ops, int(Z.shape[1]), values, X, ldx, Y_bf16, Y_bf16.stride(0), Z, Z.stride(0),
                               stream)
+
+    def execute_f64(self, ops, X, Y, Z, values=None, stream=None) -> None:
+        if isinstance(ops, str):
+            ops = fusedmm_ops_preset(ops)
+        for t in (X, Y, Z, values):
+            if t is not None and not (t.is_cuda and str(t.dtype) == "torch.float64" and (t.dim() < 2 or t.stride(-1) == 1)):
+                raise TypeError("operands must be CUDA float64 tensors with unit stride along the feature dimension")
+        ldx = 0 if X is None else X.stride(0)
+        fusedmm_execute_f64(self._plan, ops, int(Z.shape[1]), values, X, ldx, Y, Y.stride(0), Z, Z.stride(0), stream)
 
     def execute_f16y(self, ops, X, Y_f16, Z, values=None, stream=None) -> None:
         """Y_f16: CUDA tensor of 2-byte elements (torch.float16, int16 or uint16 bits), n x d."""

@@ -610,6 +610,45 @@ int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t
   return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y_f16, kYF16, ldy, d_Z, ldz, stream_);
 }
 
+int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const double* d_values,
+                        const double* d_X, int64_t ldx, const double* d_Y, int64_t ldy, double* d_Z, int64_t ldz,
+                        void* stream_) {
+  if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (!ops_valid(*ops)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
+  const bool uses_x = ops->vop != FUSEDMM_VOP_SEL2ND;
+  if (plan->m == 0) return FUSEDMM_OK;
+  if (!d_Z || ldz < d) return FUSEDMM_ERR_INVALID_ARG;
+  if (plan->nnz > 0) {
+    if (!d_Y || ldy < d) return FUSEDMM_ERR_INVALID_ARG;
+    if (ops->sop == FUSEDMM_SOP_EDGE_VALUE && !d_values) return FUSEDMM_ERR_INVALID_ARG;
+  }
+  if (uses_x && (!d_X || ldx < d)) return FUSEDMM_ERR_INVALID_ARG;
+  auto range = [d](const double* p, int64_t rows, int64_t ld, uintptr_t* lo, uintptr_t* hi) {
+    *lo = reinterpret_cast<uintptr_t>(p);
+    *hi = *lo + (uintptr_t)((rows > 0 ? rows - 1 : 0) * ld + d) * sizeof(double);
+  };
+  uintptr_t z0, z1, o0, o1;
+  range(d_Z, plan->m, ldz, &z0, &z1);
+  if (d_Y && plan->n > 0) {
+    range(d_Y, plan->n, ldy, &o0, &o1);
+    if (z0 < o1 && o0 < z1) return FUSEDMM_ERR_ALIAS;
+  }
+  if (uses_x) {
+    range(d_X, plan->m, ldx, &o0, &o1);
+    if (z0 < o1 && o0 < z1) return FUSEDMM_ERR_ALIAS;
+  }
+  GenericArgsT<double> g;
+  g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
+  g.X = d_X; g.Y = d_Y; g.Z = d_Z;
+  g.ldx = ldx; g.ldy = ldy; g.ldz = ldz;
+  g.m = plan->m; g.d = d;
+  g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
+  g.alpha = (double)ops->alpha;
+  g.visit_counts = nullptr;
+  return launch_generic(g, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+}
+
 int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream_) {
   if (count > 0 && (!d_dst || !d_src)) return FUSEDMM_ERR_INVALID_ARG;
   return launch_to_f16(d_dst, d_src, count, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;

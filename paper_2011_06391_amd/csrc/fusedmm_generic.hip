@@ -7,19 +7,22 @@ namespace fmm {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float wave_allreduce(float v) {
+template <class T>
+__device__ __forceinline__ T wave_allreduce(T v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
   return v;
 }
 
-__device__ __forceinline__ float wave_allreduce_mul(float v) {
+template <class T>
+__device__ __forceinline__ T wave_allreduce_mul(T v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v *= __shfl_xor(v, off);
   return v;
 }
 
-__device__ __forceinline__ float vop_apply(int vop, float x, float y) {
+template <class T>
+__device__ __forceinline__ T vop_apply(int vop, T x, T y) {
   switch (vop) {
     case FUSEDMM_VOP_MUL: return x * y;
     case FUSEDMM_VOP_SEL2ND: return y;
@@ -28,11 +31,17 @@ __device__ __forceinline__ float vop_apply(int vop, float x, float y) {
   }
 }
 
-__device__ __forceinline__ float sop_apply(int sop, float s, float alpha) {
+__device__ __forceinline__ float exp_of(float v) { return expf(v); }
+__device__ __forceinline__ double exp_of(double v) { return exp(v); }
+__device__ __forceinline__ float sqrt_of(float v) { return sqrtf(v); }
+__device__ __forceinline__ double sqrt_of(double v) { return sqrt(v); }
+
+template <class T>
+__device__ __forceinline__ T sop_apply(int sop, T s, T alpha) {
   switch (sop) {
-    case FUSEDMM_SOP_SIGMOID: return 1.0f / (1.0f + expf(-s));
-    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return 1.0f / (1.0f + expf(s));
-    case FUSEDMM_SOP_INV_1P: return 1.0f / (1.0f + s);
+    case FUSEDMM_SOP_SIGMOID: return T(1) / (T(1) + exp_of(-s));
+    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return T(1) / (T(1) + exp_of(s));
+    case FUSEDMM_SOP_INV_1P: return T(1) / (T(1) + s);
     case FUSEDMM_SOP_SCAL: return alpha * s;
     default: return s;  // NOOP
   }
@@ -43,10 +52,12 @@ __device__ __forceinline__ float sop_apply(int sop, float s, float alpha) {
 // row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
 // Covers every op of Table II: scalar messages (after a reduction, or the edge value) and
 // vector messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation
-// from a zero-initialised z_u, and MEAN (the sum divided by the row length).
+// from a zero-initialised z_u, and MEAN (the sum divided by the row length).  T is float or
+// double (Section V: the method is not tied to single precision).
 constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
 
-__global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgs a) {
+template <class T>
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgsT<T> a) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   if (row >= a.m) return;
@@ -58,47 +69,47 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
   }
   const bool uses_x = a.vop != FUSEDMM_VOP_SEL2ND;
   const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
-  const float* xr = uses_x ? a.X + row * a.ldx : nullptr;
-  float acc[kGenericAcc];
+  const T* xr = uses_x ? a.X + row * a.ldx : nullptr;
+  T acc[kGenericAcc];
 #pragma unroll
-  for (int i = 0; i < kGenericAcc; ++i) acc[i] = 0.f;  // z_u <- 0
+  for (int i = 0; i < kGenericAcc; ++i) acc[i] = T(0);  // z_u <- 0
 
   for (int64_t e = e0; e < e1; ++e) {
-    const float* yr = a.Y + (int64_t)a.colidx[e] * a.ldy;
-    float h = 0.f;
+    const T* yr = a.Y + (int64_t)a.colidx[e] * a.ldy;
+    T h = T(0);
     if (a.sop == FUSEDMM_SOP_EDGE_VALUE) {
       h = a.values[e];
     } else if (a.rop != FUSEDMM_ROP_NOOP) {
-      float p = (a.rop == FUSEDMM_ROP_RMUL) ? 1.f : 0.f;
+      T p = (a.rop == FUSEDMM_ROP_RMUL) ? T(1) : T(0);
       for (int k = lane; k < d; k += 64) {
-        const float t = vop_apply(a.vop, uses_x ? xr[k] : 0.f, yr[k]);  // VOP
+        const T t = vop_apply<T>(a.vop, uses_x ? xr[k] : T(0), yr[k]);  // VOP
         if (a.rop == FUSEDMM_ROP_RSUM) p += t;                            // ROP (per-lane share)
         else if (a.rop == FUSEDMM_ROP_RMUL) p *= t;
         else p += t * t;
       }
-      float s = (a.rop == FUSEDMM_ROP_RMUL) ? wave_allreduce_mul(p) : wave_allreduce(p);
-      if (a.rop == FUSEDMM_ROP_NORM2) s = sqrtf(s);
-      h = sop_apply(a.sop, s, a.alpha);  // SOP on the scalar
+      T s = (a.rop == FUSEDMM_ROP_RMUL) ? wave_allreduce_mul<T>(p) : wave_allreduce<T>(p);
+      if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_of(s);
+      h = sop_apply<T>(a.sop, s, a.alpha);  // SOP on the scalar
     }
 #pragma unroll
     for (int i = 0; i < kGenericAcc; ++i) {
       const int k = lane + 64 * i;
       if (k < d) {
-        const float y = yr[k];
-        const float t = vop_apply(a.vop, uses_x ? xr[k] : 0.f, y);
-        const float hk = scalar_h ? h : sop_apply(a.sop, t, a.alpha);  // SOP on the element
-        float w;                                                         // MOP
+        const T y = yr[k];
+        const T t = vop_apply<T>(a.vop, uses_x ? xr[k] : T(0), y);
+        const T hk = scalar_h ? h : sop_apply<T>(a.sop, t, a.alpha);  // SOP on the element
+        T w;                                                             // MOP
         if (a.mop == FUSEDMM_MOP_SEL2ND) w = y;
         else if (a.mop == FUSEDMM_MOP_MUL_Y) w = hk * y;
         else w = hk * t;
         if (a.aop == FUSEDMM_AOP_SUM || a.aop == FUSEDMM_AOP_MEAN) acc[i] += w;  // AOP
-        else if (a.aop == FUSEDMM_AOP_MAX) acc[i] = fmaxf(acc[i], w);
-        else acc[i] = fminf(acc[i], w);
+        else if (a.aop == FUSEDMM_AOP_MAX) acc[i] = w > acc[i] ? w : acc[i];  // a NaN message is skipped, as by fmax
+        else acc[i] = w < acc[i] ? w : acc[i];
       }
     }
   }
-  float* zr = a.Z + row * a.ldz;
-  const float post = (a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? 1.0f / (float)(e1 - e0) : 1.0f;  // mean pooling
+  T* zr = a.Z + row * a.ldz;
+  const T post = (a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? T(1) / (T)(e1 - e0) : T(1);  // mean pooling
 #pragma unroll
   for (int i = 0; i < kGenericAcc; ++i) {
     const int k = lane + 64 * i;
@@ -106,12 +117,15 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
   }
 }
 
-hipError_t launch_generic(const GenericArgs& a, hipStream_t stream) {
+template <class T>
+static hipError_t launch_generic_t(const GenericArgsT<T>& a, hipStream_t stream) {
   if (a.m <= 0) return hipSuccess;
   const int64_t blocks = (a.m + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(fusedmm_generic_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a);
+  hipLaunchKernelGGL(fusedmm_generic_kernel<T>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a);
   return hipGetLastError();
 }
+hipError_t launch_generic(const GenericArgsT<float>& a, hipStream_t stream) { return launch_generic_t(a, stream); }
+hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream) { return launch_generic_t(a, stream); }
 
 // z_u = sum of the row's partial rows, in slot order (fixed order => run-to-run deterministic).
 // A workgroup covers 256 / (d/4) rows; a thread owns one 16-byte column of one row and keeps

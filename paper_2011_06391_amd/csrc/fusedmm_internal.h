@@ -90,21 +90,25 @@ hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStre
 hipError_t launch_to_f16(uint16_t* dst, const float* src, size_t count, hipStream_t stream);
 
 // General kernel: any 1 <= d <= 2048, any op tuple, any alignment; one wavefront per row.
-struct GenericArgs {
+// T = float, or double (storage and arithmetic both in T).
+template <class T>
+struct GenericArgsT {
   const int64_t* rowptr;
   const int32_t* colidx;
-  const float* values;
-  const float* X;
-  const float* Y;
-  float* Z;
+  const T* values;
+  const T* X;
+  const T* Y;
+  T* Z;
   int64_t ldx, ldy, ldz;
   int64_t m;
   int32_t d;
   int32_t vop, rop, sop, mop, aop;
-  float alpha;
+  T alpha;
   uint32_t* visit_counts;  // non-null: count visits instead of computing
 };
-hipError_t launch_generic(const GenericArgs& a, hipStream_t stream);
+using GenericArgs = GenericArgsT<float>;
+hipError_t launch_generic(const GenericArgsT<float>& a, hipStream_t stream);
+hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream);
 
 // aop: FUSEDMM_AOP_SUM / MAX / MIN, how partial rows are combined; FUSEDMM_AOP_MEAN: summed, then
 // divided by the row's length taken from rowptr
