@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 # HBM bytes per main-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.
 # They belong to the kernel build and default plan the profiles were taken with.
-MEASURED_TRAFFIC_BYTES = {"c2": 373873117, "c3": 26519053068, "c4": 6687978670, "c5": 80809486814}
+MEASURED_TRAFFIC_BYTES = {"c2": 374191723, "c3": 26654681846, "c4": 6689682927, "c5": 80827779190}
 
 
 def parity_sample(w, rows, Z_rows):
