@@ -15,7 +15,7 @@ struct fusedmm_plan {
   const int64_t* d_rowptr = nullptr;
   const int32_t* d_colidx = nullptr;
   int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0;
-  int32_t n_wave = 0, n_packed = 0, n_chunks = 0, n_merges = 0, n_parts = 0;
+  int32_t n_wave = 0, n_packed = 0, n_empty = 0, n_chunks = 0, n_merges = 0, n_parts = 0;  // n_packed: non-empty
   int32_t n_items = 0, n_tile_descs = 0, n_tiled_rows = 0, n_classes = 1;
   int32_t* d_order = nullptr;
   ChunkDesc* d_chunks = nullptr;
@@ -139,6 +139,8 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, KernelArgs* a) {
   a->n_chunks = p->n_chunks;
   a->n_wave = p->n_wave;
   a->n_packed = p->n_packed;
+  a->n_empty = p->n_empty;
+  a->nb_zero = (p->n_empty + kZeroRowsPerBlock - 1) / kZeroRowsPerBlock;
   a->nb_chunk = p->n_chunks;
   a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
   const int rpb = packed_rows_per_block(d);
@@ -452,7 +454,8 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     }
     if (tile_descs.size() >= (size_t)INT32_MAX || items.size() >= (size_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
     p->n_wave = (int32_t)n_wave;
-    p->n_packed = (int32_t)((m - n_long) - n_wave);
+    p->n_empty = (int32_t)bucket[0];  // they sort last: zero-filled by workgroups of their own
+    p->n_packed = (int32_t)((m - n_long) - n_wave - bucket[0]);
     p->n_chunks = (int32_t)chunks.size();
     p->n_merges = (int32_t)merges.size();
     p->n_parts = next_part;
@@ -487,7 +490,7 @@ int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
   if (!plan || !out) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  size_t b = (size_t)(plan->n_wave + plan->n_packed) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
+  size_t b = (size_t)(plan->n_wave + plan->n_packed + plan->n_empty) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
              (size_t)plan->n_merges * sizeof(MergeDesc) + (size_t)plan->n_items * sizeof(BlockItem) +
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
   if (is_fast_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(d, plan->partials_d) * sizeof(float);
@@ -499,7 +502,7 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
                        int64_t* n_split_rows, int64_t* n_partials, int64_t* n_tiled_rows, int64_t* n_tile_segments,
                        int64_t* n_column_classes) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
-  if (n_packed_rows) *n_packed_rows = plan->n_packed;
+  if (n_packed_rows) *n_packed_rows = plan->n_packed + plan->n_empty;
   if (n_wave_rows) *n_wave_rows = plan->n_wave;
   if (n_chunks) *n_chunks = plan->n_chunks;
   if (n_split_rows) *n_split_rows = plan->n_merges;

@@ -424,10 +424,13 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
   } else if (b < a.nb_tiled + a.nb_chunk + a.nb_wave) {
     kind = kItemWave; first = (b - a.nb_tiled - a.nb_chunk) * kWavesPerBlock;
     count = a.n_wave - first < kWavesPerBlock ? a.n_wave - first : kWavesPerBlock; from_desc = false;
-  } else {
+  } else if (b < a.nb_tiled + a.nb_chunk + a.nb_wave + a.nb_packed) {
     constexpr int kRows = kWavesPerBlock * (64 / GP);
     kind = kItemPacked; first = (b - a.nb_tiled - a.nb_chunk - a.nb_wave) * kRows;
     count = a.n_packed - first < kRows ? a.n_packed - first : kRows; from_desc = false;
+  } else {
+    kind = kItemZero; first = (b - a.nb_tiled - a.nb_chunk - a.nb_wave - a.nb_packed) * kZeroRowsPerBlock;
+    count = a.n_empty - first < kZeroRowsPerBlock ? a.n_empty - first : kZeroRowsPerBlock; from_desc = false;
   }
 
   if (kind == kItemChunk) {
@@ -577,6 +580,17 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
         }
         if (has_seg) store_row<D, GP>(dst, g, z);
+      }
+    }
+  }
+  else if (kind == kItemZero) {
+    // ---- rows without stored entries: z_u = 0 (Algorithm 1 initialises z_u and adds nothing) ----
+    if constexpr (T::loads_y) {
+      constexpr int kPieces = D / 4;
+      const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
+      for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
+        const int64_t row = rows[i / kPieces];
+        __builtin_nontemporal_store(v4f{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<v4f*>(a.Z + row * a.ldz + 4 * (i % kPieces)));
       }
     }
   }

@@ -9,7 +9,7 @@ namespace fmm {
 
 template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
-  const int64_t blocks = (int64_t)a.nb_tiled + a.nb_chunk + a.nb_wave + a.nb_packed;
+  const int64_t blocks = (int64_t)a.nb_tiled + a.nb_chunk + a.nb_wave + a.nb_packed + a.nb_zero;
   if (blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP, YF>), dim3((unsigned)blocks),
                      dim3(kBlockThreads), 0, stream, a);

@@ -25,7 +25,9 @@ struct ChunkDesc {
 // What a workgroup of the tiled region does: kind, index of its first descriptor in
 // tile_descs[], and how many descriptors (1 for a chunk, <= 4 wave segments, <= 32 packed
 // segments).  Items are stored interleaved by XCD: items[j * 8 + k] is the j-th item of XCD k.
-enum : int { kItemNone = 0, kItemChunk = 1, kItemWave = 2, kItemPacked = 3 };
+enum : int { kItemNone = 0, kItemChunk = 1, kItemWave = 2, kItemPacked = 3, kItemZero = 4 };
+// rows without stored entries are only zero-filled: this many per workgroup
+constexpr int kZeroRowsPerBlock = 128;
 constexpr int kNumXcd = 8;
 constexpr int kPackedSegsPerItem = 32;
 struct BlockItem {
@@ -55,15 +57,16 @@ struct KernelArgs {
   int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only; aop is SUM, MAX or MIN here
   int32_t mean;                     // PAT_RUNTIME: a row stored whole is divided by its length (mean pooling)
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
-  // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed).
+  // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed), rows without entries
+  // (zero fill only) from order[n_wave+n_packed .. n_wave+n_packed+n_empty).
   const int32_t* order;
   const ChunkDesc* chunks;
   const BlockItem* items;       // tiled region, nb_tiled entries
   const ChunkDesc* tile_descs;  // segments of tiled rows; part is always a partial row
   float* partials;
   uint32_t* visit_counts;
-  int32_t n_chunks, n_wave, n_packed;
-  int32_t nb_tiled, nb_chunk, nb_wave, nb_packed;
+  int32_t n_chunks, n_wave, n_packed, n_empty;
+  int32_t nb_tiled, nb_chunk, nb_wave, nb_packed, nb_zero;
 };
 
 // Column-class boundaries of the tiled rows.  Row rows[i] is cut into level[i] classes, each
