@@ -187,9 +187,10 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
 /* The same operation with Y stored as bfloat16 (the upper 16 bits of each fp32 value): the
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
  * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
- * 8-byte aligned: ldy % 4 == 0).  Only d in {32, 64, 128, 256, 512} with aligned operands
- * (FUSEDMM_ERR_UNSUPPORTED_DIM / FUSEDMM_ERR_INVALID_ARG otherwise).  The result equals
- * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back. */
+ * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes per lane).  Only d in {32, 64, 128, 256, 512} with aligned operands
+ * (FUSEDMM_ERR_UNSUPPORTED_DIM / FUSEDMM_ERR_INVALID_ARG otherwise).  The result is that of
+ * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back, up to the
+ * order of the fp32 sums (the lane groups are half as wide). */
 int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                           const float* d_values, const float* d_X, int64_t ldx,
                           const uint16_t* d_Y_bf16, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
@@ -201,7 +202,8 @@ int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* str
 /* The same again with Y stored in IEEE half precision (binary16: 11 significant bits instead of
  * bfloat16's 8, range up to 65504): same layout, alignment and error rules as fusedmm_execute_bf16y;
  * fusedmm_to_f16 converts with round to nearest even (values beyond the half range become infinity).
- * The result equals fusedmm_execute on the fp32 matrix whose entries are the half values widened back. */
+ * The result is that of fusedmm_execute on the fp32 matrix whose entries are the half values widened
+ * back, up to the order of the fp32 sums. */
 int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                          const float* d_values, const float* d_X, int64_t ldx,
                          const uint16_t* d_Y_f16, int64_t ldy, float* d_Z, int64_t ldz, void* stream);

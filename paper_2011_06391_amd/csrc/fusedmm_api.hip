@@ -126,7 +126,7 @@ int ensure_partials(fusedmm_plan* p, int32_t d) {
   return FUSEDMM_OK;
 }
 
-void fill_schedule_args(const fusedmm_plan* p, int32_t d, KernelArgs* a) {
+void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelArgs* a) {
   a->rowptr = p->d_rowptr;
   a->colidx = p->d_colidx;
   a->order = p->d_order;
@@ -143,7 +143,7 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, KernelArgs* a) {
   a->nb_zero = (p->n_empty + kZeroRowsPerBlock - 1) / kZeroRowsPerBlock;
   a->nb_chunk = p->n_chunks;
   a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int rpb = packed_rows_per_block(d);
+  const int rpb = packed_rows_per_block(d, y_format);
   a->nb_packed = rpb > 0 ? (p->n_packed + rpb - 1) / rpb : 0;
 }
 
@@ -547,7 +547,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   // structure with the ops decided at run time; odd shapes fall back to the general kernel
   const int recognised = recognise(*ops);
   const int pattern = recognised >= 0 ? recognised : PAT_RUNTIME;
-  const bool y_ok = plan->nnz == 0 || (y_bf16 ? ((reinterpret_cast<uintptr_t>(d_Y) & 7u) == 0 && ldy % 4 == 0)
+  const bool y_ok = plan->nnz == 0 || (y_bf16 ? (aligned16(d_Y) && ldy % 8 == 0)
                                               : (aligned16(d_Y) && ldy % 4 == 0));
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
   const bool fast = is_fast_dim(d) && ldy < (int64_t(1) << 29) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
@@ -566,7 +566,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     const int st = ensure_partials(plan, d);
     if (st != FUSEDMM_OK) return st;
     KernelArgs a;
-    fill_schedule_args(plan, d, &a);
+    fill_schedule_args(plan, d, y_format, &a);
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
@@ -673,7 +673,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
   hipError_t e;
   if (fast_path) {
     KernelArgs a;
-    fill_schedule_args(plan, d, &a);
+    fill_schedule_args(plan, d, kYF32, &a);
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;

@@ -131,6 +131,46 @@ __device__ __forceinline__ v4f gather4(const void* Y, int col, int64_t ldy, int 
   }
 }
 
+// Which 4-float piece of a row register i of lane g holds.  C = 1: piece g + G*i (a lane group reads
+// G consecutive 16-byte pieces per step).  C = 2 (rows of 2-byte elements read 16 bytes = 8 elements
+// at a time): registers 2j and 2j+1 hold the two pieces of chunk g + G*j.
+template <int G, int C>
+__device__ __forceinline__ int piece_index(int g, int i) {
+  if constexpr (C == 1) return g + G * i; else return 2 * (g + G * (i / 2)) + (i & 1);
+}
+
+// One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>.  With C = 2 a
+// lane fetches 16 bytes of 2-byte elements per load: half as many load instructions per row as
+// 8-byte loads need, and it is the number of load instructions that occupies the return path.
+template <int YF, int G, int V, int C>
+__device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, v4f (&y)[V]) {
+  if constexpr (C == 1) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) y[i] = gather4<YF>(a.Y, col, a.ldy, g + G * i);
+  } else {
+    static_assert(YF != kYF32 && V % 2 == 0, "16-byte chunks of 2-byte elements");
+    const uint32_t pitch = (uint32_t)a.ldy * 2u;
+    const char* base = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+#pragma unroll
+    for (int j = 0; j < V / 2; ++j) {
+      const char* p = base + (size_t)(g + G * j) * 16u;
+      if constexpr (YF == kYBf16) {
+        typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+        const v4u raw = *reinterpret_cast<const v4u*>(p);
+        y[2 * j] = v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
+                       __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
+        y[2 * j + 1] = v4f{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xffff0000u),
+                           __builtin_bit_cast(float, raw.w << 16), __builtin_bit_cast(float, raw.w & 0xffff0000u)};
+      } else {
+        typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+        const v8h raw = *reinterpret_cast<const v8h*>(p);
+        y[2 * j] = v4f{(float)raw.s0, (float)raw.s1, (float)raw.s2, (float)raw.s3};
+        y[2 * j + 1] = v4f{(float)raw.s4, (float)raw.s5, (float)raw.s6, (float)raw.s7};
+      }
+    }
+  }
+}
+
 // Loads of data that is read once (column indices, edge values, x_u).  A non-temporal hint
 // on them was measured: -1 % kernel time on the two largest workloads, +3..10 % on the two
 // where X aliases Y (x_u is then also somebody's y_v), so it is off.
@@ -290,7 +330,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 // One wavefront accumulates the stored entries [e0, e1) of a single row.  The S lane groups
 // take entries round-robin inside batches of 64; z holds this group's partial sum.
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int G, int U, int YF>
+template <int P, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
                                                 const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int lane) {
   constexpr int V = D / (4 * G);
@@ -323,10 +363,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + G * i);
-          }
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C>(a, c[u], g, y[u]);
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z);
         } else {
@@ -348,10 +385,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) {
-#pragma unroll
-              for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + G * i);
-            }
+            if (ok[u]) gather_row<YF, G, V, C>(a, c[u], g, y[u]);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z);
@@ -365,11 +399,11 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   }
 }
 
-template <int D, int G>
+template <int D, int G, int C>
 __device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
-  const float* xr = a.X + row * a.ldx + 4 * g;
+  const float* xr = a.X + row * a.ldx;
 #pragma unroll
-  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4_stream(xr + 4 * G * i);
+  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4_stream(xr + 4 * piece_index<G, C>(g, i));
 }
 
 template <int V>
@@ -384,11 +418,11 @@ __device__ __forceinline__ void scale(v4f (&z)[V], float f) {
   for (int i = 0; i < V; ++i) z[i] *= f;
 }
 
-template <int D, int G>
+template <int D, int G, int C>
 __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / (4 * G)]) {
 #pragma unroll
   for (int i = 0; i < D / (4 * G); ++i)
-    __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * g + 4 * G * i));
+    __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * piece_index<G, C>(g, i)));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -406,9 +440,14 @@ __device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / 
 // and then runs one of three bodies: chunk, wave segments, packed segments.  A segment is
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int GW, int UW, int GP, int UP, int YF>
+template <int P, int D, int GW0, int UW0, int GP0, int UP0, int YF>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   using T = PatTraits<P>;
+  // Rows of 2-byte elements are read 16 bytes per lane where the lane group can be halved (it must
+  // keep 8 lanes): same bytes in flight per wavefront, half as many load instructions.
+  constexpr bool kWideW = YF != kYF32 && GW0 >= 16, kWideP = YF != kYF32 && GP0 >= 16;
+  constexpr int GW = kWideW ? GW0 / 2 : GW0, UW = kWideW && UW0 > 1 ? UW0 / 2 : UW0, CW = kWideW ? 2 : 1;
+  constexpr int GP = kWideP ? GP0 / 2 : GP0, UP = kWideP && UP0 > 1 ? UP0 / 2 : UP0, CP = kWideP ? 2 : 1;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int b = blockIdx.x;
@@ -443,13 +482,13 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW>(a, ch.row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YF>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
+    if (reads_x<P>(a)) load_x<D, GW, CW>(a, ch.row, g, x); else zero(x);
+    wave_accumulate<P, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if (lane < GW) {
 #pragma unroll
-        for (int i = 0; i < V; ++i) stage[wave][g + GW * i] = z[i];
+        for (int i = 0; i < V; ++i) stage[wave][piece_index<GW, CW>(g, i)] = z[i];
       }
       __syncthreads();
       if (threadIdx.x < D / 4) {
@@ -490,14 +529,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW>(a, row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YF>(a, e0, e1, x, z, lane);
+    if (reads_x<P>(a)) load_x<D, GW, CW>(a, row, g, x); else zero(x);
+    wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if constexpr (P == PAT_RUNTIME) {
         if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
       }
-      if (lane < GW) store_row<D, GW>(dst, g, z);
+      if (lane < GW) store_row<D, GW, CW>(dst, g, z);
     }
   } else if (kind == kItemPacked) {
     // ---- one short segment per lane group ----------------------------------------------
@@ -529,7 +568,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
-        if (deg > 0) load_x<D, GP>(a, row, g, x);
+        if (deg > 0) load_x<D, GP, CP>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
       if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
@@ -561,10 +600,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
             for (int u = 0; u < UP; ++u) {
 #pragma unroll
               for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-              if (ok[u]) {
-#pragma unroll
-                for (int i = 0; i < V; ++i) y[u][i] = gather4<YF>(a.Y, c[u], a.ldy, g + GP * i);
-              }
+              if (ok[u]) gather_row<YF, GP, V, CP>(a, c[u], g, y[u]);
             }
 #pragma unroll
             for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a, ok[u], z);
@@ -579,7 +615,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         if constexpr (P == PAT_RUNTIME) {
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
         }
-        if (has_seg) store_row<D, GP>(dst, g, z);
+        if (has_seg) store_row<D, GP, CP>(dst, g, z);
       }
     }
   }

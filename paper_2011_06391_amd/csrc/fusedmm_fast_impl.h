@@ -16,7 +16,11 @@ static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-int FMM_CAT(packed_rows_per_block_d, FMM_D)() { return kWavesPerBlock * (64 / FMM_GP); }
+// rows of 2-byte elements use lane groups half as wide where that leaves 8 lanes (see the kernel)
+int FMM_CAT(packed_rows_per_block_d, FMM_D)(int y_format) {
+  const int gp = (y_format != kYF32 && FMM_GP >= 16) ? FMM_GP / 2 : FMM_GP;
+  return kWavesPerBlock * (64 / gp);
+}
 
 template <int YF>
 static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t stream) {

@@ -247,17 +247,17 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
   hipError_t launch_fast_d##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
-  int packed_rows_per_block_d##D();
+  int packed_rows_per_block_d##D(int y_format);
 FMM_DECL(32) FMM_DECL(64) FMM_DECL(128) FMM_DECL(256) FMM_DECL(512)
 #undef FMM_DECL
 
-int packed_rows_per_block(int d) {
+int packed_rows_per_block(int d, int y_format) {
   switch (d) {
-    case 32: return packed_rows_per_block_d32();
-    case 64: return packed_rows_per_block_d64();
-    case 128: return packed_rows_per_block_d128();
-    case 256: return packed_rows_per_block_d256();
-    case 512: return packed_rows_per_block_d512();
+    case 32: return packed_rows_per_block_d32(y_format);
+    case 64: return packed_rows_per_block_d64(y_format);
+    case 128: return packed_rows_per_block_d128(y_format);
+    case 256: return packed_rows_per_block_d256(y_format);
+    case 512: return packed_rows_per_block_d512(y_format);
     default: return 0;
   }
 }

@@ -77,8 +77,8 @@ hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, cons
                               const int64_t* out_off, int32_t n_rows, int32_t n_classes, int64_t class_width,
                               int32_t* bounds, int32_t* unsorted, hipStream_t stream);
 
-// Rows per workgroup in the packed range for dimension d (host needs it for the grid).
-int packed_rows_per_block(int d);
+// Rows per workgroup in the packed range for dimension d and storage format of Y (host needs it for the grid).
+int packed_rows_per_block(int d, int y_format);
 
 // Storage formats of Y the specialised kernels read (arithmetic is fp32 in all of them).
 enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2 };

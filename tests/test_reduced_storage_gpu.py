@@ -120,7 +120,9 @@ def test_half_storage_parity(B, pattern, d):
         Z32 = torch.empty_like(Z)
         plan.execute(ops, None if pattern == "gcn" else Xd, torch.from_numpy(Yr).cuda(), Z32, vd)
         torch.cuda.synchronize()
-        assert torch.equal(Z, Z32)        # same numbers as the fp32 entry point on the widened matrix
+        # the fp32 entry point on the widened matrix computes the same sums in another order
+        e32, _, _ = oracle.compare(Z.cpu().numpy(), Z32.cpu().numpy().astype(np.float64), S)
+        assert e32 <= TOL
         plan.close()
 
 
@@ -157,11 +159,12 @@ def test_bf16_storage_parity(B, pattern, d):
         torch.cuda.synchronize()
         err, am, viol = oracle.compare(Z.cpu().numpy(), Zr, S)
         assert viol == 0 and err <= TOL, f"{pattern} d={d} {options}: err {err:.3e} at {am}, viol {viol}"
-        # the fp32 entry point on the widened matrix gives the same numbers bit for bit
+        # the fp32 entry point on the widened matrix computes the same sums in another order
         Z32 = torch.empty_like(Z)
         plan.execute(ops, None if pattern == "gcn" else Xd, torch.from_numpy(Yr).cuda(), Z32, vd)
         torch.cuda.synchronize()
-        assert torch.equal(Z, Z32)
+        e32, _, _ = oracle.compare(Z.cpu().numpy(), Z32.cpu().numpy().astype(np.float64), S)
+        assert e32 <= TOL
         plan.close()
 
 
