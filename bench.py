@@ -146,7 +146,8 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    kernel_ms_sum, empty_ms_sum, calls = plan.read_profile()
+    samples, empties = plan.read_profile_samples()
+    kernel_ms_sum, empty_ms_sum, calls = sum(samples), sum(empties), len(samples)
     plan.set_profiling(False)
     assert torch.isfinite(Z[: min(g.m, 4096)]).all().item()
     deg = g.degrees()
@@ -184,6 +185,9 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                      "kernel_timing": "HIP events around the main kernel on the launch stream, same K executes repeated "
                                       "right after the timed region; an empty event bracket per call is subtracted",
                      "kernel_ms_with_bracket": kernel_ms_sum / max(1, calls),
+                     "kernel_ms_median": (sorted(samples)[len(samples) // 2] - sorted(empties)[len(empties) // 2])
+                     if samples else None,
+                     "kernel_ms_min": (min(samples) - sorted(empties)[len(empties) // 2]) if samples else None,
                      "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
                      "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
     }

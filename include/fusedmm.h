@@ -236,6 +236,10 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
 int fusedmm_plan_set_profiling(fusedmm_plan_t* plan, int32_t enabled);
 int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, double* empty_bracket_ms_sum,
                               int64_t* calls);
+/* The same record call by call (for medians): fills at most `capacity` entries of both host arrays,
+ * returns how many in *calls, then clears the record. */
+int fusedmm_plan_read_profile_samples(fusedmm_plan_t* plan, double* main_kernel_ms, double* empty_bracket_ms,
+                                      int64_t capacity, int64_t* calls);
 
 /* Measurement aid: a plain grid-stride copy kernel, dst[i] = src[i] for `bytes` bytes
  * (device pointers, 16-byte aligned, bytes a multiple of 16, non-overlapping),

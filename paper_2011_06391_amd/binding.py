@@ -35,6 +35,7 @@ EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
     "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
+    "fusedmm_plan_read_profile_samples",
     "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
     "fusedmm_to_bf16", "fusedmm_execute_f16y", "fusedmm_to_f16", "fusedmm_execute_f64",
     "fusedmm_minibatch_create", "fusedmm_minibatch_reserve", "fusedmm_minibatch_epoch",
@@ -112,6 +113,9 @@ def load():
     lib.fusedmm_plan_read_profile.restype = ctypes.c_int
     lib.fusedmm_plan_read_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                               ctypes.POINTER(i64)]
+    lib.fusedmm_plan_read_profile_samples.restype = ctypes.c_int
+    lib.fusedmm_plan_read_profile_samples.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                                      i64, ctypes.POINTER(i64)]
     lib.fusedmm_debug_copy.restype = ctypes.c_int
     lib.fusedmm_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_plan_destroy.restype = ctypes.c_int
@@ -264,6 +268,16 @@ def fusedmm_plan_read_profile(plan):
     return float(ms.value), float(empty.value), int(calls.value)
 
 
+def fusedmm_plan_read_profile_samples(plan, capacity: int = 4096):
+    """(list of main-kernel ms incl. bracket cost, list of empty-bracket ms), one entry per timed call."""
+    ms = (ctypes.c_double * capacity)()
+    empty = (ctypes.c_double * capacity)()
+    calls = ctypes.c_int64()
+    _check(load().fusedmm_plan_read_profile_samples(plan, ms, empty, capacity, ctypes.byref(calls)),
+           "fusedmm_plan_read_profile_samples")
+    return list(ms[:calls.value]), list(empty[:calls.value])
+
+
 def fusedmm_debug_copy(d_dst, d_src, nbytes: int, stream=None) -> None:
     _check(load().fusedmm_debug_copy(_dptr(d_dst), _dptr(d_src), nbytes, _stream(stream)), "fusedmm_debug_copy")
 
@@ -389,6 +403,9 @@ class Plan:
 
     def read_profile(self):
         return fusedmm_plan_read_profile(self._plan)
+
+    def read_profile_samples(self):
+        return fusedmm_plan_read_profile_samples(self._plan)
 
     def close(self) -> None:
         if self._plan is not None:

@@ -731,6 +731,24 @@ int fusedmm_plan_read_profile(fusedmm_plan_t* plan, double* main_kernel_ms_sum, 
   return FUSEDMM_OK;
 }
 
+int fusedmm_plan_read_profile_samples(fusedmm_plan_t* plan, double* main_kernel_ms, double* empty_bracket_ms,
+                                      int64_t capacity, int64_t* calls) {
+  if (!plan || !main_kernel_ms || !empty_bracket_ms || !calls || capacity < 0) return FUSEDMM_ERR_INVALID_ARG;
+  const size_t n = plan->events_used < (size_t)capacity ? plan->events_used : (size_t)capacity;
+  for (size_t i = 0; i < n; ++i) {
+    const auto& ev = plan->events[i];
+    if (hipEventSynchronize(ev.after2) != hipSuccess) return FUSEDMM_ERR_HIP;
+    float ms = 0.f, ms0 = 0.f;
+    if (hipEventElapsedTime(&ms, ev.before, ev.after) != hipSuccess) return FUSEDMM_ERR_HIP;
+    if (hipEventElapsedTime(&ms0, ev.after, ev.after2) != hipSuccess) return FUSEDMM_ERR_HIP;
+    main_kernel_ms[i] = ms;
+    empty_bracket_ms[i] = ms0;
+  }
+  *calls = (int64_t)n;
+  plan->events_used = 0;
+  return FUSEDMM_OK;
+}
+
 int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz, const int64_t* d_rowptr,
                               const int32_t* d_colidx, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
                               const float* d_X, int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz,
