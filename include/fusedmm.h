@@ -262,13 +262,16 @@ int fusedmm_plan_destroy(fusedmm_plan_t* plan);
  *     X[B_i] <- X[B_i] + lr * (Zpos - Zneg)
  * N_i is the |B_i| x n pattern whose every row holds the n_negative sample columns of batch i.
  * Both calls of a batch read X as the earlier batches left it; the rows of the batch are written
- * after both have finished (stream order), so results do not depend on scheduling.
+ * after both have finished (stream order), so results do not depend on scheduling.  The library
+ * issues the two calls as one FusedMM over the concatenated pattern [A[B_i, :] | N_i] with the scaling
+ * step h = a - SIGMOID(s), a = 1 on stored entries and 0 on samples (the same sum, Zpos - Zneg).
  *
- * create : d_rowptr (n+1 int64, device), d_colidx (nnz int32, device) as for fusedmm_plan_create and
- *          borrowed for the life of the handle; d_negatives: device, n_batches * n_negative int32,
- *          batch-major, read once here (copied), may be NULL when n_negative == 0.  Builds two plans
- *          per batch; synchronises the stream.  Samples outside [0, n) -> FUSEDMM_ERR_INVALID_ARG.
- * reserve: allocates the two batch_rows x d result buffers and the plans' scratch for dimension d,
+ * create : d_rowptr (n+1 int64, device), d_colidx (nnz int32, device) as for fusedmm_plan_create;
+ *          d_negatives: device, n_batches * n_negative int32, batch-major, may be NULL when
+ *          n_negative == 0.  All three are read once here (the handle keeps its own concatenated
+ *          copies and does not refer to them afterwards).  Builds one plan per batch; synchronises
+ *          the stream.  Samples outside [0, n) -> FUSEDMM_ERR_INVALID_ARG.
+ * reserve: allocates the batch_rows x d result buffer and the plans' scratch for dimension d,
  *          so that fusedmm_minibatch_epoch allocates nothing afterwards (e.g. under stream capture).
  * epoch  : one pass over all batches, asynchronous on `stream`, in place on d_X (n rows, leading
  *          dimension ldx >= d).  Any 1 <= d <= FUSEDMM_MAX_D; d in {32,...,512} with 16-byte aligned

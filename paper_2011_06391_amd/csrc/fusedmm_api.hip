@@ -48,7 +48,10 @@ constexpr size_t kMaxProfiledCalls = 4096;
 
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
 
-bool ops_valid(const fusedmm_ops_t& o) {
+bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
+  if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value
+    return o.vop >= FUSEDMM_VOP_MUL && o.vop <= FUSEDMM_VOP_ADD && o.rop > FUSEDMM_ROP_NOOP && o.rop <= FUSEDMM_ROP_RMUL &&
+           o.mop >= FUSEDMM_MOP_MUL_Y && o.mop <= FUSEDMM_MOP_SEL2ND && o.aop >= FUSEDMM_AOP_SUM && o.aop <= FUSEDMM_AOP_MEAN;
   if (o.vop < FUSEDMM_VOP_MUL || o.vop > FUSEDMM_VOP_ADD) return false;
   if (o.rop < FUSEDMM_ROP_NOOP || o.rop > FUSEDMM_ROP_RMUL) return false;
   if (o.sop < FUSEDMM_SOP_EDGE_VALUE || o.sop > FUSEDMM_SOP_NOOP) return false;
@@ -61,6 +64,7 @@ bool ops_valid(const fusedmm_ops_t& o) {
 int recognise(const fusedmm_ops_t& o) {
   if (o.aop != FUSEDMM_AOP_SUM) return -1;
   if (o.vop == FUSEDMM_VOP_MUL && o.rop == FUSEDMM_ROP_RSUM && o.mop == FUSEDMM_MOP_MUL_Y) {
+    if (o.sop == kSopValueMinusSigmoid) return PAT_SIGNED_SIGMOID;
     if (o.sop == FUSEDMM_SOP_SIGMOID) return PAT_SIGMOID;
     if (o.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID) return PAT_ONE_MINUS_SIGMOID;
   }
@@ -518,13 +522,14 @@ namespace {
 // Shared body of fusedmm_execute, fusedmm_execute_bf16y and fusedmm_execute_f16y.  y_format other than
 // kYF32: d_Y points at rows of 2-byte elements (ldy in elements); only the fast instances exist for those.
 int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
-                 int64_t ldx, const void* d_Y, int y_format, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
+                 int64_t ldx, const void* d_Y, int y_format, int64_t ldy, float* d_Z, int64_t ldz, void* stream_,
+                 bool allow_private = false) {
   const bool y_bf16 = y_format != kYF32;  // any 2-byte storage
   if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  if (!ops_valid(*ops)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
+  if (!ops_valid(*ops, allow_private)) return FUSEDMM_ERR_UNSUPPORTED_OPS;
   const bool uses_x = ops->vop != FUSEDMM_VOP_SEL2ND;
-  const bool uses_val = ops->sop == FUSEDMM_SOP_EDGE_VALUE;
+  const bool uses_val = ops->sop == FUSEDMM_SOP_EDGE_VALUE || ops->sop == kSopValueMinusSigmoid;
   if (plan->m == 0) return FUSEDMM_OK;
   if (!d_Z || ldz < d) return FUSEDMM_ERR_INVALID_ARG;
   if (plan->nnz > 0) {
@@ -595,6 +600,16 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 }
 
 }  // namespace
+
+}  // extern "C"
+
+int fusedmm_execute_private_ops(fusedmm_plan* plan, const fusedmm_ops* ops, int32_t d, const float* d_values,
+                                const float* d_X, int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz,
+                                void* stream) {
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, kYF32, ldy, d_Z, ldz, stream, true);
+}
+
+extern "C" {
 
 int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
                     int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {

@@ -199,7 +199,7 @@ __device__ __forceinline__ v4f ld4_stream(const float* p) {
 template <int P>
 struct PatTraits {
   static constexpr bool uses_x = (P != PAT_GCN && P != PAT_VISIT);
-  static constexpr bool uses_val = (P == PAT_GCN);
+  static constexpr bool uses_val = (P == PAT_GCN || P == PAT_SIGNED_SIGMOID);
   static constexpr bool loads_y = (P != PAT_VISIT);
 };
 // whether x_u / the edge values are read: fixed per pattern, a (uniform) run-time fact for PAT_RUNTIME
@@ -209,7 +209,8 @@ __device__ __forceinline__ bool reads_x(const KernelArgs& a) {
 }
 template <int P>
 __device__ __forceinline__ bool reads_values(const KernelArgs& a) {
-  if constexpr (P == PAT_RUNTIME) return a.sop == FUSEDMM_SOP_EDGE_VALUE; else return PatTraits<P>::uses_val;
+  if constexpr (P == PAT_RUNTIME) return a.sop == FUSEDMM_SOP_EDGE_VALUE || a.sop == kSopValueMinusSigmoid;
+  else return PatTraits<P>::uses_val;
 }
 
 __device__ __forceinline__ float rt_vop(int vop, float x, float y) {
@@ -265,7 +266,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
         s = group_allreduce<G>(p);
         if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
       }
-      h = rt_sop(a.sop, s, alpha);
+      h = a.sop == kSopValueMinusSigmoid ? aval - rt_sop(FUSEDMM_SOP_SIGMOID, s, alpha) : rt_sop(a.sop, s, alpha);
     }
 #pragma unroll
     for (int i = 0; i < V; ++i) {
@@ -291,7 +292,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) z[i] += h * y[i];
-  } else if constexpr (P == PAT_SIGMOID || P == PAT_ONE_MINUS_SIGMOID) {
+  } else if constexpr (P == PAT_SIGMOID || P == PAT_ONE_MINUS_SIGMOID || P == PAT_SIGNED_SIGMOID) {
     float p = 0.f;  // VOP = MUL and this lane's share of ROP = RSUM
 #pragma unroll
     for (int i = 0; i < V; ++i) {
@@ -302,8 +303,9 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     }
     const float s = group_allreduce<G>(p);
     // SOP: sigma(s) = 1/(1+2^(-s log2 e)); 1-sigma(s) = sigma(-s).  2^big = inf -> h = 0, no NaN.
-    const float e = __builtin_amdgcn_exp2f(P == PAT_SIGMOID ? -s * kLog2e : s * kLog2e);
+    const float e = __builtin_amdgcn_exp2f(P == PAT_ONE_MINUS_SIGMOID ? s * kLog2e : -s * kLog2e);
     float h = __builtin_amdgcn_rcpf(1.0f + e);
+    if constexpr (P == PAT_SIGNED_SIGMOID) h = aval - h;  // 1 - sigmoid on stored entries, -sigmoid on samples
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) z[i] += h * y[i];  // MOP = MUL with y_v, AOP = SUM

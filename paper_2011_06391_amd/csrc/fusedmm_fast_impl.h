@@ -34,6 +34,9 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
     case PAT_VISIT:  // the edge-visit instance reads no Y: one form is enough
       if constexpr (YF == kYF32) return launch_one<PAT_VISIT, kYF32>(a, stream);
       return hipErrorInvalidValue;
+    case PAT_SIGNED_SIGMOID:  // used by the minibatch layer on fp32 embeddings only
+      if constexpr (YF == kYF32) return launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
+      return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }

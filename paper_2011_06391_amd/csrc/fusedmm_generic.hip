@@ -89,7 +89,8 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
       }
       T s = (a.rop == FUSEDMM_ROP_RMUL) ? wave_allreduce_mul<T>(p) : wave_allreduce<T>(p);
       if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_of(s);
-      h = sop_apply<T>(a.sop, s, a.alpha);  // SOP on the scalar
+      h = a.sop == kSopValueMinusSigmoid ? a.values[e] - sop_apply<T>(FUSEDMM_SOP_SIGMOID, s, a.alpha)
+                                         : sop_apply<T>(a.sop, s, a.alpha);  // SOP on the scalar
     }
 #pragma unroll
     for (int i = 0; i < kGenericAcc; ++i) {

@@ -7,7 +7,9 @@ namespace fmm {
 
 // Pattern ids of the specialised kernels (host dispatch -> template instance).
 // PAT_RUNTIME: the same kernel structure with the five ops read from KernelArgs at run time (any valid tuple).
-enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6 };
+// PAT_SIGNED_SIGMOID: the sigmoid embedding pattern with the scaling step h = a_uv - sigmoid(s) (kSopValueMinusSigmoid).
+enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6,
+             PAT_SIGNED_SIGMOID = 7 };
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
@@ -80,6 +82,12 @@ hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, cons
 // Rows per workgroup in the packed range for dimension d and storage format of Y (host needs it for the grid).
 int packed_rows_per_block(int d, int y_format);
 
+// A scaling step outside the public selector, used by the minibatch layer (the paper's SOP is
+// user-definable, Section III-A): h = a_uv - sigmoid(s), which with a_uv = 1 on the stored entries of
+// A and a_uv = 0 on negative samples makes attraction and repulsion one FusedMM call.
+constexpr int kSopValueMinusSigmoid = 100;
+
+
 // Storage formats of Y the specialised kernels read (arithmetic is fp32 in all of them).
 enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2 };
 
@@ -124,3 +132,11 @@ hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n,
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
 }  // namespace fmm
+
+// fusedmm_execute for callers inside the library: also accepts fmm::kSopValueMinusSigmoid (needs d_values).
+struct fusedmm_plan;
+struct fusedmm_ops;
+__attribute__((visibility("hidden"))) int fusedmm_execute_private_ops(fusedmm_plan* plan, const fusedmm_ops* ops,
+                                                                      int32_t d, const float* d_values, const float* d_X,
+                                                                      int64_t ldx, const float* d_Y, int64_t ldy,
+                                                                      float* d_Z, int64_t ldz, void* stream);
