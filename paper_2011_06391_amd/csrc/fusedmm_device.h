@@ -238,14 +238,25 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
   constexpr float kLog2e = 1.4426950408889634f;
   const float alpha = a.alpha;
   if constexpr (P == PAT_RUNTIME) {
-    // every op of the selector, decided by wave-uniform branches: the five steps in order
+    // Every op of the selector, the five steps in order.  The selectors are wave-uniform, so each
+    // step is one scalar branch around a loop over this lane's elements, not a choice per element.
     v4f t[V];
+    switch (a.vop) {  // VOP
+      case FUSEDMM_VOP_MUL:
 #pragma unroll
-    for (int i = 0; i < V; ++i) {  // VOP
-      t[i].x = rt_vop(a.vop, x[i].x, y[i].x);
-      t[i].y = rt_vop(a.vop, x[i].y, y[i].y);
-      t[i].z = rt_vop(a.vop, x[i].z, y[i].z);
-      t[i].w = rt_vop(a.vop, x[i].w, y[i].w);
+        for (int i = 0; i < V; ++i) t[i] = x[i] * y[i];
+        break;
+      case FUSEDMM_VOP_SEL2ND:
+#pragma unroll
+        for (int i = 0; i < V; ++i) t[i] = y[i];
+        break;
+      case FUSEDMM_VOP_SUB:
+#pragma unroll
+        for (int i = 0; i < V; ++i) t[i] = x[i] - y[i];
+        break;
+      default:
+#pragma unroll
+        for (int i = 0; i < V; ++i) t[i] = x[i] + y[i];
     }
     const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
     float h = aval;
@@ -256,33 +267,87 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 #pragma unroll
         for (int i = 0; i < V; ++i) p *= t[i].x * t[i].y * t[i].z * t[i].w;
         s = group_allreduce_mul<G>(p);
+      } else if (a.rop == FUSEDMM_ROP_RSUM) {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) p += (t[i].x + t[i].y) + (t[i].z + t[i].w);
+        s = group_allreduce<G>(p);
       } else {
         float p = 0.f;
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-          if (a.rop == FUSEDMM_ROP_RSUM) p += (t[i].x + t[i].y) + (t[i].z + t[i].w);
-          else p += (t[i].x * t[i].x + t[i].y * t[i].y) + (t[i].z * t[i].z + t[i].w * t[i].w);
-        }
+        for (int i = 0; i < V; ++i) p += (t[i].x * t[i].x + t[i].y * t[i].y) + (t[i].z * t[i].z + t[i].w * t[i].w);
         s = group_allreduce<G>(p);
         if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
       }
       h = a.sop == kSopValueMinusSigmoid ? aval - rt_sop(FUSEDMM_SOP_SIGMOID, s, alpha) : rt_sop(a.sop, s, alpha);
     }
+    v4f w[V];
+    if (scalar_h) {  // MOP with a scalar message
+      if (a.mop == FUSEDMM_MOP_SEL2ND) {
 #pragma unroll
-    for (int i = 0; i < V; ++i) {
-      v4f hv;  // SOP on each element when the message is a vector
-      if (scalar_h) {
-        hv = v4f{h, h, h, h};
+        for (int i = 0; i < V; ++i) w[i] = y[i];
+      } else if (a.mop == FUSEDMM_MOP_MUL_Y) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = h * y[i];
       } else {
-        hv.x = rt_sop(a.sop, t[i].x, alpha); hv.y = rt_sop(a.sop, t[i].y, alpha);
-        hv.z = rt_sop(a.sop, t[i].z, alpha); hv.w = rt_sop(a.sop, t[i].w, alpha);
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = h * t[i];
       }
-      v4f w = a.mop == FUSEDMM_MOP_SEL2ND ? y[i] : (a.mop == FUSEDMM_MOP_MUL_Y ? hv * y[i] : hv * t[i]);  // MOP
-      if (CHECK && !valid) w = v4f{0.f, 0.f, 0.f, 0.f};  // 0 is neutral for SUM and, from a zero start, for MAX and MIN
-      z[i].x = aop_apply(a.aop, z[i].x, w.x);  // AOP
-      z[i].y = aop_apply(a.aop, z[i].y, w.y);
-      z[i].z = aop_apply(a.aop, z[i].z, w.z);
-      z[i].w = aop_apply(a.aop, z[i].w, w.w);
+    } else {  // vector message: SOP on every element of t, then MOP element by element
+      v4f hv[V];
+      switch (a.sop) {
+        case FUSEDMM_SOP_SIGMOID:
+#pragma unroll
+          for (int i = 0; i < V; ++i)
+            hv[i] = v4f{rt_sop(FUSEDMM_SOP_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_SIGMOID, t[i].y, alpha),
+                        rt_sop(FUSEDMM_SOP_SIGMOID, t[i].z, alpha), rt_sop(FUSEDMM_SOP_SIGMOID, t[i].w, alpha)};
+          break;
+        case FUSEDMM_SOP_ONE_MINUS_SIGMOID:
+#pragma unroll
+          for (int i = 0; i < V; ++i)
+            hv[i] = v4f{rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].y, alpha),
+                        rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].z, alpha), rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].w, alpha)};
+          break;
+        case FUSEDMM_SOP_INV_1P:
+#pragma unroll
+          for (int i = 0; i < V; ++i)
+            hv[i] = v4f{rt_sop(FUSEDMM_SOP_INV_1P, t[i].x, alpha), rt_sop(FUSEDMM_SOP_INV_1P, t[i].y, alpha),
+                        rt_sop(FUSEDMM_SOP_INV_1P, t[i].z, alpha), rt_sop(FUSEDMM_SOP_INV_1P, t[i].w, alpha)};
+          break;
+        case FUSEDMM_SOP_SCAL:
+#pragma unroll
+          for (int i = 0; i < V; ++i) hv[i] = alpha * t[i];
+          break;
+        default:
+#pragma unroll
+          for (int i = 0; i < V; ++i) hv[i] = t[i];
+      }
+      if (a.mop == FUSEDMM_MOP_SEL2ND) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = y[i];
+      } else if (a.mop == FUSEDMM_MOP_MUL_Y) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = hv[i] * y[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = hv[i] * t[i];
+      }
+    }
+    if (CHECK && !valid) {  // 0 is neutral for SUM and, from a zero start, for MAX and MIN
+#pragma unroll
+      for (int i = 0; i < V; ++i) w[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+    if (a.aop == FUSEDMM_AOP_SUM) {  // AOP
+#pragma unroll
+      for (int i = 0; i < V; ++i) z[i] += w[i];
+    } else if (a.aop == FUSEDMM_AOP_MAX) {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        z[i] = v4f{fmaxf(z[i].x, w[i].x), fmaxf(z[i].y, w[i].y), fmaxf(z[i].z, w[i].z), fmaxf(z[i].w, w[i].w)};
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i)
+        z[i] = v4f{fminf(z[i].x, w[i].x), fminf(z[i].y, w[i].y), fminf(z[i].z, w[i].z), fminf(z[i].w, w[i].w)};
     }
     return;
   }
