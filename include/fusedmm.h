@@ -87,8 +87,11 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
 /* The op selector.  Every combination of the values above is valid except that
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
  * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
- * The five application patterns below run the specialised kernels (d in {32,...,512}); every
- * other tuple runs the general kernel (one wavefront per row, any d up to FUSEDMM_MAX_D). */
+ * The five application patterns below run the specialised kernels when d is 32, 64, 128, 256 or
+ * 512; every other tuple, and every other d that is a multiple of 4 up to 512, runs the same
+ * schedule with the ops read at run time (on the next larger kernel size, skipping the columns
+ * beyond d); any other d up to FUSEDMM_MAX_D, or operands that are not 16-byte aligned, run the
+ * general kernel (one wavefront per row, no row splitting: a correctness path). */
 typedef struct fusedmm_ops {
   int32_t vop, rop, sop, mop, aop;
   float alpha; /* used by FUSEDMM_SOP_SCAL only */

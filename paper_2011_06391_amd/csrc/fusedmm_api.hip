@@ -48,6 +48,16 @@ constexpr size_t kMaxProfiledCalls = 4096;
 
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
 
+// The instance size a dimension runs on: itself if it has instances of its own, else the next larger
+// one (multiples of 4 up to 512: the run-time-ops instance then skips the pieces beyond d), else 0.
+int32_t instance_dim(int32_t d) {
+  if (is_fast_dim(d)) return d;
+  if (d < 4 || d > 512 || d % 4 != 0) return 0;
+  int32_t D = 32;
+  while (D < d) D *= 2;
+  return D;
+}
+
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value
     return o.vop >= FUSEDMM_VOP_MUL && o.vop <= FUSEDMM_VOP_ADD && o.rop > FUSEDMM_ROP_NOOP && o.rop <= FUSEDMM_ROP_RMUL &&
@@ -488,7 +498,7 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
 int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  return is_fast_dim(d) ? ensure_partials(plan, d) : FUSEDMM_OK;
+  return instance_dim(d) ? ensure_partials(plan, instance_dim(d)) : FUSEDMM_OK;
 }
 
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
@@ -497,7 +507,7 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
   size_t b = (size_t)(plan->n_wave + plan->n_packed + plan->n_empty) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
              (size_t)plan->n_merges * sizeof(MergeDesc) + (size_t)plan->n_items * sizeof(BlockItem) +
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
-  if (is_fast_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(d, plan->partials_d) * sizeof(float);
+  if (instance_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(instance_dim(d), plan->partials_d) * sizeof(float);
   *out = b;
   return FUSEDMM_OK;
 }
@@ -550,12 +560,14 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
   // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
   // structure with the ops decided at run time; odd shapes fall back to the general kernel
+  // a dimension between two instance sizes runs the run-time-ops instance of the next larger size (fp32 storage only)
+  const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);
-  const int pattern = recognised >= 0 ? recognised : PAT_RUNTIME;
+  const int pattern = (recognised >= 0 && D == d) ? recognised : PAT_RUNTIME;
   const bool y_ok = plan->nnz == 0 || (y_bf16 ? (aligned16(d_Y) && ldy % 8 == 0)
                                               : (aligned16(d_Y) && ldy % 4 == 0));
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
-  const bool fast = is_fast_dim(d) && ldy < (int64_t(1) << 29) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
+  const bool fast = D != 0 && ldy < (int64_t(1) << 29) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
                     (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
   if (y_bf16 && !fast) return is_fast_dim(d) ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 
@@ -568,10 +580,11 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
   hipError_t e = hipSuccess;
   if (fast) {
-    const int st = ensure_partials(plan, d);
+    const int st = ensure_partials(plan, D);
     if (st != FUSEDMM_OK) return st;
     KernelArgs a;
-    fill_schedule_args(plan, d, y_format, &a);
+    fill_schedule_args(plan, D, y_format, &a);
+    a.d_pieces = d / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
@@ -579,10 +592,11 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     a.mean = ops->aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
     a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;
     if (ev0) (void)hipEventRecord(ev0, stream);
-    e = launch_fast(pattern, d, y_format, a, stream);
+    e = launch_fast(pattern, D, y_format, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
-    // partial rows are stored densely with stride d, whatever the scratch capacity is
-    if (e == hipSuccess) e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
+    // partial rows are stored with the instance size as their stride, whatever the scratch capacity is
+    if (e == hipSuccess)
+      e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, D, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
   } else {
     GenericArgs g;
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
@@ -681,20 +695,22 @@ int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* str
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path, uint32_t* d_counts, void* stream_) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  if (fast_path && !is_fast_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (fast_path && !instance_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   if (plan->m == 0 || plan->nnz == 0) return FUSEDMM_OK;
   if (!d_counts) return FUSEDMM_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   hipError_t e;
   if (fast_path) {
     KernelArgs a;
-    fill_schedule_args(plan, d, kYF32, &a);
+    const int32_t D = instance_dim(d);
+    fill_schedule_args(plan, D, kYF32, &a);
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
+    a.d_pieces = d / 4;
     a.visit_counts = d_counts;
-    e = launch_fast(PAT_VISIT, d, kYF32, a, stream);
+    e = launch_fast(PAT_VISIT, D, kYF32, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;

@@ -142,17 +142,26 @@ __device__ __forceinline__ int piece_index(int g, int i) {
 // One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>.  With C = 2 a
 // lane fetches 16 bytes of 2-byte elements per load: half as many load instructions per row as
 // 8-byte loads need, and it is the number of load instructions that occupies the return path.
-template <int YF, int G, int V, int C>
+// M: pieces at or beyond a.d_pieces are left at zero instead of being loaded (the run-time-ops instance
+// on a dimension below its own).
+template <int YF, int G, int V, int C, bool M>
 __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, v4f (&y)[V]) {
   if constexpr (C == 1) {
 #pragma unroll
-    for (int i = 0; i < V; ++i) y[i] = gather4<YF>(a.Y, col, a.ldy, g + G * i);
+    for (int i = 0; i < V; ++i) {
+      if (!M || g + G * i < a.d_pieces) y[i] = gather4<YF>(a.Y, col, a.ldy, g + G * i);
+      else y[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
   } else {
     static_assert(YF != kYF32 && V % 2 == 0, "16-byte chunks of 2-byte elements");
     const uint32_t pitch = (uint32_t)a.ldy * 2u;
     const char* base = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
 #pragma unroll
     for (int j = 0; j < V / 2; ++j) {
+      if (M && 2 * (g + G * j) + 1 >= a.d_pieces) {
+        y[2 * j] = y[2 * j + 1] = v4f{0.f, 0.f, 0.f, 0.f};
+        continue;
+      }
       const char* p = base + (size_t)(g + G * j) * 16u;
       if constexpr (YF == kYBf16) {
         typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -234,7 +243,7 @@ __device__ __forceinline__ float rt_sop(int sop, float s, float alpha) {
 
 template <int P, int G, int V, bool CHECK>
 __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V], float aval, const KernelArgs& a,
-                                            bool valid, v4f (&z)[V]) {
+                                            bool valid, v4f (&z)[V], int nv = V) {
   constexpr float kLog2e = 1.4426950408889634f;
   const float alpha = a.alpha;
   if constexpr (P == PAT_RUNTIME) {
@@ -263,9 +272,9 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     if (a.sop != FUSEDMM_SOP_EDGE_VALUE && a.rop != FUSEDMM_ROP_NOOP) {  // ROP, then SOP on the scalar
       float s;
       if (a.rop == FUSEDMM_ROP_RMUL) {
-        float p = 1.f;
+        float p = 1.f;  // registers beyond the row's width hold padding, not factors
 #pragma unroll
-        for (int i = 0; i < V; ++i) p *= t[i].x * t[i].y * t[i].z * t[i].w;
+        for (int i = 0; i < V; ++i) p *= i < nv ? t[i].x * t[i].y * t[i].z * t[i].w : 1.f;
         s = group_allreduce_mul<G>(p);
       } else if (a.rop == FUSEDMM_ROP_RSUM) {
         float p = 0.f;
@@ -407,6 +416,12 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   const int slot = lane / G;
   const int g = lane % G;
   const bool use_val = reads_values<P>(a);
+  int nv = V;  // registers of this lane that hold elements of the row (all of them unless the row is narrower)
+  if constexpr (P == PAT_RUNTIME) {
+    nv = 0;
+#pragma unroll
+    for (int i = 0; i < V; ++i) nv += piece_index<G, C>(g, i) < a.d_pieces ? 1 : 0;
+  }
 
   for (int64_t base = e0; base < e1; base += 64) {
     const int cnt = (int)((e1 - base) < 64 ? (e1 - base) : 64);  // wave-uniform
@@ -430,9 +445,9 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C>(a, c[u], g, y[u]);
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -452,10 +467,10 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) gather_row<YF, G, V, C>(a, c[u], g, y[u]);
+            if (ok[u]) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -466,11 +481,14 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   }
 }
 
-template <int D, int G, int C>
+template <int D, int G, int C, bool M>
 __device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
   const float* xr = a.X + row * a.ldx;
 #pragma unroll
-  for (int i = 0; i < D / (4 * G); ++i) x[i] = ld4_stream(xr + 4 * piece_index<G, C>(g, i));
+  for (int i = 0; i < D / (4 * G); ++i) {
+    const int p = piece_index<G, C>(g, i);
+    if (!M || p < a.d_pieces) x[i] = ld4_stream(xr + 4 * p); else x[i] = v4f{0.f, 0.f, 0.f, 0.f};
+  }
 }
 
 template <int V>
@@ -485,11 +503,13 @@ __device__ __forceinline__ void scale(v4f (&z)[V], float f) {
   for (int i = 0; i < V; ++i) z[i] *= f;
 }
 
-template <int D, int G, int C>
-__device__ __forceinline__ void store_row(float* dst, int g, const v4f (&z)[D / (4 * G)]) {
+template <int D, int G, int C, bool M>
+__device__ __forceinline__ void store_row(const KernelArgs& a, float* dst, int g, const v4f (&z)[D / (4 * G)]) {
 #pragma unroll
-  for (int i = 0; i < D / (4 * G); ++i)
-    __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * piece_index<G, C>(g, i)));
+  for (int i = 0; i < D / (4 * G); ++i) {
+    const int p = piece_index<G, C>(g, i);
+    if (!M || p < a.d_pieces) __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * p));
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -549,7 +569,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW>(a, ch.row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, P == PAT_RUNTIME>(a, ch.row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
@@ -558,7 +578,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         for (int i = 0; i < V; ++i) stage[wave][piece_index<GW, CW>(g, i)] = z[i];
       }
       __syncthreads();
-      if (threadIdx.x < D / 4) {
+      if (threadIdx.x < (P == PAT_RUNTIME ? a.d_pieces : D / 4)) {
         v4f s = stage[0][threadIdx.x];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) {
@@ -596,14 +616,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW>(a, row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, P == PAT_RUNTIME>(a, row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if constexpr (P == PAT_RUNTIME) {
         if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
       }
-      if (lane < GW) store_row<D, GW, CW>(dst, g, z);
+      if (lane < GW) store_row<D, GW, CW, P == PAT_RUNTIME>(a, dst, g, z);
     }
   } else if (kind == kItemPacked) {
     // ---- one short segment per lane group ----------------------------------------------
@@ -613,6 +633,12 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int slot = lane / GP;
     const int g = lane % GP;
     const bool use_val = reads_values<P>(a);
+    int nv = V;
+    if constexpr (P == PAT_RUNTIME) {
+      nv = 0;
+#pragma unroll
+      for (int i = 0; i < V; ++i) nv += piece_index<GP, CP>(g, i) < a.d_pieces ? 1 : 0;
+    }
     for (int round = 0; round < count; round += kWavesPerBlock * S) {
       const int idx = round + wave * S + slot;
       const bool has_seg = idx < count;
@@ -635,7 +661,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
-        if (deg > 0) load_x<D, GP, CP>(a, row, g, x);
+        if (deg > 0) load_x<D, GP, CP, P == PAT_RUNTIME>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
       if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
@@ -667,10 +693,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
             for (int u = 0; u < UP; ++u) {
 #pragma unroll
               for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-              if (ok[u]) gather_row<YF, GP, V, CP>(a, c[u], g, y[u]);
+              if (ok[u]) gather_row<YF, GP, V, CP, P == PAT_RUNTIME>(a, c[u], g, y[u]);
             }
 #pragma unroll
-            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a, ok[u], z);
+            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a, ok[u], z, nv);
           } else {
 #pragma unroll
             for (int u = 0; u < UP; ++u)
@@ -682,14 +708,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         if constexpr (P == PAT_RUNTIME) {
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
         }
-        if (has_seg) store_row<D, GP, CP>(dst, g, z);
+        if (has_seg) store_row<D, GP, CP, P == PAT_RUNTIME>(a, dst, g, z);
       }
     }
   }
   else if (kind == kItemZero) {
     // ---- rows without stored entries: z_u = 0 (Algorithm 1 initialises z_u and adds nothing) ----
     if constexpr (T::loads_y) {
-      constexpr int kPieces = D / 4;
+      const int kPieces = P == PAT_RUNTIME ? a.d_pieces : D / 4;
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
       for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
         const int64_t row = rows[i / kPieces];

@@ -138,37 +138,37 @@ __device__ __forceinline__ v4f merge_two(int aop, v4f s, v4f t) {
 }
 
 __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
-                                                           const float* partials, int32_t d, int32_t aop,
-                                                           const int64_t* rowptr, float* Z, int64_t ldz) {
+                                                           const float* partials, int32_t d, int32_t pstride,
+                                                           int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz) {
   const int cols = d >> 2;
   const int rows_per_block = 256 / cols;
   const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
   const int64_t mi = (int64_t)blockIdx.x * rows_per_block + r;
   if (r >= rows_per_block || mi >= n_merges) return;
   const MergeDesc md = merges[mi];
-  const float* src = partials + (int64_t)md.first_part * d + 4 * c;
+  const float* src = partials + (int64_t)md.first_part * pstride + 4 * c;
   v4f s = {0.f, 0.f, 0.f, 0.f};
   int p = 0;
   for (; p + 8 <= md.n_parts; p += 8) {
     v4f t[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)(p + k) * d));
+    for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)(p + k) * pstride));
 #pragma unroll
     for (int k = 0; k < 8; ++k) s = merge_two(aop, s, t[k]);
   }
   for (; p < md.n_parts; ++p)
-    s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * d)));
+    s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * pstride)));
   if (aop == FUSEDMM_AOP_MEAN) s *= 1.0f / (float)(rowptr[md.row + 1] - rowptr[md.row]);  // split rows are never empty
   __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(Z + (int64_t)md.row * ldz + 4 * c));
 }
 
-hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
-                        const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream) {
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
+                        int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
   const int rows_per_block = 256 / (d >> 2);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
-                     aop, rowptr, Z, ldz);
+                     pstride, aop, rowptr, Z, ldz);
   return hipGetLastError();
 }
 

@@ -58,6 +58,9 @@ struct KernelArgs {
   float alpha;
   int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only; aop is SUM, MAX or MIN here
   int32_t mean;                     // PAT_RUNTIME: a row stored whole is divided by its length (mean pooling)
+  // PAT_RUNTIME: rows have this many 4-float pieces; below D/4 when a dimension between two instance
+  // sizes runs on the next larger instance (pieces beyond it are neither loaded nor stored)
+  int32_t d_pieces;
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
   // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed), rows without entries
   // (zero fill only) from order[n_wave+n_packed .. n_wave+n_packed+n_empty).
@@ -123,8 +126,9 @@ hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream);
 
 // aop: FUSEDMM_AOP_SUM / MAX / MIN, how partial rows are combined; FUSEDMM_AOP_MEAN: summed, then
 // divided by the row's length taken from rowptr
-hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
-                        const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
+// d: row width; pstride: distance in floats between partial rows (>= d)
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
+                        int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
 
 // flag[0] |= 1 if any colidx entry is outside [0, n).
 hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag, hipStream_t stream);

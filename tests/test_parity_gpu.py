@@ -219,6 +219,59 @@ def test_runtime_ops_fast_kernel_all_bins(B, tuples, d):
         assert (stats["tiled_rows"] > 0) == (options is TILED)
 
 
+IN_BETWEEN_CASES = [
+    ("one_minus_sigmoid", "SUM", "one_minus_sigmoid", "ASUM"),
+    ("gcn", "SUM", "gcn", "ASUM"),
+    ("tdist", "SUM", "tdist", "ASUM"),
+    ("fr", "SUM", "fr", "ASUM"),
+    (("ADD", "RMUL", "NOOP", "MUL_T"), "SUM", ("ADD", "RMUL", "NOOP", "MUL_T"), "ASUM"),      # product over d factors only
+    (("SUB", "NOOP", "SIGMOID", "MUL_T"), "MAX", ("SUB", "NOOP", "SIGMOID", "MUL_T"), "AMAX"),  # vector message
+    (("MUL", "RSUM", "SIGMOID", "MUL_Y"), "MEAN", ("MUL", "RSUM", "SIGMOID", "MUL_Y"), "AMEAN"),
+]
+
+
+@pytest.mark.parametrize("d", (4, 36, 100, 200, 300, 508))
+@pytest.mark.parametrize("case", IN_BETWEEN_CASES, ids=[str(c[0]) + "-" + c[1] for c in IN_BETWEEN_CASES])
+def test_dimensions_between_instance_sizes(B, case, d):
+    """A multiple of 4 that is not one of the five instance sizes runs the whole schedule (packed rows,
+    wave rows, chunks, tiles, merge) on the next larger instance with the columns beyond d skipped:
+    parity against the oracle, memory right of column d untouched, every stored entry visited once."""
+    gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
+    rng = np.random.default_rng(31 * d)
+    m, n = 211, 1500
+    long_rows = {3: 64, 5: 120, 11: 257, 57: 700, 100: 1025, 210: 4000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    rmul = "RMUL" in (gpu_ops if not isinstance(gpu_ops, str) else ())
+    lo, hi = (0.49, 0.51) if rmul else (-0.9, 0.9)
+    pad = 8
+    Xw = rng.uniform(lo, hi, (m, d + pad)).astype(np.float32)
+    Yw = rng.uniform(lo, hi, (n, d + pad)).astype(np.float32)
+    Yw[:, d:] = 1e30                       # would wreck any sum that reached beyond column d
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    names = oracle.PATTERNS[oracle_ops] if isinstance(oracle_ops, str) else oracle_ops
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, Xw[:, :d], Yw[:, :d], names, oracle_aop, alpha=ALPHA)
+    ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
+    ops.alpha = ALPHA
+    rp, ci = dev(rowptr), dev(colidx)
+    Xd, Yd, vd = dev(Xw), dev(Yw), dev(vals)
+    for options in ({"column_classes": 1}, TILED):
+        plan = B.Plan(m, n, rp, ci, options)
+        assert (plan.stats()["tiled_rows"] > 0) == (options is TILED)
+        Zb = torch.full((m, d + pad), 7.0, dtype=torch.float32, device="cuda")
+        uses_x = ops.vop != B.VOP["SEL2ND"]
+        plan.execute(ops, Xd[:, :d] if uses_x else None, Yd[:, :d], Zb[:, :d], vd)
+        torch.cuda.synchronize()
+        out = Zb.cpu().numpy()
+        check(out[:, :d], Zr, S, f"{gpu_ops} {gpu_aop} d={d} {options}")
+        assert (out[:, d:] == 7.0).all()
+        counts = torch.zeros(len(colidx), dtype=torch.int32, device="cuda")
+        plan.edge_visits(d, True, counts)
+        torch.cuda.synchronize()
+        c = counts.cpu().numpy()
+        assert c.min() == 1 and c.max() == 1
+        plan.close()
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
