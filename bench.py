@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 # HBM bytes per main-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.
 # They belong to the kernel build and default plan the profiles were taken with.
-MEASURED_TRAFFIC_BYTES = {"c2": 374191723, "c3": 26654681846, "c4": 6689682927, "c5": 80827779190}
+MEASURED_TRAFFIC_BYTES = {"c2": 372505292, "c3": 26648249513, "c4": 6676424610, "c5": 80830477141}
 
 
 def parity_sample(w, rows, Z_rows):
