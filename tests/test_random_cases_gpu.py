@@ -62,20 +62,35 @@ def make_case(seed):
     if sorted_cols:
         for u in range(m):
             colidx[rowptr[u]:rowptr[u + 1]].sort()
-    d = int(rng.choice([32, 64, 128, 256, 512]))
+    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508]))
     share = rng.random() < 0.3 and m <= n
     ld = d + int(rng.choice([0, 0, 4, 12]))
     Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
     Xb = Yb[:m] if share else rng.uniform(-0.7, 0.7, (m, ld)).astype(np.float32)
     vals = rng.uniform(-1, 1, max(1, nnz)).astype(np.float32)[:nnz]
-    return m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts
+    fmt = str(rng.choice(["f32", "f32", "bf16", "f16"]))
+    if d not in (32, 64, 128, 256, 512) or ld % 8 != 0:
+        fmt = "f32"       # 2-byte storage of Y exists for the five instance sizes and 16-byte aligned rows
+    return m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts, fmt
+
+
+def rounded(Y, fmt):
+    """Y as the kernel sees it after fusedmm_to_bf16 / fusedmm_to_f16 (round to nearest even)."""
+    if fmt == "f16":
+        return Y.astype(np.float16).astype(np.float32)
+    u = np.ascontiguousarray(Y, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    keep, rest = u >> 16, u & 0xFFFF
+    keep = keep + ((rest > 0x8000) | ((rest == 0x8000) & ((keep & 1) == 1)))
+    return (keep.astype(np.uint32) << 16).view(np.float32)
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("FUSEDMM_RANDOM_CASES", "60"))))
 def test_random_case(B, seed):
-    m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts = make_case(1000 + seed)
+    m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts, fmt = make_case(1000 + seed)
     rng = np.random.default_rng(seed)
     X, Y = np.ascontiguousarray(Xb[:, :d]), np.ascontiguousarray(Yb[:, :d])
+    if fmt != "f32":
+        Y = rounded(Y, fmt)          # x_u stays fp32 even where X and Y share storage
     if seed % 3 == 2:
         gnames, gaop, onames, oaop = TUPLES[(seed // 3) % len(TUPLES)]
         Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, onames, oaop, alpha=0.21)
@@ -94,11 +109,16 @@ def test_random_case(B, seed):
     vd = torch.from_numpy(vals).cuda()
     Zb = torch.full((m, Yb.shape[1]), np.nan, dtype=torch.float32, device="cuda")
     plan = B.Plan(m, n, rp, ci, opts)
-    plan.execute(ops, Xd[:, :d], Yd[:, :d], Zb[:, :d], vd)
+    if fmt == "f32":
+        plan.execute(ops, Xd[:, :d], Yd[:, :d], Zb[:, :d], vd)
+    else:
+        Yh = torch.zeros((n, Yb.shape[1]), dtype=torch.int16, device="cuda")
+        (B.fusedmm_to_bf16 if fmt == "bf16" else B.fusedmm_to_f16)(Yh, Yd, Yh.numel())
+        (plan.execute_bf16y if fmt == "bf16" else plan.execute_f16y)(ops, Xd[:, :d], Yh[:, :d], Zb[:, :d], vd)
     torch.cuda.synchronize()
     out = Zb.cpu().numpy()
     err, am, viol = oracle.compare(out[:, :d], Zr, S)
-    info = f"seed {seed} {what} m={m} n={n} d={d} nnz={len(colidx)} opts={opts} stats={plan.stats()}"
+    info = f"seed {seed} {what} {fmt} m={m} n={n} d={d} nnz={len(colidx)} opts={opts} stats={plan.stats()}"
     assert viol == 0, info
     assert err <= TOL, f"{info}: max rel err {err:.3e} at {am}"
     assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
