@@ -519,12 +519,14 @@ __device__ __forceinline__ void store_row(const KernelArgs& a, float* dst, int g
 // A workgroup first decodes what it has been given (uniform across the workgroup):
 //   tiled region   blockIdx <  nb_tiled : a BlockItem written by the plan.  Long rows are cut
 //                  by column class (a contiguous range of column ids) into tiles; block b runs
-//                  on XCD b % 8, and the plan puts all tiles of class c on XCD c % 8, class
-//                  after class, so each XCD's L2 only ever holds its own slices of Y.
+//                  on XCD b % 8, and the plan gives XCD k the classes of the k-th eighth of the
+//                  column range, class after class, so each XCD's L2 only ever holds its own
+//                  slices of Y.
 //   chunk region   one ChunkDesc per workgroup (long rows that are not tiled)
 //   wave region    4 rows, one per wavefront
 //   packed region  4*S short rows, one per lane group
-// and then runs one of three bodies: chunk, wave segments, packed segments.  A segment is
+//   zero region    rows without stored entries, kZeroRowsPerBlock per workgroup
+// and then runs one of four bodies: chunk, wave segments, packed segments, zero fill.  A segment is
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
 template <int P, int D, int GW0, int UW0, int GP0, int UP0, int YF>
