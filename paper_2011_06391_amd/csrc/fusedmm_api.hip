@@ -24,6 +24,12 @@ struct fusedmm_plan {
   MergeDesc* d_merges = nullptr;
   float* d_partials = nullptr;
   int32_t partials_d = 0;  // scratch holds n_parts rows of this many floats
+  // the general kernel's own cut of the rows longer than kGenericSplit (any d, fp32 or fp64)
+  ChunkDesc* d_gen_segs = nullptr;
+  MergeDesc* d_gen_merges = nullptr;
+  int32_t n_gen_segs = 0, n_gen_merges = 0;
+  void* d_gen_partials = nullptr;
+  size_t gen_partials_bytes = 0;
   bool profiling = false;
   struct EventTriple { hipEvent_t before, after, after2; };
   std::vector<EventTriple> events;  // main kernel between before/after; nothing between after/after2
@@ -103,6 +109,9 @@ void free_plan_device(fusedmm_plan* p) {
   if (p->d_items) (void)hipFree(p->d_items);
   if (p->d_tile_descs) (void)hipFree(p->d_tile_descs);
   if (p->d_partials) (void)hipFree(p->d_partials);
+  if (p->d_gen_segs) (void)hipFree(p->d_gen_segs);
+  if (p->d_gen_merges) (void)hipFree(p->d_gen_merges);
+  if (p->d_gen_partials) (void)hipFree(p->d_gen_partials);
   for (auto& ev : p->events) {
     (void)hipEventDestroy(ev.before);
     (void)hipEventDestroy(ev.after);
@@ -138,6 +147,33 @@ int ensure_partials(fusedmm_plan* p, int32_t d) {
   }
   p->partials_d = d;
   return FUSEDMM_OK;
+}
+
+// Scratch of the general kernel: n_gen_segs partial rows of d elements of elem_bytes each.
+int ensure_gen_partials(fusedmm_plan* p, int32_t d, size_t elem_bytes) {
+  const size_t need = (size_t)p->n_gen_segs * (size_t)d * elem_bytes;
+  if (need <= p->gen_partials_bytes) return FUSEDMM_OK;
+  if (p->d_gen_partials) {
+    if (hipDeviceSynchronize() != hipSuccess) return FUSEDMM_ERR_HIP;  // earlier launches may still use it
+    (void)hipFree(p->d_gen_partials);
+    p->d_gen_partials = nullptr;
+    p->gen_partials_bytes = 0;
+  }
+  if (hipMalloc(&p->d_gen_partials, need) != hipSuccess) {
+    (void)hipGetLastError();
+    return FUSEDMM_ERR_ALLOC;
+  }
+  p->gen_partials_bytes = need;
+  return FUSEDMM_OK;
+}
+
+template <class T>
+void fill_generic_segments(const fusedmm_plan* p, GenericArgsT<T>* g) {
+  g->segs = p->d_gen_segs;
+  g->n_segs = p->n_gen_segs;
+  g->merges = p->d_gen_merges;
+  g->n_merges = p->n_gen_merges;
+  g->partials = static_cast<T*>(p->d_gen_partials);
 }
 
 void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelArgs* a) {
@@ -480,7 +516,30 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     return FUSEDMM_ERR_ALLOC;
   }
 
+  // ---- the general kernel's segments: rows longer than kGenericSplit, cut into runs of that length
+  std::vector<ChunkDesc> gen_segs;
+  std::vector<MergeDesc> gen_merges;
+  try {
+    for (int64_t u = 0; u < m; ++u) {
+      const int64_t deg = rp[u + 1] - rp[u];
+      if (deg <= kGenericSplit) continue;
+      const int32_t first = (int32_t)gen_segs.size();
+      for (int64_t off = 0; off < deg; off += kGenericSplit)
+        gen_segs.push_back(ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(kGenericSplit, deg - off), (int32_t)u,
+                                     (int32_t)gen_segs.size(), 0});
+      gen_merges.push_back(MergeDesc{(int32_t)u, first, (int32_t)gen_segs.size() - first, 0});
+      if (gen_segs.size() >= (size_t)INT32_MAX / 2) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
+    }
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return FUSEDMM_ERR_ALLOC;
+  }
+  p->n_gen_segs = (int32_t)gen_segs.size();
+  p->n_gen_merges = (int32_t)gen_merges.size();
+
   st = upload(&p->d_order, order, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_gen_segs, gen_segs, stream);
+  if (st == FUSEDMM_OK) st = upload(&p->d_gen_merges, gen_merges, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_chunks, chunks, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_merges, merges, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_items, items, stream);
@@ -498,7 +557,7 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
 int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  return instance_dim(d) ? ensure_partials(plan, instance_dim(d)) : FUSEDMM_OK;
+  return instance_dim(d) ? ensure_partials(plan, instance_dim(d)) : ensure_gen_partials(plan, d, sizeof(float));
 }
 
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
@@ -507,7 +566,9 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
   size_t b = (size_t)(plan->n_wave + plan->n_packed + plan->n_empty) * sizeof(int32_t) + (size_t)plan->n_chunks * sizeof(ChunkDesc) +
              (size_t)plan->n_merges * sizeof(MergeDesc) + (size_t)plan->n_items * sizeof(BlockItem) +
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
+  b += (size_t)plan->n_gen_segs * sizeof(ChunkDesc) + (size_t)plan->n_gen_merges * sizeof(MergeDesc);
   if (instance_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(instance_dim(d), plan->partials_d) * sizeof(float);
+  else b += std::max((size_t)plan->n_gen_segs * (size_t)d * sizeof(float), plan->gen_partials_bytes);
   *out = b;
   return FUSEDMM_OK;
 }
@@ -606,6 +667,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
     g.alpha = ops->alpha;
     g.visit_counts = nullptr;
+    const int gst = ensure_gen_partials(plan, d, sizeof(float));
+    if (gst != FUSEDMM_OK) return gst;
+    fill_generic_segments(plan, &g);
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_generic(g, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
@@ -678,6 +742,9 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
   g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
   g.alpha = (double)ops->alpha;
   g.visit_counts = nullptr;
+  const int gst = ensure_gen_partials(plan, d, sizeof(double));
+  if (gst != FUSEDMM_OK) return gst;
+  fill_generic_segments(plan, &g);
   return launch_generic(g, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }
 
@@ -716,6 +783,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;
     g.m = plan->m; g.d = d;
     g.visit_counts = d_counts;
+    fill_generic_segments(plan, &g);  // the same cut of the long rows as an execute (no partial rows are written)
     e = launch_generic(g, stream);
   }
   return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;

@@ -47,8 +47,8 @@ __device__ __forceinline__ T sop_apply(int sop, T s, T alpha) {
   }
 }
 
-// Algorithm 1, UpdateU, one wavefront per row: lane l owns elements l, l+64, l+128, ...
-// of z_u in registers.  The five steps run per stored entry in the paper's order; the
+// Algorithm 1, UpdateU, one wavefront per row (or per segment of a long row): lane l owns elements
+// l, l+64, l+128, ... of z_u in registers.  The five steps run per stored entry in the paper's order; the
 // row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
 // Covers every op of Table II: scalar messages (after a reduction, or the edge value) and
 // vector messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation
@@ -59,9 +59,28 @@ constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
 template <class T>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgsT<T> a) {
   const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-  if (row >= a.m) return;
-  const int64_t e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
+  // wavefronts [0, m): one row each (rows longer than kGenericSplit are left to the segment
+  // wavefronts that follow); wavefronts [m, m + n_segs): one segment of a long row each
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (w >= a.m + a.n_segs) return;
+  int64_t row, e0, e1;
+  T* zr;
+  bool whole_row;  // the wavefront stores z_u itself (mean pooling divides here)
+  if (w < a.m) {
+    row = w;
+    e0 = a.rowptr[row];
+    e1 = a.rowptr[row + 1];
+    if (e1 - e0 > kGenericSplit) return;
+    zr = a.Z + row * a.ldz;
+    whole_row = true;
+  } else {
+    const ChunkDesc sg = a.segs[w - a.m];
+    row = sg.row;
+    e0 = sg.e_begin;
+    e1 = sg.e_begin + sg.e_count;
+    zr = a.partials + (int64_t)sg.part * a.d;
+    whole_row = false;
+  }
   const int d = a.d;
   if (a.visit_counts) {
     for (int64_t e = e0 + lane; e < e1; e += 64) atomicAdd(a.visit_counts + e, 1u);
@@ -109,8 +128,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
       }
     }
   }
-  T* zr = a.Z + row * a.ldz;
-  const T post = (a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? T(1) / (T)(e1 - e0) : T(1);  // mean pooling
+  const T post = (whole_row && a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? T(1) / (T)(e1 - e0) : T(1);  // mean pooling
 #pragma unroll
   for (int i = 0; i < kGenericAcc; ++i) {
     const int k = lane + 64 * i;
@@ -118,12 +136,41 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
   }
 }
 
+// z_u of a row that the general kernel cut into segments: its partial rows combined in segment
+// order (SUM / MAX / MIN; MEAN: summed, then divided by the row length).  One wavefront per row.
+template <class T>
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_merge_kernel(const GenericArgsT<T> a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (w >= a.n_merges) return;
+  const MergeDesc md = a.merges[w];
+  const T* src = a.partials + (int64_t)md.first_part * a.d;
+  const T post = a.aop == FUSEDMM_AOP_MEAN ? T(1) / (T)(a.rowptr[md.row + 1] - a.rowptr[md.row]) : T(1);
+  for (int k = lane; k < a.d; k += 64) {
+    T s = src[k];
+    for (int p = 1; p < md.n_parts; ++p) {
+      const T v = src[(int64_t)p * a.d + k];
+      if (a.aop == FUSEDMM_AOP_SUM || a.aop == FUSEDMM_AOP_MEAN) s += v;
+      else if (a.aop == FUSEDMM_AOP_MAX) s = v > s ? v : s;
+      else s = v < s ? v : s;
+    }
+    a.Z[(int64_t)md.row * a.ldz + k] = s * post;
+  }
+}
+
 template <class T>
 static hipError_t launch_generic_t(const GenericArgsT<T>& a, hipStream_t stream) {
   if (a.m <= 0) return hipSuccess;
-  const int64_t blocks = (a.m + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int64_t waves = a.m + a.n_segs;
+  const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
   hipLaunchKernelGGL(fusedmm_generic_kernel<T>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && a.n_merges > 0 && !a.visit_counts) {
+    const int64_t mblocks = ((int64_t)a.n_merges + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(fusedmm_generic_merge_kernel<T>, dim3((unsigned)mblocks), dim3(kBlockThreads), 0, stream, a);
+    e = hipGetLastError();
+  }
+  return e;
 }
 hipError_t launch_generic(const GenericArgsT<float>& a, hipStream_t stream) { return launch_generic_t(a, stream); }
 hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream) { return launch_generic_t(a, stream); }

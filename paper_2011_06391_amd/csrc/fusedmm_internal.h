@@ -103,8 +103,11 @@ hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStre
 // dst[i] = half(src[i]), round to nearest even.
 hipError_t launch_to_f16(uint16_t* dst, const float* src, size_t count, hipStream_t stream);
 
-// General kernel: any 1 <= d <= 2048, any op tuple, any alignment; one wavefront per row.
+// General kernel: any 1 <= d <= 2048, any op tuple, any alignment.  One wavefront per row of up to
+// kGenericSplit stored entries; longer rows are cut into segments of that length, one wavefront each,
+// whose partial rows a second kernel combines in segment order (so a hub row does not serialise it).
 // T = float, or double (storage and arithmetic both in T).
+constexpr int kGenericSplit = 256;
 template <class T>
 struct GenericArgsT {
   const int64_t* rowptr;
@@ -119,6 +122,11 @@ struct GenericArgsT {
   int32_t vop, rop, sop, mop, aop;
   T alpha;
   uint32_t* visit_counts;  // non-null: count visits instead of computing
+  const ChunkDesc* segs;   // segments of the rows longer than kGenericSplit; part = partial-row slot
+  int32_t n_segs;
+  const MergeDesc* merges;  // one per such row
+  int32_t n_merges;
+  T* partials;              // n_segs rows of d elements
 };
 using GenericArgs = GenericArgsT<float>;
 hipError_t launch_generic(const GenericArgsT<float>& a, hipStream_t stream);

@@ -272,6 +272,49 @@ def test_dimensions_between_instance_sizes(B, case, d):
         plan.close()
 
 
+@pytest.mark.parametrize("d", (5, 50, 130, 516, 1027))
+@pytest.mark.parametrize("case", IN_BETWEEN_CASES, ids=[str(c[0]) + "-" + c[1] for c in IN_BETWEEN_CASES])
+def test_general_kernel_long_rows(B, case, d):
+    """Dimensions the fast schedule cannot take (not a multiple of 4, or above 512) run the general
+    kernel, which cuts rows longer than 256 entries into segments and merges their partial rows:
+    rows of 256, 257, 700, 4000 and 12000 entries, every accumulation kind, visits counted once."""
+    gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
+    rng = np.random.default_rng(77 * d)
+    m, n = 150, 900
+    long_rows = {3: 256, 5: 257, 11: 700, 57: 4000, 149: 12000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows)
+    rmul = "RMUL" in (gpu_ops if not isinstance(gpu_ops, str) else ())
+    lo, hi = (0.4995, 0.5005) if rmul else (-0.9, 0.9)   # keeps a product of up to 1027 factors in range
+    X = rng.uniform(lo, hi, (m, d)).astype(np.float32)
+    Y = rng.uniform(lo, hi, (n, d)).astype(np.float32)
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    names = oracle.PATTERNS[oracle_ops] if isinstance(oracle_ops, str) else oracle_ops
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, oracle_aop, alpha=ALPHA)
+    ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
+    ops.alpha = ALPHA
+    rp, ci = dev(rowptr), dev(colidx)
+    plan = B.Plan(m, n, rp, ci)
+    uses_x = ops.vop != B.VOP["SEL2ND"]
+    Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+    plan.execute(ops, dev(X) if uses_x else None, dev(Y), Z, dev(vals))
+    torch.cuda.synchronize()
+    check(Z.cpu().numpy(), Zr, S, f"{gpu_ops} {gpu_aop} d={d}")
+    counts = torch.zeros(len(colidx), dtype=torch.int32, device="cuda")
+    plan.edge_visits(d, False, counts)
+    torch.cuda.synchronize()
+    c = counts.cpu().numpy()
+    assert c.min() == 1 and c.max() == 1
+    if d in (5, 130):   # the double-precision entry point shares the segments
+        Z64 = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+        plan.execute_f64(ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z64,
+                         dev(vals.astype(np.float64)))
+        torch.cuda.synchronize()
+        Zr32a, S64, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, oracle_aop, alpha=float(np.float32(ALPHA)))
+        e64 = np.abs(Z64.cpu().numpy() - Zr32a) / np.where(S64 > 0, S64, 1.0)
+        assert e64.max() <= 1e-12, f"f64 {gpu_ops} {gpu_aop} d={d}: {e64.max():.3e}"
+    plan.close()
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
