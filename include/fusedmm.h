@@ -91,7 +91,8 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * 512; every other tuple, and every other d that is a multiple of 4 up to 512, runs the same
  * schedule with the ops read at run time (on the next larger kernel size, skipping the columns
  * beyond d); any other d up to FUSEDMM_MAX_D, or operands that are not 16-byte aligned, run the
- * general kernel (one wavefront per row, no row splitting: a correctness path). */
+ * general kernel (one wavefront per row or per 256-entry segment of a long row: a correctness path,
+ * an order of magnitude slower). */
 typedef struct fusedmm_ops {
   int32_t vop, rop, sop, mop, aop;
   float alpha; /* used by FUSEDMM_SOP_SCAL only */
@@ -214,7 +215,7 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic.  Runs the general kernel (one wavefront per
- * row, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the specialised schedule is
+ * row or 256-entry segment, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the specialised schedule is
  * fp32 only.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened. */
 int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                         const double* d_values, const double* d_X, int64_t ldx,
