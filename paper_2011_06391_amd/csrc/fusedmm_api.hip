@@ -78,13 +78,19 @@ bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
 
 // The pattern recogniser: map an op tuple to a specialised kernel, or -1 for the general one.
 int recognise(const fusedmm_ops_t& o) {
+  if (o.vop == FUSEDMM_VOP_SEL2ND && o.rop == FUSEDMM_ROP_NOOP && o.sop == FUSEDMM_SOP_EDGE_VALUE &&
+      o.mop != FUSEDMM_MOP_SEL2ND) {  // the GCN message a_uv * y_v (t = y_v here, so MUL_T is the same) with any
+                                      // pooling: sum and mean share an instance
+    if (o.aop == FUSEDMM_AOP_MAX) return PAT_GCN_MAX;
+    if (o.aop == FUSEDMM_AOP_MIN) return PAT_GCN_MIN;
+    return PAT_GCN;
+  }
   if (o.aop != FUSEDMM_AOP_SUM) return -1;
   if (o.vop == FUSEDMM_VOP_MUL && o.rop == FUSEDMM_ROP_RSUM && o.mop == FUSEDMM_MOP_MUL_Y) {
     if (o.sop == kSopValueMinusSigmoid) return PAT_SIGNED_SIGMOID;
     if (o.sop == FUSEDMM_SOP_SIGMOID) return PAT_SIGMOID;
     if (o.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID) return PAT_ONE_MINUS_SIGMOID;
   }
-  if (o.vop == FUSEDMM_VOP_SEL2ND && o.rop == FUSEDMM_ROP_NOOP && o.sop == FUSEDMM_SOP_EDGE_VALUE) return PAT_GCN;
   if (o.vop == FUSEDMM_VOP_SUB && o.mop == FUSEDMM_MOP_MUL_T) {
     if (o.rop == FUSEDMM_ROP_SUMSQ && o.sop == FUSEDMM_SOP_INV_1P) return PAT_TDIST;
     if (o.rop == FUSEDMM_ROP_NORM2 && o.sop == FUSEDMM_SOP_SCAL) return PAT_FR;

@@ -69,6 +69,18 @@ __device__ __forceinline__ float aop_apply(int aop, float z, float w) {
   return aop == FUSEDMM_AOP_SUM ? z + w : (aop == FUSEDMM_AOP_MAX ? fmaxf(z, w) : fminf(z, w));
 }
 
+// What a compile-time pattern fixes (PAT_RUNTIME decides the same things from the launch arguments).
+template <int P>
+struct PatTraits {
+  static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
+  static constexpr bool uses_x = (!gcn && P != PAT_VISIT);
+  static constexpr bool uses_val = (gcn || P == PAT_SIGNED_SIGMOID);
+  static constexpr bool loads_y = (P != PAT_VISIT);
+  // how messages are accumulated when it is fixed at compile time, and whether a row stored whole
+  // may have to be divided by its length (mean pooling: a.mean)
+  static constexpr int aop = P == PAT_GCN_MAX ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
+  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN);
+};
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
 __device__ __forceinline__ float cross_group_allreduce(float v) {
@@ -96,6 +108,11 @@ __device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V])
       z[i].y = cross_group_allreduce_aop<G>(a.aop, z[i].y);
       z[i].z = cross_group_allreduce_aop<G>(a.aop, z[i].z);
       z[i].w = cross_group_allreduce_aop<G>(a.aop, z[i].w);
+    } else if constexpr (PatTraits<P>::aop != FUSEDMM_AOP_SUM) {
+      z[i].x = cross_group_allreduce_aop<G>(PatTraits<P>::aop, z[i].x);
+      z[i].y = cross_group_allreduce_aop<G>(PatTraits<P>::aop, z[i].y);
+      z[i].z = cross_group_allreduce_aop<G>(PatTraits<P>::aop, z[i].z);
+      z[i].w = cross_group_allreduce_aop<G>(PatTraits<P>::aop, z[i].w);
     } else {
       z[i].x = cross_group_allreduce<G>(z[i].x);
       z[i].y = cross_group_allreduce<G>(z[i].y);
@@ -205,12 +222,6 @@ __device__ __forceinline__ v4f ld4_stream(const float* p) {
 // ---------------------------------------------------------------------------------------
 // per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
 // ---------------------------------------------------------------------------------------
-template <int P>
-struct PatTraits {
-  static constexpr bool uses_x = (P != PAT_GCN && P != PAT_VISIT);
-  static constexpr bool uses_val = (P == PAT_GCN || P == PAT_SIGNED_SIGMOID);
-  static constexpr bool loads_y = (P != PAT_VISIT);
-};
 // whether x_u / the edge values are read: fixed per pattern, a (uniform) run-time fact for PAT_RUNTIME
 template <int P>
 __device__ __forceinline__ bool reads_x(const KernelArgs& a) {
@@ -360,12 +371,21 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     }
     return;
   }
-  if constexpr (P == PAT_GCN) {
-    // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP+AOP: z += h * y
+  if constexpr (PatTraits<P>::gcn) {
+    // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP: w = h * y; AOP: sum, or maximum / minimum from the
+    // zero start (an entry beyond the end contributes w = 0, neutral for all three)
     float h = aval;
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
-    for (int i = 0; i < V; ++i) z[i] += h * y[i];
+    for (int i = 0; i < V; ++i) {
+      if constexpr (P == PAT_GCN) {
+        z[i] += h * y[i];
+      } else {
+        const v4f w = h * y[i];
+        z[i].x = aop_apply(PatTraits<P>::aop, z[i].x, w.x); z[i].y = aop_apply(PatTraits<P>::aop, z[i].y, w.y);
+        z[i].z = aop_apply(PatTraits<P>::aop, z[i].z, w.z); z[i].w = aop_apply(PatTraits<P>::aop, z[i].w, w.w);
+      }
+    }
   } else if constexpr (P == PAT_SIGMOID || P == PAT_ONE_MINUS_SIGMOID || P == PAT_SIGNED_SIGMOID) {
     float p = 0.f;  // VOP = MUL and this lane's share of ROP = RSUM
 #pragma unroll
@@ -588,11 +608,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
           if constexpr (P == PAT_RUNTIME) {
             s.x = aop_apply(a.aop, s.x, o.x); s.y = aop_apply(a.aop, s.y, o.y);
             s.z = aop_apply(a.aop, s.z, o.z); s.w = aop_apply(a.aop, s.w, o.w);
+          } else if constexpr (T::aop != FUSEDMM_AOP_SUM) {
+            s.x = aop_apply(T::aop, s.x, o.x); s.y = aop_apply(T::aop, s.y, o.y);
+            s.z = aop_apply(T::aop, s.z, o.z); s.w = aop_apply(T::aop, s.w, o.w);
           } else {
             s += o;
           }
         }
-        if constexpr (P == PAT_RUNTIME) {
+        if constexpr (T::means) {
           if (a.mean && ch.part < 0) s *= 1.0f / (float)ch.e_count;  // the chunk is the whole row
         }
         float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * D;
@@ -622,7 +645,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
-      if constexpr (P == PAT_RUNTIME) {
+      if constexpr (T::means) {
         if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
       }
       if (lane < GW) store_row<D, GW, CW, P == PAT_RUNTIME>(a, dst, g, z);
@@ -707,7 +730,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         }
       }
       if constexpr (T::loads_y) {
-        if constexpr (P == PAT_RUNTIME) {
+        if constexpr (T::means) {
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
         }
         if (has_seg) store_row<D, GP, CP, P == PAT_RUNTIME>(a, dst, g, z);

@@ -28,6 +28,8 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
     case PAT_SIGMOID: return launch_one<PAT_SIGMOID, YF>(a, stream);
     case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, YF>(a, stream);
     case PAT_GCN: return launch_one<PAT_GCN, YF>(a, stream);
+    case PAT_GCN_MAX: return launch_one<PAT_GCN_MAX, YF>(a, stream);
+    case PAT_GCN_MIN: return launch_one<PAT_GCN_MIN, YF>(a, stream);
     case PAT_TDIST: return launch_one<PAT_TDIST, YF>(a, stream);
     case PAT_FR: return launch_one<PAT_FR, YF>(a, stream);
     case PAT_RUNTIME: return launch_one<PAT_RUNTIME, YF>(a, stream);

@@ -8,8 +8,10 @@ namespace fmm {
 // Pattern ids of the specialised kernels (host dispatch -> template instance).
 // PAT_RUNTIME: the same kernel structure with the five ops read from KernelArgs at run time (any valid tuple).
 // PAT_SIGNED_SIGMOID: the sigmoid embedding pattern with the scaling step h = a_uv - sigmoid(s) (kSopValueMinusSigmoid).
+// PAT_GCN_MAX / PAT_GCN_MIN: the GCN message (h = a_uv, w = h * y_v) pooled by maximum / minimum instead of
+// summed (the pooling variants of Section III-B); mean pooling runs PAT_GCN with the division at the store.
 enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6,
-             PAT_SIGNED_SIGMOID = 7 };
+             PAT_SIGNED_SIGMOID = 7, PAT_GCN_MAX = 8, PAT_GCN_MIN = 9 };
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;

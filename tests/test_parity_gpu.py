@@ -170,6 +170,10 @@ GENERAL_TUPLES = [
     ((("MUL", "RSUM", "SIGMOID", "SEL2ND"), "SUM"), (("MUL", "RSUM", "SIGMOID", "SEL2ND"), "ASUM")),
     ((("ADD", "NORM2", "SCAL", "MUL_Y"), "MAX"), (("ADD", "NORM", "SCAL", "MUL_Y"), "AMAX")),
     ((("MUL", "NOOP", "INV_1P", "MUL_Y"), "SUM"), (("MUL", "NOOP", "INV1P", "MUL_Y"), "ASUM")),  # |x y| < 0.81: away from the pole of 1/(1+t)
+    # the edge value as message with the other two MOPs: MUL_T is a_uv * y_v again, SEL2ND forwards y_v alone
+    ((("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_T"), "SUM"), (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_T"), "ASUM")),
+    ((("SEL2ND", "NOOP", "EDGE_VALUE", "SEL2ND"), "SUM"), (("SEL2ND", "NOOP", "EDGE_VALUE", "SEL2ND"), "ASUM")),
+    ((("SEL2ND", "NOOP", "EDGE_VALUE", "SEL2ND"), "MAX"), (("SEL2ND", "NOOP", "EDGE_VALUE", "SEL2ND"), "AMAX")),
     # mean pooling: plain (GCN with the mean instead of the sum), and on a nonlinear scalar / vector message
     ((("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MEAN"), (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMEAN")),
     ((("MUL", "RSUM", "ONE_MINUS_SIGMOID", "MUL_Y"), "MEAN"), (("MUL", "RSUM", "ONE_MINUS_SIGMOID", "MUL_Y"), "AMEAN")),
