@@ -96,7 +96,9 @@ static real sop_scalar(int sop, real s, real a_uv, real alpha) {
   switch (sop) {
     case O_SOP_EDGE_VALUE: return a_uv;
     case O_SOP_SIGMOID: return (real)(1.0 / (1.0 + exp(-(double)s)));
-    case O_SOP_ONE_MINUS_SIGMOID: return (real)(1.0 - 1.0 / (1.0 + exp(-(double)s)));
+    /* 1 - sigmoid(s) = sigmoid(-s) identically; written this way because the literal difference
+     * cancels (it is 0 in double from s = 37 on, where the true value is still 1e-16 and falling) */
+    case O_SOP_ONE_MINUS_SIGMOID: return (real)(1.0 / (1.0 + exp((double)s)));
     case O_SOP_INV1P: return (real)1 / ((real)1 + s);
     default: return alpha * s; /* O_SOP_SCAL */
   }
@@ -258,7 +260,9 @@ static inline real g_sop(int sop, real s, real a_uv, real alpha) {
   switch (sop) {
     case O_SOP_EDGE_VALUE: return a_uv;
     case O_SOP_SIGMOID: return (real)(1.0 / (1.0 + exp(-(double)s)));
-    case O_SOP_ONE_MINUS_SIGMOID: return (real)(1.0 - 1.0 / (1.0 + exp(-(double)s)));
+    /* 1 - sigmoid(s) = sigmoid(-s) identically; written this way because the literal difference
+     * cancels (it is 0 in double from s = 37 on, where the true value is still 1e-16 and falling) */
+    case O_SOP_ONE_MINUS_SIGMOID: return (real)(1.0 / (1.0 + exp((double)s)));
     case O_SOP_INV1P: return (real)1 / ((real)1 + s);
     case O_SOP_SCAL: return alpha * s;
     default: return s; /* O_SOP_NOOP */

@@ -49,11 +49,8 @@ def test_every_valid_tuple(B, d):
     # x - y >= 0 and everything positive: no scaling step comes near the pole of 1/(1+s)
     Xs = rng.uniform(0.30, 0.50, (m, d)).astype(np.float32)
     Ys = rng.uniform(0.05, 0.25, (n, d)).astype(np.float32)
-    # products of d factors stay in range: factors near 1 (SEL2ND, SUB), 2 (MUL) and 3 (ADD); and they stay
-    # out of 37 < s < 88, where the oracle's literal 1 - sigma(s) is already exactly 0 in double while
-    # sigma(-s), which the kernels evaluate, is still a (correct) 1e-17 ... 1e-38
-    lo, hi = (1.9, 2.1) if d >= 20 else (1.3, 1.5)
-    Xp = rng.uniform(lo, hi, (m, d)).astype(np.float32)
+    # products of d factors stay in fp32 range: factors near 1 (SEL2ND, SUB), 2 (MUL) and 3 (ADD)
+    Xp = rng.uniform(1.9, 2.1, (m, d)).astype(np.float32)
     Yp = rng.uniform(0.9, 1.1, (n, d)).astype(np.float32)
     rp, ci, vd = (torch.from_numpy(a).cuda() for a in (rowptr, colidx, vals))
     dev = {k: torch.from_numpy(v).cuda() for k, v in (("Xs", Xs), ("Ys", Ys), ("Xp", Xp), ("Yp", Yp))}
@@ -71,7 +68,15 @@ def test_every_valid_tuple(B, d):
         Z.fill_(float("nan"))
         plan.execute(ops, None if vop == "SEL2ND" else Xd, Yd, Z, vd)
         torch.cuda.synchronize()
-        err, am, viol = oracle.compare(Z.cpu().numpy(), Zr, S)
+        Zg = Z.cpu().numpy()
+        # results below fp32's range (a sigmoid of several hundred): the double oracle still holds 1e-200,
+        # fp32 holds 0; there the rule is "nothing but such a tiny number", not a relative error
+        tiny = S < 1e-30
+        assert (np.abs(Zg[tiny]) <= 1e-30).all()
+        S = np.where(tiny, 0.0, S)
+        Zg = np.where(tiny, 0.0, Zg)
+        Zr = np.where(tiny, 0.0, Zr)
+        err, am, viol = oracle.compare(Zg.astype(np.float32), Zr, S)
         count += 1
         if viol != 0 or not err <= TOL:
             failures.append(f"{(vop, rop, sop, mop, aop)}: err {err:.3e} at {am}, viol {viol}")
