@@ -1,7 +1,8 @@
 """Every valid op tuple of the selector (4 VOP x 26 valid ROP/SOP pairs x 3 MOP x 4 AOP = 1248) against the
-oracle, on a small pattern that reaches every bin of the schedule, at a dimension with instances of its own
-(32), one between instance sizes (20, masked) and one only the general kernel takes (6).  A dispatch slip --
-a tuple recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
+oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
+(32, 128), one between instance sizes (20, masked) and one only the general kernel takes (6), and with Y
+stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128).  A dispatch slip -- a tuple
+recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
 import itertools
 
 import numpy as np
@@ -33,8 +34,20 @@ def all_valid_tuples(B):
         yield vop, rop, sop, mop, aop
 
 
-@pytest.mark.parametrize("d", (32, 20, 6))
-def test_every_valid_tuple(B, d):
+def rounded(Y, fmt):
+    if fmt == "f16":
+        return Y.astype(np.float16).astype(np.float32)
+    if fmt == "bf16":
+        u = np.ascontiguousarray(Y, dtype=np.float32).view(np.uint32).astype(np.uint64)
+        keep, rest = u >> 16, u & 0xFFFF
+        keep = keep + ((rest > 0x8000) | ((rest == 0x8000) & ((keep & 1) == 1)))
+        return (keep.astype(np.uint32) << 16).view(np.float32)
+    return Y
+
+
+@pytest.mark.parametrize("d,fmt", [(32, "f32"), (20, "f32"), (6, "f32"), (128, "f32"), (32, "bf16"), (64, "f16"),
+                                   (128, "bf16"), (128, "f16")])
+def test_every_valid_tuple(B, d, fmt):
     rng = np.random.default_rng(2024 + d)
     m, n = 48, 90
     degs = rng.integers(0, 9, m)
@@ -49,9 +62,15 @@ def test_every_valid_tuple(B, d):
     # x - y >= 0 and everything positive: no scaling step comes near the pole of 1/(1+s)
     Xs = rng.uniform(0.30, 0.50, (m, d)).astype(np.float32)
     Ys = rng.uniform(0.05, 0.25, (n, d)).astype(np.float32)
-    # products of d factors stay in fp32 range: factors near 1 (SEL2ND, SUB), 2 (MUL) and 3 (ADD)
-    Xp = rng.uniform(1.9, 2.1, (m, d)).astype(np.float32)
-    Yp = rng.uniform(0.9, 1.1, (n, d)).astype(np.float32)
+    # products of d factors must not overflow fp32: factors near 1 (SEL2ND, SUB), 2 (MUL) and 3 (ADD) up to
+    # d = 32; for longer rows x + y near 1 (the other products then run below the fp32 range: see `tiny`)
+    if d <= 32:
+        Xp = rng.uniform(1.9, 2.1, (m, d)).astype(np.float32)
+        Yp = rng.uniform(0.9, 1.1, (n, d)).astype(np.float32)
+    else:
+        Xp = rng.uniform(0.50, 0.52, (m, d)).astype(np.float32)
+        Yp = rng.uniform(0.49, 0.51, (n, d)).astype(np.float32)
+    Ys, Yp = rounded(Ys, fmt), rounded(Yp, fmt)      # what the kernels see when Y is stored in 2 bytes
     rp, ci, vd = (torch.from_numpy(a).cuda() for a in (rowptr, colidx, vals))
     dev = {k: torch.from_numpy(v).cuda() for k, v in (("Xs", Xs), ("Ys", Ys), ("Xp", Xp), ("Yp", Yp))}
     plan = B.Plan(m, n, rp, ci, {"small_row_max": 4, "split_row_min": 32, "chunk_edges": 256, "column_classes": 8,
@@ -59,6 +78,11 @@ def test_every_valid_tuple(B, d):
     st = plan.stats()
     assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0
     Z = torch.empty((m, d), dtype=torch.float32, device="cuda")
+    if fmt != "f32":
+        for k in ("Ys", "Yp"):
+            h = torch.zeros((n, d), dtype=torch.int16, device="cuda")
+            (B.fusedmm_to_bf16 if fmt == "bf16" else B.fusedmm_to_f16)(h, dev[k], n * d)
+            dev[k + "h"] = h
     failures, count = [], 0
     for vop, rop, sop, mop, aop in all_valid_tuples(B):
         X, Y, Xd, Yd = (Xp, Yp, dev["Xp"], dev["Yp"]) if rop == "RMUL" else (Xs, Ys, dev["Xs"], dev["Ys"])
@@ -66,7 +90,12 @@ def test_every_valid_tuple(B, d):
         Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, OAOP[aop], alpha=0.37)
         ops = B.make_ops(vop, rop, sop, mop, aop=aop, alpha=0.37)
         Z.fill_(float("nan"))
-        plan.execute(ops, None if vop == "SEL2ND" else Xd, Yd, Z, vd)
+        Xarg = None if vop == "SEL2ND" else Xd
+        if fmt == "f32":
+            plan.execute(ops, Xarg, Yd, Z, vd)
+        else:
+            Yh = dev["Yph" if rop == "RMUL" else "Ysh"]
+            (plan.execute_bf16y if fmt == "bf16" else plan.execute_f16y)(ops, Xarg, Yh, Z, vd)
         torch.cuda.synchronize()
         Zg = Z.cpu().numpy()
         # results below fp32's range (a sigmoid of several hundred): the double oracle still holds 1e-200,
@@ -82,4 +111,4 @@ def test_every_valid_tuple(B, d):
             failures.append(f"{(vop, rop, sop, mop, aop)}: err {err:.3e} at {am}, viol {viol}")
     plan.close()
     assert count == 1248
-    assert not failures, f"d={d}: {len(failures)} of {count} tuples differ from the oracle, first: {failures[:5]}"
+    assert not failures, f"d={d} {fmt}: {len(failures)} of {count} tuples differ from the oracle, first: {failures[:5]}"
