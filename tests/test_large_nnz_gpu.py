@@ -81,3 +81,54 @@ def test_offsets_beyond_2_to_31(B):
     Zg = Z.cpu().numpy()
     plan.close()
     assert np.array_equal(Zg, closed_form(deg, step, first))
+
+
+def test_operand_offsets_beyond_4_gib(B):
+    """X, Y and Z of 6.5 GB each (3.2 M rows of 512 floats): row offsets in bytes need more than 32 bits.  A GCN sum
+    and a tuple that reads X (s = sum_j (x_uj - y_vj), w = s * y_v), on integer data, against closed forms."""
+    d, m = 512, 3_200_000
+    n = m
+    u = np.arange(m, dtype=np.int64)
+    deg = u % 3
+    long_rows = u % 5000 == 7
+    deg[long_rows] = 3000
+    step = np.ones(m, dtype=np.int64)
+    step[long_rows] = n // 3000
+    first = np.where(step == 1, (u * 7919) % (n - deg), 0)
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(deg)
+    nnz = int(rowptr[-1])
+    rp, degd, stepd, firstd = (torch.from_numpy(a).cuda() for a in (rowptr, deg, step, first))
+    rows = torch.repeat_interleave(torch.arange(m, dtype=torch.int64, device="cuda"), degd)
+    k = torch.arange(nnz, dtype=torch.int64, device="cuda") - rp[rows]
+    ci = (firstd[rows] + k * stepd[rows]).to(torch.int32)
+    del rows, k
+    assert int(ci.max()) * d * 4 > (1 << 32)
+    j = torch.arange(d, device="cuda")
+    Y = ((torch.arange(n, device="cuda")[:, None] + j[None, :]) % 4).float()
+    X = torch.zeros((m, d), dtype=torch.float32, device="cuda")
+    X[:, 0] = (torch.arange(m, device="cuda") % 3).float()          # sum_j x_uj = u mod 3
+    vals = torch.ones(nnz, dtype=torch.float32, device="cuda")
+    Z = torch.empty((m, d), dtype=torch.float32, device="cuda")
+    plan = B.Plan(m, n, rp, ci)
+
+    def gcn_block(lo, hi):      # sum_k ((first + k*step + j) mod 4), rows lo .. hi-1
+        out = torch.zeros((hi - lo, d), dtype=torch.int64, device="cuda")
+        for r in range(4):
+            cnt = (degd[lo:hi] + 3 - r) // 4
+            out += cnt[:, None] * ((firstd[lo:hi, None] + r * stepd[lo:hi, None] + j[None, :]) % 4)
+        return out
+
+    row_sum_y = (d // 4) * 6                                         # sum_j y_vj for any v: d is a multiple of 4
+    for ops, scale in (("gcn", None), (B.make_ops("SUB", "RSUM", "NOOP", "MUL_Y"), "x")):
+        Z.fill_(float("nan"))
+        plan.execute(ops, None if scale is None else X, Y, Z, vals if scale is None else None)
+        torch.cuda.synchronize()
+        for lo in range(0, m, 400_000):
+            hi = min(m, lo + 400_000)
+            want = gcn_block(lo, hi)
+            if scale is not None:
+                want = want * ((torch.arange(lo, hi, device="cuda") % 3) - row_sum_y)[:, None]
+            assert int(want.abs().max()) < (1 << 24)
+            assert torch.equal(Z[lo:hi], want.float()), f"{ops if scale is None else 'SUB/RSUM tuple'}: rows {lo}..{hi}"
+    plan.close()
