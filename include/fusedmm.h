@@ -47,7 +47,9 @@ extern "C" {
 
 /* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
  * paper's sweep, Table VI) with 16-byte aligned rows runs the specialised
- * kernels; any other 1 <= d <= FUSEDMM_MAX_D runs the general kernel. */
+ * kernels, every other multiple of 4 up to 512 the same schedule on the next
+ * larger of them; any other 1 <= d <= FUSEDMM_MAX_D runs the general kernel
+ * (see fusedmm_ops_t below). */
 #define FUSEDMM_MAX_D 2048
 
 typedef enum fusedmm_status {
@@ -87,8 +89,9 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
 /* The op selector.  Every combination of the values above is valid except that
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
  * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
- * The five application patterns below run the specialised kernels when d is 32, 64, 128, 256 or
- * 512; every other tuple, and every other d that is a multiple of 4 up to 512, runs the same
+ * The five application patterns below, and the GCN pattern with MAX, MIN or MEAN pooling instead of
+ * the sum, run the specialised kernels when d is 32, 64, 128, 256 or 512; every other tuple, and
+ * every other d that is a multiple of 4 up to 512, runs the same
  * schedule with the ops read at run time (on the next larger kernel size, skipping the columns
  * beyond d); any other d up to FUSEDMM_MAX_D, or operands that are not 16-byte aligned, run the
  * general kernel (one wavefront per row or per 256-entry segment of a long row: a correctness path,
@@ -191,8 +194,9 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
 /* The same operation with Y stored as bfloat16 (the upper 16 bits of each fp32 value): the
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
  * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
- * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes per lane).  Only d in {32, 64, 128, 256, 512} with aligned operands
- * (FUSEDMM_ERR_UNSUPPORTED_DIM / FUSEDMM_ERR_INVALID_ARG otherwise).  The result is that of
+ * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes per lane).  Only d in
+ * {32, 64, 128, 256, 512} with aligned operands (FUSEDMM_ERR_UNSUPPORTED_DIM /
+ * FUSEDMM_ERR_INVALID_ARG otherwise).  The result is that of
  * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back, up to the
  * order of the fp32 sums (the lane groups are half as wide). */
 int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
@@ -215,8 +219,9 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic.  Runs the general kernel (one wavefront per
- * row or 256-entry segment, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the specialised schedule is
- * fp32 only.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened. */
+ * row or 256-entry segment, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the
+ * specialised schedule is fp32 only.  Arguments, layout, ownership and errors as for
+ * fusedmm_execute; ops->alpha is widened. */
 int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                         const double* d_values, const double* d_X, int64_t ldx,
                         const double* d_Y, int64_t ldy, double* d_Z, int64_t ldz, void* stream);
