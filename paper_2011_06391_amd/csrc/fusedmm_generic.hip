@@ -8,20 +8,6 @@ namespace fmm {
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 template <class T>
-__device__ __forceinline__ T wave_allreduce(T v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
-template <class T>
-__device__ __forceinline__ T wave_allreduce_mul(T v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v *= __shfl_xor(v, off);
-  return v;
-}
-
-template <class T>
 __device__ __forceinline__ T vop_apply(int vop, T x, T y) {
   switch (vop) {
     case FUSEDMM_VOP_MUL: return x * y;
@@ -47,18 +33,39 @@ __device__ __forceinline__ T sop_apply(int sop, T s, T alpha) {
   }
 }
 
-// Algorithm 1, UpdateU, one wavefront per row (or per segment of a long row): lane l owns elements
-// l, l+64, l+128, ... of z_u in registers.  The five steps run per stored entry in the paper's order; the
-// row of Y is read twice (VOP/ROP pass, then MOP/AOP pass), the second time from cache.
-// Covers every op of Table II: scalar messages (after a reduction, or the edge value) and
-// vector messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation
-// from a zero-initialised z_u, and MEAN (the sum divided by the row length).  T is float or
-// double (Section V: the method is not tied to single precision).
-constexpr int kGenericAcc = FUSEDMM_MAX_D / 64;
+// Algorithm 1, UpdateU, one wavefront per row (or per segment of a long row).  The five steps run per
+// stored entry in the paper's order.  A group of G lanes works on one stored entry and owns z_u (lane g of
+// the group: elements g, g+G, ... ; NP of them, in registers); rows of up to 32 elements use groups of
+// 2 ... 32 lanes, so that a wavefront works on 64/G entries at once, and the groups' results are combined at
+// the end (exchange by lane index in a fixed order: reproducible).  Column indices are read 64 at a time;
+// x_u is read once; U entries per group are in flight, and the row of Y read for VOP/ROP is kept for MOP.
+// Covers every op of Table II: scalar messages (after a reduction, or the edge value) and vector
+// messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation from a
+// zero-initialised z_u, and MEAN (the sum divided by the row length).  T is float or double (Section V: the
+// method is not tied to single precision).
+template <class T, int G>
+__device__ __forceinline__ T group_allreduce(T v, bool product) {
+#pragma unroll
+  for (int off = G / 2; off >= 1; off >>= 1) {
+    const T o = __shfl_xor(v, off);
+    v = product ? v * o : v + o;
+  }
+  return v;
+}
 
 template <class T>
+__device__ __forceinline__ T aop_apply(int aop, T acc, T w) {
+  if (aop == FUSEDMM_AOP_SUM || aop == FUSEDMM_AOP_MEAN) return acc + w;
+  if (aop == FUSEDMM_AOP_MAX) return w > acc ? w : acc;  // a NaN message is skipped, as by fmax
+  return w < acc ? w : acc;
+}
+
+template <class T, int NP, int G, int U>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const GenericArgsT<T> a) {
+  static_assert(G == 64 || NP == 1, "lane groups narrower than a wavefront hold one element per lane");
+  constexpr int S = 64 / G;  // stored entries a wavefront works on at once
   const int lane = threadIdx.x & 63;
+  const int slot = lane / G, g = lane % G;
   // wavefronts [0, m): one row each (rows longer than kGenericSplit are left to the segment
   // wavefronts that follow); wavefronts [m, m + n_segs): one segment of a long row each
   const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
@@ -88,51 +95,88 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_generic_kernel(const Ge
   }
   const bool uses_x = a.vop != FUSEDMM_VOP_SEL2ND;
   const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
-  const T* xr = uses_x ? a.X + row * a.ldx : nullptr;
-  T acc[kGenericAcc];
+  const bool reads_val = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.sop == kSopValueMinusSigmoid;
+  const bool product = a.rop == FUSEDMM_ROP_RMUL;
+  T x[NP], acc[NP];
 #pragma unroll
-  for (int i = 0; i < kGenericAcc; ++i) acc[i] = T(0);  // z_u <- 0
+  for (int i = 0; i < NP; ++i) {
+    const int k = g + G * i;
+    x[i] = (uses_x && k < d) ? a.X[row * a.ldx + k] : T(0);
+    acc[i] = T(0);  // z_u <- 0
+  }
 
-  for (int64_t e = e0; e < e1; ++e) {
-    const T* yr = a.Y + (int64_t)a.colidx[e] * a.ldy;
-    T h = T(0);
-    if (a.sop == FUSEDMM_SOP_EDGE_VALUE) {
-      h = a.values[e];
-    } else if (a.rop != FUSEDMM_ROP_NOOP) {
-      T p = (a.rop == FUSEDMM_ROP_RMUL) ? T(1) : T(0);
-      for (int k = lane; k < d; k += 64) {
-        const T t = vop_apply<T>(a.vop, uses_x ? xr[k] : T(0), yr[k]);  // VOP
-        if (a.rop == FUSEDMM_ROP_RSUM) p += t;                            // ROP (per-lane share)
-        else if (a.rop == FUSEDMM_ROP_RMUL) p *= t;
-        else p += t * t;
-      }
-      T s = (a.rop == FUSEDMM_ROP_RMUL) ? wave_allreduce_mul<T>(p) : wave_allreduce<T>(p);
-      if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_of(s);
-      h = a.sop == kSopValueMinusSigmoid ? a.values[e] - sop_apply<T>(FUSEDMM_SOP_SIGMOID, s, a.alpha)
-                                         : sop_apply<T>(a.sop, s, a.alpha);  // SOP on the scalar
+  for (int64_t base = e0; base < e1; base += 64) {
+    const int cnt = (int)((e1 - base) < 64 ? (e1 - base) : 64);  // wave-uniform
+    int colb = 0;
+    T valb = T(0);
+    if (lane < cnt) {
+      colb = a.colidx[base + lane];
+      if (reads_val) valb = a.values[base + lane];
     }
+    for (int k0 = 0; k0 < cnt; k0 += S * U) {
+      bool ok[U];
+      T av[U];
+      T y[U][NP];
 #pragma unroll
-    for (int i = 0; i < kGenericAcc; ++i) {
-      const int k = lane + 64 * i;
-      if (k < d) {
-        const T y = yr[k];
-        const T t = vop_apply<T>(a.vop, uses_x ? xr[k] : T(0), y);
-        const T hk = scalar_h ? h : sop_apply<T>(a.sop, t, a.alpha);  // SOP on the element
-        T w;                                                             // MOP
-        if (a.mop == FUSEDMM_MOP_SEL2ND) w = y;
-        else if (a.mop == FUSEDMM_MOP_MUL_Y) w = hk * y;
-        else w = hk * t;
-        if (a.aop == FUSEDMM_AOP_SUM || a.aop == FUSEDMM_AOP_MEAN) acc[i] += w;  // AOP
-        else if (a.aop == FUSEDMM_AOP_MAX) acc[i] = w > acc[i] ? w : acc[i];  // a NaN message is skipped, as by fmax
-        else acc[i] = w < acc[i] ? w : acc[i];
+      for (int u = 0; u < U; ++u) {
+        const int j = k0 + u * S + slot;
+        ok[u] = j < cnt;
+        const int c = __shfl(colb, j & 63);
+        av[u] = __shfl(valb, j & 63);
+        const T* yr = a.Y + (int64_t)c * a.ldy;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          const int k = g + G * i;
+          y[u][i] = (ok[u] && k < d) ? yr[k] : T(0);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (k0 + u * S >= cnt) break;  // wave-uniform: no group has an entry in this step
+        T h = T(0);
+        if (a.sop == FUSEDMM_SOP_EDGE_VALUE) {
+          h = av[u];
+        } else if (a.rop != FUSEDMM_ROP_NOOP) {
+          T p = product ? T(1) : T(0);
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            const T t = vop_apply<T>(a.vop, x[i], y[u][i]);  // VOP (0 beyond d: x and y are 0 there)
+            if (a.rop == FUSEDMM_ROP_RSUM) p += t;            // ROP (per-lane share)
+            else if (product) p *= (g + G * i < d) ? t : T(1);
+            else p += t * t;
+          }
+          T s = group_allreduce<T, G>(p, product);
+          if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_of(s);
+          h = a.sop == kSopValueMinusSigmoid ? av[u] - sop_apply<T>(FUSEDMM_SOP_SIGMOID, s, a.alpha)
+                                             : sop_apply<T>(a.sop, s, a.alpha);  // SOP on the scalar
+        }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          if (ok[u] && g + G * i < d) {
+            const T yk = y[u][i];
+            const T t = vop_apply<T>(a.vop, x[i], yk);
+            const T hk = scalar_h ? h : sop_apply<T>(a.sop, t, a.alpha);  // SOP on the element
+            T wk;                                                           // MOP
+            if (a.mop == FUSEDMM_MOP_SEL2ND) wk = yk;
+            else if (a.mop == FUSEDMM_MOP_MUL_Y) wk = hk * yk;
+            else wk = hk * t;
+            acc[i] = aop_apply<T>(a.aop, acc[i], wk);                       // AOP
+          }
+        }
       }
     }
   }
-  const T post = (whole_row && a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? T(1) / (T)(e1 - e0) : T(1);  // mean pooling
+  if constexpr (S > 1) {  // the groups' shares of z_u
 #pragma unroll
-  for (int i = 0; i < kGenericAcc; ++i) {
-    const int k = lane + 64 * i;
-    if (k < d) zr[k] = acc[i] * post;
+    for (int off = G; off < 64; off <<= 1) acc[0] = aop_apply<T>(a.aop, acc[0], __shfl_xor(acc[0], off));
+  }
+  const T post = (whole_row && a.aop == FUSEDMM_AOP_MEAN && e1 > e0) ? T(1) / (T)(e1 - e0) : T(1);  // mean pooling
+  if (slot == 0) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int k = g + G * i;
+      if (k < d) zr[k] = acc[i] * post;
+    }
   }
 }
 
@@ -163,7 +207,20 @@ static hipError_t launch_generic_t(const GenericArgsT<T>& a, hipStream_t stream)
   if (a.m <= 0) return hipSuccess;
   const int64_t waves = a.m + a.n_segs;
   const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(fusedmm_generic_kernel<T>, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a);
+  static_assert(FUSEDMM_MAX_D == 64 * 32, "the widest instance holds 32 elements per lane");
+#define FMM_GENERIC(NP, G, U) \
+  hipLaunchKernelGGL((fusedmm_generic_kernel<T, NP, G, U>), dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, a)
+  if (a.d <= 2) FMM_GENERIC(1, 2, 4);
+  else if (a.d <= 4) FMM_GENERIC(1, 4, 4);
+  else if (a.d <= 8) FMM_GENERIC(1, 8, 4);
+  else if (a.d <= 16) FMM_GENERIC(1, 16, 4);
+  else if (a.d <= 32) FMM_GENERIC(1, 32, 4);
+  else if (a.d <= 64) FMM_GENERIC(1, 64, 4);
+  else if (a.d <= 128) FMM_GENERIC(2, 64, 4);
+  else if (a.d <= 256) FMM_GENERIC(4, 64, 2);
+  else if (a.d <= 512) FMM_GENERIC(8, 64, 2);
+  else FMM_GENERIC(32, 64, 1);
+#undef FMM_GENERIC
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && a.n_merges > 0 && !a.visit_counts) {
     const int64_t mblocks = ((int64_t)a.n_merges + kWavesPerBlock - 1) / kWavesPerBlock;
