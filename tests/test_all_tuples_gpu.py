@@ -1,6 +1,7 @@
 """Every valid op tuple of the selector (4 VOP x 26 valid ROP/SOP pairs x 3 MOP x 4 AOP = 1248) against the
 oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
-(32, 128), one between instance sizes (20, masked) and one only the general kernel takes (6), and with Y
+(32, 128), one between instance sizes (20, masked) and those only the general kernel takes (6 and seven
+more, one per instance of that kernel), and with Y
 stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128).  A dispatch slip -- a tuple
 recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
 import itertools
@@ -46,7 +47,10 @@ def rounded(Y, fmt):
 
 
 @pytest.mark.parametrize("d,fmt", [(32, "f32"), (20, "f32"), (6, "f32"), (128, "f32"), (32, "bf16"), (64, "f16"),
-                                   (128, "bf16"), (128, "f16")])
+                                   (128, "bf16"), (128, "f16"),
+                                   # the general kernel's other lane-group widths and register counts
+                                   (2, "f32"), (3, "f32"), (13, "f32"), (27, "f32"), (97, "f32"), (301, "f32"),
+                                   (700, "f32")])
 def test_every_valid_tuple(B, d, fmt):
     rng = np.random.default_rng(2024 + d)
     m, n = 48, 90

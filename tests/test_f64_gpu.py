@@ -43,7 +43,8 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("d", (5, 64, 128, 200))
+# every lane-group width and register count of the kernel
+@pytest.mark.parametrize("d", (2, 3, 5, 13, 27, 64, 128, 200, 301, 700))
 @pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
 def test_f64_matches_oracle(B, case, d):
     gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
