@@ -20,6 +20,13 @@ def B():
     return binding
 
 
+@pytest.fixture(autouse=True)
+def release_cached_memory():
+    """These tests hold tens of GB; hand them back so the library's own allocations in later tests find room."""
+    yield
+    torch.cuda.empty_cache()
+
+
 def build_pattern():
     """Row u holds deg[u] entries at columns first[u] + k * step[u], k = 0 .. deg[u]-1 (sorted, distinct)."""
     m, n = (1 << 20) + 6000, 3_200_000
