@@ -593,3 +593,45 @@ def test_workload_full_size_sampled_rows(B, name):
     assert counts.min().item() == 1 and counts.max().item() == 1
     print(f"{name}: nnz={g.nnz} sampled rows {len(rows)} max rel err {err:.2e} plan {plan.stats()}")
     plan.close()
+
+
+def test_one_plan_many_dimensions_and_entry_points(B):
+    """One plan serves calls of different feature dimensions and entry points in turn: the partial-row scratch
+    grows (512 after 32), is reused with a wider stride than the call needs (64 after 512), and the general
+    kernel, the 2-byte storage modes and fp64 keep scratch of their own.  Every call against the oracle."""
+    rng = np.random.default_rng(77)
+    m, n = 257, 400
+    long_rows = {5: 130, 9: 700, 100: 2500, 256: 97}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    vals = rng.uniform(-1, 1, len(colidx)).astype(np.float32)
+    rp, ci, vd = dev(rowptr), dev(colidx), dev(vals)
+    plan = B.Plan(m, n, rp, ci, TILED)
+    assert plan.stats()["tiled_rows"] > 0 and plan.stats()["split_rows"] > 0
+    f16 = lambda a: a.astype(np.float16).astype(np.float32)
+    sequence = [(32, "f32", "sigmoid"), (512, "f32", "tdist"), (64, "f32", "gcn"), (6, "f32", "fr"), (128, "f16", "sigmoid"),
+                (100, "f32", "one_minus_sigmoid"), (200, "f64", "tdist"), (512, "f32", "fr"), (32, "f32", "gcn"),
+                (1027, "f32", "sigmoid"), (128, "f32", "one_minus_sigmoid")]
+    for d, kind, pattern in sequence:
+        X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+        Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+        if kind == "f16":
+            Y = f16(Y)
+        Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
+        ops = B.fusedmm_ops_preset(pattern)
+        ops.alpha = ALPHA
+        if kind == "f64":
+            Xd, Yd, v64 = dev(X.astype(np.float64)), dev(Y.astype(np.float64)), dev(vals.astype(np.float64))
+            Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+            plan.execute_f64(ops, Xd, Yd, Z, v64)
+        else:
+            Xd, Yd = dev(X), dev(Y)
+            Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+            if kind == "f16":
+                Yh = torch.zeros((n, d), dtype=torch.int16, device="cuda")
+                B.fusedmm_to_f16(Yh, Yd, n * d)
+                plan.execute_f16y(ops, Xd, Yh, Z, vd)
+            else:
+                plan.execute(ops, Xd, Yd, Z, vd)
+        torch.cuda.synchronize()
+        check(Z.cpu().numpy(), Zr, S, f"{pattern} d={d} {kind}")
+    plan.close()
