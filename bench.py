@@ -377,7 +377,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2); e1, e2: minibatch embedding epochs (secondary)")
+    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2); e1, e2: minibatch embedding epochs (secondary); rmat:SCALE:PAIRS: an R-MAT "
+                         "graph of that size for density sweeps (secondary)")
     ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",

@@ -249,6 +249,21 @@ def make_workload(name: str, d: Optional[int] = None, relabel: bool = True) -> W
         Y = fill_uniform((g.n, dd), 3005, -0.5, 0.5)
         return Workload(name, "one_minus_sigmoid", dd, g, X, Y,
                         "R-MAT scale 22, 2^26 pairs symmetrised, X!=Y U[-0.5,0.5)")
+    if name.startswith("rmat:"):
+        # density sweeps (the paper's sensitivity experiment: an R-MAT graph whose edge count is doubled
+        # repeatedly): "rmat:SCALE:PAIRS", sigmoid-embedding pattern, features as c2
+        try:
+            _, scale, pairs = name.split(":")
+            scale, pairs = int(scale), int(pairs)
+        except ValueError:
+            raise ValueError(f"workload {name!r}: expected rmat:SCALE:PAIRS") from None
+        if not (4 <= scale <= 24 and 1 <= pairs <= (1 << 28)):
+            raise ValueError(f"workload {name!r}: scale 4..24, pairs 1..2^28")
+        dd = d or 128
+        g = rmat(scale, pairs, 1100 + scale, relabel=relabel)
+        X = fill_uniform((g.m, dd), 2100 + scale, -0.5, 0.5)
+        return Workload(name, "one_minus_sigmoid", dd, g, X, X,
+                        f"R-MAT scale {scale}, {pairs} pairs symmetrised, X=Y U[-0.5,0.5)")
     raise ValueError(f"unknown workload {name!r}")
 
 
