@@ -135,3 +135,19 @@ def test_epoch_workloads():
         w2 = synth.make_epoch_workload(name)
         assert np.array_equal(w.negatives, w2.negatives) and np.array_equal(w.X0, w2.X0)
         assert np.array_equal(g.colidx, w2.csr.colidx)
+
+
+def test_density_sweep_workload_spec():
+    """rmat:SCALE:PAIRS builds an R-MAT graph of that size (deterministic, symmetric); bad specs are rejected."""
+    a = synth.make_workload("rmat:10:4096", d=8)
+    b = synth.make_workload("rmat:10:4096", d=8)
+    assert a.csr.m == 1024 and a.d == 8 and a.pattern == "one_minus_sigmoid"
+    assert np.array_equal(a.csr.colidx, b.csr.colidx) and np.array_equal(a.X, b.X)
+    dense = np.zeros((1024, 1024), dtype=bool)
+    rows = np.repeat(np.arange(1024), np.diff(a.csr.rowptr))
+    dense[rows, a.csr.colidx] = True
+    assert (dense == dense.T).all() and not dense.diagonal().any()
+    assert synth.make_workload("rmat:10:8192", d=8).csr.nnz > a.csr.nnz
+    for bad in ("rmat:10", "rmat:x:5", "rmat:40:5", "rmat:10:0"):
+        with pytest.raises(ValueError):
+            synth.make_workload(bad)
