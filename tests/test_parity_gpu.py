@@ -635,3 +635,35 @@ def test_one_plan_many_dimensions_and_entry_points(B):
         torch.cuda.synchronize()
         check(Z.cpu().numpy(), Zr, S, f"{pattern} d={d} {kind}")
     plan.close()
+
+
+def test_bound_call_equals_execute(B):
+    """Plan.bind marshals the arguments once; the call it returns must issue exactly what execute issues
+    (fp32 and half storage), any number of times, and report errors as exceptions."""
+    rng = np.random.default_rng(5)
+    m, n, d = 300, 450, 64
+    rowptr, colidx = skewed_csr(rng, m, n, {7: 900, 8: 200}, sort_cols=True)
+    X = rng.uniform(-0.5, 0.5, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
+    rp, ci, Xd, Yd = dev(rowptr), dev(colidx), dev(X), dev(Y)
+    plan = B.Plan(m, n, rp, ci, TILED)
+    Z1 = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+    Z2 = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+    plan.execute("tdist", Xd, Yd, Z1)
+    call = plan.bind("tdist", Xd, Yd, Z2)
+    for _ in range(3):
+        Z2.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(Z1, Z2)
+    Yh = torch.zeros((n, d), dtype=torch.int16, device="cuda")
+    B.fusedmm_to_f16(Yh, Yd, n * d)
+    plan.execute_f16y("sigmoid", Xd, Yh, Z1)
+    plan.bind("sigmoid", Xd, Yh, Z2, y_format="f16")()
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z2)
+    with pytest.raises(B.FusedMMError):
+        plan.bind("sigmoid", Xd, Yd, Yd[:m])()      # Z overlaps Y
+    with pytest.raises(ValueError):
+        plan.bind("sigmoid", Xd, Yd, Z2, y_format="fp8")
+    plan.close()
