@@ -17,17 +17,21 @@ __device__ __forceinline__ T vop_apply(int vop, T x, T y) {
   }
 }
 
-__device__ __forceinline__ float exp_of(float v) { return expf(v); }
+// fp32 uses the hardware's exp2 / reciprocal / square root (1 ulp each, as the specialised kernels do);
+// fp64 the library routines.  e^big = inf gives 1/(1+inf) = 0, never NaN.
+__device__ __forceinline__ float exp_of(float v) { return __builtin_amdgcn_exp2f(v * 1.4426950408889634f); }
 __device__ __forceinline__ double exp_of(double v) { return exp(v); }
-__device__ __forceinline__ float sqrt_of(float v) { return sqrtf(v); }
+__device__ __forceinline__ float sqrt_of(float v) { return __builtin_amdgcn_sqrtf(v); }
 __device__ __forceinline__ double sqrt_of(double v) { return sqrt(v); }
+__device__ __forceinline__ float recip_of(float v) { return __builtin_amdgcn_rcpf(v); }
+__device__ __forceinline__ double recip_of(double v) { return 1.0 / v; }
 
 template <class T>
 __device__ __forceinline__ T sop_apply(int sop, T s, T alpha) {
   switch (sop) {
-    case FUSEDMM_SOP_SIGMOID: return T(1) / (T(1) + exp_of(-s));
-    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return T(1) / (T(1) + exp_of(s));
-    case FUSEDMM_SOP_INV_1P: return T(1) / (T(1) + s);
+    case FUSEDMM_SOP_SIGMOID: return recip_of(T(1) + exp_of(-s));
+    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return recip_of(T(1) + exp_of(s));
+    case FUSEDMM_SOP_INV_1P: return recip_of(T(1) + s);
     case FUSEDMM_SOP_SCAL: return alpha * s;
     default: return s;  // NOOP
   }
@@ -43,14 +47,34 @@ __device__ __forceinline__ T sop_apply(int sop, T s, T alpha) {
 // messages (no reduction: SOP acts on each element of t); SUM / MAX / MIN accumulation from a
 // zero-initialised z_u, and MEAN (the sum divided by the row length).  T is float or double (Section V: the
 // method is not tied to single precision).
+// Sum (or product) over each aligned group of G lanes, result in every lane of the group.  fp32 takes
+// the data-parallel-primitive moves inside a row of 16 lanes (neighbour, quad halves, mirror within 8,
+// mirror within 16) and a lane exchange beyond; fp64 exchanges lanes all the way.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
 template <class T, int G>
 __device__ __forceinline__ T group_allreduce(T v, bool product) {
-#pragma unroll
-  for (int off = G / 2; off >= 1; off >>= 1) {
-    const T o = __shfl_xor(v, off);
+  if constexpr (sizeof(T) == 4) {
+    float o;
+    o = dpp_lane<0xB1>(v);  // quad_perm [1,0,3,2]
     v = product ? v * o : v + o;
+    if constexpr (G >= 4) { o = dpp_lane<0x4E>(v); v = product ? v * o : v + o; }   // quad_perm [2,3,0,1]
+    if constexpr (G >= 8) { o = dpp_lane<0x141>(v); v = product ? v * o : v + o; }  // row_half_mirror
+    if constexpr (G >= 16) { o = dpp_lane<0x140>(v); v = product ? v * o : v + o; } // row_mirror
+    if constexpr (G >= 32) { o = __shfl_xor(v, 16); v = product ? v * o : v + o; }
+    if constexpr (G >= 64) { o = __shfl_xor(v, 32); v = product ? v * o : v + o; }
+    return v;
+  } else {
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) {
+      const T o = __shfl_xor(v, off);
+      v = product ? v * o : v + o;
+    }
+    return v;
   }
-  return v;
 }
 
 template <class T>
