@@ -56,6 +56,24 @@ def build(jobs: int = 8, verbose: bool = False) -> str:
     return LIB
 
 
+MICROBENCH_SRC = "bench_l2_delivery.hip"
+MICROBENCH = os.path.join(HERE, "bench_l2_delivery")
+
+
+def build_microbench(verbose: bool = False) -> str:
+    """The load-only delivery-rate microbenchmark: a stand-alone program, not linked into the library."""
+    cmd = ["hipcc", *[f for f in HIPCC_FLAGS if f != "-fPIC"], "-o", MICROBENCH, os.path.join(CSRC, MICROBENCH_SRC)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {MICROBENCH_SRC}:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {MICROBENCH}")
+    return MICROBENCH
+
+
 if __name__ == "__main__":
-    build(verbose=True)
+    if sys.argv[1:] == ["microbench"]:
+        build_microbench(verbose=True)
+    else:
+        build(verbose=True)
     sys.exit(0)
