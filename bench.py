@@ -5,15 +5,24 @@ A step is one fusedmm_execute call (the whole hot path: schedule lookup, gather,
 VOP/ROP/SOP/MOP/AOP, store, split-row merge) over one synthetic workload whose
 inputs already sit in HBM.  Prints ONE JSON line.
 
-    python bench.py [--workload c2] [--steps K] [--warmup W] [--gpus 1]
+    python bench.py [--workload c5] [--steps K] [--warmup W] [--gpus 1]
 
-Metric: G(edge*dim)/s = nnz * d / seconds per step.  The roofline object prices the
-main kernel's algorithmic bytes (no reuse of Y rows assumed) against the 8 TB/s HBM
-peak; cpu_baseline times the unfused CPU oracle (fp32 build) on the host cores.
+The default workload is c5, the largest configuration that fits one GPU (Y = 4 GiB, far
+beyond the caches).  Without --workload the same line also carries, under
+config.all_workloads, value / ms_per_step / kernel_ms / parity for c2, c3 and c4.
+
+Metric: G(edge*dim)/s = nnz * d / seconds per step.  The roofline object prices the bytes
+the main kernel really moved between the L2s and the memory fabric (rocprofv3 FETCH_SIZE +
+WRITE_SIZE per launch, taken from profiles/hbm_traffic_per_launch.txt when that table was
+measured on this very build and plan) against the 8 TB/s HBM peak: a fraction that cannot
+exceed 1.  The algorithmic rate (the paper's "no reuse of Y rows" byte model, Section IV-C)
+is reported beside it as algorithmic_GBs / algorithmic_over_peak; it exceeds the peak when
+the caches serve repeated rows.  cpu_baseline times the unfused CPU oracle (fp32 build).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -23,10 +32,43 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per main-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# each scaled by the same counter's reading for a copy kernel of known size; see profiles/.
-# They belong to the kernel build and default plan the profiles were taken with.
-MEASURED_TRAFFIC_BYTES = {"c2": 372505292, "c3": 26648249513, "c4": 6676424610, "c5": 80830477141}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+
+
+def kernel_sources_sha16() -> str:
+    """Identifies the build the traffic table belongs to: a hash of the library's sources."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2011_06391_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.startswith("fusedmm_") and name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, plan_stats: dict):
+    """L2 <-> fabric bytes per launch of the main kernel from the tracked table, if the table's row was
+    measured with these kernel sources and this plan; else (None, None, why).  Rows: workload, sources
+    hash, partial rows, tile segments, column classes, fetch bytes, write bytes, L2 hit rate, commit."""
+    if not os.path.exists(TRAFFIC_TABLE):
+        return None, None, "no traffic table (profiles/hbm_traffic_per_launch.txt)"
+    sha = kernel_sources_sha16()
+    why = f"no row for workload {workload}"
+    for line in open(TRAFFIC_TABLE):
+        f = line.split("#")[0].split()
+        if len(f) < 9 or f[0] != workload:
+            continue
+        if f[1] != sha:
+            why = f"stale: the table's {workload} row was measured on kernel sources {f[1]}, this build is {sha}"
+            continue
+        if (int(f[2]), int(f[3]), int(f[4])) != (plan_stats["partials"], plan_stats["tile_segments"],
+                                                 plan_stats["column_classes"]):
+            why = f"stale: the table's {workload} row was measured with another plan"
+            continue
+        src = (f"profiles/hbm_traffic_per_launch.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, calibrated "
+               f"with the copy kernel; measured at commit {f[8]}, kernel sources {sha}")
+        return int(f[5]) + int(f[6]), float(f[7]), src
+    return None, None, why
 
 
 def parity_sample(w, rows, Z_rows):
@@ -75,7 +117,8 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
 
 
 def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0,
-        autotune: bool = False, y_storage: str = "f32", with_context: bool = True):
+        autotune: bool = False, y_storage: str = "f32", with_context: bool = True, relabel: bool = True,
+        time_cpu: bool = True):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -84,7 +127,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     binding.load()
     torch.cuda.set_device(0)
     t0 = time.perf_counter()
-    w = synth.make_workload(workload, d=d)
+    w = synth.make_workload(workload, d=d, relabel=relabel)
     g = w.csr
     gen_s = time.perf_counter() - t0
 
@@ -156,8 +199,18 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     kernel_ms = (kernel_ms_sum - empty_ms_sum) / max(1, calls)  # bracket cost measured by an empty bracket per call
     if kernel_ms <= 0.0:  # a kernel of a few microseconds can vanish in the bracket's own jitter
         kernel_ms = kernel_ms_sum / max(1, calls)
-    achieved = tr.model_bytes / (kernel_ms * 1e-3) / 1e9
-    traffic_bytes = None if (y_bf16 or autotune or d or custom_plan) else MEASURED_TRAFFIC_BYTES.get(workload)
+    kernel_s = kernel_ms * 1e-3
+    stats = plan.stats()
+    if y_bf16 or not relabel:
+        traffic_bytes, l2_hit, traffic_source = None, None, "not measured for this storage mode / vertex order"
+    else:
+        traffic_bytes, l2_hit, traffic_source = measured_traffic(workload if not d else f"{workload}:d{w.d}", stats)
+    # the priced bytes: what the kernel moved beyond the L2s when that was measured on this build and plan,
+    # else the compulsory bytes (every array once), a lower bound of it; both keep the fraction below 1
+    priced = traffic_bytes if traffic_bytes is not None else tr.min_bytes
+    basis = ("measured L2<->fabric bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)"
+             if traffic_bytes is not None else "compulsory bytes (every array moved once): a lower bound of the traffic")
+    achieved = priced / kernel_s / 1e9
     out = {
         "metric": "fused SDDMM-SpMM throughput: G(edge*dim)/s + achieved HBM GB/s vs peak, 1 GPU",
         "value": g.nnz * w.d / (ms_per_step * 1e-3) / 1e9,
@@ -166,16 +219,18 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": f"f32 (Y stored as {y_storage})" if y_bf16 else "f32", "data": "synthetic",
         "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
+                   "vertex_order": "seeded random permutation" if relabel else "as generated (natural order)",
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
-                   "empty_rows": int((deg == 0).sum()), "plan": plan.stats(), "plan_ms": plan_ms,
+                   "empty_rows": int((deg == 0).sum()), "plan": stats, "plan_ms": plan_ms,
                    "plan_plus_first_execute_ms": plan_plus_first_execute_ms, "plan_options": options, "autotuned": autotune,
-                   "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s},
+                   "workspace_bytes": plan.workspace_bytes(w.d), "generate_s": gen_s,
+                   "kernel_sources_sha16": kernel_sources_sha16()},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": model.MI355X_HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / model.MI355X_HBM_PEAK_GBS,
-                     "traffic": traffic_bytes,
-                     "traffic_GBs": None if traffic_bytes is None else traffic_bytes / (kernel_ms * 1e-3) / 1e9,
-                     "traffic_frac_of_peak": None if traffic_bytes is None
-                     else traffic_bytes / (kernel_ms * 1e-3) / 1e9 / model.MI355X_HBM_PEAK_GBS,
+                     "frac": achieved / model.MI355X_HBM_PEAK_GBS, "achieved_basis": basis,
+                     "traffic": traffic_bytes, "traffic_source": traffic_source, "l2_hit_rate": l2_hit,
+                     "algorithmic_bytes": tr.model_bytes, "algorithmic_GBs": tr.model_bytes / kernel_s / 1e9,
+                     "algorithmic_over_peak": tr.model_bytes / kernel_s / 1e9 / model.MI355X_HBM_PEAK_GBS,
+                     "compulsory_bytes": tr.min_bytes, "compulsory_GBs": tr.min_bytes / kernel_s / 1e9,
                      "kernel": "fusedmm_fast_kernel", "kernel_ms": kernel_ms,
                      "kernel_timing": "HIP events around the main kernel on the launch stream, same K executes repeated "
                                       "right after the timed region; an empty event bracket per call is subtracted",
@@ -183,7 +238,6 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
                      "kernel_ms_median": (sorted(samples)[len(samples) // 2] - sorted(empties)[len(empties) // 2])
                      if samples else None,
                      "kernel_ms_min": (min(samples) - sorted(empties)[len(empties) // 2]) if samples else None,
-                     "algorithmic_bytes": tr.model_bytes, "compulsory_bytes": tr.min_bytes,
                      "bytes_per_edge": tr.per_edge_bytes, "bytes_per_row": tr.per_row_bytes},
     }
     # Context figures, measured after and outside the timed region (never part of `value`):
@@ -273,7 +327,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     del Z, Xd, Yd, rp, ci
     torch.cuda.empty_cache()
     if with_cpu:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w) if time_cpu else {}
         if not y_bf16:  # the oracle would have to be fed the rounded Y; tests/test_reduced_storage_gpu.py does that
             out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample)
     return out
@@ -367,14 +421,24 @@ def run_epoch(workload: str, steps: int, warmup: int, with_cpu: bool):
     return out
 
 
+HEADLINE = "c5"            # the largest configuration that fits one GPU: the workload of the default line
+OTHER_WORKLOADS = ("c2", "c3", "c4")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2); e1, e2: minibatch embedding epochs (secondary); rmat:SCALE:PAIRS: an R-MAT "
-                         "graph of that size for density sweeps (secondary)")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=None, help="c1..c5 (default c5, the largest single-GPU configuration; the default run also "
+                         "reports c2, c3 and c4 under config.all_workloads); e1, e2: minibatch embedding epochs (secondary); "
+                         "rmat:SCALE:PAIRS: an R-MAT graph of that size for density sweeps (secondary)")
+    ap.add_argument("--all-workloads", action="store_true",
+                    help="also measure c2, c3 and c4 and report them under config.all_workloads (on when --workload is not given)")
     ap.add_argument("--d", type=int, default=None, help="override the feature dimension")
+    ap.add_argument("--natural-order", action="store_true",
+                    help="keep the vertex labels as generated (hubs at low ids) instead of the seeded random permutation "
+                         "(secondary column: the gathers are then flattered by locality)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context measurements after the timed region (HIP-graph replay, copy bandwidth, "
@@ -394,19 +458,39 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
-    if args.workload.lower() in ("e1", "e2"):
-        steps = args.steps if args.steps != 200 else 50
-        warmup = args.warmup if args.warmup != 200 else 5
-        print(json.dumps(run_epoch(args.workload.lower(), steps, warmup, not args.no_cpu_baseline)))
+    workload = (args.workload or HEADLINE).lower()
+    if workload in ("e1", "e2"):
+        steps = args.steps if args.steps != 100 else 50
+        warmup = args.warmup if args.warmup != 20 else 5
+        print(json.dumps(run_epoch(workload, steps, warmup, not args.no_cpu_baseline)))
         return
     options = None
     if args.small_row_max or args.split_row_min or args.chunk_edges or args.column_classes or args.tile_row_min:
         options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,
                    "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
                    "tile_row_min": args.tile_row_min}
-    out = run(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
-              args.copy_calibration_mib, args.autotune, "bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32"),
-              not args.no_context)
+    y_storage = "bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32")
+    out = run(workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
+              args.copy_calibration_mib, args.autotune, y_storage, not args.no_context, not args.natural_order)
+    if args.all_workloads or args.workload is None:
+        # the other large configurations, same protocol (the same K timed steps, default plan), shorter report
+        others = {}
+        for name in OTHER_WORKLOADS:
+            if name == workload:
+                continue
+            try:
+                o = run(name, args.steps, args.warmup, not args.no_cpu_baseline, None, None, 0, False, "f32", False,
+                        not args.natural_order, time_cpu=False)
+                r = o["roofline"]
+                others[name] = {"value": o["value"], "ms_per_step": o["ms_per_step"], "kernel_ms": r["kernel_ms"],
+                                "nnz": o["config"]["nnz"], "d": o["config"]["d"], "pattern": o["config"]["pattern"],
+                                "roofline_frac": r["frac"], "roofline_achieved_basis": r["achieved_basis"],
+                                "traffic": r["traffic"], "l2_hit_rate": r["l2_hit_rate"],
+                                "algorithmic_over_peak": r["algorithmic_over_peak"],
+                                "parity_of_timed_result": o.get("cpu_baseline", {}).get("parity_of_timed_result")}
+            except Exception as exc:   # secondary figures never break the headline line
+                others[name] = {"error": repr(exc)[:300]}
+        out["config"]["all_workloads"] = others
     print(json.dumps(out))
 
 

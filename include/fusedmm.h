@@ -27,7 +27,13 @@
  *     d_rowptr / d_colidx alive and unchanged for the life of the plan (the
  *     plan borrows them).  The plan owns its schedule lists and scratch.
  *   - Errors: every call returns a fusedmm_status.  No exceptions, no abort.
- *     On a non-OK status no output has been written by that call.
+ *     Arguments are validated before anything is launched: on every status except
+ *     FUSEDMM_ERR_HIP no output has been written by that call.  FUSEDMM_ERR_HIP reports a
+ *     failed launch; kernels of the same call launched before it may already have written Z.
+ *   - The execute entry points are asynchronous and neither allocate nor synchronise: the
+ *     scratch they need (partial rows of split rows) is reserved by fusedmm_plan_create for
+ *     the hinted dimension and by fusedmm_plan_reserve / fusedmm_plan_reserve_f64 beyond it;
+ *     a call that would need more returns FUSEDMM_ERR_NOT_RESERVED.
  *   - Threading: calls on one plan must not overlap in time (they share the
  *     plan's scratch).  Different plans are independent.
  *   - stream arguments are hipStream_t handles passed as void* (NULL = the
@@ -59,7 +65,8 @@ typedef enum fusedmm_status {
   FUSEDMM_ERR_UNSUPPORTED_DIM = 3, /* d < 1 or d > FUSEDMM_MAX_D */
   FUSEDMM_ERR_ALIAS = 4,           /* Z overlaps X or Y */
   FUSEDMM_ERR_ALLOC = 5,           /* host or device allocation failed */
-  FUSEDMM_ERR_HIP = 6              /* a HIP runtime call failed */
+  FUSEDMM_ERR_HIP = 6,             /* a HIP runtime call failed */
+  FUSEDMM_ERR_NOT_RESERVED = 7     /* the plan's scratch was not reserved for this dimension (fusedmm_plan_reserve) */
 } fusedmm_status;
 
 /* Step 1, VOP(x_u, y_v) -> t (Section III-A step 1; Table II binary ops). */
@@ -70,11 +77,12 @@ typedef enum {
 } fusedmm_rop;
 /* Step 3, SOP -> h (step 3).  EDGE_VALUE: h = a_uv (the GCN row of Table III).  After a reduction
  * SOP acts on the scalar s; when ROP is NOOP (and SOP is not EDGE_VALUE) it acts on every element
- * of t and the message h is a vector (Algorithm 1: "directly use z if ROP is a NOOP"). */
+ * of t and the message h is a vector (Algorithm 1, SOP step: without a reduction the VOP output is
+ * what SOP takes). */
 typedef enum {
   FUSEDMM_SOP_EDGE_VALUE = 0,
   FUSEDMM_SOP_SIGMOID = 1,           /* 1/(1+exp(-s)) */
-  FUSEDMM_SOP_ONE_MINUS_SIGMOID = 2, /* 1 - 1/(1+exp(-s)) */
+  FUSEDMM_SOP_ONE_MINUS_SIGMOID = 2, /* 1 - sigmoid(s), evaluated as sigmoid(-s) = 1/(1+exp(s)): no cancellation for large s */
   FUSEDMM_SOP_INV_1P = 3,            /* 1/(1+s) */
   FUSEDMM_SOP_SCAL = 4,              /* alpha * s */
   FUSEDMM_SOP_NOOP = 5               /* h = s (or h = t) */
@@ -124,8 +132,9 @@ typedef struct fusedmm_plan_options {
                               within the long rows, else it is skipped. */
   int32_t tile_row_min;    /* rows with >= this many entries are cut into 8 classes, with twice as many
                               into 16, and so on; 0 = 128 (16 entries per class) */
-  int32_t feature_dim_hint;/* feature dimension the plan will mostly run with, used by the automatic
-                              choice of column_classes; 0 = 128 */
+  int32_t feature_dim_hint;/* feature dimension the plan will mostly run with: used by the automatic
+                              choice of column_classes, and fusedmm_plan_create reserves the scratch
+                              for it (as fusedmm_plan_reserve does); 0 = 128 */
   int32_t reserved[2];
 } fusedmm_plan_options_t;
 
@@ -147,7 +156,8 @@ int fusedmm_ops_preset(int pattern, fusedmm_ops_t* out);
  *   d_rowptr   device, m+1 int64;  d_colidx  device, nnz int32 (may be NULL if nnz == 0)
  *   options    host, may be NULL
  * Reads rowptr back to the host and validates rowptr and colidx; synchronises
- * the stream; allocates the plan's lists.  Not part of the timed hot path. */
+ * the stream; allocates the plan's lists and the scratch for dimensions up to
+ * options->feature_dim_hint (128 without options).  Not part of the timed hot path. */
 int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
                         const int64_t* d_rowptr, const int32_t* d_colidx,
                         const fusedmm_plan_options_t* options, void* stream);
@@ -166,9 +176,13 @@ int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_
                               float* d_Z, int64_t ldz, void* stream,
                               fusedmm_plan_options_t* chosen, float* best_ms);
 
-/* Allocate the partial-sum scratch for feature dimension d up front, so that
- * later fusedmm_execute calls with dimension <= d never allocate. */
+/* Grow the plan's scratch (partial rows of split rows, for the specialised and the general kernels)
+ * so that every later fusedmm_execute / _bf16y / _f16y call with dimension <= d finds it in place;
+ * fusedmm_plan_reserve_f64 does the same for fusedmm_execute_f64.  A dimension that is already covered
+ * costs nothing.  May synchronise the device, free and allocate: call it outside the hot path (and
+ * outside stream capture).  FUSEDMM_ERR_ALLOC leaves the plan without that scratch. */
 int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d);
+int fusedmm_plan_reserve_f64(fusedmm_plan_t* plan, int32_t d);
 
 /* Device bytes the plan owns when executing with dimension d. */
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out);
@@ -185,8 +199,9 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
  *   d_values  device, nnz fp32 edge values a_uv; NULL unless SOP == EDGE_VALUE
  *   d_X       device, m x d (ldx); may be NULL when VOP == SEL2ND
  *   d_Y       device, n x d (ldy);  d_Z  device, m x d (ldz), overwritten
- * Does not synchronise.  Does not allocate, except that the first call with a
- * larger d than any before (and no fusedmm_plan_reserve) grows the scratch. */
+ * Does not synchronise and does not allocate.  FUSEDMM_ERR_NOT_RESERVED when the pattern has split
+ * rows and d exceeds what fusedmm_plan_create / fusedmm_plan_reserve reserved.  Z must not overlap
+ * X, Y or d_values (FUSEDMM_ERR_ALIAS). */
 int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                     const float* d_values, const float* d_X, int64_t ldx,
                     const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
@@ -221,7 +236,8 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
  * values are fp64 and so is every step's arithmetic.  Runs the general kernel (one wavefront per
  * row or 256-entry segment, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the
  * specialised schedule is fp32 only.  Arguments, layout, ownership and errors as for
- * fusedmm_execute; ops->alpha is widened. */
+ * fusedmm_execute; ops->alpha is widened.  Patterns with rows longer than 256 entries need
+ * fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise). */
 int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                         const double* d_values, const double* d_X, int64_t ldx,
                         const double* d_Y, int64_t ldy, double* d_Z, int64_t ldz, void* stream);
@@ -280,8 +296,9 @@ int fusedmm_plan_destroy(fusedmm_plan_t* plan);
  *          n_negative == 0.  All three are read once here (the handle keeps its own concatenated
  *          copies and does not refer to them afterwards).  Builds one plan per batch; synchronises
  *          the stream.  Samples outside [0, n) -> FUSEDMM_ERR_INVALID_ARG.
- * reserve: allocates the batch_rows x d result buffer and the plans' scratch for dimension d,
- *          so that fusedmm_minibatch_epoch allocates nothing afterwards (e.g. under stream capture).
+ * reserve: allocates the batch_rows x d result buffer and the plans' scratch for dimension d;
+ *          required before the first epoch with a dimension above any reserved so far
+ *          (fusedmm_minibatch_epoch never allocates: FUSEDMM_ERR_NOT_RESERVED otherwise).
  * epoch  : one pass over all batches, asynchronous on `stream`, in place on d_X (n rows, leading
  *          dimension ldx >= d).  Any 1 <= d <= FUSEDMM_MAX_D; d in {32,...,512} with 16-byte aligned
  *          rows runs the specialised kernels.  Overlapping epochs on one handle must be on one stream.

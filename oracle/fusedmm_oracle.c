@@ -226,8 +226,8 @@ int FN(fmm_oracle_update_u_all)(int64_t m, int64_t d, const int64_t* rowptr, con
  *   ROP  RMUL (product of the elements)                Table II "RMUL"
  *   SOP  NOOP (h = s, or h = t when there was no ROP)  Section III-A: a step may be skipped
  *   SOP  on a VECTOR: when ROP is a no-op, SOP is applied to every element of t and the edge
- *        message h is a length-d vector (Algorithm 1: "directly use z if ROP is a NOOP";
- *        Fig. 3: messages can be vectors); MOP is then element-wise h (.) operand
+ *        message h is a length-d vector (Algorithm 1, SOP step: without a reduction SOP takes the
+ *        VOP output; Fig. 3: messages can be vectors); MOP is then element-wise h (.) operand
  *   MOP  SEL2ND (w = y_v, the second operand)          Table II "SEL2ND ... VOP, MOP"
  *   AOP  AMAX / AMIN                                   Table II "AMAX" (AMIN: its mirror image)
  *   AOP  AMEAN                                         Section III-B, GCN paragraph: mean pooling

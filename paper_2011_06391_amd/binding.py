@@ -21,6 +21,7 @@ FUSEDMM_ERR_UNSUPPORTED_DIM = 3
 FUSEDMM_ERR_ALIAS = 4
 FUSEDMM_ERR_ALLOC = 5
 FUSEDMM_ERR_HIP = 6
+FUSEDMM_ERR_NOT_RESERVED = 7
 
 FUSEDMM_MAX_D = 2048
 
@@ -33,7 +34,7 @@ PATTERN = {"sigmoid": 0, "one_minus_sigmoid": 1, "gcn": 2, "tdist": 3, "fr": 4}
 
 EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
-    "fusedmm_plan_reserve", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
+    "fusedmm_plan_reserve", "fusedmm_plan_reserve_f64", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
     "fusedmm_plan_read_profile_samples",
     "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
@@ -90,6 +91,8 @@ def load():
                                               ctypes.POINTER(fusedmm_plan_options_t), ctypes.POINTER(ctypes.c_float)]
     lib.fusedmm_plan_reserve.restype = ctypes.c_int
     lib.fusedmm_plan_reserve.argtypes = [vp, i32]
+    lib.fusedmm_plan_reserve_f64.restype = ctypes.c_int
+    lib.fusedmm_plan_reserve_f64.argtypes = [vp, i32]
     lib.fusedmm_plan_workspace_bytes.restype = ctypes.c_int
     lib.fusedmm_plan_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.fusedmm_plan_stats.restype = ctypes.c_int
@@ -199,6 +202,10 @@ def fusedmm_plan_create_tuned(m: int, n: int, nnz: int, d_rowptr, d_colidx, ops:
 
 def fusedmm_plan_reserve(plan, d: int) -> None:
     _check(load().fusedmm_plan_reserve(plan, d), "fusedmm_plan_reserve")
+
+
+def fusedmm_plan_reserve_f64(plan, d: int) -> None:
+    _check(load().fusedmm_plan_reserve_f64(plan, d), "fusedmm_plan_reserve_f64")
 
 
 def fusedmm_plan_workspace_bytes(plan, d: int) -> int:
@@ -418,6 +425,9 @@ class Plan:
 
     def reserve(self, d: int) -> None:
         fusedmm_plan_reserve(self._plan, d)
+
+    def reserve_f64(self, d: int) -> None:
+        fusedmm_plan_reserve_f64(self._plan, d)
 
     def workspace_bytes(self, d: int) -> int:
         return fusedmm_plan_workspace_bytes(self._plan, d)

@@ -139,6 +139,9 @@ int upload(T** dst, const std::vector<T>& src, hipStream_t stream) {
   return FUSEDMM_OK;
 }
 
+// Reserve-time only (fusedmm_plan_create, fusedmm_plan_reserve*): may synchronise the device, free and
+// allocate.  The execute entry points never call these; they compare capacities and return
+// FUSEDMM_ERR_NOT_RESERVED.
 int ensure_partials(fusedmm_plan* p, int32_t d) {
   if (p->n_parts == 0 || d <= p->partials_d) return FUSEDMM_OK;
   if (p->d_partials) {
@@ -218,6 +221,7 @@ const char* fusedmm_status_string(int status) {
     case FUSEDMM_ERR_ALIAS: return "output overlaps an input";
     case FUSEDMM_ERR_ALLOC: return "allocation failed";
     case FUSEDMM_ERR_HIP: return "HIP runtime error";
+    case FUSEDMM_ERR_NOT_RESERVED: return "scratch not reserved for this dimension (call fusedmm_plan_reserve first)";
     default: return "unknown status";
   }
 }
@@ -551,6 +555,8 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   if (st == FUSEDMM_OK) st = upload(&p->d_items, items, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_tile_descs, tile_descs, stream);
   if (st == FUSEDMM_OK && hipStreamSynchronize(stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+  // the scratch of the hinted dimension, so that execute never has to allocate
+  if (st == FUSEDMM_OK) st = fusedmm_plan_reserve(p, std::min<int32_t>(d_hint, FUSEDMM_MAX_D));
   if (st != FUSEDMM_OK) {
     free_plan_device(p);
     delete p;
@@ -563,7 +569,17 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
 int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  return instance_dim(d) ? ensure_partials(plan, instance_dim(d)) : ensure_gen_partials(plan, d, sizeof(float));
+  // every dimension <= d: the largest instance size one of them runs on, and the general kernel's rows of d elements
+  const int32_t D = d >= 512 ? 512 : instance_dim(d / 4 * 4);
+  int st = D ? ensure_partials(plan, D) : FUSEDMM_OK;
+  if (st == FUSEDMM_OK) st = ensure_gen_partials(plan, d, sizeof(float));
+  return st;
+}
+
+int fusedmm_plan_reserve_f64(fusedmm_plan_t* plan, int32_t d) {
+  if (!plan) return FUSEDMM_ERR_INVALID_ARG;
+  if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  return ensure_gen_partials(plan, d, sizeof(double));
 }
 
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
@@ -573,8 +589,10 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
              (size_t)plan->n_merges * sizeof(MergeDesc) + (size_t)plan->n_items * sizeof(BlockItem) +
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
   b += (size_t)plan->n_gen_segs * sizeof(ChunkDesc) + (size_t)plan->n_gen_merges * sizeof(MergeDesc);
-  if (instance_dim(d)) b += (size_t)plan->n_parts * (size_t)std::max(instance_dim(d), plan->partials_d) * sizeof(float);
-  else b += std::max((size_t)plan->n_gen_segs * (size_t)d * sizeof(float), plan->gen_partials_bytes);
+  // what the plan holds once fusedmm_plan_reserve(plan, d) has run: partial rows of both kernels
+  const int32_t D = d >= 512 ? 512 : instance_dim(d / 4 * 4);
+  b += (size_t)plan->n_parts * (size_t)std::max(D, plan->partials_d) * sizeof(float);
+  b += std::max((size_t)plan->n_gen_segs * (size_t)d * sizeof(float), plan->gen_partials_bytes);
   *out = b;
   return FUSEDMM_OK;
 }
@@ -623,6 +641,12 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     if (d_Y && plan->n > 0 && z0 < y1 && y0 < z1) return FUSEDMM_ERR_ALIAS;
   }
   if (uses_x && overlaps(d_Z, plan->m, ldz, d_X, plan->m, ldx, d)) return FUSEDMM_ERR_ALIAS;
+  if (uses_val && plan->nnz > 0) {  // the edge values are read while Z is written
+    const uintptr_t z0 = reinterpret_cast<uintptr_t>(d_Z);
+    const uintptr_t z1 = z0 + (uintptr_t)((plan->m - 1) * ldz + d) * sizeof(float);
+    const uintptr_t v0 = reinterpret_cast<uintptr_t>(d_values), v1 = v0 + (uintptr_t)plan->nnz * sizeof(float);
+    if (z0 < v1 && v0 < z1) return FUSEDMM_ERR_ALIAS;
+  }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
   // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
@@ -647,8 +671,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
   hipError_t e = hipSuccess;
   if (fast) {
-    const int st = ensure_partials(plan, D);
-    if (st != FUSEDMM_OK) return st;
+    if (plan->n_parts > 0 && D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
     KernelArgs a;
     fill_schedule_args(plan, D, y_format, &a);
     a.d_pieces = d / 4;
@@ -673,8 +696,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
     g.alpha = ops->alpha;
     g.visit_counts = nullptr;
-    const int gst = ensure_gen_partials(plan, d, sizeof(float));
-    if (gst != FUSEDMM_OK) return gst;
+    if ((size_t)plan->n_gen_segs * (size_t)d * sizeof(float) > plan->gen_partials_bytes) return FUSEDMM_ERR_NOT_RESERVED;
     fill_generic_segments(plan, &g);
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_generic(g, stream);
@@ -740,6 +762,11 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     range(d_X, plan->m, ldx, &o0, &o1);
     if (z0 < o1 && o0 < z1) return FUSEDMM_ERR_ALIAS;
   }
+  if (ops->sop == FUSEDMM_SOP_EDGE_VALUE && plan->nnz > 0) {
+    o0 = reinterpret_cast<uintptr_t>(d_values);
+    o1 = o0 + (uintptr_t)plan->nnz * sizeof(double);
+    if (z0 < o1 && o0 < z1) return FUSEDMM_ERR_ALIAS;
+  }
   GenericArgsT<double> g;
   g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
   g.X = d_X; g.Y = d_Y; g.Z = d_Z;
@@ -748,8 +775,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
   g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
   g.alpha = (double)ops->alpha;
   g.visit_counts = nullptr;
-  const int gst = ensure_gen_partials(plan, d, sizeof(double));
-  if (gst != FUSEDMM_OK) return gst;
+  if ((size_t)plan->n_gen_segs * (size_t)d * sizeof(double) > plan->gen_partials_bytes) return FUSEDMM_ERR_NOT_RESERVED;
   fill_generic_segments(plan, &g);
   return launch_generic(g, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }

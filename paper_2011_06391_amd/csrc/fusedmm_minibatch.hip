@@ -180,8 +180,7 @@ int fusedmm_minibatch_reserve(fusedmm_minibatch_t* h, int32_t d) {
 int fusedmm_minibatch_epoch(fusedmm_minibatch_t* h, int32_t d, float lr, float* d_X, int64_t ldx, void* stream_) {
   if (!h || !d_X || ldx < d) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  const int st = fusedmm_minibatch_reserve(h, d);  // allocates on the first call for a larger d only
-  if (st != FUSEDMM_OK) return st;
+  if (h->z_d < d) return FUSEDMM_ERR_NOT_RESERVED;  // fusedmm_minibatch_reserve(h, d) allocates; an epoch never does
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   // attraction and repulsion in one call: h = a_uv - sigmoid(x_u . x_v), a_uv = 1 on stored entries
   // (1 - sigmoid) and 0 on negative samples (-sigmoid)

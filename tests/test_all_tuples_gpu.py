@@ -66,30 +66,42 @@ def test_every_valid_tuple(B, d, fmt):
     # x - y >= 0 and everything positive: no scaling step comes near the pole of 1/(1+s)
     Xs = rng.uniform(0.30, 0.50, (m, d)).astype(np.float32)
     Ys = rng.uniform(0.05, 0.25, (n, d)).astype(np.float32)
-    # products of d factors must not overflow fp32: factors near 1 (SEL2ND, SUB), 2 (MUL) and 3 (ADD) up to
-    # d = 32; for longer rows x + y near 1 (the other products then run below the fp32 range: see `tiny`)
+    # ROP = RMUL: the product of d factors must stay inside fp32's normal range for every VOP, so that it is
+    # compared as a number.  Up to d = 32 one pair of matrices does (factors near 1 for SEL2ND and SUB, 2 for
+    # MUL, 3 for ADD); for longer rows every VOP gets operands that put its own factors near 1.
     if d <= 32:
         Xp = rng.uniform(1.9, 2.1, (m, d)).astype(np.float32)
         Yp = rng.uniform(0.9, 1.1, (n, d)).astype(np.float32)
+        rmul_sets = {v: ("Xp", "Yp") for v in B.VOP}
+        mats = {"Xp": Xp, "Yp": Yp}
     else:
-        Xp = rng.uniform(0.50, 0.52, (m, d)).astype(np.float32)
-        Yp = rng.uniform(0.49, 0.51, (n, d)).astype(np.float32)
-    Ys, Yp = rounded(Ys, fmt), rounded(Yp, fmt)      # what the kernels see when Y is stored in 2 bytes
+        mats = {"Xone": rng.uniform(0.98, 1.02, (m, d)).astype(np.float32),     # MUL: x * y near 1 (SEL2ND: y)
+                "Xtwo": rng.uniform(1.98, 2.02, (m, d)).astype(np.float32),     # SUB: x - y near 1
+                "Xhalf": rng.uniform(0.49, 0.51, (m, d)).astype(np.float32),    # ADD: x + y near 1
+                "Yone": rng.uniform(0.98, 1.02, (n, d)).astype(np.float32),
+                "Yhalf": rng.uniform(0.49, 0.51, (n, d)).astype(np.float32)}
+        rmul_sets = {"MUL": ("Xone", "Yone"), "SEL2ND": ("Xone", "Yone"), "SUB": ("Xtwo", "Yone"), "ADD": ("Xhalf", "Yhalf")}
+    mats["Xs"] = Xs
+    mats["Ys"] = Ys
+    for k in [k for k in mats if k.startswith("Y")]:
+        mats[k] = rounded(mats[k], fmt)      # what the kernels see when Y is stored in 2 bytes
     rp, ci, vd = (torch.from_numpy(a).cuda() for a in (rowptr, colidx, vals))
-    dev = {k: torch.from_numpy(v).cuda() for k, v in (("Xs", Xs), ("Ys", Ys), ("Xp", Xp), ("Yp", Yp))}
+    dev = {k: torch.from_numpy(v).cuda() for k, v in mats.items()}
     plan = B.Plan(m, n, rp, ci, {"small_row_max": 4, "split_row_min": 32, "chunk_edges": 256, "column_classes": 8,
-                                 "tile_row_min": 64})
+                                 "tile_row_min": 64, "feature_dim_hint": d})
+    plan.reserve(d)
     st = plan.stats()
     assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0
     Z = torch.empty((m, d), dtype=torch.float32, device="cuda")
     if fmt != "f32":
-        for k in ("Ys", "Yp"):
+        for k in [k for k in mats if k.startswith("Y")]:
             h = torch.zeros((n, d), dtype=torch.int16, device="cuda")
             (B.fusedmm_to_bf16 if fmt == "bf16" else B.fusedmm_to_f16)(h, dev[k], n * d)
             dev[k + "h"] = h
     failures, count = [], 0
     for vop, rop, sop, mop, aop in all_valid_tuples(B):
-        X, Y, Xd, Yd = (Xp, Yp, dev["Xp"], dev["Yp"]) if rop == "RMUL" else (Xs, Ys, dev["Xs"], dev["Ys"])
+        xk, yk = rmul_sets[vop] if rop == "RMUL" else ("Xs", "Ys")
+        X, Y, Xd, Yd = mats[xk], mats[yk], dev[xk], dev[yk]
         names = (vop, ONAME.get(rop, rop), ONAME.get(sop, sop), mop)
         Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, OAOP[aop], alpha=0.37)
         ops = B.make_ops(vop, rop, sop, mop, aop=aop, alpha=0.37)
@@ -98,7 +110,7 @@ def test_every_valid_tuple(B, d, fmt):
         if fmt == "f32":
             plan.execute(ops, Xarg, Yd, Z, vd)
         else:
-            Yh = dev["Yph" if rop == "RMUL" else "Ysh"]
+            Yh = dev[yk + "h"]
             (plan.execute_bf16y if fmt == "bf16" else plan.execute_f16y)(ops, Xarg, Yh, Z, vd)
         torch.cuda.synchronize()
         Zg = Z.cpu().numpy()
@@ -106,6 +118,10 @@ def test_every_valid_tuple(B, d, fmt):
         # fp32 holds 0; there the rule is "nothing but such a tiny number", not a relative error
         tiny = S < 1e-30
         assert (np.abs(Zg[tiny]) <= 1e-30).all()
+        # the product itself is always a normal number here: compared as such, never as 0 = 0 (short rows with
+        # factors 2 and 3 reach products of hundreds, whose 1 - sigmoid is legitimately below fp32's range)
+        if rop == "RMUL" and (d > 32 or sop != "ONE_MINUS_SIGMOID"):
+            assert not (tiny & (S > 0)).any(), (vop, rop, sop, mop, aop)
         S = np.where(tiny, 0.0, S)
         Zg = np.where(tiny, 0.0, Zg)
         Zr = np.where(tiny, 0.0, Zr)

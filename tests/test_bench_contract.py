@@ -26,4 +26,22 @@ def test_defaults_name_the_headline_workload():
     text = r.stdout
     for flag in ("--gpus", "--steps", "--warmup", "--workload", "--no-cpu-baseline"):
         assert flag in text
-    assert "default c2" in text
+    assert "default c5" in text and "--natural-order" in text and "--all-workloads" in text
+
+
+def test_traffic_table_rows_are_well_formed():
+    """profiles/hbm_traffic_per_launch.txt is read by bench.py: every data row has the nine fields it parses,
+    and a row only counts for the build whose kernel sources it names."""
+    sys.path.insert(0, ROOT)
+    import bench
+    sha = bench.kernel_sources_sha16()
+    assert len(sha) == 16 and int(sha, 16) >= 0
+    if os.path.exists(bench.TRAFFIC_TABLE):
+        for line in open(bench.TRAFFIC_TABLE):
+            f = line.split("#")[0].split()
+            if not f:
+                continue
+            assert len(f) == 9, line
+            assert len(f[1]) == 16 and all(int(x) >= 0 for x in f[2:7]) and 0.0 <= float(f[7]) <= 1.0
+    t, hit, why = bench.measured_traffic("no-such-workload", {"partials": 0, "tile_segments": 0, "column_classes": 1})
+    assert t is None and hit is None and why

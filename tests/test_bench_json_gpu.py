@@ -35,7 +35,12 @@ def test_bench_line_small_workload():
     r = o["roofline"]
     assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and r["kernel_ms"] > 0 and "traffic" in r
-    assert abs(r["achieved"] - r["algorithmic_bytes"] / (r["kernel_ms"] * 1e-3) / 1e9) < 1e-6 * r["achieved"]
+    assert 0.0 < r["frac"] <= 1.0 and r["traffic_source"] and r["achieved_basis"]
+    priced = r["traffic"] if r["traffic"] is not None else r["compulsory_bytes"]
+    assert abs(r["achieved"] - priced / (r["kernel_ms"] * 1e-3) / 1e9) < 1e-6 * r["achieved"]
+    assert abs(r["algorithmic_GBs"] - r["algorithmic_bytes"] / (r["kernel_ms"] * 1e-3) / 1e9) < 1e-6 * r["algorithmic_GBs"]
+    assert abs(r["algorithmic_over_peak"] - r["algorithmic_GBs"] / r["peak"]) < 1e-12
+    assert "all_workloads" not in o["config"]      # only the default line carries the other workloads
     c = o["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == o["unit"] and c["value"] > 0 and c["cores"] >= 1 and c["sample"]
     p = c["parity_of_timed_result"]

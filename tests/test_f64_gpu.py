@@ -62,6 +62,7 @@ def test_f64_matches_oracle(B, case, d):
         ops = B.make_ops(*gpu_ops, aop=gpu_aop)
     ops.alpha = alpha
     plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx))
+    plan.reserve_f64(d)
     uses_x = ops.vop != B.VOP["SEL2ND"]
     Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
     plan.execute_f64(ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z,

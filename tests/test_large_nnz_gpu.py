@@ -117,7 +117,7 @@ def test_operand_offsets_beyond_4_gib(B):
     X[:, 0] = (torch.arange(m, device="cuda") % 3).float()          # sum_j x_uj = u mod 3
     vals = torch.ones(nnz, dtype=torch.float32, device="cuda")
     Z = torch.empty((m, d), dtype=torch.float32, device="cuda")
-    plan = B.Plan(m, n, rp, ci)
+    plan = B.Plan(m, n, rp, ci, {"feature_dim_hint": d})
 
     def gcn_block(lo, hi):      # sum_k ((first + k*step + j) mod 4), rows lo .. hi-1
         out = torch.zeros((hi - lo, d), dtype=torch.int64, device="cuda")

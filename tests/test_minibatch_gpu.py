@@ -64,6 +64,10 @@ def test_epoch_matches_oracle(B, n, d, batch_rows, s):
     info = mb.info()
     assert info["n_batches"] == (n + batch_rows - 1) // batch_rows
     X = dev(X0)
+    with pytest.raises(B.FusedMMError) as ei:   # an epoch never allocates: the result buffer must be reserved first
+        mb.epoch(X, lr)
+    assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED
+    mb.reserve(d)
     mb.epoch(X, lr)
     torch.cuda.synchronize()
     X1 = X.cpu().numpy()
@@ -86,6 +90,7 @@ def test_epoch_leading_dimension_and_isolated_vertices(B):
     neg = negatives_for(n, batch_rows, s, 5)
     mb = B.Minibatch(n, dev(g.rowptr), dev(g.colidx), batch_rows, dev(neg))
     Xw = dev(wide)
+    mb.reserve(d)
     mb.epoch(Xw[:, :d], 0.05)
     torch.cuda.synchronize()
     out = Xw.cpu().numpy()

@@ -167,6 +167,35 @@ def test_sigmoid_extreme_arguments_stay_finite():
     assert np.isfinite(Z).all() and H[0] == 1.0 and H[1] == 0.0
 
 
+@pytest.mark.parametrize("s", [37.0, 40.0, 100.0, 700.0])
+def test_one_minus_sigmoid_tail_is_not_cancelled(s):
+    """Large positive s: 1 - sigmoid(s) = e^-s / (1 + e^-s), still a positive number (2e-304 at s = 700)
+    although the literal difference 1 - 1/(1 + e^-s) is exactly 0 in double from s = 37 on.  One edge,
+    x = (s, 0), y = (1, 1): the scalar pattern, the general path with a reduction, and the vector message
+    (no reduction: SOP on each element of t = x * y = (s, 0), whose second element pins the value 1/2)."""
+    expected = math.exp(-s) / (1.0 + math.exp(-s))           # no subtraction from 1 anywhere
+    alt = math.exp(-s - math.log1p(math.exp(-s)))            # the same number through its logarithm
+    assert expected > 0.0 and abs(alt - expected) <= 4e-14 * expected   # exp of an argument near 700 loses ~|arg| ulps
+    assert 1.0 - 1.0 / (1.0 + math.exp(-s)) == 0.0            # the cancellation this pin is about
+    rowptr = np.array([0, 1], dtype=np.int64)
+    colidx = np.array([0], dtype=np.int32)
+    X = np.array([[s, 0.0]], dtype=np.float32)
+    Y = np.array([[1.0, 1.0]], dtype=np.float32)
+    Z, S, H = oracle.unfused(rowptr, colidx, None, X, Y, "one_minus_sigmoid")
+    assert H[0] > 0.0 and abs(H[0] - expected) <= 1e-15 * expected
+    np.testing.assert_allclose(Z[0], [expected, expected], rtol=1e-15, atol=0.0)
+    np.testing.assert_allclose(S[0], [expected, expected], rtol=1e-15, atol=0.0)
+    Zg, _, Hg = oracle.unfused_general(rowptr, colidx, None, X, Y, ("MUL", "RSUM", "ONE_MINUS_SIGMOID", "MUL_Y"))
+    assert Hg[0] > 0.0 and abs(Hg[0] - expected) <= 1e-15 * expected and np.array_equal(Zg, Z)
+    Zv, _, Hv = oracle.unfused_general(rowptr, colidx, None, X, Y, ("MUL", "NOOP", "ONE_MINUS_SIGMOID", "MUL_Y"))
+    assert Hv.shape == (1, 2) and Hv[0, 1] == 0.5
+    assert Hv[0, 0] > 0.0 and abs(Hv[0, 0] - expected) <= 1e-15 * expected
+    np.testing.assert_allclose(Zv[0], [expected, 0.5], rtol=1e-15, atol=0.0)
+    # and the two halves still add up to one where both are representable
+    _, _, Hs = oracle.unfused(rowptr, colidx, None, X, Y, "sigmoid")
+    assert Hs[0] + H[0] == 1.0
+
+
 @pytest.mark.parametrize("pattern", ["tdist", "fr"])
 def test_difference_patterns_vanish_on_equal_rows(pattern, rng):
     n, d = 40, 6

@@ -38,6 +38,7 @@ def run_gpu(B, rowptr, colidx, vals, X, Y, pattern_or_ops, m, n, alpha=1.0, opti
     d = Y.shape[1]
     rp, ci = dev(rowptr), dev(colidx)
     plan = B.Plan(m, n, rp, ci, options)
+    plan.reserve(d)  # scratch beyond the plan's hinted dimension (128) is reserved outside execute
     Xd, Yd, vd = dev(X), (dev(Y) if Y is not X else None), dev(vals)
     if Yd is None:
         Yd = Xd
@@ -260,6 +261,7 @@ def test_dimensions_between_instance_sizes(B, case, d):
     Xd, Yd, vd = dev(Xw), dev(Yw), dev(vals)
     for options in ({"column_classes": 1}, TILED):
         plan = B.Plan(m, n, rp, ci, options)
+        plan.reserve(d)
         assert (plan.stats()["tiled_rows"] > 0) == (options is TILED)
         Zb = torch.full((m, d + pad), 7.0, dtype=torch.float32, device="cuda")
         uses_x = ops.vop != B.VOP["SEL2ND"]
@@ -298,6 +300,7 @@ def test_general_kernel_long_rows(B, case, d):
     ops.alpha = ALPHA
     rp, ci = dev(rowptr), dev(colidx)
     plan = B.Plan(m, n, rp, ci)
+    plan.reserve(d)
     uses_x = ops.vop != B.VOP["SEL2ND"]
     Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
     plan.execute(ops, dev(X) if uses_x else None, dev(Y), Z, dev(vals))
@@ -310,6 +313,7 @@ def test_general_kernel_long_rows(B, case, d):
     assert c.min() == 1 and c.max() == 1
     if d in (5, 130):   # the double-precision entry point shares the segments
         Z64 = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+        plan.reserve_f64(d)
         plan.execute_f64(ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z64,
                          dev(vals.astype(np.float64)))
         torch.cuda.synchronize()
@@ -437,33 +441,43 @@ def test_run_to_run_determinism(B):
 
 
 def test_execute_can_be_captured_in_a_hip_graph(B):
-    """fusedmm_execute neither allocates nor synchronises once the scratch is reserved, so a
-    caller can record it into a HIP graph.  Each replay (with eager work in between) must
-    reproduce the eager result bit for bit."""
+    """fusedmm_execute neither allocates nor synchronises, so a caller can record it into a HIP graph:
+    one plan, reserved once for the largest dimension, captured at two different dimensions.  Each
+    replay (with eager work in between) must reproduce the eager result bit for bit.  Without the
+    reservation the call is refused with a status instead of allocating."""
     g = synth.rmat(12, (1 << 11) * 16, seed=55)
-    d = 64
-    X = synth.fill_uniform((g.m, d), 56, -0.5, 0.5)
-    rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(X)
+    rp, ci = dev(g.rowptr), dev(g.colidx)
     plan = B.Plan(g.m, g.n, rp, ci, {"small_row_max": 8, "split_row_min": 64, "chunk_edges": 256,
-                                     "column_classes": 8, "tile_row_min": 48})
+                                     "column_classes": 8, "tile_row_min": 48, "feature_dim_hint": 64})
     s = plan.stats()
     assert s["tiled_rows"] > 0 and s["split_rows"] > 0
-    plan.reserve(d)
     ops = B.fusedmm_ops_preset("tdist")
-    Z_eager = torch.empty((g.m, d), dtype=torch.float32, device="cuda")
-    plan.execute(ops, Xd, Xd, Z_eager)
+    X256 = dev(synth.fill_uniform((g.m, 256), 57, -0.5, 0.5))
+    Zn = torch.full((g.m, 256), float("nan"), dtype=torch.float32, device="cuda")
+    with pytest.raises(B.FusedMMError) as ei:
+        plan.execute(ops, X256, X256, Zn)
     torch.cuda.synchronize()
-    Z = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        plan.execute(ops, Xd, Xd, Z)
+    assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED and torch.isnan(Zn).all().item()
+    plan.reserve(256)
+    graphs = []
+    for d in (64, 256):
+        Xd = X256 if d == 256 else dev(synth.fill_uniform((g.m, d), 56, -0.5, 0.5))
+        Z_eager = torch.empty((g.m, d), dtype=torch.float32, device="cuda")
+        plan.execute(ops, Xd, Xd, Z_eager)
+        torch.cuda.synchronize()
+        Z = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            plan.execute(ops, Xd, Xd, Z)
+        graphs.append((graph, Z, Z_eager, Xd))
     for _ in range(3):
-        Z.fill_(7.0)               # eager work between replays
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(Z, Z_eager)
-    del graph
+        for graph, Z, Z_eager, _ in graphs:   # the two graphs share the plan's scratch: replayed one after the other
+            Z.fill_(7.0)               # eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Z, Z_eager)
+    del graphs
     plan.close()
 
 
@@ -509,6 +523,9 @@ def test_status_codes(B):
     assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, None, d, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
     assert status(lambda: B.fusedmm_execute(plan._plan, ops, d, None, X, d, X, d, X, d)) == B.FUSEDMM_ERR_ALIAS
     gcn = B.fusedmm_ops_preset("gcn")
+    # the edge values are read while Z is written: Z laid over them is refused (here: values inside Z's buffer)
+    Zbig = torch.zeros((max(g.m, (g.nnz + d - 1) // d), d), dtype=torch.float32, device="cuda")
+    assert status(lambda: B.fusedmm_execute(plan._plan, gcn, d, Zbig, None, 0, X, d, Zbig, d)) == B.FUSEDMM_ERR_ALIAS
     assert status(lambda: B.fusedmm_execute(plan._plan, gcn, d, None, None, 0, X, d, Z, d)) == B.FUSEDMM_ERR_INVALID_ARG
     bad = B.make_ops("MUL", "RSUM", "EDGE_VALUE", "MUL_Y")  # the edge value is not the result of a reduction
     assert status(lambda: B.fusedmm_execute(plan._plan, bad, d, None, X, d, X, d, Z, d)) == B.FUSEDMM_ERR_UNSUPPORTED_OPS
@@ -535,8 +552,10 @@ def test_workspace_is_not_per_edge_message(B):
     plan = B.Plan(g.m, g.n, rp, ci)
     s = plan.stats()
     ws = plan.workspace_bytes(w.d)
+    deg = g.degrees()
+    gen_segs = int(((deg[deg > 256] + 255) // 256).sum())   # the general kernel's cut of the long rows and its partial rows
     assert ws <= 4 * g.m + 24 * (s["chunks"] + s["tile_segments"]) + 16 * s["split_rows"] + 4 * w.d * s["partials"] \
-        + 16 * (s["tile_segments"] + 8)
+        + 16 * (s["tile_segments"] + 8) + (24 + 16 + 4 * w.d) * gen_segs
     assert ws < 0.02 * 4 * g.nnz * w.d  # far below the nnz x d message tensor
     if s["tiled_rows"] == 0:
         assert s["packed_rows"] + s["wave_rows"] + s["chunks"] - s["partials"] + s["split_rows"] == g.m
@@ -595,18 +614,57 @@ def test_workload_full_size_sampled_rows(B, name):
     plan.close()
 
 
+@pytest.mark.parametrize("name", ("c3", "c4", "c5"))
+def test_workload_full_size_whole_output(B, name):
+    """The whole output of the three large workloads, in the launch configuration bench.py times, against
+    the fp64 oracle: every row of Z, element by element (Eq. 1 / Algorithm 1 over all of A).  The oracle
+    runs on blocks of 262 144 consecutive rows (a rectangular slice of A against all of Y) and the matching
+    block of Z is copied back, so host memory stays bounded at c5's 4 GiB matrices."""
+    w = synth.make_workload(name)
+    g = w.csr
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    plan = B.Plan(g.m, g.n, rp, ci, {"feature_dim_hint": w.d})  # as bench.py creates it
+    stats = plan.stats()
+    assert stats["tiled_rows"] > 0 and stats["split_rows"] > 0
+    Xd = dev(w.X)
+    Yd = Xd if w.Y is w.X else dev(w.Y)
+    vd = dev(g.values)
+    Z = torch.full((g.m, w.d), np.nan, dtype=torch.float32, device="cuda")
+    plan.execute(w.pattern, None if w.pattern == "gcn" else Xd, Yd, Z, vd)
+    torch.cuda.synchronize()
+    block, worst, worst_row, checked = 262144, 0.0, -1, 0
+    for b0 in range(0, g.m, block):
+        b1 = min(g.m, b0 + block)
+        sub = g.take_rows(np.arange(b0, b1, dtype=np.int64))
+        Zr, S, _ = oracle.unfused(sub.rowptr, sub.colidx, sub.values, w.X[b0:b1], w.Y, w.pattern)
+        Zg = Z[b0:b1].cpu().numpy()
+        err, am, viol = oracle.compare(Zg, Zr, S)
+        assert viol == 0, f"{name} rows {b0}..{b1}: {viol} entries with no terms are not exactly zero"
+        assert err <= TOL, f"{name}: max rel err {err:.3e} in row {b0 + am // w.d}, column {am % w.d}"
+        if err > worst:
+            worst, worst_row = err, b0 + am // w.d
+        checked += sub.nnz
+        print(f"{name}: rows {b0}..{b1} ({sub.nnz} stored entries) max rel err {err:.2e}", flush=True)
+    assert checked == g.nnz
+    print(f"{name}: all {g.m} rows x {w.d} columns compared, max rel err {worst:.2e} (row {worst_row}, "
+          f"{int(g.degrees()[worst_row])} entries), plan {stats}")
+    plan.close()
+
+
 def test_one_plan_many_dimensions_and_entry_points(B):
     """One plan serves calls of different feature dimensions and entry points in turn: the partial-row scratch
-    grows (512 after 32), is reused with a wider stride than the call needs (64 after 512), and the general
-    kernel, the 2-byte storage modes and fp64 keep scratch of their own.  Every call against the oracle."""
+    grows when reserved for more (512 after 32), is reused with a wider stride than the call needs (64 after
+    512), and the general kernel, the 2-byte storage modes and fp64 keep scratch of their own.  A call beyond
+    what was reserved is refused and writes nothing.  Every accepted call against the oracle."""
     rng = np.random.default_rng(77)
     m, n = 257, 400
     long_rows = {5: 130, 9: 700, 100: 2500, 256: 97}
     rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
     vals = rng.uniform(-1, 1, len(colidx)).astype(np.float32)
     rp, ci, vd = dev(rowptr), dev(colidx), dev(vals)
-    plan = B.Plan(m, n, rp, ci, TILED)
+    plan = B.Plan(m, n, rp, ci, dict(TILED, feature_dim_hint=32))
     assert plan.stats()["tiled_rows"] > 0 and plan.stats()["split_rows"] > 0
+    reserved, reserved64 = 32, 0
     f16 = lambda a: a.astype(np.float16).astype(np.float32)
     sequence = [(32, "f32", "sigmoid"), (512, "f32", "tdist"), (64, "f32", "gcn"), (6, "f32", "fr"), (128, "f16", "sigmoid"),
                 (100, "f32", "one_minus_sigmoid"), (200, "f64", "tdist"), (512, "f32", "fr"), (32, "f32", "gcn"),
@@ -622,10 +680,23 @@ def test_one_plan_many_dimensions_and_entry_points(B):
         if kind == "f64":
             Xd, Yd, v64 = dev(X.astype(np.float64)), dev(Y.astype(np.float64)), dev(vals.astype(np.float64))
             Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+            if d > reserved64:   # refused, nothing written, until the scratch has been reserved
+                with pytest.raises(B.FusedMMError) as ei:
+                    plan.execute_f64(ops, Xd, Yd, Z, v64)
+                assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED and torch.isnan(Z).all().item()
+                plan.reserve_f64(d)
+                reserved64 = d
             plan.execute_f64(ops, Xd, Yd, Z, v64)
         else:
             Xd, Yd = dev(X), dev(Y)
             Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+            if d > reserved:
+                with pytest.raises(B.FusedMMError) as ei:
+                    plan.execute(ops, Xd, Yd, Z, vd)
+                torch.cuda.synchronize()
+                assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED and torch.isnan(Z).all().item()
+                plan.reserve(d)
+                reserved = d
             if kind == "f16":
                 Yh = torch.zeros((n, d), dtype=torch.int16, device="cuda")
                 B.fusedmm_to_f16(Yh, Yd, n * d)

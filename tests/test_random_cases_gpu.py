@@ -109,6 +109,7 @@ def test_random_case(B, seed):
     vd = torch.from_numpy(vals).cuda()
     Zb = torch.full((m, Yb.shape[1]), np.nan, dtype=torch.float32, device="cuda")
     plan = B.Plan(m, n, rp, ci, opts)
+    plan.reserve(d)
     if fmt == "f32":
         plan.execute(ops, Xd[:, :d], Yd[:, :d], Zb[:, :d], vd)
     else:

@@ -112,6 +112,7 @@ def test_half_storage_parity(B, pattern, d):
     np.testing.assert_array_equal(Yh.cpu().numpy().view(np.uint16), bits)
     for options in ({"column_classes": 1}, {"column_classes": 16, "tile_row_min": 64, "split_row_min": 128}):
         plan = B.Plan(m, n, rp, ci, options)
+        plan.reserve(d)
         Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
         plan.execute_f16y(ops, None if pattern == "gcn" else Xd, Yh, Z, vd)
         torch.cuda.synchronize()
@@ -154,6 +155,7 @@ def test_bf16_storage_parity(B, pattern, d):
     np.testing.assert_array_equal(Yb.cpu().numpy().view(np.uint16), bits)
     for options in ({"column_classes": 1}, {"column_classes": 16, "tile_row_min": 64, "split_row_min": 128}):
         plan = B.Plan(m, n, rp, ci, options)
+        plan.reserve(d)
         Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
         plan.execute_bf16y(ops, None if pattern == "gcn" else Xd, Yb, Z, vd)
         torch.cuda.synchronize()
