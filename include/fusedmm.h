@@ -66,7 +66,8 @@ typedef enum fusedmm_status {
   FUSEDMM_ERR_ALIAS = 4,           /* Z overlaps X or Y */
   FUSEDMM_ERR_ALLOC = 5,           /* host or device allocation failed */
   FUSEDMM_ERR_HIP = 6,             /* a HIP runtime call failed */
-  FUSEDMM_ERR_NOT_RESERVED = 7     /* the plan's scratch was not reserved for this dimension (fusedmm_plan_reserve) */
+  FUSEDMM_ERR_NOT_RESERVED = 7,    /* the plan's scratch was not reserved for this dimension (fusedmm_plan_reserve) */
+  FUSEDMM_ERR_SCRATCH_LIMIT = 8    /* fusedmm_execute_static_scratch: the call needs more than FUSEDMM_STATIC_SCRATCH_BYTES */
 } fusedmm_status;
 
 /* Step 1, VOP(x_u, y_v) -> t (Section III-A step 1; Table II binary ops). */
@@ -205,6 +206,24 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
 int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                     const float* d_values, const float* d_X, int64_t ldx,
                     const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
+
+/* fusedmm_execute for callers that cannot allocate and cannot have the plan reserve for them either:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * layout, ownership, errors and result (bit for bit) as fusedmm_execute, same kernels; the only difference
+ * is where the partial rows of split rows go: into a fixed array in the library's device image
+ * (FUSEDMM_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of the plan's scratch, so the
+ * call works at any dimension whatever was reserved.  It calls no allocation routine of any kind.
+ *   - Limit: partial rows x kernel size x 4 bytes (fusedmm_plan_stats gives the partial rows; the kernel size
+ *     is d rounded up to 32/64/128/256/512; for the general kernel: 256-entry segments of long rows x d x 4)
+ *     must fit, else FUSEDMM_ERR_SCRATCH_LIMIT and nothing is launched.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, or
+ *     two plans) race on it.  Calls on one stream are ordered and safe.  Nothing in it has to start at
+ *     zero (every partial row read was written by the same call), so nothing is cleared.
+ *   - The plan must have been created on the device that is current at the call. */
+#define FUSEDMM_STATIC_SCRATCH_BYTES (64u << 20)
+int fusedmm_execute_static_scratch(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
+                                   const float* d_values, const float* d_X, int64_t ldx,
+                                   const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream);
 
 /* The same operation with Y stored as bfloat16 (the upper 16 bits of each fp32 value): the
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,

@@ -22,6 +22,8 @@ FUSEDMM_ERR_ALIAS = 4
 FUSEDMM_ERR_ALLOC = 5
 FUSEDMM_ERR_HIP = 6
 FUSEDMM_ERR_NOT_RESERVED = 7
+FUSEDMM_ERR_SCRATCH_LIMIT = 8
+FUSEDMM_STATIC_SCRATCH_BYTES = 64 << 20
 
 FUSEDMM_MAX_D = 2048
 
@@ -35,7 +37,7 @@ PATTERN = {"sigmoid": 0, "one_minus_sigmoid": 1, "gcn": 2, "tdist": 3, "fr": 4}
 EXPORTS = (
     "fusedmm_version", "fusedmm_status_string", "fusedmm_ops_preset", "fusedmm_plan_create",
     "fusedmm_plan_reserve", "fusedmm_plan_reserve_f64", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
-    "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
+    "fusedmm_execute_static_scratch", "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
     "fusedmm_plan_read_profile_samples",
     "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
     "fusedmm_to_bf16", "fusedmm_execute_f16y", "fusedmm_to_f16", "fusedmm_execute_f64",
@@ -99,6 +101,8 @@ def load():
     lib.fusedmm_plan_stats.argtypes = [vp] + [ctypes.POINTER(i64)] * 8
     lib.fusedmm_execute.restype = ctypes.c_int
     lib.fusedmm_execute.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.fusedmm_execute_static_scratch.restype = ctypes.c_int
+    lib.fusedmm_execute_static_scratch.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.fusedmm_execute_bf16y.restype = ctypes.c_int
     lib.fusedmm_execute_bf16y.argtypes = [vp, ctypes.POINTER(fusedmm_ops_t), i32, vp, vp, i64, vp, i64, vp, i64, vp]
     lib.fusedmm_to_bf16.restype = ctypes.c_int
@@ -227,6 +231,13 @@ def fusedmm_execute(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d
     st = load().fusedmm_execute(plan, ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
                                 _dptr(d_Z), ldz, _stream(stream))
     _check(st, "fusedmm_execute")
+
+
+def fusedmm_execute_static_scratch(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d_Y, ldy: int, d_Z, ldz: int,
+                                   stream=None) -> None:
+    st = load().fusedmm_execute_static_scratch(plan, ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
+                                               _dptr(d_Z), ldz, _stream(stream))
+    _check(st, "fusedmm_execute_static_scratch")
 
 
 def fusedmm_execute_bf16y(plan, ops: fusedmm_ops_t, d: int, d_values, d_X, ldx: int, d_Y_bf16, ldy: int, d_Z, ldz: int,

@@ -4,6 +4,7 @@
 #include "fusedmm_internal.h"
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -36,7 +37,35 @@ struct fusedmm_plan {
   size_t events_used = 0;
 };
 
+// Fixed scratch of fusedmm_execute_static_scratch: partial rows of split rows, for callers that cannot
+// allocate.  One copy per GPU the library runs on, held until the process ends.  In host code the array's
+// name only stands for the symbol: its device address is looked up once per device
+// (static_scratch_for_current_device) and that pointer is what kernels, copies and fills are given.
+static __device__ __align__(256) unsigned char scratch[FUSEDMM_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxScratchDevices = 64;
+void* g_scratch_ptr[kMaxScratchDevices] = {};
+std::mutex g_scratch_mutex;
+
+// The address of `scratch` on the current device (every GPU holds its own copy at its own address).
+int static_scratch_for_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FUSEDMM_ERR_HIP;
+  if (dev < 0 || dev >= kMaxScratchDevices) return FUSEDMM_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return FUSEDMM_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FUSEDMM_OK;
+}
 
 constexpr int32_t kDefaultSmallRowMax = 64;
 constexpr int32_t kDefaultSplitRowMin = 512;
@@ -222,6 +251,7 @@ const char* fusedmm_status_string(int status) {
     case FUSEDMM_ERR_ALLOC: return "allocation failed";
     case FUSEDMM_ERR_HIP: return "HIP runtime error";
     case FUSEDMM_ERR_NOT_RESERVED: return "scratch not reserved for this dimension (call fusedmm_plan_reserve first)";
+    case FUSEDMM_ERR_SCRATCH_LIMIT: return "the partial rows of this call exceed the fixed scratch of fusedmm_execute_static_scratch";
     default: return "unknown status";
   }
 }
@@ -555,6 +585,12 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   if (st == FUSEDMM_OK) st = upload(&p->d_items, items, stream);
   if (st == FUSEDMM_OK) st = upload(&p->d_tile_descs, tile_descs, stream);
   if (st == FUSEDMM_OK && hipStreamSynchronize(stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+  // the address of the static scratch on this device is looked up here, once, so that
+  // fusedmm_execute_static_scratch finds it in place (its own first call would look it up otherwise)
+  if (st == FUSEDMM_OK) {
+    void* unused = nullptr;
+    (void)static_scratch_for_current_device(&unused);  // a failure is reported by that entry point, not here
+  }
   // the scratch of the hinted dimension, so that execute never has to allocate
   if (st == FUSEDMM_OK) st = fusedmm_plan_reserve(p, std::min<int32_t>(d_hint, FUSEDMM_MAX_D));
   if (st != FUSEDMM_OK) {
@@ -616,9 +652,11 @@ namespace {
 
 // Shared body of fusedmm_execute, fusedmm_execute_bf16y and fusedmm_execute_f16y.  y_format other than
 // kYF32: d_Y points at rows of 2-byte elements (ldy in elements); only the fast instances exist for those.
+// static_scratch: null = the partial rows live in the plan's own scratch; else they go to this buffer of
+// FUSEDMM_STATIC_SCRATCH_BYTES (fusedmm_execute_static_scratch), whatever the plan has reserved.
 int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
                  int64_t ldx, const void* d_Y, int y_format, int64_t ldy, float* d_Z, int64_t ldz, void* stream_,
-                 bool allow_private = false) {
+                 bool allow_private = false, void* static_scratch = nullptr) {
   const bool y_bf16 = y_format != kYF32;  // any 2-byte storage
   if (!plan || !ops) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
@@ -671,9 +709,15 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
   hipError_t e = hipSuccess;
   if (fast) {
-    if (plan->n_parts > 0 && D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
+    if (static_scratch) {
+      if ((size_t)plan->n_parts * (size_t)D * sizeof(float) > (size_t)FUSEDMM_STATIC_SCRATCH_BYTES) return FUSEDMM_ERR_SCRATCH_LIMIT;
+    } else if (plan->n_parts > 0 && D > plan->partials_d) {
+      return FUSEDMM_ERR_NOT_RESERVED;
+    }
+    float* partials = static_scratch ? static_cast<float*>(static_scratch) : plan->d_partials;
     KernelArgs a;
     fill_schedule_args(plan, D, y_format, &a);
+    a.partials = partials;
     a.d_pieces = d / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
@@ -686,7 +730,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     // partial rows are stored with the instance size as their stride, whatever the scratch capacity is
     if (e == hipSuccess)
-      e = launch_merge(plan->d_merges, plan->n_merges, plan->d_partials, d, D, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
+      e = launch_merge(plan->d_merges, plan->n_merges, partials, d, D, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
   } else {
     GenericArgs g;
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
@@ -696,8 +740,14 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     g.vop = ops->vop; g.rop = ops->rop; g.sop = ops->sop; g.mop = ops->mop; g.aop = ops->aop;
     g.alpha = ops->alpha;
     g.visit_counts = nullptr;
-    if ((size_t)plan->n_gen_segs * (size_t)d * sizeof(float) > plan->gen_partials_bytes) return FUSEDMM_ERR_NOT_RESERVED;
+    const size_t gen_need = (size_t)plan->n_gen_segs * (size_t)d * sizeof(float);
+    if (static_scratch) {
+      if (gen_need > (size_t)FUSEDMM_STATIC_SCRATCH_BYTES) return FUSEDMM_ERR_SCRATCH_LIMIT;
+    } else if (gen_need > plan->gen_partials_bytes) {
+      return FUSEDMM_ERR_NOT_RESERVED;
+    }
     fill_generic_segments(plan, &g);
+    if (static_scratch) g.partials = static_cast<float*>(static_scratch);
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_generic(g, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
@@ -720,6 +770,16 @@ extern "C" {
 int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values, const float* d_X,
                     int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz, void* stream_) {
   return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, kYF32, ldy, d_Z, ldz, stream_);
+}
+
+int fusedmm_execute_static_scratch(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
+                                   const float* d_X, int64_t ldx, const float* d_Y, int64_t ldy, float* d_Z, int64_t ldz,
+                                   void* stream_) {
+  void* ptr = nullptr;
+  const int st = static_scratch_for_current_device(&ptr);
+  if (st != FUSEDMM_OK) return st;
+  // nothing in the scratch has to start at zero: every partial row a merge reads was written by this call
+  return execute_impl(plan, ops, d, d_values, d_X, ldx, d_Y, kYF32, ldy, d_Z, ldz, stream_, false, ptr);
 }
 
 int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, const float* d_values,
