@@ -197,27 +197,13 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
   }
 }
 
-// Loads of data that is read once (column indices, edge values, x_u).  A non-temporal hint
-// on them was measured: -1 % kernel time on the two largest workloads, +3..10 % on the two
-// where X aliases Y (x_u is then also somebody's y_v), so it is off.
-#ifndef FMM_STREAM_HINT
-#define FMM_STREAM_HINT 0
-#endif
+// Loads of data that is read once (column indices, edge values, x_u) carry no cache hint: a non-temporal
+// hint on them was measured at -1 % kernel time on the two largest workloads and +3..10 % on the two where
+// X aliases Y (x_u is then also somebody's y_v).  Hinting the gathers of rarely used rows of Y (chosen by
+// the plan from the entry counts of the columns) raised the L2 hit rate by 3.5 points and cost 15-100 %.
 template <class T>
-__device__ __forceinline__ T ld_stream(const T* p) {
-#if FMM_STREAM_HINT
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
-}
-__device__ __forceinline__ v4f ld4_stream(const float* p) {
-#if FMM_STREAM_HINT
-  return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-#else
-  return *reinterpret_cast<const v4f*>(p);
-#endif
-}
+__device__ __forceinline__ T ld_stream(const T* p) { return *p; }
+__device__ __forceinline__ v4f ld4_stream(const float* p) { return *reinterpret_cast<const v4f*>(p); }
 
 // ---------------------------------------------------------------------------------------
 // per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
@@ -501,6 +487,54 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// One lane group accumulates the `deg` stored entries that start at e0 (a short row, a tile, or one
+// column-class piece of a row); the S lane groups of the wavefront work on different runs in
+// lockstep, maxdeg being the longest of them (wave-uniform).
+// ---------------------------------------------------------------------------------------
+template <int P, int D, int G, int U, int YF, int C>
+__device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0, int deg, int maxdeg,
+                                                 const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int slot, int g, int nv,
+                                                 bool use_val) {
+  constexpr int V = D / (4 * G);
+  using T = PatTraits<P>;
+  for (int bb = 0; bb < maxdeg; bb += G) {
+    int colb = 0;
+    float valb = 0.f;
+    if (bb + g < deg) {
+      colb = ld_stream(a.colidx + e0 + bb + g);
+      if (use_val) valb = ld_stream(a.values + e0 + bb + g);
+    }
+    const int steps = (maxdeg - bb) < G ? (maxdeg - bb) : G;
+    for (int k = 0; k < steps; k += U) {
+      bool ok[U];
+      int c[U];
+      float av[U];
+      v4f y[U][V];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        ok[u] = (bb + k + u) < deg;
+        c[u] = __shfl(colb, slot * G + k + u);
+        av[u] = use_val ? __shfl(valb, slot * G + k + u) : 0.f;
+      }
+      if constexpr (T::loads_y) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+          if (ok[u]) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (ok[u] && g == 0) atomicAdd(a.visit_counts + (e0 + bb + k + u), 1u);
+      }
+    }
+  }
+}
+
 template <int D, int G, int C, bool M>
 __device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
   const float* xr = a.X + row * a.ldx;
@@ -693,42 +727,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
       if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
       maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
-
-      for (int bb = 0; bb < maxdeg; bb += GP) {
-        int colb = 0;
-        float valb = 0.f;
-        if (bb + g < deg) {
-          colb = ld_stream(a.colidx + e0 + bb + g);
-          if (use_val) valb = ld_stream(a.values + e0 + bb + g);
-        }
-        const int steps = (maxdeg - bb) < GP ? (maxdeg - bb) : GP;
-        for (int k = 0; k < steps; k += UP) {
-          bool ok[UP];
-          int c[UP];
-          float av[UP];
-          v4f y[UP][V];
-#pragma unroll
-          for (int u = 0; u < UP; ++u) {
-            ok[u] = (bb + k + u) < deg;
-            c[u] = __shfl(colb, slot * GP + k + u);
-            av[u] = use_val ? __shfl(valb, slot * GP + k + u) : 0.f;
-          }
-          if constexpr (T::loads_y) {
-#pragma unroll
-            for (int u = 0; u < UP; ++u) {
-#pragma unroll
-              for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-              if (ok[u]) gather_row<YF, GP, V, CP, P == PAT_RUNTIME>(a, c[u], g, y[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < UP; ++u) edge_update<P, GP, V, true>(x, y[u], av[u], a, ok[u], z, nv);
-          } else {
-#pragma unroll
-            for (int u = 0; u < UP; ++u)
-              if (ok[u] && g == 0) atomicAdd(a.visit_counts + (e0 + bb + k + u), 1u);
-          }
-        }
-      }
+      group_accumulate<P, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, use_val);
       if constexpr (T::loads_y) {
         if constexpr (T::means) {
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
