@@ -122,9 +122,12 @@ typedef enum {
 /* Scheduling knobs of the degree-binned plan (the GPU counterpart of the
  * nnz-balanced 1-D partition, Section III-C).  Zero fields take defaults. */
 typedef struct fusedmm_plan_options {
-  int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront (default 64) */
-  int32_t split_row_min;   /* rows with  > this many entries get whole workgroups (default 512) */
-  int32_t chunk_edges;     /* entries per workgroup chunk of a split row (default 1024) */
+  int32_t small_row_max;   /* rows with <= this many entries are packed several per wavefront (default 64;
+                              128 when feature_dim_hint <= 16) */
+  int32_t split_row_min;   /* rows with  > this many entries get whole workgroups (default 512; 2048 when
+                              feature_dim_hint <= 16) */
+  int32_t chunk_edges;     /* entries per workgroup chunk of a split row (default 1024; 8192 when
+                              feature_dim_hint <= 16) */
   int32_t column_classes;  /* long rows are cut by contiguous column ranges ("classes") into tiles and
                               all tiles of a class run on one XCD, so that its slice of Y stays in that
                               XCD's L2.  This is the finest number of classes (8, 16, 32, ... up to 512,
@@ -164,12 +167,15 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
                         const fusedmm_plan_options_t* options, void* stream);
 
 /* Build the schedule by measurement (the counterpart of the paper's autotuned kernels,
- * Section IV-B: parameters chosen per machine by timing candidates).  Creates a plan for each of
- * a small set of candidate schedules (column-class tiling off / 8..64 classes / two minimum row
- * lengths), times three fusedmm_execute calls of each with the given operands on `stream`,
- * keeps the fastest and destroys the others.  Arguments as for fusedmm_plan_create and
- * fusedmm_execute; d_Z is overwritten.  `chosen` (host, may be NULL) receives the winning options,
- * `best_ms` (host, may be NULL) its time per execute.  Synchronises the stream; not for the hot path. */
+ * Section IV-B: parameters chosen per machine by timing candidates).  The default plan of
+ * fusedmm_plan_create is timed first and stays unless a candidate beats it by 1 %; then one scheduling
+ * knob at a time is varied around the best plan so far: finest column classes (off, 8 ... 128), shortest
+ * tiled row, chunk length, and the row lengths that separate packed rows, one-wavefront rows and chunked
+ * rows (about 16 plans in all).  Every plan is timed by the median of 11 fusedmm_execute calls with the
+ * given operands on `stream` (5 or 3 for kernels of more than 5 / 20 ms); the losers are destroyed.
+ * Arguments as for fusedmm_plan_create and fusedmm_execute; d_Z is overwritten.  `chosen` (host, may be
+ * NULL) receives the winning options, `best_ms` (host, may be NULL) its median time per execute.
+ * Synchronises the stream; not for the hot path. */
 int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
                               const int64_t* d_rowptr, const int32_t* d_colidx,
                               const fusedmm_ops_t* ops, int32_t d, const float* d_values,

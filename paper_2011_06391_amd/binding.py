@@ -199,7 +199,8 @@ def fusedmm_plan_create_tuned(m: int, n: int, nnz: int, d_rowptr, d_colidx, ops:
                                           ctypes.byref(ops), d, _dptr(d_values), _dptr(d_X), ldx, _dptr(d_Y), ldy,
                                           _dptr(d_Z), ldz, _stream(stream), ctypes.byref(chosen), ctypes.byref(ms))
     _check(st, "fusedmm_plan_create_tuned")
-    opts = {"column_classes": chosen.column_classes, "tile_row_min": chosen.tile_row_min,
+    opts = {"small_row_max": chosen.small_row_max, "split_row_min": chosen.split_row_min, "chunk_edges": chosen.chunk_edges,
+            "column_classes": chosen.column_classes, "tile_row_min": chosen.tile_row_min,
             "feature_dim_hint": chosen.feature_dim_hint}
     return plan, opts, float(ms.value)
 

@@ -19,6 +19,7 @@ SOURCES = [
     "fusedmm_api.hip",
     "fusedmm_generic.hip",
     "fusedmm_minibatch.hip",
+    "fusedmm_small.hip",
     "fusedmm_fast_d32.hip",
     "fusedmm_fast_d64.hip",
     "fusedmm_fast_d128.hip",

@@ -70,6 +70,10 @@ int static_scratch_for_current_device(void** out) {
 constexpr int32_t kDefaultSmallRowMax = 64;
 constexpr int32_t kDefaultSplitRowMin = 512;
 constexpr int32_t kDefaultChunkEdges = 1024;
+// the same three when the plan is hinted a feature dimension of at most 16
+constexpr int32_t kShortDimSmallRowMax = 128;
+constexpr int32_t kShortDimSplitRowMin = 2048;
+constexpr int32_t kShortDimChunkEdges = 8192;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
 // dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB); the finest
 // level keeps a class slice of Y at >= 4 MiB and stops at 64 classes; a row needs 16 entries per
@@ -214,6 +218,7 @@ void fill_generic_segments(const fusedmm_plan* p, GenericArgsT<T>* g) {
   g->partials = static_cast<T*>(p->d_gen_partials);
 }
 
+// d: the instance size of a wide kernel, or the dimension itself for the kernels for very short feature vectors
 void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelArgs* a) {
   a->rowptr = p->d_rowptr;
   a->colidx = p->d_colidx;
@@ -231,7 +236,7 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelAr
   a->nb_zero = (p->n_empty + kZeroRowsPerBlock - 1) / kZeroRowsPerBlock;
   a->nb_chunk = p->n_chunks;
   a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int rpb = packed_rows_per_block(d, y_format);
+  const int rpb = is_small_dim(d) ? small_packed_rows_per_block(d) : packed_rows_per_block(d, y_format);
   a->nb_packed = rpb > 0 ? (p->n_packed + rpb - 1) / rpb : 0;
 }
 
@@ -287,6 +292,11 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
   int32_t small_max = kDefaultSmallRowMax, split_min = kDefaultSplitRowMin, chunk = kDefaultChunkEdges;
+  if (options && options->feature_dim_hint > 0 && options->feature_dim_hint <= 16) {
+    // very short feature vectors (one lane per stored entry): a work item's fixed cost -- its descriptor, the
+    // reduction across lanes, the store -- is spread over more entries
+    small_max = kShortDimSmallRowMax; split_min = kShortDimSplitRowMin; chunk = kShortDimChunkEdges;
+  }
   if (options) {
     if (options->small_row_max < 0 || options->split_row_min < 0 || options->chunk_edges < 0) return FUSEDMM_ERR_INVALID_ARG;
     if (options->small_row_max > 0) small_max = options->small_row_max;
@@ -606,8 +616,8 @@ int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   // every dimension <= d: the largest instance size one of them runs on, and the general kernel's rows of d elements
-  const int32_t D = d >= 512 ? 512 : instance_dim(d / 4 * 4);
-  int st = D ? ensure_partials(plan, D) : FUSEDMM_OK;
+  const int32_t D = std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
+  int st = ensure_partials(plan, D);
   if (st == FUSEDMM_OK) st = ensure_gen_partials(plan, d, sizeof(float));
   return st;
 }
@@ -626,7 +636,7 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
   b += (size_t)plan->n_gen_segs * sizeof(ChunkDesc) + (size_t)plan->n_gen_merges * sizeof(MergeDesc);
   // what the plan holds once fusedmm_plan_reserve(plan, d) has run: partial rows of both kernels
-  const int32_t D = d >= 512 ? 512 : instance_dim(d / 4 * 4);
+  const int32_t D = std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
   b += (size_t)plan->n_parts * (size_t)std::max(D, plan->partials_d) * sizeof(float);
   b += std::max((size_t)plan->n_gen_segs * (size_t)d * sizeof(float), plan->gen_partials_bytes);
   *out = b;
@@ -690,6 +700,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
   // structure with the ops decided at run time; odd shapes fall back to the general kernel
   // a dimension between two instance sizes runs the run-time-ops instance of the next larger size (fp32 storage only)
+  const bool small = !y_bf16 && is_small_dim(d);  // one lane per stored entry; rows need no alignment beyond 4 bytes
   const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);
   const int pattern = (recognised >= 0 && D == d) ? recognised : PAT_RUNTIME;
@@ -708,7 +719,29 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   }
 
   hipError_t e = hipSuccess;
-  if (fast) {
+  if (small && ldy < (int64_t(1) << 29)) {
+    if (static_scratch) {
+      if ((size_t)plan->n_parts * kSmallPartialStride * sizeof(float) > (size_t)FUSEDMM_STATIC_SCRATCH_BYTES) return FUSEDMM_ERR_SCRATCH_LIMIT;
+    } else if (plan->n_parts > 0 && kSmallPartialStride > plan->partials_d) {
+      return FUSEDMM_ERR_NOT_RESERVED;
+    }
+    float* partials = static_scratch ? static_cast<float*>(static_scratch) : plan->d_partials;
+    KernelArgs a;
+    fill_schedule_args(plan, d, kYF32, &a);
+    a.partials = partials;
+    a.d_pieces = 0;
+    a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
+    a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
+    a.alpha = ops->alpha;
+    a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop;
+    a.mean = ops->aop == FUSEDMM_AOP_MEAN;
+    a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;
+    if (ev0) (void)hipEventRecord(ev0, stream);
+    e = launch_small(recognised, d, a, stream);
+    if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
+    if (e == hipSuccess)
+      e = launch_small_merge(plan->d_merges, plan->n_merges, partials, d, ops->aop, plan->d_rowptr, d_Z, ldz, stream);
+  } else if (fast) {
     if (static_scratch) {
       if ((size_t)plan->n_parts * (size_t)D * sizeof(float) > (size_t)FUSEDMM_STATIC_SCRATCH_BYTES) return FUSEDMM_ERR_SCRATCH_LIMIT;
     } else if (plan->n_parts > 0 && D > plan->partials_d) {
@@ -854,22 +887,22 @@ int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* str
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path, uint32_t* d_counts, void* stream_) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  if (fast_path && !instance_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (fast_path && !instance_dim(d) && !is_small_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   if (plan->m == 0 || plan->nnz == 0) return FUSEDMM_OK;
   if (!d_counts) return FUSEDMM_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   hipError_t e;
   if (fast_path) {
     KernelArgs a;
-    const int32_t D = instance_dim(d);
-    fill_schedule_args(plan, D, kYF32, &a);
+    const int32_t D = is_small_dim(d) ? 0 : instance_dim(d);  // 0: the kernels for very short feature vectors
+    fill_schedule_args(plan, D ? D : d, kYF32, &a);
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.d_pieces = d / 4;
     a.visit_counts = d_counts;
-    e = launch_fast(PAT_VISIT, D, kYF32, a, stream);
+    e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(PAT_VISIT, D, kYF32, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;
@@ -946,55 +979,104 @@ int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_
                               void* stream_, fusedmm_plan_options_t* chosen, float* best_ms) {
   if (!out || !ops) return FUSEDMM_ERR_INVALID_ARG;
   *out = nullptr;
-  // candidate schedules: no column-class tiling, and nested tiling with 8..64 finest classes at
-  // two minimum row lengths; everything else at its default
-  static const int32_t kCandidates[][2] = {{1, 0}, {8, 64}, {8, 128}, {16, 128}, {32, 128}, {64, 128}, {16, 256}, {64, 256}};
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (hipEventCreate(&e0) != hipSuccess) return FUSEDMM_ERR_HIP;
-  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FUSEDMM_ERR_HIP; }
+  constexpr int kMaxTimed = 11;
+  hipEvent_t ev[kMaxTimed + 1] = {};
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) {
+      for (auto& f : ev) if (f) (void)hipEventDestroy(f);
+      return FUSEDMM_ERR_HIP;
+    }
+
+  // Median time of one execute under a plan built with `opt`; the plan is returned in *made.
+  auto measure = [&](const fusedmm_plan_options_t& opt, fusedmm_plan_t** made, float* median_ms) -> int {
+    *made = nullptr;
+    fusedmm_plan_t* p = nullptr;
+    int st = fusedmm_plan_create(&p, m, n, nnz, d_rowptr, d_colidx, &opt, stream_);
+    if (st != FUSEDMM_OK) return st;
+    // two untimed executes, the second one timed to size the sample: 11 executes, fewer for kernels of several ms
+    float first_ms = 0.f;
+    for (int it = 0; it < 2 && st == FUSEDMM_OK; ++it) {
+      if (hipEventRecord(ev[0], stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+      if (st == FUSEDMM_OK) st = fusedmm_execute(p, ops, d, d_values, d_X, ldx, d_Y, ldy, d_Z, ldz, stream_);
+      if (st == FUSEDMM_OK && (hipEventRecord(ev[1], stream) != hipSuccess || hipEventSynchronize(ev[1]) != hipSuccess ||
+                               hipEventElapsedTime(&first_ms, ev[0], ev[1]) != hipSuccess))
+        st = FUSEDMM_ERR_HIP;
+    }
+    const int timed = first_ms > 20.f ? 3 : (first_ms > 5.f ? 5 : kMaxTimed);
+    for (int it = 0; it < timed && st == FUSEDMM_OK; ++it) {
+      if (it == 0 && hipEventRecord(ev[0], stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+      if (st == FUSEDMM_OK) st = fusedmm_execute(p, ops, d, d_values, d_X, ldx, d_Y, ldy, d_Z, ldz, stream_);
+      if (st == FUSEDMM_OK && hipEventRecord(ev[it + 1], stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
+    }
+    if (st == FUSEDMM_OK && hipEventSynchronize(ev[timed]) != hipSuccess) st = FUSEDMM_ERR_HIP;
+    float ms[kMaxTimed];
+    for (int it = 0; it < timed && st == FUSEDMM_OK; ++it)
+      if (hipEventElapsedTime(&ms[it], ev[it], ev[it + 1]) != hipSuccess) st = FUSEDMM_ERR_HIP;
+    if (st != FUSEDMM_OK) {
+      (void)fusedmm_plan_destroy(p);
+      return st;
+    }
+    std::sort(ms, ms + timed);
+    *median_ms = ms[timed / 2];
+    *made = p;
+    return FUSEDMM_OK;
+  };
+
+  // The incumbent starts as the default plan, so the result is never slower than fusedmm_plan_create's
+  // (beyond timing noise: a candidate has to win by 1 %).  Then one knob at a time is varied around the
+  // incumbent, in the order of their measured influence: column classes, shortest tiled row, chunk length,
+  // and the two row-length thresholds of the bins.
+  fusedmm_plan_options_t best_opt = {};
+  best_opt.feature_dim_hint = d;
   fusedmm_plan_t* best = nullptr;
   float best_time = 0.f;
-  fusedmm_plan_options_t best_opt = {};
-  int st = FUSEDMM_OK;
-  for (const auto& cand : kCandidates) {
-    fusedmm_plan_options_t opt = {};
-    opt.column_classes = cand[0];
-    opt.tile_row_min = cand[1];
-    opt.feature_dim_hint = d;
+  int st = measure(best_opt, &best, &best_time);
+  auto consider = [&](fusedmm_plan_options_t opt) {
+    if (st != FUSEDMM_OK) return;
     fusedmm_plan_t* p = nullptr;
-    st = fusedmm_plan_create(&p, m, n, nnz, d_rowptr, d_colidx, &opt, stream_);
-    if (st != FUSEDMM_OK) break;
-    if (cand[0] > 1 && p->n_tiled_rows == 0) {  // tiling did not engage (short or unsorted rows): same as {1, 0}
-      (void)fusedmm_plan_destroy(p);
-      continue;
-    }
-    constexpr int kWarm = 2, kTimed = 3;
-    for (int it = 0; it < kWarm + kTimed && st == FUSEDMM_OK; ++it) {
-      if (it == kWarm && hipEventRecord(e0, stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
-      if (st == FUSEDMM_OK) st = fusedmm_execute(p, ops, d, d_values, d_X, ldx, d_Y, ldy, d_Z, ldz, stream_);
-    }
-    float ms = 0.f;
-    if (st == FUSEDMM_OK && (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-                             hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
-      st = FUSEDMM_ERR_HIP;
-    if (st != FUSEDMM_OK) { (void)fusedmm_plan_destroy(p); break; }
-    ms /= kTimed;
-    if (!best || ms < best_time) {
-      if (best) (void)fusedmm_plan_destroy(best);
-      best = p; best_time = ms; best_opt = opt;
+    float t = 0.f;
+    st = measure(opt, &p, &t);
+    if (st != FUSEDMM_OK) return;
+    if (t < 0.99f * best_time) {
+      (void)fusedmm_plan_destroy(best);
+      best = p; best_time = t; best_opt = opt;
     } else {
       (void)fusedmm_plan_destroy(p);
     }
+  };
+  if (st == FUSEDMM_OK) {
+    const int32_t default_classes = best->n_classes;
+    for (int32_t c : {1, 8, 16, 32, 64, 128}) {
+      if (c == default_classes) continue;
+      fusedmm_plan_options_t o = best_opt;
+      o.column_classes = c;
+      consider(o);
+    }
+    if (st == FUSEDMM_OK && best->n_classes > 1)
+      for (int32_t t : {64, 256}) {
+        fusedmm_plan_options_t o = best_opt;
+        o.column_classes = best->n_classes;
+        o.tile_row_min = t;
+        consider(o);
+      }
+    for (int32_t c : {512, 2048}) { fusedmm_plan_options_t o = best_opt; o.chunk_edges = c; consider(o); }
+    for (int32_t v : {256, 1024}) { fusedmm_plan_options_t o = best_opt; o.split_row_min = v; consider(o); }
+    for (int32_t v : {32, 128}) { fusedmm_plan_options_t o = best_opt; o.small_row_max = v; consider(o); }
   }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
+  for (auto& e : ev) (void)hipEventDestroy(e);
   if (st != FUSEDMM_OK) {
     if (best) (void)fusedmm_plan_destroy(best);
     return st;
   }
   *out = best;
-  if (chosen) *chosen = best_opt;
+  if (chosen) {
+    *chosen = best_opt;  // what was asked of fusedmm_plan_create, with the values the plan resolved them to
+    chosen->small_row_max = best->small_row_max;
+    chosen->split_row_min = best->split_row_min;
+    chosen->chunk_edges = best->chunk_edges;
+    chosen->column_classes = best->n_classes;
+  }
   if (best_ms) *best_ms = best_time;
   return FUSEDMM_OK;
 }

@@ -100,6 +100,16 @@ enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2 };
 // kYF32: a.Y holds 2-byte elements (the five sum patterns and the run-time-ops instance exist in that form).
 hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream);
 
+// The kernels for very short feature vectors (one lane per stored entry): d must be 2, 3, 4, 8 or 16, fp32,
+// rows of any 4-byte aligned pitch.  Same plan, descriptors and block ranges as launch_fast (the packed range is
+// cut into small_packed_rows_per_block(d) rows per workgroup); partial rows are kSmallPartialStride floats apart.
+constexpr int kSmallPartialStride = 16;
+inline bool is_small_dim(int d) { return d == 2 || d == 3 || d == 4 || d == 8 || d == 16; }
+int small_packed_rows_per_block(int d);
+hipError_t launch_small(int pattern, int d, const KernelArgs& a, hipStream_t stream);
+hipError_t launch_small_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t aop,
+                              const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
+
 // dst[i] = bfloat16(src[i]), round to nearest even; NaN stays NaN.
 hipError_t launch_to_bf16(uint16_t* dst, const float* src, size_t count, hipStream_t stream);
 // dst[i] = half(src[i]), round to nearest even.

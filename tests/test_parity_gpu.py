@@ -123,6 +123,55 @@ def test_fast_kernels_column_class_tiles(B, pattern, d):
         assert stats["column_classes"] == options["column_classes"]
 
 
+SMALL_CASES = [(p, "SUM", p, "ASUM") for p in PATTERNS] + [
+    (("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "MAX", ("SEL2ND", "NOOP", "EDGE_VALUE", "MUL_Y"), "AMAX"),
+    (("SUB", "NOOP", "SIGMOID", "MUL_T"), "MIN", ("SUB", "NOOP", "SIGMOID", "MUL_T"), "AMIN"),
+    (("MUL", "RSUM", "SIGMOID", "MUL_Y"), "MEAN", ("MUL", "RSUM", "SIGMOID", "MUL_Y"), "AMEAN"),
+    (("ADD", "RMUL", "NOOP", "MUL_T"), "SUM", ("ADD", "RMUL", "NOOP", "MUL_T"), "ASUM"),
+]
+
+
+@pytest.mark.parametrize("d", (2, 3, 4, 8, 16))
+@pytest.mark.parametrize("case", SMALL_CASES, ids=[str(c[0]) + "-" + c[1] for c in SMALL_CASES])
+def test_short_feature_vectors_all_bins(B, case, d):
+    """d = 2, 3, 4, 8, 16 (the layout application's sizes among them) run the one-lane-per-entry kernels on
+    the plan's own schedule: packed rows, one-wavefront rows, workgroup chunks, column-class tiles and their
+    merge, rows without entries; leading dimensions that are odd and views that start one float in (rows only
+    4-byte aligned); every stored entry visited once."""
+    gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
+    rng = np.random.default_rng(6000 + d)
+    m, n = 301, 4000
+    long_rows = {3: 64, 4: 65, 5: 120, 10: 127, 11: 257, 57: 700, 200: 1024, 201: 1025, 299: 3001, 300: 9000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    pad = 3
+    Xw = rng.uniform(0.2, 0.9, (m, d + pad)).astype(np.float32)
+    Yw = rng.uniform(0.2, 0.9, (n, d + pad)).astype(np.float32)
+    Yw[:, 0] = 1e30                        # the views below start at column 1: this one must never be read
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    names = oracle.PATTERNS[oracle_ops] if isinstance(oracle_ops, str) else oracle_ops
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, Xw[:, 1:d + 1], Yw[:, 1:d + 1], names, oracle_aop, alpha=ALPHA)
+    ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
+    ops.alpha = ALPHA
+    uses_x = ops.vop != B.VOP["SEL2ND"]
+    rp, ci = dev(rowptr), dev(colidx)
+    Xd, Yd, vd = dev(Xw), dev(Yw), dev(vals)
+    for options in (None, {"small_row_max": 8, "split_row_min": 96, "chunk_edges": 512}, TILED,
+                    dict(TILED, column_classes=64, tile_row_min=64, small_row_max=2, split_row_min=40)):
+        plan = B.Plan(m, n, rp, ci, options)
+        Zb = torch.full((m, d + pad), 7.0, dtype=torch.float32, device="cuda")
+        plan.execute(ops, Xd[:, 1:d + 1] if uses_x else None, Yd[:, 1:d + 1], Zb[:, 1:d + 1], vd)
+        torch.cuda.synchronize()
+        out = Zb.cpu().numpy()
+        check(out[:, 1:d + 1], Zr, S, f"{gpu_ops} {gpu_aop} d={d} {options}")
+        assert (out[:, 0] == 7.0).all() and (out[:, d + 1:] == 7.0).all()
+        counts = torch.zeros(len(colidx), dtype=torch.int32, device="cuda")
+        plan.edge_visits(d, True, counts)
+        torch.cuda.synchronize()
+        c = counts.cpu().numpy()
+        assert c.min() == 1 and c.max() == 1
+        plan.close()
+
+
 @pytest.mark.parametrize("d", (1, 3, 4, 33, 100, 130, 2048))
 @pytest.mark.parametrize("pattern", PATTERNS)
 def test_general_kernel_odd_dims(B, pattern, d):
@@ -490,7 +539,8 @@ def test_tuned_plan_is_a_valid_plan(B):
     rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(X)
     Z = torch.empty((g.m, d), dtype=torch.float32, device="cuda")
     plan = B.Plan.tuned(g.m, g.n, rp, ci, "one_minus_sigmoid", Xd, Xd, Z)
-    assert plan.tuned_ms > 0 and plan.tuned_options["column_classes"] in (1, 8, 16, 32, 64)
+    assert plan.tuned_ms > 0 and plan.tuned_options["column_classes"] in (1, 8, 16, 32, 64, 128)
+    assert plan.tuned_options["chunk_edges"] in (512, 1024, 2048) and plan.tuned_options["split_row_min"] in (256, 512, 1024)
     Z.fill_(float("nan"))
     plan.execute("one_minus_sigmoid", Xd, Xd, Z)
     torch.cuda.synchronize()
