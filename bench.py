@@ -71,13 +71,17 @@ def measured_traffic(workload: str, plan_stats: dict):
     return None, None, why
 
 
-def parity_sample(w, rows, Z_rows):
+def parity_sample(w, rows, Z_rows, aop="SUM"):
     """Part of the CPU leg: the fp64 oracle recomputes a sample of rows of the timed result."""
     import numpy as np
     import oracle
 
     sub = w.csr.take_rows(rows)
-    Zr, S, _ = oracle.unfused(sub.rowptr, sub.colidx, sub.values, w.X[rows], w.Y, w.pattern)
+    if aop == "SUM":
+        Zr, S, _ = oracle.unfused(sub.rowptr, sub.colidx, sub.values, w.X[rows], w.Y, w.pattern)
+    else:
+        Zr, S, _ = oracle.unfused_general(sub.rowptr, sub.colidx, sub.values, w.X[rows], w.Y, oracle.PATTERNS[w.pattern],
+                                          {"MAX": "AMAX", "MIN": "AMIN", "MEAN": "AMEAN"}[aop])
     err, _, viol = oracle.compare(Z_rows, Zr, S)
     return {"rows_checked": int(len(rows)), "stored_entries_checked": int(sub.nnz), "max_rel_err": err,
             "tolerance": 1e-4, "nonzero_where_all_terms_zero": viol,
@@ -118,7 +122,7 @@ def cpu_baseline(w, budget_edges_dim: float = 6.0e10):
 
 def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=None, copy_mib: int = 0,
         autotune: bool = False, y_storage: str = "f32", with_context: bool = True, relabel: bool = True,
-        time_cpu: bool = True):
+        time_cpu: bool = True, aop: str = "SUM"):
     import torch
     from paper_2011_06391_amd import binding, model, synth
 
@@ -139,6 +143,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     Z = torch.empty((g.m, w.d), dtype=torch.float32, device="cuda")
     uses_x = w.pattern != "gcn"
     ops = binding.fusedmm_ops_preset(w.pattern)
+    ops.aop = binding.AOP[aop]   # the pattern's messages pooled another way (secondary measurements)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -218,7 +223,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": f"f32 (Y stored as {y_storage})" if y_bf16 else "f32", "data": "synthetic",
-        "config": {"workload": workload, "description": w.description, "pattern": w.pattern,
+        "config": {"workload": workload, "description": w.description, "pattern": w.pattern, "aop": aop,
                    "vertex_order": "seeded random permutation" if relabel else "as generated (natural order)",
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
                    "empty_rows": int((deg == 0).sum()), "plan": stats, "plan_ms": plan_ms,
@@ -329,7 +334,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(w) if time_cpu else {}
         if not y_bf16:  # the oracle would have to be fed the rounded Y; tests/test_reduced_storage_gpu.py does that
-            out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample)
+            out["cpu_baseline"]["parity_of_timed_result"] = parity_sample(w, sample_rows, Z_sample, aop)
     return out
 
 
@@ -439,6 +444,8 @@ def main():
     ap.add_argument("--natural-order", action="store_true",
                     help="keep the vertex labels as generated (hubs at low ids) instead of the seeded random permutation "
                          "(secondary column: the gathers are then flattered by locality)")
+    ap.add_argument("--aop", default="SUM", choices=("SUM", "MAX", "MIN", "MEAN"),
+                    help="pool the workload's messages this way instead of summing them (secondary measurements)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the context measurements after the timed region (HIP-graph replay, copy bandwidth, "
@@ -471,7 +478,8 @@ def main():
                    "tile_row_min": args.tile_row_min}
     y_storage = "bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32")
     out = run(workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
-              args.copy_calibration_mib, args.autotune, y_storage, not args.no_context, not args.natural_order)
+              args.copy_calibration_mib, args.autotune, y_storage, not args.no_context, not args.natural_order,
+              aop=args.aop)
     if args.all_workloads or args.workload is None:
         # the other large configurations, same protocol (the same K timed steps, default plan), shorter report
         others = {}

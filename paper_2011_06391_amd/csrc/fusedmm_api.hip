@@ -131,6 +131,19 @@ int recognise(const fusedmm_ops_t& o) {
   return -1;
 }
 
+// The tuple family with compile-time vector loops an op tuple belongs to (scalar message from a dot product,
+// or from the sum / difference of the operands), or -1: such a tuple runs faster there than with every step
+// read at run time, and the families also take the dimensions between two instance sizes.
+int recognise_family(const fusedmm_ops_t& o) {
+  if (o.rop == FUSEDMM_ROP_NOOP || o.sop == FUSEDMM_SOP_EDGE_VALUE) return -1;  // vector message, or the edge value
+  const bool mm = o.aop == FUSEDMM_AOP_MAX || o.aop == FUSEDMM_AOP_MIN;
+  if (o.vop == FUSEDMM_VOP_MUL && o.rop == FUSEDMM_ROP_RSUM) return mm ? PAT_DOT_MM : PAT_DOT;
+  if ((o.vop == FUSEDMM_VOP_SUB || o.vop == FUSEDMM_VOP_ADD) &&
+      (o.rop == FUSEDMM_ROP_RSUM || o.rop == FUSEDMM_ROP_SUMSQ || o.rop == FUSEDMM_ROP_NORM2))
+    return mm ? PAT_DIST_MM : PAT_DIST;
+  return -1;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int64_t rows_b, int64_t ld_b, int32_t d) {
@@ -703,7 +716,8 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   const bool small = !y_bf16 && is_small_dim(d);  // one lane per stored entry; rows need no alignment beyond 4 bytes
   const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);
-  const int pattern = (recognised >= 0 && D == d) ? recognised : PAT_RUNTIME;
+  const int family = recognise_family(*ops);
+  const int pattern = (recognised >= 0 && D == d) ? recognised : (family >= 0 ? family : PAT_RUNTIME);
   const bool y_ok = plan->nnz == 0 || (y_bf16 ? (aligned16(d_Y) && ldy % 8 == 0)
                                               : (aligned16(d_Y) && ldy % 4 == 0));
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
@@ -755,6 +769,12 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
+    a.sign = ops->aop == FUSEDMM_AOP_MIN ? -1.0f : 1.0f;
+    a.ysign = ops->vop == FUSEDMM_VOP_SUB ? -1.0f : 1.0f;
+    a.sop_exp = ops->sop == FUSEDMM_SOP_SIGMOID || ops->sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID || ops->sop == kSopValueMinusSigmoid;
+    a.sop_c1 = ops->sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID ? 1.4426950408889634f : -1.4426950408889634f;
+    a.sop_rcp = a.sop_exp || ops->sop == FUSEDMM_SOP_INV_1P;
+    a.sop_lin = ops->sop == FUSEDMM_SOP_SCAL ? ops->alpha : 1.0f;
     a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop;
     a.mean = ops->aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
     a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;

@@ -73,13 +73,19 @@ __device__ __forceinline__ float aop_apply(int aop, float z, float w) {
 template <int P>
 struct PatTraits {
   static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
+  static constexpr bool dot = (P == PAT_DOT || P == PAT_DOT_MM);
+  static constexpr bool dist = (P == PAT_DIST || P == PAT_DIST_MM);
+  static constexpr bool family = dot || dist;                       // scalar steps read at run time
+  static constexpr bool flips = (P == PAT_DOT_MM || P == PAT_DIST_MM);  // accumulates sign * w by MAX, stores sign * z
   static constexpr bool uses_x = (!gcn && P != PAT_VISIT);
   static constexpr bool uses_val = (gcn || P == PAT_SIGNED_SIGMOID);
   static constexpr bool loads_y = (P != PAT_VISIT);
+  // rows may be narrower than the instance: pieces at or beyond a.d_pieces are neither loaded nor stored
+  static constexpr bool masked = (P == PAT_RUNTIME || family);
   // how messages are accumulated when it is fixed at compile time, and whether a row stored whole
   // may have to be divided by its length (mean pooling: a.mean)
-  static constexpr int aop = P == PAT_GCN_MAX ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
-  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN);
+  static constexpr int aop = (P == PAT_GCN_MAX || flips) ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
+  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_DOT || P == PAT_DIST);
 };
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
@@ -216,6 +222,7 @@ __device__ __forceinline__ bool reads_x(const KernelArgs& a) {
 template <int P>
 __device__ __forceinline__ bool reads_values(const KernelArgs& a) {
   if constexpr (P == PAT_RUNTIME) return a.sop == FUSEDMM_SOP_EDGE_VALUE || a.sop == kSopValueMinusSigmoid;
+  else if constexpr (PatTraits<P>::family) return a.sop == kSopValueMinusSigmoid;
   else return PatTraits<P>::uses_val;
 }
 
@@ -357,7 +364,69 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     }
     return;
   }
-  if constexpr (PatTraits<P>::gcn) {
+  if constexpr (PatTraits<P>::family) {
+    // The vector loops of the tuple are fixed (dot product or difference / sum of the operands, scalar times
+    // vector, SUM or MAX); what acts on the scalar -- NORM2's square root, SOP, SEL2ND's h = 1, the sign of a
+    // MIN -- is read from the arguments, wave-uniform.
+    v4f t[V];
+    float p = 0.f;
+    if constexpr (PatTraits<P>::dot) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        p = __builtin_fmaf(x[i].x, y[i].x, p);
+        p = __builtin_fmaf(x[i].y, y[i].y, p);
+        p = __builtin_fmaf(x[i].z, y[i].z, p);
+        p = __builtin_fmaf(x[i].w, y[i].w, p);
+      }
+    } else {
+      const float ys = a.ysign;
+#pragma unroll
+      for (int i = 0; i < V; ++i) t[i] = ys * y[i] + x[i];
+      if (a.rop == FUSEDMM_ROP_RSUM) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) p += (t[i].x + t[i].y) + (t[i].z + t[i].w);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          p = __builtin_fmaf(t[i].x, t[i].x, p);
+          p = __builtin_fmaf(t[i].y, t[i].y, p);
+          p = __builtin_fmaf(t[i].z, t[i].z, p);
+          p = __builtin_fmaf(t[i].w, t[i].w, p);
+        }
+      }
+    }
+    float s = group_allreduce<G>(p);
+    if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
+    const float u = a.sop_exp ? __builtin_amdgcn_exp2f(a.sop_c1 * s) : s;
+    float h = a.sop_rcp ? __builtin_amdgcn_rcpf(1.0f + u) : a.sop_lin * s;
+    if (a.sop == kSopValueMinusSigmoid) h = aval - h;
+    if (a.mop == FUSEDMM_MOP_SEL2ND) h = 1.0f;
+    if constexpr (PatTraits<P>::flips) h *= a.sign;
+    if (CHECK && !valid) h = 0.f;
+    if (a.mop == FUSEDMM_MOP_MUL_T) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        v4f o;
+        if constexpr (PatTraits<P>::dot) o = x[i] * y[i]; else o = t[i];
+        if constexpr (PatTraits<P>::flips) {
+          const v4f w = h * o;
+          z[i] = v4f{fmaxf(z[i].x, w.x), fmaxf(z[i].y, w.y), fmaxf(z[i].z, w.z), fmaxf(z[i].w, w.w)};
+        } else {
+          z[i] += h * o;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        if constexpr (PatTraits<P>::flips) {
+          const v4f w = h * y[i];
+          z[i] = v4f{fmaxf(z[i].x, w.x), fmaxf(z[i].y, w.y), fmaxf(z[i].z, w.z), fmaxf(z[i].w, w.w)};
+        } else {
+          z[i] += h * y[i];
+        }
+      }
+    }
+  } else if constexpr (PatTraits<P>::gcn) {
     // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP: w = h * y; AOP: sum, or maximum / minimum from the
     // zero start (an entry beyond the end contributes w = 0, neutral for all three)
     float h = aval;
@@ -451,7 +520,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv);
         } else {
@@ -473,7 +542,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
+            if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
@@ -522,7 +591,7 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
         for (int u = 0; u < U; ++u) {
 #pragma unroll
           for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
-          if (ok[u]) gather_row<YF, G, V, C, P == PAT_RUNTIME>(a, c[u], g, y[u]);
+          if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
@@ -625,7 +694,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, P == PAT_RUNTIME>(a, ch.row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, ch.row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
@@ -634,7 +703,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         for (int i = 0; i < V; ++i) stage[wave][piece_index<GW, CW>(g, i)] = z[i];
       }
       __syncthreads();
-      if (threadIdx.x < (P == PAT_RUNTIME ? a.d_pieces : D / 4)) {
+      if (threadIdx.x < (T::masked ? a.d_pieces : D / 4)) {
         v4f s = stage[0][threadIdx.x];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) {
@@ -649,6 +718,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
             s += o;
           }
         }
+        if constexpr (T::flips) s *= a.sign;  // a minimum was run as the maximum of the negated messages
         if constexpr (T::means) {
           if (a.mean && ch.part < 0) s *= 1.0f / (float)ch.e_count;  // the chunk is the whole row
         }
@@ -675,14 +745,15 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     v4f x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, P == PAT_RUNTIME>(a, row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
+      if constexpr (T::flips) scale(z, a.sign);
       if constexpr (T::means) {
         if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
       }
-      if (lane < GW) store_row<D, GW, CW, P == PAT_RUNTIME>(a, dst, g, z);
+      if (lane < GW) store_row<D, GW, CW, T::masked>(a, dst, g, z);
     }
   } else if (kind == kItemPacked) {
     // ---- one short segment per lane group ----------------------------------------------
@@ -720,7 +791,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
-        if (deg > 0) load_x<D, GP, CP, P == PAT_RUNTIME>(a, row, g, x);
+        if (deg > 0) load_x<D, GP, CP, T::masked>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
       if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
@@ -729,17 +800,18 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
       group_accumulate<P, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, use_val);
       if constexpr (T::loads_y) {
+        if constexpr (T::flips) scale(z, a.sign);
         if constexpr (T::means) {
           if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
         }
-        if (has_seg) store_row<D, GP, CP, P == PAT_RUNTIME>(a, dst, g, z);
+        if (has_seg) store_row<D, GP, CP, T::masked>(a, dst, g, z);
       }
     }
   }
   else if (kind == kItemZero) {
     // ---- rows without stored entries: z_u = 0 (Algorithm 1 initialises z_u and adds nothing) ----
     if constexpr (T::loads_y) {
-      const int kPieces = P == PAT_RUNTIME ? a.d_pieces : D / 4;
+      const int kPieces = T::masked ? a.d_pieces : D / 4;
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
       for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
         const int64_t row = rows[i / kPieces];

@@ -33,6 +33,10 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
     case PAT_TDIST: return launch_one<PAT_TDIST, YF>(a, stream);
     case PAT_FR: return launch_one<PAT_FR, YF>(a, stream);
     case PAT_RUNTIME: return launch_one<PAT_RUNTIME, YF>(a, stream);
+    case PAT_DOT: return launch_one<PAT_DOT, YF>(a, stream);
+    case PAT_DOT_MM: return launch_one<PAT_DOT_MM, YF>(a, stream);
+    case PAT_DIST: return launch_one<PAT_DIST, YF>(a, stream);
+    case PAT_DIST_MM: return launch_one<PAT_DIST_MM, YF>(a, stream);
     case PAT_VISIT:  // the edge-visit instance reads no Y: one form is enough
       if constexpr (YF == kYF32) return launch_one<PAT_VISIT, kYF32>(a, stream);
       return hipErrorInvalidValue;

@@ -10,8 +10,14 @@ namespace fmm {
 // PAT_SIGNED_SIGMOID: the sigmoid embedding pattern with the scaling step h = a_uv - sigmoid(s) (kSopValueMinusSigmoid).
 // PAT_GCN_MAX / PAT_GCN_MIN: the GCN message (h = a_uv, w = h * y_v) pooled by maximum / minimum instead of
 // summed (the pooling variants of Section III-B); mean pooling runs PAT_GCN with the division at the store.
+// PAT_DOT / PAT_DIST: two families of tuples with a scalar message, their vector loops fixed at compile time and
+// the scalar steps read at run time.  PAT_DOT: VOP = MUL, ROP = RSUM (s = x_u . y_v), any SOP on s, any MOP;
+// PAT_DIST: VOP = SUB or ADD, ROP = RSUM, SUMSQ or NORM2, any SOP, any MOP.  The plain ones accumulate by SUM
+// (MEAN divides at the store), the _MM ones by MAX or MIN (MIN as the maximum of the negated messages).  They
+// also serve the dimensions between two instance sizes for the application patterns they contain.
 enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6,
-             PAT_SIGNED_SIGMOID = 7, PAT_GCN_MAX = 8, PAT_GCN_MIN = 9 };
+             PAT_SIGNED_SIGMOID = 7, PAT_GCN_MAX = 8, PAT_GCN_MIN = 9, PAT_DOT = 10, PAT_DOT_MM = 11, PAT_DIST = 12,
+             PAT_DIST_MM = 13 };
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
@@ -58,7 +64,13 @@ struct KernelArgs {
   float* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
-  int32_t vop, rop, sop, mop, aop;  // read by the PAT_RUNTIME instance only; aop is SUM, MAX or MIN here
+  float sign;   // PAT_DOT_MM / PAT_DIST_MM: -1 when the messages are pooled by MIN (run as MAX of the negated messages), else 1
+  float ysign;  // PAT_DIST / PAT_DIST_MM: t = x_u + ysign * y_v (-1 for VOP = SUB, 1 for ADD)
+  // the families' SOP on the scalar s without a branch: u = sop_exp ? 2^(sop_c1 * s) : s;  h = sop_rcp ? 1 / (1 + u)
+  // : sop_lin * s  (sigmoid: c1 = -log2 e; its complement: +log2 e; 1/(1+s): no exponential; SCAL / NOOP: linear)
+  float sop_c1, sop_lin;
+  int32_t sop_exp, sop_rcp;
+  int32_t vop, rop, sop, mop, aop;  // read by the run-time-ops and family instances; aop is SUM, MAX or MIN here
   int32_t mean;                     // PAT_RUNTIME: a row stored whole is divided by its length (mean pooling)
   // PAT_RUNTIME: rows have this many 4-float pieces; below D/4 when a dimension between two instance
   // sizes runs on the next larger instance (pieces beyond it are neither loaded nor stored)
