@@ -75,11 +75,16 @@ constexpr int32_t kShortDimSmallRowMax = 128;
 constexpr int32_t kShortDimSplitRowMin = 2048;
 constexpr int32_t kShortDimChunkEdges = 8192;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
-// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB); the finest
-// level keeps a class slice of Y at >= 4 MiB and stops at 64 classes; a row needs 16 entries per
-// class on average for a partial row per class to be worth it.
+// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB).  The finest level
+// keeps a class slice of Y at about 64 MiB on sparse patterns -- there only the often-gathered rows of
+// a slice are reused, and they fit an L2 from that size down; finer classes only add partial rows --
+// and at about 8 MiB on dense ones (128 stored entries per row on average: every row of the slice is
+// reused many times, so the slice itself should come near an L2); it stops at 64 classes.  A row needs
+// 16 entries per class on average for a partial row per class to be worth it.
 constexpr int64_t kTilingMinYBytes = 48ll << 20;
-constexpr int64_t kTilingMinSliceBytes = 4ll << 20;
+constexpr int64_t kTilingSliceBytesSparse = 64ll << 20;
+constexpr int64_t kTilingSliceBytesDense = 8ll << 20;
+constexpr int64_t kDenseEntriesPerRow = 128;
 constexpr int32_t kAutoMaxColumnClasses = 64;
 constexpr int32_t kMaxColumnClasses = 512;
 constexpr int32_t kDefaultTileEdgesPerClass = 16;
@@ -324,13 +329,14 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     if (options->feature_dim_hint > 0) d_hint = options->feature_dim_hint;
   }
   if (n_classes == 0) {
-    // automatic: off while Y (n rows of the hinted dimension) is small; else the finest level keeps
-    // a class slice of Y at >= 4 MiB (finer slices than an L2 holds gain nothing), at most 64 classes
+    // automatic: off while Y (n rows of the hinted dimension) is small; else as many finest classes as
+    // bring a class slice of Y down to the size that pays for the pattern's density, at most 64
     const int64_t y_bytes = n * (int64_t)d_hint * (int64_t)sizeof(float);
     n_classes = 1;
     if (y_bytes >= kTilingMinYBytes) {
       n_classes = kNumXcd;
-      while (n_classes < kAutoMaxColumnClasses && y_bytes / (2 * n_classes) >= kTilingMinSliceBytes) n_classes *= 2;
+      const int64_t slice = (m > 0 && nnz / m >= kDenseEntriesPerRow) ? kTilingSliceBytesDense : kTilingSliceBytesSparse;
+      while (n_classes < kAutoMaxColumnClasses && y_bytes / n_classes > slice) n_classes *= 2;
     }
   }
   if (n_classes > 1) {  // levels are nested: 8, 16, 32, ... classes
