@@ -317,19 +317,40 @@ hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n,
   return hipGetLastError();
 }
 
+// hist[b] += 1 for every `stride`-th stored entry, b the bucket of its column (column * n_buckets / n): where
+// the stored entries lie along the column range, for class boundaries that balance them.
+__global__ __launch_bounds__(256) void column_histogram_kernel(const int32_t* colidx, int64_t nnz, int64_t stride, int64_t n,
+                                                               int32_t n_buckets, uint32_t* hist) {
+  const int64_t samples = (nnz + stride - 1) / stride;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < samples; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t c = colidx[i * stride];
+    atomicAdd(hist + (int32_t)(c * n_buckets / n), 1u);
+  }
+}
+
+hipError_t launch_column_histogram(const int32_t* colidx, int64_t nnz, int64_t stride, int64_t n, int32_t n_buckets,
+                                   uint32_t* hist, hipStream_t stream) {
+  if (nnz <= 0) return hipSuccess;
+  const int64_t samples = (nnz + stride - 1) / stride;
+  int64_t blocks = (samples + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(column_histogram_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, colidx, nnz, stride, n, n_buckets, hist);
+  return hipGetLastError();
+}
+
 // One wavefront per tiled row: is the row sorted by column, and where does each of its column
 // classes start?  A row of level L has L classes, each n_classes / L finest classes wide.
 __global__ __launch_bounds__(kBlockThreads) void tile_bounds_kernel(const int64_t* rowptr, const int32_t* colidx,
                                                                     const int32_t* rows, const int32_t* level,
                                                                     const int64_t* out_off, int32_t n_rows,
-                                                                    int32_t n_classes, int64_t class_width,
+                                                                    int32_t n_classes, const int32_t* class_start,
                                                                     int32_t* bounds, int32_t* unsorted) {
   const int lane = threadIdx.x & 63;
   const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   if (w >= n_rows) return;
   const int32_t row = rows[w];
   const int32_t L = level[w];
-  const int64_t width = class_width * (n_classes / L);
+  const int stride = n_classes / L;  // finest classes per class of this row
   const int64_t e0 = rowptr[row];
   const int64_t len = rowptr[row + 1] - e0;
   bool bad = false;
@@ -337,7 +358,7 @@ __global__ __launch_bounds__(kBlockThreads) void tile_bounds_kernel(const int64_
   if (bad) atomicOr(unsorted, 1);
   int32_t* out = bounds + out_off[w];
   for (int c = lane; c <= L; c += 64) {
-    const int64_t target = (int64_t)c * width;  // first column id of class c
+    const int64_t target = class_start[c * stride];  // first column id of class c
     int64_t lo = 0, hi = len;
     while (lo < hi) {
       const int64_t mid = (lo + hi) >> 1;
@@ -348,12 +369,12 @@ __global__ __launch_bounds__(kBlockThreads) void tile_bounds_kernel(const int64_
 }
 
 hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, const int32_t* level,
-                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, int64_t class_width,
+                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, const int32_t* class_start,
                               int32_t* bounds, int32_t* unsorted, hipStream_t stream) {
   if (n_rows <= 0) return hipSuccess;
   const int blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
   hipLaunchKernelGGL(tile_bounds_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream, rowptr, colidx, rows,
-                     level, out_off, n_rows, n_classes, class_width, bounds, unsorted);
+                     level, out_off, n_rows, n_classes, class_start, bounds, unsorted);
   return hipGetLastError();
 }
 

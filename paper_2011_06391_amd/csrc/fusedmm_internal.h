@@ -89,11 +89,12 @@ struct KernelArgs {
 };
 
 // Column-class boundaries of the tiled rows.  Row rows[i] is cut into level[i] classes, each
-// n_classes / level[i] finest classes (class_width columns) wide; bounds[out_off[i] + c] = offset
+// n_classes / level[i] finest classes wide (finest class k = columns class_start[k] .. class_start[k + 1] - 1,
+// class_start holding n_classes + 1 entries on the device); bounds[out_off[i] + c] = offset
 // within the row of the first stored entry whose column is in class c or later (c = 0..level[i]).
 // unsorted[0] is set if any of those rows has decreasing column indices.
 hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, const int32_t* rows, const int32_t* level,
-                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, int64_t class_width,
+                              const int64_t* out_off, int32_t n_rows, int32_t n_classes, const int32_t* class_start,
                               int32_t* bounds, int32_t* unsorted, hipStream_t stream);
 
 // Rows per workgroup in the packed range for dimension d and storage format of Y (host needs it for the grid).
@@ -161,6 +162,10 @@ hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream);
 // d: row width; pstride: distance in floats between partial rows (>= d)
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
                         int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
+
+// Where the stored entries lie along the column range: hist[column * n_buckets / n] += 1 for every stride-th entry.
+hipError_t launch_column_histogram(const int32_t* colidx, int64_t nnz, int64_t stride, int64_t n, int32_t n_buckets,
+                                   uint32_t* hist, hipStream_t stream);
 
 // flag[0] |= 1 if any colidx entry is outside [0, n).
 hipError_t launch_validate_colidx(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag, hipStream_t stream);
