@@ -1,7 +1,7 @@
 """Every valid op tuple of the selector (4 VOP x 26 valid ROP/SOP pairs x 3 MOP x 4 AOP = 1248) against the
 oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
-(32, 128), one between instance sizes (20, masked) and those only the general kernel takes (6 and seven
-more, one per instance of that kernel), and with Y
+(32, 128), one between instance sizes (20, masked), two of the one-lane-per-entry kernels (2, 3) and those only
+the general kernel takes (6, 13, 27, 97, 301, 700: its lane-group widths and register counts), and with Y
 stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128).  A dispatch slip -- a tuple
 recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
 import itertools
