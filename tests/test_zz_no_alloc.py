@@ -58,8 +58,11 @@ def test_two_calls_in_a_row_second_one_smaller(B):
     big = one_case(B, 13, (1 << 12) * 16, 128, "tdist", 601)
     small = one_case(B, 10, (1 << 9) * 16, 64, "one_minus_sigmoid", 602)
     assert small["partials"] < big["partials"]
-    # and once more through the general kernel (d not a multiple of 4), whose segments use the same array
+    # and once more through the general kernel (d not a multiple of 4), whose segments use the same array,
+    # and through the one-lane-per-entry kernels (partial rows 16 floats apart)
     one_case(B, 11, (1 << 10) * 16, 50, "fr", 603)
+    one_case(B, 11, (1 << 10) * 16, 3, "fr", 604)
+    one_case(B, 12, (1 << 11) * 16, 16, "sigmoid", 605)
 
 
 def test_sizes_beyond_the_static_scratch_are_refused(B):
