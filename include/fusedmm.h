@@ -258,19 +258,24 @@ int fusedmm_execute_f16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t
 int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream);
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
- * values are fp64 and so is every step's arithmetic.  Runs the general kernel (one wavefront per
- * row or 256-entry segment, any 1 <= d <= FUSEDMM_MAX_D, any valid op tuple, any alignment); the
- * specialised schedule is fp32 only.  Arguments, layout, ownership and errors as for
- * fusedmm_execute; ops->alpha is widened.  Patterns with rows longer than 256 entries need
- * fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise). */
+ * values are fp64 and so is every step's arithmetic (the sigmoid's exponential, reciprocals and square
+ * roots are the correctly rounded library ones, not the fp32 hardware approximations).  Multiples of 4
+ * up to d = 256 with 32-byte aligned X, Y, Z and leading dimensions that are multiples of 4 run the
+ * specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256; a dimension
+ * in between runs on the next larger one); everything else -- any 1 <= d <= FUSEDMM_MAX_D, any alignment
+ * -- runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
+ * way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan
+ * with split rows needs fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise):
+ * fusedmm_plan_create reserves for fp32 rows only. */
 int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
                         const double* d_values, const double* d_X, int64_t ldx,
                         const double* d_Y, int64_t ldy, double* d_Z, int64_t ldz, void* stream);
 
 /* Test hook: run the same schedule and edge indexing as fusedmm_execute would
  * for dimension d (row pointers may be of any alignment class: pass
- * fast_path != 0 to exercise the specialised kernels' indexing, 0 for the
- * general kernel's) and add 1 to d_counts[e] for every stored entry e visited.
+ * fast_path = 1 to exercise the specialised kernels' indexing, 2 for that of their
+ * double-precision instances, 0 for the general kernel's) and add 1 to d_counts[e]
+ * for every stored entry e visited.
  * d_counts: device, nnz uint32, zeroed by the caller.  Correct schedules leave
  * every count equal to 1. */
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path,

@@ -270,7 +270,8 @@ def fusedmm_to_f16(d_dst, d_src, count: int, stream=None) -> None:
     _check(load().fusedmm_to_f16(_dptr(d_dst), _dptr(d_src), count, _stream(stream)), "fusedmm_to_f16")
 
 
-def fusedmm_debug_edge_visits(plan, d: int, fast_path: bool, d_counts, stream=None) -> None:
+def fusedmm_debug_edge_visits(plan, d: int, fast_path, d_counts, stream=None) -> None:
+    """fast_path: False / 0 the general kernel, True / 1 the specialised kernels, 2 their fp64 instances."""
     st = load().fusedmm_debug_edge_visits(plan, d, int(fast_path), _dptr(d_counts), _stream(stream))
     _check(st, "fusedmm_debug_edge_visits")
 
@@ -432,7 +433,7 @@ class Plan:
         fusedmm_execute_f16y(self._plan, ops, int(Z.shape[1]), values, X, ldx, Y_f16, Y_f16.stride(0), Z, Z.stride(0),
                              stream)
 
-    def edge_visits(self, d: int, fast_path: bool, counts, stream=None) -> None:
+    def edge_visits(self, d: int, fast_path, counts, stream=None) -> None:
         fusedmm_debug_edge_visits(self._plan, d, fast_path, counts, stream)
 
     def reserve(self, d: int) -> None:

@@ -25,6 +25,10 @@ SOURCES = [
     "fusedmm_fast_d128.hip",
     "fusedmm_fast_d256.hip",
     "fusedmm_fast_d512.hip",
+    "fusedmm_fast_f64_d32.hip",
+    "fusedmm_fast_f64_d64.hip",
+    "fusedmm_fast_f64_d128.hip",
+    "fusedmm_fast_f64_d256.hip",
 ]
 
 # packed FP32 instructions are switched off for all device code

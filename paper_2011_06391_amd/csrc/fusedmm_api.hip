@@ -106,6 +106,20 @@ int32_t instance_dim(int32_t d) {
   return D;
 }
 
+// The same for double precision: instances of 32, 64, 128 and 256 elements.
+int32_t instance_dim_f64(int32_t d) {
+  const int32_t D = instance_dim(d);
+  return D > 256 ? 0 : D;
+}
+
+// How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
+// fp32 (the largest instance size among them, and the short-vector kernels' fixed stride) ...
+int32_t partial_floats_f32(int32_t d) {
+  return std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
+}
+// ... and in fp64 (two floats per element; nothing above 256 runs on the specialised schedule)
+int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 256 ? 256 : instance_dim_f64(d / 4 * 4)); }
+
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value
     return o.vop >= FUSEDMM_VOP_MUL && o.vop <= FUSEDMM_VOP_ADD && o.rop > FUSEDMM_ROP_NOOP && o.rop <= FUSEDMM_ROP_RMUL &&
@@ -154,6 +168,7 @@ int recognise_family(const fusedmm_ops_t& o) {
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned32(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 31u) == 0; }
 
 bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int64_t rows_b, int64_t ld_b, int32_t d) {
   if (!a || !b || rows_a <= 0 || rows_b <= 0) return false;
@@ -258,8 +273,22 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelAr
   a->nb_zero = (p->n_empty + kZeroRowsPerBlock - 1) / kZeroRowsPerBlock;
   a->nb_chunk = p->n_chunks;
   a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int rpb = is_small_dim(d) ? small_packed_rows_per_block(d) : packed_rows_per_block(d, y_format);
+  const int rpb = (is_small_dim(d) && y_format != kYF64) ? small_packed_rows_per_block(d) : packed_rows_per_block(d, y_format);
   a->nb_packed = rpb > 0 ? (p->n_packed + rpb - 1) / rpb : 0;
+}
+
+// what the specialised kernels read of the op tuple
+void fill_op_args(const fusedmm_ops_t& ops, KernelArgs* a) {
+  a->alpha = ops.alpha;
+  a->sign = ops.aop == FUSEDMM_AOP_MIN ? -1.0f : 1.0f;
+  a->ysign = ops.vop == FUSEDMM_VOP_SUB ? -1.0f : 1.0f;
+  a->sop_exp = ops.sop == FUSEDMM_SOP_SIGMOID || ops.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID || ops.sop == kSopValueMinusSigmoid;
+  a->sop_c1 = ops.sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID ? 1.4426950408889634f : -1.4426950408889634f;
+  a->sop_rcp = a->sop_exp || ops.sop == FUSEDMM_SOP_INV_1P;
+  a->sop_lin = ops.sop == FUSEDMM_SOP_SCAL ? ops.alpha : 1.0f;
+  a->vop = ops.vop; a->rop = ops.rop; a->sop = ops.sop; a->mop = ops.mop;
+  a->mean = ops.aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
+  a->aop = a->mean ? FUSEDMM_AOP_SUM : ops.aop;
 }
 
 }  // namespace
@@ -694,8 +723,7 @@ int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   // every dimension <= d: the largest instance size one of them runs on, and the general kernel's rows of d elements
-  const int32_t D = std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
-  int st = ensure_partials(plan, D);
+  int st = ensure_partials(plan, partial_floats_f32(d));
   if (st == FUSEDMM_OK) st = ensure_gen_partials(plan, d, sizeof(float));
   return st;
 }
@@ -703,7 +731,9 @@ int fusedmm_plan_reserve(fusedmm_plan_t* plan, int32_t d) {
 int fusedmm_plan_reserve_f64(fusedmm_plan_t* plan, int32_t d) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  return ensure_gen_partials(plan, d, sizeof(double));
+  int st = ensure_partials(plan, partial_floats_f64(d));
+  if (st == FUSEDMM_OK) st = ensure_gen_partials(plan, d, sizeof(double));
+  return st;
 }
 
 int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* out) {
@@ -714,8 +744,7 @@ int fusedmm_plan_workspace_bytes(const fusedmm_plan_t* plan, int32_t d, size_t* 
              (size_t)plan->n_tile_descs * sizeof(ChunkDesc);
   b += (size_t)plan->n_gen_segs * sizeof(ChunkDesc) + (size_t)plan->n_gen_merges * sizeof(MergeDesc);
   // what the plan holds once fusedmm_plan_reserve(plan, d) has run: partial rows of both kernels
-  const int32_t D = std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
-  b += (size_t)plan->n_parts * (size_t)std::max(D, plan->partials_d) * sizeof(float);
+  b += (size_t)plan->n_parts * (size_t)std::max(partial_floats_f32(d), plan->partials_d) * sizeof(float);
   b += std::max((size_t)plan->n_gen_segs * (size_t)d * sizeof(float), plan->gen_partials_bytes);
   *out = b;
   return FUSEDMM_OK;
@@ -833,16 +862,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     a.d_pieces = d / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
-    a.alpha = ops->alpha;
-    a.sign = ops->aop == FUSEDMM_AOP_MIN ? -1.0f : 1.0f;
-    a.ysign = ops->vop == FUSEDMM_VOP_SUB ? -1.0f : 1.0f;
-    a.sop_exp = ops->sop == FUSEDMM_SOP_SIGMOID || ops->sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID || ops->sop == kSopValueMinusSigmoid;
-    a.sop_c1 = ops->sop == FUSEDMM_SOP_ONE_MINUS_SIGMOID ? 1.4426950408889634f : -1.4426950408889634f;
-    a.sop_rcp = a.sop_exp || ops->sop == FUSEDMM_SOP_INV_1P;
-    a.sop_lin = ops->sop == FUSEDMM_SOP_SCAL ? ops->alpha : 1.0f;
-    a.vop = ops->vop; a.rop = ops->rop; a.sop = ops->sop; a.mop = ops->mop;
-    a.mean = ops->aop == FUSEDMM_AOP_MEAN;  // accumulated as a sum; whole rows are scaled at the store, split rows in the merge
-    a.aop = a.mean ? FUSEDMM_AOP_SUM : ops->aop;
+    fill_op_args(*ops, &a);
     if (ev0) (void)hipEventRecord(ev0, stream);
     e = launch_fast(pattern, D, y_format, a, stream);
     if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
@@ -945,6 +965,31 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     o1 = o0 + (uintptr_t)plan->nnz * sizeof(double);
     if (z0 < o1 && o0 < z1) return FUSEDMM_ERR_ALIAS;
   }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  // the specialised schedule in double precision: the same dispatch as fp32 (a recognised pattern at an instance
+  // size, else its tuple family, else the ops at run time) on row registers of four doubles
+  const int32_t D = instance_dim_f64(d);
+  const bool fast = D != 0 && ldy < (int64_t(1) << 28) && aligned32(d_Z) && ldz % 4 == 0 &&
+                    (plan->nnz == 0 || (aligned32(d_Y) && ldy % 4 == 0)) && (!uses_x || (aligned32(d_X) && ldx % 4 == 0));
+  if (fast) {
+    if (plan->n_parts > 0 && 2 * D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
+    const int recognised = recognise(*ops);
+    const int family = recognise_family(*ops);
+    const int pattern = (recognised >= 0 && D == d) ? recognised : (family >= 0 ? family : PAT_RUNTIME);
+    KernelArgs a;
+    fill_schedule_args(plan, D, kYF64, &a);
+    fill_op_args(*ops, &a);
+    a.d_pieces = d / 4;
+    // the pointers travel under their fp32 names; the double-precision instances read them as doubles
+    a.values = reinterpret_cast<const float*>(d_values); a.X = reinterpret_cast<const float*>(d_X); a.Y = d_Y;
+    a.Z = reinterpret_cast<float*>(d_Z);
+    a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
+    hipError_t e = launch_fast(pattern, D, kYF64, a, stream);
+    if (e == hipSuccess)
+      e = launch_merge(plan->d_merges, plan->n_merges, reinterpret_cast<const double*>(plan->d_partials), d, D, ops->aop,
+                       plan->d_rowptr, d_Z, ldz, stream);
+    return e == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+  }
   GenericArgsT<double> g;
   g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx; g.values = d_values;
   g.X = d_X; g.Y = d_Y; g.Z = d_Z;
@@ -955,7 +1000,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
   g.visit_counts = nullptr;
   if ((size_t)plan->n_gen_segs * (size_t)d * sizeof(double) > plan->gen_partials_bytes) return FUSEDMM_ERR_NOT_RESERVED;
   fill_generic_segments(plan, &g);
-  return launch_generic(g, static_cast<hipStream_t>(stream_)) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
+  return launch_generic(g, stream) == hipSuccess ? FUSEDMM_OK : FUSEDMM_ERR_HIP;
 }
 
 int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stream_) {
@@ -972,22 +1017,26 @@ int fusedmm_to_bf16(uint16_t* d_dst, const float* d_src, size_t count, void* str
 int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path, uint32_t* d_counts, void* stream_) {
   if (!plan) return FUSEDMM_ERR_INVALID_ARG;
   if (d < 1 || d > FUSEDMM_MAX_D) return FUSEDMM_ERR_UNSUPPORTED_DIM;
-  if (fast_path && !instance_dim(d) && !is_small_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (fast_path < 0 || fast_path > 2) return FUSEDMM_ERR_INVALID_ARG;
+  if (fast_path == 1 && !instance_dim(d) && !is_small_dim(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (fast_path == 2 && !instance_dim_f64(d)) return FUSEDMM_ERR_UNSUPPORTED_DIM;
   if (plan->m == 0 || plan->nnz == 0) return FUSEDMM_OK;
   if (!d_counts) return FUSEDMM_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   hipError_t e;
   if (fast_path) {
     KernelArgs a;
-    const int32_t D = is_small_dim(d) ? 0 : instance_dim(d);  // 0: the kernels for very short feature vectors
-    fill_schedule_args(plan, D ? D : d, kYF32, &a);
+    const int fmt = fast_path == 2 ? kYF64 : kYF32;
+    const int32_t D = fast_path == 2 ? instance_dim_f64(d)
+                                     : (is_small_dim(d) ? 0 : instance_dim(d));  // 0: the kernels for very short feature vectors
+    fill_schedule_args(plan, D ? D : d, fmt, &a);
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.d_pieces = d / 4;
     a.visit_counts = d_counts;
-    e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(PAT_VISIT, D, kYF32, a, stream);
+    e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(PAT_VISIT, D, fmt, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;

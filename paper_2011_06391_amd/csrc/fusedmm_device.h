@@ -18,7 +18,36 @@
 
 namespace fmm {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
+// The element type of X, Y, Z, the edge values and all arithmetic: float, or double when a translation unit
+// defines FMM_F64 before including this header (the instances behind fusedmm_execute_f64).  A row register
+// then holds four doubles (32 bytes, two 16-byte loads); everything else is the same code.
+#ifdef FMM_F64
+typedef double real;
+#else
+typedef float real;
+#endif
+typedef real vec4 __attribute__((ext_vector_type(4)));
+
+// the typed views of the untyped-by-precision pointers of KernelArgs
+__device__ __forceinline__ const real* values_of(const KernelArgs& a) { return reinterpret_cast<const real*>(a.values); }
+__device__ __forceinline__ const real* X_of(const KernelArgs& a) { return reinterpret_cast<const real*>(a.X); }
+__device__ __forceinline__ real* Z_of(const KernelArgs& a) { return reinterpret_cast<real*>(a.Z); }
+__device__ __forceinline__ real* partials_of(const KernelArgs& a) { return reinterpret_cast<real*>(a.partials); }
+
+// hardware approximations in fp32 (1 ulp), library routines in fp64
+__device__ __forceinline__ float rcp_(float v) { return __builtin_amdgcn_rcpf(v); }
+__device__ __forceinline__ double rcp_(double v) { return 1.0 / v; }
+__device__ __forceinline__ float exp2_(float v) { return __builtin_amdgcn_exp2f(v); }
+__device__ __forceinline__ double exp2_(double v) { return exp2(v); }
+__device__ __forceinline__ float sqrt_(float v) { return __builtin_amdgcn_sqrtf(v); }
+__device__ __forceinline__ double sqrt_(double v) { return sqrt(v); }
+__device__ __forceinline__ float fma_(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float max_(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ double max_(double a, double b) { return fmax(a, b); }
+__device__ __forceinline__ float min_(float a, float b) { return fminf(a, b); }
+__device__ __forceinline__ double min_(double a, double b) { return fmin(a, b); }
+constexpr real kLog2e = (real)1.4426950408889634;
 
 // ---------------------------------------------------------------------------------------
 // cross-lane helpers
@@ -28,7 +57,27 @@ __device__ __forceinline__ float dpp_mov(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v) {  // the two halves move separately
+  const uint64_t u = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xF, 0xF, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
 // value of lane (lane ^ MASK); MASK a power of two
+template <int MASK>
+__device__ __forceinline__ double lane_xor(double v) {
+  if constexpr (MASK == 1) return dpp_mov<0xB1>(v);
+  else if constexpr (MASK == 2) return dpp_mov<0x4E>(v);
+  else if constexpr (MASK == 8) return dpp_mov<0x128>(v);
+  else if constexpr (MASK == 16) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)u, 0x401F);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)(u >> 32), 0x401F);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+  } else return __shfl_xor(v, MASK);
+}
 template <int MASK>
 __device__ __forceinline__ float lane_xor(float v) {
   if constexpr (MASK == 1) return dpp_mov<0xB1>(v);        // quad_perm [1,0,3,2]
@@ -41,7 +90,7 @@ __device__ __forceinline__ float lane_xor(float v) {
 
 // Sum over each aligned group of G lanes, result in every lane of the group.
 template <int G>
-__device__ __forceinline__ float group_allreduce(float v) {
+__device__ __forceinline__ real group_allreduce(real v) {
   static_assert(G == 8 || G == 16 || G == 32 || G == 64, "lane group size");
   v += dpp_mov<0xB1>(v);                      // lanes ^1
   v += dpp_mov<0x4E>(v);                      // lanes ^2   -> quad sums
@@ -54,7 +103,7 @@ __device__ __forceinline__ float group_allreduce(float v) {
 
 // Product over each aligned group of G lanes (ROP = RMUL), result in every lane of the group.
 template <int G>
-__device__ __forceinline__ float group_allreduce_mul(float v) {
+__device__ __forceinline__ real group_allreduce_mul(real v) {
   v *= dpp_mov<0xB1>(v);
   v *= dpp_mov<0x4E>(v);
   v *= dpp_mov<0x141>(v);
@@ -64,9 +113,9 @@ __device__ __forceinline__ float group_allreduce_mul(float v) {
   return v;
 }
 
-// AOP on two floats: SUM, MAX or MIN (aop is wave-uniform).
-__device__ __forceinline__ float aop_apply(int aop, float z, float w) {
-  return aop == FUSEDMM_AOP_SUM ? z + w : (aop == FUSEDMM_AOP_MAX ? fmaxf(z, w) : fminf(z, w));
+// AOP on two values: SUM, MAX or MIN (aop is wave-uniform).
+__device__ __forceinline__ real aop_apply(int aop, real z, real w) {
+  return aop == FUSEDMM_AOP_SUM ? z + w : (aop == FUSEDMM_AOP_MAX ? max_(z, w) : min_(z, w));
 }
 
 // What a compile-time pattern fixes (PAT_RUNTIME decides the same things from the launch arguments).
@@ -89,7 +138,7 @@ struct PatTraits {
 };
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
-__device__ __forceinline__ float cross_group_allreduce(float v) {
+__device__ __forceinline__ real cross_group_allreduce(real v) {
   if constexpr (G <= 8) v += lane_xor<8>(v);
   if constexpr (G <= 16) v += lane_xor<16>(v);
   if constexpr (G <= 32) v += lane_xor<32>(v);
@@ -98,7 +147,7 @@ __device__ __forceinline__ float cross_group_allreduce(float v) {
 
 // The same across-group combination with a run-time AOP.
 template <int G>
-__device__ __forceinline__ float cross_group_allreduce_aop(int aop, float v) {
+__device__ __forceinline__ real cross_group_allreduce_aop(int aop, real v) {
   if constexpr (G <= 8) v = aop_apply(aop, v, lane_xor<8>(v));
   if constexpr (G <= 16) v = aop_apply(aop, v, lane_xor<16>(v));
   if constexpr (G <= 32) v = aop_apply(aop, v, lane_xor<32>(v));
@@ -106,7 +155,7 @@ __device__ __forceinline__ float cross_group_allreduce_aop(int aop, float v) {
 }
 
 template <int P, int G, int V>
-__device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V]) {
+__device__ __forceinline__ void combine_groups(const KernelArgs& a, vec4 (&z)[V]) {
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     if constexpr (P == PAT_RUNTIME) {
@@ -128,7 +177,7 @@ __device__ __forceinline__ void combine_groups(const KernelArgs& a, v4f (&z)[V])
   }
 }
 
-__device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+__device__ __forceinline__ vec4 ld4(const real* p) { return *reinterpret_cast<const vec4*>(p); }
 
 // Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YF = kYF32: Y is fp32, one
 // 16-byte load.  YF = kYBf16: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
@@ -137,20 +186,20 @@ __device__ __forceinline__ v4f ld4(const float* p) { return *reinterpret_cast<co
 // The address is one 32 x 32 -> 64-bit multiply-add: column index (validated, non-negative) times
 // the row pitch in bytes (below 2^32, checked by the host) plus the lane's own base.
 template <int YF>
-__device__ __forceinline__ v4f gather4(const void* Y, int col, int64_t ldy, int piece) {
-  const uint32_t pitch = (uint32_t)ldy * (YF == kYF32 ? 4u : 2u);
-  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YF == kYF32 ? 16u : 8u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+__device__ __forceinline__ vec4 gather4(const void* Y, int col, int64_t ldy, int piece) {
+  const uint32_t pitch = (uint32_t)ldy * (YF == kYF32 ? (uint32_t)sizeof(real) : 2u);
+  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YF == kYF32 ? (uint32_t)sizeof(vec4) : 8u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
   if constexpr (YF == kYBf16) {
     typedef unsigned int v2u __attribute__((ext_vector_type(2)));
     const v2u raw = *reinterpret_cast<const v2u*>(p);
-    return v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
+    return vec4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
                __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
   } else if constexpr (YF == kYF16) {
     typedef _Float16 v4h __attribute__((ext_vector_type(4)));
     const v4h raw = *reinterpret_cast<const v4h*>(p);
-    return v4f{(float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w};
+    return vec4{(float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w};
   } else {
-    return *reinterpret_cast<const v4f*>(p);
+    return *reinterpret_cast<const vec4*>(p);
   }
 }
 
@@ -168,12 +217,12 @@ __device__ __forceinline__ int piece_index(int g, int i) {
 // M: pieces at or beyond a.d_pieces are left at zero instead of being loaded (the run-time-ops instance
 // on a dimension below its own).
 template <int YF, int G, int V, int C, bool M>
-__device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, v4f (&y)[V]) {
+__device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, vec4 (&y)[V]) {
   if constexpr (C == 1) {
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       if (!M || g + G * i < a.d_pieces) y[i] = gather4<YF>(a.Y, col, a.ldy, g + G * i);
-      else y[i] = v4f{0.f, 0.f, 0.f, 0.f};
+      else y[i] = vec4{0.f, 0.f, 0.f, 0.f};
     }
   } else {
     static_assert(YF != kYF32 && V % 2 == 0, "16-byte chunks of 2-byte elements");
@@ -182,22 +231,22 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
 #pragma unroll
     for (int j = 0; j < V / 2; ++j) {
       if (M && 2 * (g + G * j) + 1 >= a.d_pieces) {
-        y[2 * j] = y[2 * j + 1] = v4f{0.f, 0.f, 0.f, 0.f};
+        y[2 * j] = y[2 * j + 1] = vec4{0.f, 0.f, 0.f, 0.f};
         continue;
       }
       const char* p = base + (size_t)(g + G * j) * 16u;
       if constexpr (YF == kYBf16) {
         typedef unsigned int v4u __attribute__((ext_vector_type(4)));
         const v4u raw = *reinterpret_cast<const v4u*>(p);
-        y[2 * j] = v4f{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
+        y[2 * j] = vec4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
                        __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
-        y[2 * j + 1] = v4f{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xffff0000u),
+        y[2 * j + 1] = vec4{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xffff0000u),
                            __builtin_bit_cast(float, raw.w << 16), __builtin_bit_cast(float, raw.w & 0xffff0000u)};
       } else {
         typedef _Float16 v8h __attribute__((ext_vector_type(8)));
         const v8h raw = *reinterpret_cast<const v8h*>(p);
-        y[2 * j] = v4f{(float)raw.s0, (float)raw.s1, (float)raw.s2, (float)raw.s3};
-        y[2 * j + 1] = v4f{(float)raw.s4, (float)raw.s5, (float)raw.s6, (float)raw.s7};
+        y[2 * j] = vec4{(float)raw.s0, (float)raw.s1, (float)raw.s2, (float)raw.s3};
+        y[2 * j + 1] = vec4{(float)raw.s4, (float)raw.s5, (float)raw.s6, (float)raw.s7};
       }
     }
   }
@@ -209,7 +258,7 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
 // the plan from the entry counts of the columns) raised the L2 hit rate by 3.5 points and cost 15-100 %.
 template <class T>
 __device__ __forceinline__ T ld_stream(const T* p) { return *p; }
-__device__ __forceinline__ v4f ld4_stream(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+__device__ __forceinline__ vec4 ld4_stream(const real* p) { return *reinterpret_cast<const vec4*>(p); }
 
 // ---------------------------------------------------------------------------------------
 // per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
@@ -226,7 +275,7 @@ __device__ __forceinline__ bool reads_values(const KernelArgs& a) {
   else return PatTraits<P>::uses_val;
 }
 
-__device__ __forceinline__ float rt_vop(int vop, float x, float y) {
+__device__ __forceinline__ real rt_vop(int vop, real x, real y) {
   switch (vop) {
     case FUSEDMM_VOP_MUL: return x * y;
     case FUSEDMM_VOP_SEL2ND: return y;
@@ -234,26 +283,33 @@ __device__ __forceinline__ float rt_vop(int vop, float x, float y) {
     default: return x + y;
   }
 }
-__device__ __forceinline__ float rt_sop(int sop, float s, float alpha) {
-  constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ real rt_sop(int sop, real s, real alpha) {
   switch (sop) {
-    case FUSEDMM_SOP_SIGMOID: return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-s * kLog2e));
-    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * kLog2e));
-    case FUSEDMM_SOP_INV_1P: return __builtin_amdgcn_rcpf(1.0f + s);
+    case FUSEDMM_SOP_SIGMOID: return rcp_(1.0f + exp2_(-s * kLog2e));
+    case FUSEDMM_SOP_ONE_MINUS_SIGMOID: return rcp_(1.0f + exp2_(s * kLog2e));
+    case FUSEDMM_SOP_INV_1P: return rcp_(1.0f + s);
     case FUSEDMM_SOP_SCAL: return alpha * s;
     default: return s;
   }
 }
 
+// the scale of the families' exponent, +-log2 e, in the element type's own precision
+__device__ __forceinline__ real sop_scale(const KernelArgs& a) {
+#ifdef FMM_F64
+  return a.sop_c1 < 0.f ? -kLog2e : kLog2e;
+#else
+  return a.sop_c1;
+#endif
+}
+
 template <int P, int G, int V, bool CHECK>
-__device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V], float aval, const KernelArgs& a,
-                                            bool valid, v4f (&z)[V], int nv = V) {
-  constexpr float kLog2e = 1.4426950408889634f;
-  const float alpha = a.alpha;
+__device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[V], real aval, const KernelArgs& a,
+                                            bool valid, vec4 (&z)[V], int nv = V) {
+  const real alpha = a.alpha;
   if constexpr (P == PAT_RUNTIME) {
     // Every op of the selector, the five steps in order.  The selectors are wave-uniform, so each
     // step is one scalar branch around a loop over this lane's elements, not a choice per element.
-    v4f t[V];
+    vec4 t[V];
     switch (a.vop) {  // VOP
       case FUSEDMM_VOP_MUL:
 #pragma unroll
@@ -272,29 +328,29 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
         for (int i = 0; i < V; ++i) t[i] = x[i] + y[i];
     }
     const bool scalar_h = a.sop == FUSEDMM_SOP_EDGE_VALUE || a.rop != FUSEDMM_ROP_NOOP;
-    float h = aval;
+    real h = aval;
     if (a.sop != FUSEDMM_SOP_EDGE_VALUE && a.rop != FUSEDMM_ROP_NOOP) {  // ROP, then SOP on the scalar
-      float s;
+      real s;
       if (a.rop == FUSEDMM_ROP_RMUL) {
-        float p = 1.f;  // registers beyond the row's width hold padding, not factors
+        real p = 1.f;  // registers beyond the row's width hold padding, not factors
 #pragma unroll
         for (int i = 0; i < V; ++i) p *= i < nv ? t[i].x * t[i].y * t[i].z * t[i].w : 1.f;
         s = group_allreduce_mul<G>(p);
       } else if (a.rop == FUSEDMM_ROP_RSUM) {
-        float p = 0.f;
+        real p = 0.f;
 #pragma unroll
         for (int i = 0; i < V; ++i) p += (t[i].x + t[i].y) + (t[i].z + t[i].w);
         s = group_allreduce<G>(p);
       } else {
-        float p = 0.f;
+        real p = 0.f;
 #pragma unroll
         for (int i = 0; i < V; ++i) p += (t[i].x * t[i].x + t[i].y * t[i].y) + (t[i].z * t[i].z + t[i].w * t[i].w);
         s = group_allreduce<G>(p);
-        if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
+        if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_(s);
       }
       h = a.sop == kSopValueMinusSigmoid ? aval - rt_sop(FUSEDMM_SOP_SIGMOID, s, alpha) : rt_sop(a.sop, s, alpha);
     }
-    v4f w[V];
+    vec4 w[V];
     if (scalar_h) {  // MOP with a scalar message
       if (a.mop == FUSEDMM_MOP_SEL2ND) {
 #pragma unroll
@@ -307,24 +363,24 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
         for (int i = 0; i < V; ++i) w[i] = h * t[i];
       }
     } else {  // vector message: SOP on every element of t, then MOP element by element
-      v4f hv[V];
+      vec4 hv[V];
       switch (a.sop) {
         case FUSEDMM_SOP_SIGMOID:
 #pragma unroll
           for (int i = 0; i < V; ++i)
-            hv[i] = v4f{rt_sop(FUSEDMM_SOP_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_SIGMOID, t[i].y, alpha),
+            hv[i] = vec4{rt_sop(FUSEDMM_SOP_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_SIGMOID, t[i].y, alpha),
                         rt_sop(FUSEDMM_SOP_SIGMOID, t[i].z, alpha), rt_sop(FUSEDMM_SOP_SIGMOID, t[i].w, alpha)};
           break;
         case FUSEDMM_SOP_ONE_MINUS_SIGMOID:
 #pragma unroll
           for (int i = 0; i < V; ++i)
-            hv[i] = v4f{rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].y, alpha),
+            hv[i] = vec4{rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].x, alpha), rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].y, alpha),
                         rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].z, alpha), rt_sop(FUSEDMM_SOP_ONE_MINUS_SIGMOID, t[i].w, alpha)};
           break;
         case FUSEDMM_SOP_INV_1P:
 #pragma unroll
           for (int i = 0; i < V; ++i)
-            hv[i] = v4f{rt_sop(FUSEDMM_SOP_INV_1P, t[i].x, alpha), rt_sop(FUSEDMM_SOP_INV_1P, t[i].y, alpha),
+            hv[i] = vec4{rt_sop(FUSEDMM_SOP_INV_1P, t[i].x, alpha), rt_sop(FUSEDMM_SOP_INV_1P, t[i].y, alpha),
                         rt_sop(FUSEDMM_SOP_INV_1P, t[i].z, alpha), rt_sop(FUSEDMM_SOP_INV_1P, t[i].w, alpha)};
           break;
         case FUSEDMM_SOP_SCAL:
@@ -348,7 +404,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     }
     if (CHECK && !valid) {  // 0 is neutral for SUM and, from a zero start, for MAX and MIN
 #pragma unroll
-      for (int i = 0; i < V; ++i) w[i] = v4f{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < V; ++i) w[i] = vec4{0.f, 0.f, 0.f, 0.f};
     }
     if (a.aop == FUSEDMM_AOP_SUM) {  // AOP
 #pragma unroll
@@ -356,11 +412,11 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     } else if (a.aop == FUSEDMM_AOP_MAX) {
 #pragma unroll
       for (int i = 0; i < V; ++i)
-        z[i] = v4f{fmaxf(z[i].x, w[i].x), fmaxf(z[i].y, w[i].y), fmaxf(z[i].z, w[i].z), fmaxf(z[i].w, w[i].w)};
+        z[i] = vec4{max_(z[i].x, w[i].x), max_(z[i].y, w[i].y), max_(z[i].z, w[i].z), max_(z[i].w, w[i].w)};
     } else {
 #pragma unroll
       for (int i = 0; i < V; ++i)
-        z[i] = v4f{fminf(z[i].x, w[i].x), fminf(z[i].y, w[i].y), fminf(z[i].z, w[i].z), fminf(z[i].w, w[i].w)};
+        z[i] = vec4{min_(z[i].x, w[i].x), min_(z[i].y, w[i].y), min_(z[i].z, w[i].z), min_(z[i].w, w[i].w)};
     }
     return;
   }
@@ -368,18 +424,18 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     // The vector loops of the tuple are fixed (dot product or difference / sum of the operands, scalar times
     // vector, SUM or MAX); what acts on the scalar -- NORM2's square root, SOP, SEL2ND's h = 1, the sign of a
     // MIN -- is read from the arguments, wave-uniform.
-    v4f t[V];
-    float p = 0.f;
+    vec4 t[V];
+    real p = 0.f;
     if constexpr (PatTraits<P>::dot) {
 #pragma unroll
       for (int i = 0; i < V; ++i) {
-        p = __builtin_fmaf(x[i].x, y[i].x, p);
-        p = __builtin_fmaf(x[i].y, y[i].y, p);
-        p = __builtin_fmaf(x[i].z, y[i].z, p);
-        p = __builtin_fmaf(x[i].w, y[i].w, p);
+        p = fma_(x[i].x, y[i].x, p);
+        p = fma_(x[i].y, y[i].y, p);
+        p = fma_(x[i].z, y[i].z, p);
+        p = fma_(x[i].w, y[i].w, p);
       }
     } else {
-      const float ys = a.ysign;
+      const real ys = a.ysign;
 #pragma unroll
       for (int i = 0; i < V; ++i) t[i] = ys * y[i] + x[i];
       if (a.rop == FUSEDMM_ROP_RSUM) {
@@ -388,17 +444,17 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
       } else {
 #pragma unroll
         for (int i = 0; i < V; ++i) {
-          p = __builtin_fmaf(t[i].x, t[i].x, p);
-          p = __builtin_fmaf(t[i].y, t[i].y, p);
-          p = __builtin_fmaf(t[i].z, t[i].z, p);
-          p = __builtin_fmaf(t[i].w, t[i].w, p);
+          p = fma_(t[i].x, t[i].x, p);
+          p = fma_(t[i].y, t[i].y, p);
+          p = fma_(t[i].z, t[i].z, p);
+          p = fma_(t[i].w, t[i].w, p);
         }
       }
     }
-    float s = group_allreduce<G>(p);
-    if (a.rop == FUSEDMM_ROP_NORM2) s = __builtin_amdgcn_sqrtf(s);
-    const float u = a.sop_exp ? __builtin_amdgcn_exp2f(a.sop_c1 * s) : s;
-    float h = a.sop_rcp ? __builtin_amdgcn_rcpf(1.0f + u) : a.sop_lin * s;
+    real s = group_allreduce<G>(p);
+    if (a.rop == FUSEDMM_ROP_NORM2) s = sqrt_(s);
+    const real u = a.sop_exp ? exp2_(sop_scale(a) * s) : s;
+    real h = a.sop_rcp ? rcp_(1.0f + u) : a.sop_lin * s;
     if (a.sop == kSopValueMinusSigmoid) h = aval - h;
     if (a.mop == FUSEDMM_MOP_SEL2ND) h = 1.0f;
     if constexpr (PatTraits<P>::flips) h *= a.sign;
@@ -406,11 +462,11 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
     if (a.mop == FUSEDMM_MOP_MUL_T) {
 #pragma unroll
       for (int i = 0; i < V; ++i) {
-        v4f o;
+        vec4 o;
         if constexpr (PatTraits<P>::dot) o = x[i] * y[i]; else o = t[i];
         if constexpr (PatTraits<P>::flips) {
-          const v4f w = h * o;
-          z[i] = v4f{fmaxf(z[i].x, w.x), fmaxf(z[i].y, w.y), fmaxf(z[i].z, w.z), fmaxf(z[i].w, w.w)};
+          const vec4 w = h * o;
+          z[i] = vec4{max_(z[i].x, w.x), max_(z[i].y, w.y), max_(z[i].z, w.z), max_(z[i].w, w.w)};
         } else {
           z[i] += h * o;
         }
@@ -419,8 +475,8 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 #pragma unroll
       for (int i = 0; i < V; ++i) {
         if constexpr (PatTraits<P>::flips) {
-          const v4f w = h * y[i];
-          z[i] = v4f{fmaxf(z[i].x, w.x), fmaxf(z[i].y, w.y), fmaxf(z[i].z, w.z), fmaxf(z[i].w, w.w)};
+          const vec4 w = h * y[i];
+          z[i] = vec4{max_(z[i].x, w.x), max_(z[i].y, w.y), max_(z[i].z, w.z), max_(z[i].w, w.w)};
         } else {
           z[i] += h * y[i];
         }
@@ -429,48 +485,48 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
   } else if constexpr (PatTraits<P>::gcn) {
     // VOP = SEL2ND, ROP/SOP no-ops: h = a_uv; MOP: w = h * y; AOP: sum, or maximum / minimum from the
     // zero start (an entry beyond the end contributes w = 0, neutral for all three)
-    float h = aval;
+    real h = aval;
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       if constexpr (P == PAT_GCN) {
         z[i] += h * y[i];
       } else {
-        const v4f w = h * y[i];
+        const vec4 w = h * y[i];
         z[i].x = aop_apply(PatTraits<P>::aop, z[i].x, w.x); z[i].y = aop_apply(PatTraits<P>::aop, z[i].y, w.y);
         z[i].z = aop_apply(PatTraits<P>::aop, z[i].z, w.z); z[i].w = aop_apply(PatTraits<P>::aop, z[i].w, w.w);
       }
     }
   } else if constexpr (P == PAT_SIGMOID || P == PAT_ONE_MINUS_SIGMOID || P == PAT_SIGNED_SIGMOID) {
-    float p = 0.f;  // VOP = MUL and this lane's share of ROP = RSUM
+    real p = 0.f;  // VOP = MUL and this lane's share of ROP = RSUM
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-      p = __builtin_fmaf(x[i].x, y[i].x, p);
-      p = __builtin_fmaf(x[i].y, y[i].y, p);
-      p = __builtin_fmaf(x[i].z, y[i].z, p);
-      p = __builtin_fmaf(x[i].w, y[i].w, p);
+      p = fma_(x[i].x, y[i].x, p);
+      p = fma_(x[i].y, y[i].y, p);
+      p = fma_(x[i].z, y[i].z, p);
+      p = fma_(x[i].w, y[i].w, p);
     }
-    const float s = group_allreduce<G>(p);
+    const real s = group_allreduce<G>(p);
     // SOP: sigma(s) = 1/(1+2^(-s log2 e)); 1-sigma(s) = sigma(-s).  2^big = inf -> h = 0, no NaN.
-    const float e = __builtin_amdgcn_exp2f(P == PAT_ONE_MINUS_SIGMOID ? s * kLog2e : -s * kLog2e);
-    float h = __builtin_amdgcn_rcpf(1.0f + e);
+    const real e = exp2_(P == PAT_ONE_MINUS_SIGMOID ? s * kLog2e : -s * kLog2e);
+    real h = rcp_(1.0f + e);
     if constexpr (P == PAT_SIGNED_SIGMOID) h = aval - h;  // 1 - sigmoid on stored entries, -sigmoid on samples
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) z[i] += h * y[i];  // MOP = MUL with y_v, AOP = SUM
   } else if constexpr (P == PAT_TDIST || P == PAT_FR) {
-    v4f t[V];
-    float p = 0.f;  // VOP = SUB, ROP = sum of squares
+    vec4 t[V];
+    real p = 0.f;  // VOP = SUB, ROP = sum of squares
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       t[i] = x[i] - y[i];
-      p = __builtin_fmaf(t[i].x, t[i].x, p);
-      p = __builtin_fmaf(t[i].y, t[i].y, p);
-      p = __builtin_fmaf(t[i].z, t[i].z, p);
-      p = __builtin_fmaf(t[i].w, t[i].w, p);
+      p = fma_(t[i].x, t[i].x, p);
+      p = fma_(t[i].y, t[i].y, p);
+      p = fma_(t[i].z, t[i].z, p);
+      p = fma_(t[i].w, t[i].w, p);
     }
-    const float s = group_allreduce<G>(p);
-    float h = (P == PAT_TDIST) ? __builtin_amdgcn_rcpf(1.0f + s) : alpha * __builtin_amdgcn_sqrtf(s);
+    const real s = group_allreduce<G>(p);
+    real h = (P == PAT_TDIST) ? rcp_(1.0f + s) : alpha * sqrt_(s);
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) z[i] += h * t[i];  // MOP = MUL with the VOP output
@@ -483,7 +539,7 @@ __device__ __forceinline__ void edge_update(const v4f (&x)[V], const v4f (&y)[V]
 // ---------------------------------------------------------------------------------------
 template <int P, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
-                                                const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int lane) {
+                                                const vec4 (&x)[D / (4 * G)], vec4 (&z)[D / (4 * G)], int lane) {
   constexpr int V = D / (4 * G);
   constexpr int S = 64 / G;
   static_assert(S * U <= 64 && 64 % (S * U) == 0, "unroll must tile a batch of 64 entries");
@@ -501,15 +557,15 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   for (int64_t base = e0; base < e1; base += 64) {
     const int cnt = (int)((e1 - base) < 64 ? (e1 - base) : 64);  // wave-uniform
     int colb = 0;
-    float valb = 0.f;
+    real valb = 0.f;
     if (lane < cnt) {
       colb = ld_stream(a.colidx + base + lane);
-      if (use_val) valb = ld_stream(a.values + base + lane);
+      if (use_val) valb = ld_stream(values_of(a) + base + lane);
     }
     for (int k0 = 0; k0 < cnt; k0 += S * U) {
       int c[U];
-      float av[U];
-      v4f y[U][V];
+      real av[U];
+      vec4 y[U][V];
       if (k0 + S * U <= cnt) {
         // every lane group has a stored entry in each of the U steps
 #pragma unroll
@@ -541,7 +597,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 #pragma unroll
           for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
             if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
           }
 #pragma unroll
@@ -563,23 +619,23 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 // ---------------------------------------------------------------------------------------
 template <int P, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0, int deg, int maxdeg,
-                                                 const v4f (&x)[D / (4 * G)], v4f (&z)[D / (4 * G)], int slot, int g, int nv,
+                                                 const vec4 (&x)[D / (4 * G)], vec4 (&z)[D / (4 * G)], int slot, int g, int nv,
                                                  bool use_val) {
   constexpr int V = D / (4 * G);
   using T = PatTraits<P>;
   for (int bb = 0; bb < maxdeg; bb += G) {
     int colb = 0;
-    float valb = 0.f;
+    real valb = 0.f;
     if (bb + g < deg) {
       colb = ld_stream(a.colidx + e0 + bb + g);
-      if (use_val) valb = ld_stream(a.values + e0 + bb + g);
+      if (use_val) valb = ld_stream(values_of(a) + e0 + bb + g);
     }
     const int steps = (maxdeg - bb) < G ? (maxdeg - bb) : G;
     for (int k = 0; k < steps; k += U) {
       bool ok[U];
       int c[U];
-      float av[U];
-      v4f y[U][V];
+      real av[U];
+      vec4 y[U][V];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         ok[u] = (bb + k + u) < deg;
@@ -590,7 +646,7 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-          for (int i = 0; i < V; ++i) y[u][i] = v4f{0.f, 0.f, 0.f, 0.f};
+          for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
           if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
         }
 #pragma unroll
@@ -605,33 +661,33 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
 }
 
 template <int D, int G, int C, bool M>
-__device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, v4f (&x)[D / (4 * G)]) {
-  const float* xr = a.X + row * a.ldx;
+__device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, vec4 (&x)[D / (4 * G)]) {
+  const real* xr = X_of(a) + row * a.ldx;
 #pragma unroll
   for (int i = 0; i < D / (4 * G); ++i) {
     const int p = piece_index<G, C>(g, i);
-    if (!M || p < a.d_pieces) x[i] = ld4_stream(xr + 4 * p); else x[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    if (!M || p < a.d_pieces) x[i] = ld4_stream(xr + 4 * p); else x[i] = vec4{0.f, 0.f, 0.f, 0.f};
   }
 }
 
 template <int V>
-__device__ __forceinline__ void zero(v4f (&z)[V]) {
+__device__ __forceinline__ void zero(vec4 (&z)[V]) {
 #pragma unroll
-  for (int i = 0; i < V; ++i) z[i] = v4f{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < V; ++i) z[i] = vec4{0.f, 0.f, 0.f, 0.f};
 }
 
 template <int V>
-__device__ __forceinline__ void scale(v4f (&z)[V], float f) {
+__device__ __forceinline__ void scale(vec4 (&z)[V], real f) {
 #pragma unroll
   for (int i = 0; i < V; ++i) z[i] *= f;
 }
 
 template <int D, int G, int C, bool M>
-__device__ __forceinline__ void store_row(const KernelArgs& a, float* dst, int g, const v4f (&z)[D / (4 * G)]) {
+__device__ __forceinline__ void store_row(const KernelArgs& a, real* dst, int g, const vec4 (&z)[D / (4 * G)]) {
 #pragma unroll
   for (int i = 0; i < D / (4 * G); ++i) {
     const int p = piece_index<G, C>(g, i);
-    if (!M || p < a.d_pieces) __builtin_nontemporal_store(z[i], reinterpret_cast<v4f*>(dst + 4 * p));
+    if (!M || p < a.d_pieces) __builtin_nontemporal_store(z[i], reinterpret_cast<vec4*>(dst + 4 * p));
   }
 }
 
@@ -652,8 +708,10 @@ __device__ __forceinline__ void store_row(const KernelArgs& a, float* dst, int g
 // and then runs one of four bodies: chunk, wave segments, packed segments, zero fill.  A segment is
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int GW0, int UW0, int GP0, int UP0, int YF>
+// E (always `real`) only makes the single- and double-precision instances of one shape different symbols.
+template <int P, int D, int GW0, int UW0, int GP0, int UP0, int YF, class E = real>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
+  static_assert(sizeof(E) == sizeof(real), "the element type is fixed per translation unit");
   using T = PatTraits<P>;
   // Rows of 2-byte elements are read 16 bytes per lane where the lane group can be halved (it must
   // keep 8 lanes): same bytes in flight per wavefront, half as many load instructions.
@@ -663,7 +721,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int b = blockIdx.x;
-  __shared__ v4f stage[kWavesPerBlock][D / 4];
+  __shared__ vec4 stage[kWavesPerBlock][D / 4];
 
   int kind, first, count;
   bool from_desc;  // segments come from descriptors (tiles) rather than from order[] + rowptr[]
@@ -692,7 +750,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int lo = wave * per < ch.e_count ? wave * per : ch.e_count;
     const int hi = (wave + 1) * per < ch.e_count ? (wave + 1) * per : ch.e_count;
     const int g = lane % GW;
-    v4f x[V], z[V];
+    vec4 x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, ch.row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
@@ -704,10 +762,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       }
       __syncthreads();
       if (threadIdx.x < (T::masked ? a.d_pieces : D / 4)) {
-        v4f s = stage[0][threadIdx.x];
+        vec4 s = stage[0][threadIdx.x];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) {
-          const v4f o = stage[w][threadIdx.x];
+          const vec4 o = stage[w][threadIdx.x];
           if constexpr (P == PAT_RUNTIME) {
             s.x = aop_apply(a.aop, s.x, o.x); s.y = aop_apply(a.aop, s.y, o.y);
             s.z = aop_apply(a.aop, s.z, o.z); s.w = aop_apply(a.aop, s.w, o.w);
@@ -720,10 +778,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         }
         if constexpr (T::flips) s *= a.sign;  // a minimum was run as the maximum of the negated messages
         if constexpr (T::means) {
-          if (a.mean && ch.part < 0) s *= 1.0f / (float)ch.e_count;  // the chunk is the whole row
+          if (a.mean && ch.part < 0) s *= (real)1 / (real)ch.e_count;  // the chunk is the whole row
         }
-        float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * D;
-        __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(dst + 4 * threadIdx.x));
+        real* dst = ch.part < 0 ? Z_of(a) + (int64_t)ch.row * a.ldz : partials_of(a) + (int64_t)ch.part * D;
+        __builtin_nontemporal_store(s, reinterpret_cast<vec4*>(dst + 4 * threadIdx.x));
       }
     }
   } else if (kind == kItemWave) {
@@ -732,18 +790,18 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     if (wave >= count) return;
     int row;
     int64_t e0, e1;
-    float* dst;
+    real* dst;
     if (from_desc) {
       const ChunkDesc td = a.tile_descs[first + wave];
       row = td.row; e0 = td.e_begin; e1 = td.e_begin + td.e_count;
-      dst = a.partials + (int64_t)td.part * D;
+      dst = partials_of(a) + (int64_t)td.part * D;
     } else {
       row = __builtin_amdgcn_readfirstlane(a.order[first + wave]);
       e0 = a.rowptr[row]; e1 = a.rowptr[row + 1];
-      dst = a.Z + (int64_t)row * a.ldz;
+      dst = Z_of(a) + (int64_t)row * a.ldz;
     }
     const int g = lane % GW;
-    v4f x[V], z[V];
+    vec4 x[V], z[V];
     zero(z);
     if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, row, g, x); else zero(x);
     wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
@@ -751,7 +809,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       combine_groups<P, GW, V>(a, z);
       if constexpr (T::flips) scale(z, a.sign);
       if constexpr (T::means) {
-        if (a.mean && !from_desc) scale(z, 1.0f / (float)(e1 - e0));
+        if (a.mean && !from_desc) scale(z, (real)1 / (real)(e1 - e0));
       }
       if (lane < GW) store_row<D, GW, CW, T::masked>(a, dst, g, z);
     }
@@ -774,20 +832,20 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       const bool has_seg = idx < count;
       int64_t row = 0, e0 = 0;
       int deg = 0;
-      float* dst = nullptr;
+      real* dst = nullptr;
       if (has_seg) {
         if (from_desc) {
           const ChunkDesc td = a.tile_descs[first + idx];
           row = td.row; e0 = td.e_begin; deg = td.e_count;
-          dst = a.partials + (int64_t)td.part * D;
+          dst = partials_of(a) + (int64_t)td.part * D;
         } else {
           row = a.order[a.n_wave + first + idx];
           e0 = a.rowptr[row];
           deg = (int)(a.rowptr[row + 1] - e0);
-          dst = a.Z + row * a.ldz;
+          dst = Z_of(a) + row * a.ldz;
         }
       }
-      v4f x[V], z[V];
+      vec4 x[V], z[V];
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
@@ -802,7 +860,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       if constexpr (T::loads_y) {
         if constexpr (T::flips) scale(z, a.sign);
         if constexpr (T::means) {
-          if (a.mean && !from_desc && deg > 0) scale(z, 1.0f / (float)deg);
+          if (a.mean && !from_desc && deg > 0) scale(z, (real)1 / (real)deg);
         }
         if (has_seg) store_row<D, GP, CP, T::masked>(a, dst, g, z);
       }
@@ -815,7 +873,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
       for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
         const int64_t row = rows[i / kPieces];
-        __builtin_nontemporal_store(v4f{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<v4f*>(a.Z + row * a.ldz + 4 * (i % kPieces)));
+        __builtin_nontemporal_store(vec4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<vec4*>(Z_of(a) + row * a.ldz + 4 * (i % kPieces)));
       }
     }
   }

@@ -1,11 +1,19 @@
 // Instantiates the specialised kernel for one feature dimension and defines its launcher.
-// Included by fusedmm_fast_d*.hip with FMM_D / FMM_GW / FMM_UW / FMM_GP / FMM_UP set.
+// Included by fusedmm_fast_d*.hip with FMM_D / FMM_GW / FMM_UW / FMM_GP / FMM_UP set, and by
+// fusedmm_fast_f64_d*.hip with FMM_F64 as well (double precision: launch_fast_f64_d<D>).
 #include "fusedmm_device.h"
 
 namespace fmm {
 
 #define FMM_CAT2(a, b) a##b
 #define FMM_CAT(a, b) FMM_CAT2(a, b)
+#ifdef FMM_F64
+#define FMM_FN(name) FMM_CAT(FMM_CAT(name, _f64_d), FMM_D)
+constexpr bool kDouble = true;
+#else
+#define FMM_FN(name) FMM_CAT(FMM_CAT(name, _d), FMM_D)
+constexpr bool kDouble = false;
+#endif
 
 template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
@@ -17,7 +25,7 @@ static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
 }
 
 // rows of 2-byte elements use lane groups half as wide where that leaves 8 lanes (see the kernel)
-int FMM_CAT(packed_rows_per_block_d, FMM_D)(int y_format) {
+int FMM_FN(packed_rows_per_block)(int y_format) {
   const int gp = (y_format != kYF32 && FMM_GP >= 16) ? FMM_GP / 2 : FMM_GP;
   return kWavesPerBlock * (64 / gp);
 }
@@ -41,18 +49,23 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
       if constexpr (YF == kYF32) return launch_one<PAT_VISIT, kYF32>(a, stream);
       return hipErrorInvalidValue;
     case PAT_SIGNED_SIGMOID:  // used by the minibatch layer on fp32 embeddings only
-      if constexpr (YF == kYF32) return launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
+      if constexpr (YF == kYF32 && !kDouble) return launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
 
-hipError_t FMM_CAT(launch_fast_d, FMM_D)(int pattern, int y_format, const KernelArgs& a, hipStream_t stream) {
-  switch (y_format) {
-    case kYF32: return launch_format<kYF32>(pattern, a, stream);
-    case kYBf16: return launch_format<kYBf16>(pattern, a, stream);
-    case kYF16: return launch_format<kYF16>(pattern, a, stream);
-    default: return hipErrorInvalidValue;
+// y_format kYF32 stands for "Y in the element type of the build"; the 2-byte formats exist for fp32 arithmetic only
+hipError_t FMM_FN(launch_fast)(int pattern, int y_format, const KernelArgs& a, hipStream_t stream) {
+  if constexpr (kDouble) {
+    return y_format == kYF32 ? launch_format<kYF32>(pattern, a, stream) : hipErrorInvalidValue;
+  } else {
+    switch (y_format) {
+      case kYF32: return launch_format<kYF32>(pattern, a, stream);
+      case kYBf16: return launch_format<kYBf16>(pattern, a, stream);
+      case kYF16: return launch_format<kYF16>(pattern, a, stream);
+      default: return hipErrorInvalidValue;
+    }
   }
 }
 

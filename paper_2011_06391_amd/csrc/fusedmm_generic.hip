@@ -259,45 +259,58 @@ hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream) { r
 // z_u = sum of the row's partial rows, in slot order (fixed order => run-to-run deterministic).
 // A workgroup covers 256 / (d/4) rows; a thread owns one 16-byte column of one row and keeps
 // eight partial-row loads in flight.
-__device__ __forceinline__ v4f merge_two(int aop, v4f s, v4f t) {
+template <class V4>
+__device__ __forceinline__ V4 merge_two(int aop, V4 s, V4 t) {
   if (aop == FUSEDMM_AOP_SUM || aop == FUSEDMM_AOP_MEAN) return s + t;
-  if (aop == FUSEDMM_AOP_MAX) return v4f{fmaxf(s.x, t.x), fmaxf(s.y, t.y), fmaxf(s.z, t.z), fmaxf(s.w, t.w)};
-  return v4f{fminf(s.x, t.x), fminf(s.y, t.y), fminf(s.z, t.z), fminf(s.w, t.w)};
+  if (aop == FUSEDMM_AOP_MAX) return V4{fmax(s.x, t.x), fmax(s.y, t.y), fmax(s.z, t.z), fmax(s.w, t.w)};
+  return V4{fmin(s.x, t.x), fmin(s.y, t.y), fmin(s.z, t.z), fmin(s.w, t.w)};
 }
 
+// E: float, or double (a thread then owns a 32-byte column)
+template <class E>
 __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
-                                                           const float* partials, int32_t d, int32_t pstride,
-                                                           int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz) {
+                                                           const E* partials, int32_t d, int32_t pstride,
+                                                           int32_t aop, const int64_t* rowptr, E* Z, int64_t ldz) {
+  typedef E V4 __attribute__((ext_vector_type(4)));
   const int cols = d >> 2;
   const int rows_per_block = 256 / cols;
   const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
   const int64_t mi = (int64_t)blockIdx.x * rows_per_block + r;
   if (r >= rows_per_block || mi >= n_merges) return;
   const MergeDesc md = merges[mi];
-  const float* src = partials + (int64_t)md.first_part * pstride + 4 * c;
-  v4f s = {0.f, 0.f, 0.f, 0.f};
+  const E* src = partials + (int64_t)md.first_part * pstride + 4 * c;
+  V4 s = {0, 0, 0, 0};
   int p = 0;
   for (; p + 8 <= md.n_parts; p += 8) {
-    v4f t[8];
+    V4 t[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)(p + k) * pstride));
+    for (int k = 0; k < 8; ++k) t[k] = __builtin_nontemporal_load(reinterpret_cast<const V4*>(src + (int64_t)(p + k) * pstride));
 #pragma unroll
     for (int k = 0; k < 8; ++k) s = merge_two(aop, s, t[k]);
   }
   for (; p < md.n_parts; ++p)
-    s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src + (int64_t)p * pstride)));
-  if (aop == FUSEDMM_AOP_MEAN) s *= 1.0f / (float)(rowptr[md.row + 1] - rowptr[md.row]);  // split rows are never empty
-  __builtin_nontemporal_store(s, reinterpret_cast<v4f*>(Z + (int64_t)md.row * ldz + 4 * c));
+    s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const V4*>(src + (int64_t)p * pstride)));
+  if (aop == FUSEDMM_AOP_MEAN) s *= (E)1 / (E)(rowptr[md.row + 1] - rowptr[md.row]);  // split rows are never empty
+  __builtin_nontemporal_store(s, reinterpret_cast<V4*>(Z + (int64_t)md.row * ldz + 4 * c));
 }
 
-hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
-                        int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream) {
+template <class E>
+static hipError_t launch_merge_t(const MergeDesc* merges, int32_t n_merges, const E* partials, int32_t d, int32_t pstride,
+                                 int32_t aop, const int64_t* rowptr, E* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
   const int rows_per_block = 256 / (d >> 2);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
-  hipLaunchKernelGGL(fusedmm_merge_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
+  hipLaunchKernelGGL(fusedmm_merge_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
                      pstride, aop, rowptr, Z, ldz);
   return hipGetLastError();
+}
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
+                        int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream) {
+  return launch_merge_t(merges, n_merges, partials, d, pstride, aop, rowptr, Z, ldz, stream);
+}
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const double* partials, int32_t d, int32_t pstride,
+                        int32_t aop, const int64_t* rowptr, double* Z, int64_t ldz, hipStream_t stream) {
+  return launch_merge_t(merges, n_merges, partials, d, pstride, aop, rowptr, Z, ldz, stream);
 }
 
 __global__ __launch_bounds__(256) void validate_colidx_kernel(const int32_t* colidx, int64_t nnz, int64_t n, int32_t* flag) {
@@ -396,12 +409,22 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
-  hipError_t launch_fast_d##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
-  int packed_rows_per_block_d##D(int y_format);
-FMM_DECL(32) FMM_DECL(64) FMM_DECL(128) FMM_DECL(256) FMM_DECL(512)
+  hipError_t launch_fast##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
+  int packed_rows_per_block##D(int y_format);
+FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512)
+FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256)
 #undef FMM_DECL
 
 int packed_rows_per_block(int d, int y_format) {
+  if (y_format == kYF64) {
+    switch (d) {
+      case 32: return packed_rows_per_block_f64_d32(kYF32);
+      case 64: return packed_rows_per_block_f64_d64(kYF32);
+      case 128: return packed_rows_per_block_f64_d128(kYF32);
+      case 256: return packed_rows_per_block_f64_d256(kYF32);
+      default: return 0;
+    }
+  }
   switch (d) {
     case 32: return packed_rows_per_block_d32(y_format);
     case 64: return packed_rows_per_block_d64(y_format);
@@ -413,6 +436,15 @@ int packed_rows_per_block(int d, int y_format) {
 }
 
 hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream) {
+  if (y_format == kYF64) {
+    switch (d) {
+      case 32: return launch_fast_f64_d32(pattern, kYF32, a, stream);
+      case 64: return launch_fast_f64_d64(pattern, kYF32, a, stream);
+      case 128: return launch_fast_f64_d128(pattern, kYF32, a, stream);
+      case 256: return launch_fast_f64_d256(pattern, kYF32, a, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
   switch (d) {
     case 32: return launch_fast_d32(pattern, y_format, a, stream);
     case 64: return launch_fast_d64(pattern, y_format, a, stream);

@@ -106,11 +106,13 @@ int packed_rows_per_block(int d, int y_format);
 constexpr int kSopValueMinusSigmoid = 100;
 
 
-// Storage formats of Y the specialised kernels read (arithmetic is fp32 in all of them).
-enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2 };
+// Storage formats of Y the specialised kernels read (arithmetic is fp32 in the first three).  kYF64 selects
+// the double-precision instances: values, X, Y, Z and the partial rows of KernelArgs then all point at doubles
+// (the leading dimensions count doubles) and the arithmetic is fp64.
+enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2, kYF64 = 3 };
 
-// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512.  y_format other than
-// kYF32: a.Y holds 2-byte elements (the five sum patterns and the run-time-ops instance exist in that form).
+// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512 (kYF64: up to 256).  kYBf16 /
+// kYF16: a.Y holds 2-byte elements (the five sum patterns and the run-time-ops instance exist in that form).
 hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream);
 
 // The kernels for very short feature vectors (one lane per stored entry): d must be 2, 3, 4, 8 or 16, fp32,
@@ -162,6 +164,8 @@ hipError_t launch_generic(const GenericArgsT<double>& a, hipStream_t stream);
 // d: row width; pstride: distance in floats between partial rows (>= d)
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
                         int32_t aop, const int64_t* rowptr, float* Z, int64_t ldz, hipStream_t stream);
+hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const double* partials, int32_t d, int32_t pstride,
+                        int32_t aop, const int64_t* rowptr, double* Z, int64_t ldz, hipStream_t stream);
 
 // Where the stored entries lie along the column range: hist[column * n_buckets / n] += 1 for every stride-th entry.
 hipError_t launch_column_histogram(const int32_t* colidx, int64_t nnz, int64_t stride, int64_t n, int32_t n_buckets,

@@ -2,7 +2,8 @@
 oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
 (32, 128), one between instance sizes (20, masked), two of the one-lane-per-entry kernels (2, 3) and those only
 the general kernel takes (6, 13, 27, 97, 301, 700: its lane-group widths and register counts), and with Y
-stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128).  A dispatch slip -- a tuple
+stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128), and in double precision on the
+specialised schedule (32, 256, and 20 on the masked instance; bound 1e-12).  A dispatch slip -- a tuple
 recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
 import itertools
 
@@ -15,6 +16,8 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
+TOL64 = 1e-12
+ALPHA = float(np.float32(0.37))   # alpha travels as fp32 in the op struct: the oracle gets the same value
 ONAME = {"NORM2": "NORM", "INV_1P": "INV1P"}
 OAOP = {"SUM": "ASUM", "MAX": "AMAX", "MIN": "AMIN", "MEAN": "AMEAN"}
 
@@ -50,7 +53,7 @@ def rounded(Y, fmt):
                                    (128, "bf16"), (128, "f16"),
                                    # the general kernel's other lane-group widths and register counts
                                    (2, "f32"), (3, "f32"), (13, "f32"), (27, "f32"), (97, "f32"), (301, "f32"),
-                                   (700, "f32")])
+                                   (700, "f32"), (32, "f64"), (20, "f64"), (256, "f64")])
 def test_every_valid_tuple(B, d, fmt):
     rng = np.random.default_rng(2024 + d)
     m, n = 48, 90
@@ -92,8 +95,12 @@ def test_every_valid_tuple(B, d, fmt):
     plan.reserve(d)
     st = plan.stats()
     assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0
-    Z = torch.empty((m, d), dtype=torch.float32, device="cuda")
-    if fmt != "f32":
+    Z = torch.empty((m, d), dtype=torch.float64 if fmt == "f64" else torch.float32, device="cuda")
+    if fmt == "f64":
+        plan.reserve_f64(d)
+        dev64 = {k: v.double() for k, v in dev.items()}
+        vd64 = vd.double()
+    elif fmt != "f32":
         for k in [k for k in mats if k.startswith("Y")]:
             h = torch.zeros((n, d), dtype=torch.int16, device="cuda")
             (B.fusedmm_to_bf16 if fmt == "bf16" else B.fusedmm_to_f16)(h, dev[k], n * d)
@@ -103,12 +110,14 @@ def test_every_valid_tuple(B, d, fmt):
         xk, yk = rmul_sets[vop] if rop == "RMUL" else ("Xs", "Ys")
         X, Y, Xd, Yd = mats[xk], mats[yk], dev[xk], dev[yk]
         names = (vop, ONAME.get(rop, rop), ONAME.get(sop, sop), mop)
-        Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, OAOP[aop], alpha=0.37)
-        ops = B.make_ops(vop, rop, sop, mop, aop=aop, alpha=0.37)
+        Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, names, OAOP[aop], alpha=ALPHA)
+        ops = B.make_ops(vop, rop, sop, mop, aop=aop, alpha=ALPHA)
         Z.fill_(float("nan"))
         Xarg = None if vop == "SEL2ND" else Xd
         if fmt == "f32":
             plan.execute(ops, Xarg, Yd, Z, vd)
+        elif fmt == "f64":
+            plan.execute_f64(ops, None if vop == "SEL2ND" else dev64[xk], dev64[yk], Z, vd64)
         else:
             Yh = dev[yk + "h"]
             (plan.execute_bf16y if fmt == "bf16" else plan.execute_f16y)(ops, Xarg, Yh, Z, vd)
@@ -125,9 +134,9 @@ def test_every_valid_tuple(B, d, fmt):
         S = np.where(tiny, 0.0, S)
         Zg = np.where(tiny, 0.0, Zg)
         Zr = np.where(tiny, 0.0, Zr)
-        err, am, viol = oracle.compare(Zg.astype(np.float32), Zr, S)
+        err, am, viol = oracle.compare(Zg if fmt == "f64" else Zg.astype(np.float32), Zr, S)
         count += 1
-        if viol != 0 or not err <= TOL:
+        if viol != 0 or not err <= (TOL64 if fmt == "f64" else TOL):
             failures.append(f"{(vop, rop, sop, mop, aop)}: err {err:.3e} at {am}, viol {viol}")
     plan.close()
     assert count == 1248

@@ -76,6 +76,86 @@ def test_f64_matches_oracle(B, case, d):
     plan.close()
 
 
+# the specialised schedule's double-precision instances: instance sizes and dimensions between them, on a plan
+# whose options put rows into every bin (packed, wave, chunks, column-class tiles with partial rows)
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 20, 100, 200))
+@pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
+def test_f64_specialised_schedule_all_bins(B, case, d):
+    gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
+    rng = np.random.default_rng(4000 + d)
+    m, n = 300, 500
+    degs = rng.integers(0, 9, m)
+    degs[[0, 7, 299]] = 0
+    degs[5], degs[20], degs[33], degs[47], degs[290] = 40, 70, 300, 450, 130
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(degs)
+    colidx = np.concatenate([np.sort(rng.choice(n, k, replace=False)) for k in degs]).astype(np.int32)
+    X = rng.uniform(-0.7, 0.7, (m, d)).astype(np.float32)
+    Y = rng.uniform(-0.7, 0.7, (n, d)).astype(np.float32)
+    vals = rng.uniform(-1, 1, len(colidx)).astype(np.float32)
+    alpha = float(np.float32(0.41))
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, X, Y, oracle_ops, oracle_aop, alpha=alpha)
+    ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
+    ops.alpha = alpha
+    plan = B.Plan(m, n, dev(rowptr), dev(colidx), {"small_row_max": 4, "split_row_min": 32, "chunk_edges": 256,
+                                                   "column_classes": 8, "tile_row_min": 64, "feature_dim_hint": d})
+    st = plan.stats()
+    assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0 and st["partials"] > 0
+    uses_x = ops.vop != B.VOP["SEL2ND"]
+    Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+    args = (ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z, dev(vals.astype(np.float64)))
+    # the plan has reserved partial rows of d floats: rows of d doubles are refused until they are reserved
+    with pytest.raises(B.FusedMMError) as ei:
+        plan.execute_f64(*args)
+    assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED
+    torch.cuda.synchronize()
+    assert torch.isnan(Z).all()
+    plan.reserve_f64(d)
+    plan.execute_f64(*args)
+    torch.cuda.synchronize()
+    Zg = Z.cpu().numpy()
+    err = np.abs(Zg - Zr) / np.where(S > 0, S, 1.0)
+    assert (Zg[S == 0] == 0).all()
+    assert err.max() <= TOL64, f"{case[0]} {gpu_aop} d={d}: {err.max():.3e}"
+    # every stored entry exactly once under the double-precision instances' lane groups
+    counts = torch.zeros(len(colidx), dtype=torch.int32, device="cuda")
+    plan.edge_visits(d, 2, counts)
+    torch.cuda.synchronize()
+    assert (counts == 1).all()
+    plan.close()
+
+
+def test_f64_specialised_schedule_is_the_one_that_runs(B):
+    """At an instance size with aligned operands fusedmm_execute_f64 must be several times faster than on the
+    same rows shifted by one element (unaligned: the general kernel) -- a silent fall-back would show here."""
+    g = synth.rmat(14, (1 << 14) * 32, seed=77)
+    m = n = g.m
+    d = 128
+    rng = np.random.default_rng(3)
+    Xw = torch.from_numpy(rng.uniform(-0.5, 0.5, (m, d + 4))).cuda()
+    Zw = torch.empty((m, d + 4), dtype=torch.float64, device="cuda")
+    plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx))
+    plan.reserve_f64(d)
+    ops = B.fusedmm_ops_preset("sigmoid")
+
+    def timed(off):
+        X, Z = Xw[:, off:off + d], Zw[:, off:off + d]
+        for _ in range(3):
+            plan.execute_f64(ops, X, X, Z)
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(10):
+            plan.execute_f64(ops, X, X, Z)
+        t1.record()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1) / 10
+
+    t_fast, t_gen = timed(0), timed(1)
+    assert t_fast * 2 < t_gen, (t_fast, t_gen)
+    plan.close()
+
+
 def test_f64_reads_all_64_bits(B):
     """Inputs that differ from their fp32 roundings only in the low mantissa bits: the product with a
     0/1 pattern (GCN, unit values) must match numpy's fp64 product, not the product of the roundings."""
