@@ -167,6 +167,15 @@ int recognise_family(const fusedmm_ops_t& o) {
   return -1;
 }
 
+// Which instance of the specialised kernel an op tuple runs on: its own when it is recognised and the dimension
+// is an instance size; between sizes the GCN sum / mean message has a masked instance of its own and the
+// tuple families take what they contain; everything else reads its ops at run time.
+int choose_pattern(int recognised, int family, bool exact_dim) {
+  if (recognised >= 0 && exact_dim) return recognised;
+  if (recognised == PAT_GCN) return PAT_GCN_MASKED;
+  return family >= 0 ? family : PAT_RUNTIME;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned32(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 31u) == 0; }
 
@@ -811,7 +820,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);
   const int family = recognise_family(*ops);
-  const int pattern = (recognised >= 0 && D == d) ? recognised : (family >= 0 ? family : PAT_RUNTIME);
+  const int pattern = choose_pattern(recognised, family, D == d);
   const bool y_ok = plan->nnz == 0 || (y_bf16 ? (aligned16(d_Y) && ldy % 8 == 0)
                                               : (aligned16(d_Y) && ldy % 4 == 0));
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
@@ -975,7 +984,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     if (plan->n_parts > 0 && 2 * D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
     const int recognised = recognise(*ops);
     const int family = recognise_family(*ops);
-    const int pattern = (recognised >= 0 && D == d) ? recognised : (family >= 0 ? family : PAT_RUNTIME);
+    const int pattern = choose_pattern(recognised, family, D == d);
     KernelArgs a;
     fill_schedule_args(plan, D, kYF64, &a);
     fill_op_args(*ops, &a);

@@ -121,7 +121,7 @@ __device__ __forceinline__ real aop_apply(int aop, real z, real w) {
 // What a compile-time pattern fixes (PAT_RUNTIME decides the same things from the launch arguments).
 template <int P>
 struct PatTraits {
-  static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
+  static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MASKED || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
   static constexpr bool dot = (P == PAT_DOT || P == PAT_DOT_MM);
   static constexpr bool dist = (P == PAT_DIST || P == PAT_DIST_MM);
   static constexpr bool family = dot || dist;                       // scalar steps read at run time
@@ -130,11 +130,11 @@ struct PatTraits {
   static constexpr bool uses_val = (gcn || P == PAT_SIGNED_SIGMOID);
   static constexpr bool loads_y = (P != PAT_VISIT);
   // rows may be narrower than the instance: pieces at or beyond a.d_pieces are neither loaded nor stored
-  static constexpr bool masked = (P == PAT_RUNTIME || family);
+  static constexpr bool masked = (P == PAT_RUNTIME || P == PAT_GCN_MASKED || family);
   // how messages are accumulated when it is fixed at compile time, and whether a row stored whole
   // may have to be divided by its length (mean pooling: a.mean)
   static constexpr int aop = (P == PAT_GCN_MAX || flips) ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
-  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_DOT || P == PAT_DIST);
+  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_GCN_MASKED || P == PAT_DOT || P == PAT_DIST);
 };
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
@@ -489,7 +489,7 @@ __device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-      if constexpr (P == PAT_GCN) {
+      if constexpr (P == PAT_GCN || P == PAT_GCN_MASKED) {
         z[i] += h * y[i];
       } else {
         const vec4 w = h * y[i];

@@ -36,6 +36,9 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
     case PAT_SIGMOID: return launch_one<PAT_SIGMOID, YF>(a, stream);
     case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, YF>(a, stream);
     case PAT_GCN: return launch_one<PAT_GCN, YF>(a, stream);
+    case PAT_GCN_MASKED:  // dimensions between instance sizes exist in the build's own element type only
+      if constexpr (YF == kYF32) return launch_one<PAT_GCN_MASKED, kYF32>(a, stream);
+      return hipErrorInvalidValue;
     case PAT_GCN_MAX: return launch_one<PAT_GCN_MAX, YF>(a, stream);
     case PAT_GCN_MIN: return launch_one<PAT_GCN_MIN, YF>(a, stream);
     case PAT_TDIST: return launch_one<PAT_TDIST, YF>(a, stream);
