@@ -167,12 +167,11 @@ int recognise_family(const fusedmm_ops_t& o) {
   return -1;
 }
 
-// Which instance of the specialised kernel an op tuple runs on: its own when it is recognised and the dimension
-// is an instance size; between sizes the GCN sum / mean message has a masked instance of its own and the
-// tuple families take what they contain; everything else reads its ops at run time.
+// Which instance of the specialised kernel an op tuple runs on: a recognised pattern its own (the masked form of
+// it when the dimension lies between two instance sizes), else the tuple family it belongs to, else the one that
+// reads its ops at run time.
 int choose_pattern(int recognised, int family, bool exact_dim) {
-  if (recognised >= 0 && exact_dim) return recognised;
-  if (recognised == PAT_GCN) return PAT_GCN_MASKED;
+  if (recognised >= 0) return exact_dim ? recognised : (recognised | kPatMasked);
   return family >= 0 ? family : PAT_RUNTIME;
 }
 

@@ -121,7 +121,7 @@ __device__ __forceinline__ real aop_apply(int aop, real z, real w) {
 // What a compile-time pattern fixes (PAT_RUNTIME decides the same things from the launch arguments).
 template <int P>
 struct PatTraits {
-  static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MASKED || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
+  static constexpr bool gcn = (P == PAT_GCN || P == PAT_GCN_MAX || P == PAT_GCN_MIN);
   static constexpr bool dot = (P == PAT_DOT || P == PAT_DOT_MM);
   static constexpr bool dist = (P == PAT_DIST || P == PAT_DIST_MM);
   static constexpr bool family = dot || dist;                       // scalar steps read at run time
@@ -129,12 +129,13 @@ struct PatTraits {
   static constexpr bool uses_x = (!gcn && P != PAT_VISIT);
   static constexpr bool uses_val = (gcn || P == PAT_SIGNED_SIGMOID);
   static constexpr bool loads_y = (P != PAT_VISIT);
-  // rows may be narrower than the instance: pieces at or beyond a.d_pieces are neither loaded nor stored
-  static constexpr bool masked = (P == PAT_RUNTIME || P == PAT_GCN_MASKED || family);
+  // rows may be narrower than the instance whatever the launch says (the other patterns have a masked and an
+  // unmasked instance, chosen by kPatMasked)
+  static constexpr bool masked = (P == PAT_RUNTIME || family);
   // how messages are accumulated when it is fixed at compile time, and whether a row stored whole
   // may have to be divided by its length (mean pooling: a.mean)
   static constexpr int aop = (P == PAT_GCN_MAX || flips) ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
-  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_GCN_MASKED || P == PAT_DOT || P == PAT_DIST);
+  static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_DOT || P == PAT_DIST);
 };
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
@@ -489,7 +490,7 @@ __device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[
     if (CHECK && !valid) h = 0.f;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-      if constexpr (P == PAT_GCN || P == PAT_GCN_MASKED) {
+      if constexpr (P == PAT_GCN) {
         z[i] += h * y[i];
       } else {
         const vec4 w = h * y[i];
@@ -537,12 +538,14 @@ __device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[
 // One wavefront accumulates the stored entries [e0, e1) of a single row.  The S lane groups
 // take entries round-robin inside batches of 64; z holds this group's partial sum.
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int G, int U, int YF, int C>
+template <int PM, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0, int64_t e1,
                                                 const vec4 (&x)[D / (4 * G)], vec4 (&z)[D / (4 * G)], int lane) {
   constexpr int V = D / (4 * G);
   constexpr int S = 64 / G;
   static_assert(S * U <= 64 && 64 % (S * U) == 0, "unroll must tile a batch of 64 entries");
+  constexpr int P = PM & ~kPatMasked;
+  constexpr bool kMasked = PatTraits<P>::masked || (PM & kPatMasked) != 0;
   using T = PatTraits<P>;
   const int slot = lane / G;
   const int g = lane % G;
@@ -576,7 +579,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv);
         } else {
@@ -598,7 +601,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
+            if (ok[u]) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
@@ -617,11 +620,13 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 // column-class piece of a row); the S lane groups of the wavefront work on different runs in
 // lockstep, maxdeg being the longest of them (wave-uniform).
 // ---------------------------------------------------------------------------------------
-template <int P, int D, int G, int U, int YF, int C>
+template <int PM, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0, int deg, int maxdeg,
                                                  const vec4 (&x)[D / (4 * G)], vec4 (&z)[D / (4 * G)], int slot, int g, int nv,
                                                  bool use_val) {
   constexpr int V = D / (4 * G);
+  constexpr int P = PM & ~kPatMasked;
+  constexpr bool kMasked = PatTraits<P>::masked || (PM & kPatMasked) != 0;
   using T = PatTraits<P>;
   for (int bb = 0; bb < maxdeg; bb += G) {
     int colb = 0;
@@ -647,7 +652,7 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
         for (int u = 0; u < U; ++u) {
 #pragma unroll
           for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-          if (ok[u]) gather_row<YF, G, V, C, PatTraits<P>::masked>(a, c[u], g, y[u]);
+          if (ok[u]) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
@@ -709,10 +714,14 @@ __device__ __forceinline__ void store_row(const KernelArgs& a, real* dst, int g,
 // a run of stored entries of one row with a destination (the row of Z, or a partial row).
 // ---------------------------------------------------------------------------------------
 // E (always `real`) only makes the single- and double-precision instances of one shape different symbols.
-template <int P, int D, int GW0, int UW0, int GP0, int UP0, int YF, class E = real>
+// PM: the pattern, with kPatMasked set when the rows are narrower than D (pieces at or beyond a.d_pieces are
+// neither loaded nor stored; the run-time-ops and family instances always work that way).
+template <int PM, int D, int GW0, int UW0, int GP0, int UP0, int YF, class E = real>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   static_assert(sizeof(E) == sizeof(real), "the element type is fixed per translation unit");
+  constexpr int P = PM & ~kPatMasked;
   using T = PatTraits<P>;
+  constexpr bool kMasked = T::masked || (PM & kPatMasked) != 0;
   // Rows of 2-byte elements are read 16 bytes per lane where the lane group can be halved (it must
   // keep 8 lanes): same bytes in flight per wavefront, half as many load instructions.
   constexpr bool kWideW = YF != kYF32 && GW0 >= 16, kWideP = YF != kYF32 && GP0 >= 16;
@@ -752,8 +761,8 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     vec4 x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, ch.row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
+    if (reads_x<P>(a)) load_x<D, GW, CW, kMasked>(a, ch.row, g, x); else zero(x);
+    wave_accumulate<PM, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if (lane < GW) {
@@ -761,7 +770,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         for (int i = 0; i < V; ++i) stage[wave][piece_index<GW, CW>(g, i)] = z[i];
       }
       __syncthreads();
-      if (threadIdx.x < (T::masked ? a.d_pieces : D / 4)) {
+      if (threadIdx.x < (kMasked ? a.d_pieces : D / 4)) {
         vec4 s = stage[0][threadIdx.x];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) {
@@ -803,15 +812,15 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     vec4 x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, T::masked>(a, row, g, x); else zero(x);
-    wave_accumulate<P, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
+    if (reads_x<P>(a)) load_x<D, GW, CW, kMasked>(a, row, g, x); else zero(x);
+    wave_accumulate<PM, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
       if constexpr (T::flips) scale(z, a.sign);
       if constexpr (T::means) {
         if (a.mean && !from_desc) scale(z, (real)1 / (real)(e1 - e0));
       }
-      if (lane < GW) store_row<D, GW, CW, T::masked>(a, dst, g, z);
+      if (lane < GW) store_row<D, GW, CW, kMasked>(a, dst, g, z);
     }
   } else if (kind == kItemPacked) {
     // ---- one short segment per lane group ----------------------------------------------
@@ -849,27 +858,27 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
-        if (deg > 0) load_x<D, GP, CP, T::masked>(a, row, g, x);
+        if (deg > 0) load_x<D, GP, CP, kMasked>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
       if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
       if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
       if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
       maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
-      group_accumulate<P, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, use_val);
+      group_accumulate<PM, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, use_val);
       if constexpr (T::loads_y) {
         if constexpr (T::flips) scale(z, a.sign);
         if constexpr (T::means) {
           if (a.mean && !from_desc && deg > 0) scale(z, (real)1 / (real)deg);
         }
-        if (has_seg) store_row<D, GP, CP, T::masked>(a, dst, g, z);
+        if (has_seg) store_row<D, GP, CP, kMasked>(a, dst, g, z);
       }
     }
   }
   else if (kind == kItemZero) {
     // ---- rows without stored entries: z_u = 0 (Algorithm 1 initialises z_u and adds nothing) ----
     if constexpr (T::loads_y) {
-      const int kPieces = T::masked ? a.d_pieces : D / 4;
+      const int kPieces = kMasked ? a.d_pieces : D / 4;
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
       for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
         const int64_t row = rows[i / kPieces];

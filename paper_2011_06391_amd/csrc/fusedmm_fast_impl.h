@@ -30,19 +30,26 @@ int FMM_FN(packed_rows_per_block)(int y_format) {
   return kWavesPerBlock * (64 / gp);
 }
 
+// the instance for rows narrower than FMM_D: in the build's own element type only (2-byte storage of Y is
+// offered at the instance sizes), and only for the patterns that do not mask by themselves
+template <int P, int YF>
+static hipError_t launch_masked(const KernelArgs& a, hipStream_t stream) {
+  if constexpr (YF == kYF32) return launch_one<P | kPatMasked, kYF32>(a, stream);
+  return hipErrorInvalidValue;
+}
+
 template <int YF>
 static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t stream) {
-  switch (pattern) {
-    case PAT_SIGMOID: return launch_one<PAT_SIGMOID, YF>(a, stream);
-    case PAT_ONE_MINUS_SIGMOID: return launch_one<PAT_ONE_MINUS_SIGMOID, YF>(a, stream);
-    case PAT_GCN: return launch_one<PAT_GCN, YF>(a, stream);
-    case PAT_GCN_MASKED:  // dimensions between instance sizes exist in the build's own element type only
-      if constexpr (YF == kYF32) return launch_one<PAT_GCN_MASKED, kYF32>(a, stream);
-      return hipErrorInvalidValue;
-    case PAT_GCN_MAX: return launch_one<PAT_GCN_MAX, YF>(a, stream);
-    case PAT_GCN_MIN: return launch_one<PAT_GCN_MIN, YF>(a, stream);
-    case PAT_TDIST: return launch_one<PAT_TDIST, YF>(a, stream);
-    case PAT_FR: return launch_one<PAT_FR, YF>(a, stream);
+  const bool m = (pattern & kPatMasked) != 0;
+  switch (pattern & ~kPatMasked) {
+    case PAT_SIGMOID: return m ? launch_masked<PAT_SIGMOID, YF>(a, stream) : launch_one<PAT_SIGMOID, YF>(a, stream);
+    case PAT_ONE_MINUS_SIGMOID:
+      return m ? launch_masked<PAT_ONE_MINUS_SIGMOID, YF>(a, stream) : launch_one<PAT_ONE_MINUS_SIGMOID, YF>(a, stream);
+    case PAT_GCN: return m ? launch_masked<PAT_GCN, YF>(a, stream) : launch_one<PAT_GCN, YF>(a, stream);
+    case PAT_GCN_MAX: return m ? launch_masked<PAT_GCN_MAX, YF>(a, stream) : launch_one<PAT_GCN_MAX, YF>(a, stream);
+    case PAT_GCN_MIN: return m ? launch_masked<PAT_GCN_MIN, YF>(a, stream) : launch_one<PAT_GCN_MIN, YF>(a, stream);
+    case PAT_TDIST: return m ? launch_masked<PAT_TDIST, YF>(a, stream) : launch_one<PAT_TDIST, YF>(a, stream);
+    case PAT_FR: return m ? launch_masked<PAT_FR, YF>(a, stream) : launch_one<PAT_FR, YF>(a, stream);
     case PAT_RUNTIME: return launch_one<PAT_RUNTIME, YF>(a, stream);
     case PAT_DOT: return launch_one<PAT_DOT, YF>(a, stream);
     case PAT_DOT_MM: return launch_one<PAT_DOT_MM, YF>(a, stream);
@@ -52,7 +59,8 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
       if constexpr (YF == kYF32) return launch_one<PAT_VISIT, kYF32>(a, stream);
       return hipErrorInvalidValue;
     case PAT_SIGNED_SIGMOID:  // used by the minibatch layer on fp32 embeddings only
-      if constexpr (YF == kYF32 && !kDouble) return launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
+      if constexpr (YF == kYF32 && !kDouble)
+        return m ? launch_masked<PAT_SIGNED_SIGMOID, YF>(a, stream) : launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }

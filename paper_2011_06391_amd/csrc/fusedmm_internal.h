@@ -10,7 +10,6 @@ namespace fmm {
 // PAT_SIGNED_SIGMOID: the sigmoid embedding pattern with the scaling step h = a_uv - sigmoid(s) (kSopValueMinusSigmoid).
 // PAT_GCN_MAX / PAT_GCN_MIN: the GCN message (h = a_uv, w = h * y_v) pooled by maximum / minimum instead of
 // summed (the pooling variants of Section III-B); mean pooling runs PAT_GCN with the division at the store.
-// PAT_GCN_MASKED: PAT_GCN for a dimension between two instance sizes (pieces beyond the row are skipped).
 // PAT_DOT / PAT_DIST: two families of tuples with a scalar message, their vector loops fixed at compile time and
 // the scalar steps read at run time.  PAT_DOT: VOP = MUL, ROP = RSUM (s = x_u . y_v), any SOP on s, any MOP;
 // PAT_DIST: VOP = SUB or ADD, ROP = RSUM, SUMSQ or NORM2, any SOP, any MOP.  The plain ones accumulate by SUM
@@ -18,7 +17,10 @@ namespace fmm {
 // also serve the dimensions between two instance sizes for the application patterns they contain.
 enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST = 3, PAT_FR = 4, PAT_VISIT = 5, PAT_RUNTIME = 6,
              PAT_SIGNED_SIGMOID = 7, PAT_GCN_MAX = 8, PAT_GCN_MIN = 9, PAT_DOT = 10, PAT_DOT_MM = 11, PAT_DIST = 12,
-             PAT_DIST_MM = 13, PAT_GCN_MASKED = 14 };
+             PAT_DIST_MM = 13 };
+// pattern | kPatMasked: the instance of that pattern for a dimension between two instance sizes (pieces of a row
+// at or beyond KernelArgs::d_pieces are neither loaded nor stored); fp32 / fp64 storage only
+constexpr int kPatMasked = 32;
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
