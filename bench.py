@@ -140,7 +140,13 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     Xd = torch.from_numpy(w.X).cuda()
     Yd = Xd if w.Y is w.X else torch.from_numpy(w.Y).cuda()
     vd = None if g.values is None else torch.from_numpy(g.values).cuda()
-    Z = torch.empty((g.m, w.d), dtype=torch.float32, device="cuda")
+    f64 = y_storage == "f64"   # everything in double precision (secondary measurement)
+    if f64:
+        Xd = Xd.double()
+        Yd = Xd if w.Y is w.X else Yd.double()
+        vd = None if vd is None else vd.double()
+        with_context = False
+    Z = torch.empty((g.m, w.d), dtype=torch.float64 if f64 else torch.float32, device="cuda")
     uses_x = w.pattern != "gcn"
     ops = binding.fusedmm_ops_preset(w.pattern)
     ops.aop = binding.AOP[aop]   # the pattern's messages pooled another way (secondary measurements)
@@ -149,13 +155,16 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     t0 = time.perf_counter()
     custom_plan = bool(options)
     options = dict(options or {})
-    options.setdefault("feature_dim_hint", w.d)
-    if autotune:
+    options.setdefault("feature_dim_hint", 2 * w.d if f64 else w.d)   # the hint counts 4-byte elements
+    if autotune and not f64:
         plan = binding.Plan.tuned(g.m, g.n, rp, ci, ops, Xd if uses_x else None, Yd, Z, vd)
         options = plan.tuned_options
     else:
         plan = binding.Plan(g.m, g.n, rp, ci, options)
-    plan.reserve(w.d)
+    if f64:
+        plan.reserve_f64(w.d)
+    else:
+        plan.reserve(w.d)
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3
     if y_storage == "f32":   # inspection + the very first execute, as one figure (context, never part of `value`)
@@ -164,7 +173,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     plan_plus_first_execute_ms = (time.perf_counter() - t0) * 1e3
 
     Yb = None
-    y_bf16 = y_storage != "f32"  # any 2-byte storage of Y
+    y_bf16 = y_storage in ("bf16", "f16")  # any 2-byte storage of Y
     if y_bf16:  # optional storage mode, never the default: Y rounded once to bfloat16 / half, arithmetic stays fp32
         Yb = torch.empty((g.n, w.d), dtype=torch.int16, device="cuda")
         (binding.fusedmm_to_bf16 if y_storage == "bf16" else binding.fusedmm_to_f16)(Yb, Yd, g.n * w.d)
@@ -200,13 +209,14 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
     Z_sample = Z[torch.from_numpy(sample_rows).cuda()].cpu().numpy()  # rows of the timed result, checked on the CPU leg
 
     ms_per_step = elapsed * 1e3 / steps
-    tr = model.traffic(g.m, g.n, g.nnz, w.d, uses_x, vd is not None, w.Y is w.X, y_bytes=2 if y_bf16 else 4)
+    tr = model.traffic(g.m, g.n, g.nnz, w.d, uses_x, vd is not None, w.Y is w.X, y_bytes=2 if y_bf16 else 0,
+                       elem_bytes=8 if f64 else 4)
     kernel_ms = (kernel_ms_sum - empty_ms_sum) / max(1, calls)  # bracket cost measured by an empty bracket per call
     if kernel_ms <= 0.0:  # a kernel of a few microseconds can vanish in the bracket's own jitter
         kernel_ms = kernel_ms_sum / max(1, calls)
     kernel_s = kernel_ms * 1e-3
     stats = plan.stats()
-    if y_bf16 or not relabel:
+    if y_bf16 or f64 or not relabel:
         traffic_bytes, l2_hit, traffic_source = None, None, "not measured for this storage mode / vertex order"
     else:
         traffic_bytes, l2_hit, traffic_source = measured_traffic(workload if not d else f"{workload}:d{w.d}", stats)
@@ -222,7 +232,7 @@ def run(workload: str, steps: int, warmup: int, with_cpu: bool, options=None, d=
         "unit": "G(edge*dim)/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": f"f32 (Y stored as {y_storage})" if y_bf16 else "f32", "data": "synthetic",
+        "dtype": f"f32 (Y stored as {y_storage})" if y_bf16 else y_storage, "data": "synthetic",
         "config": {"workload": workload, "description": w.description, "pattern": w.pattern, "aop": aop,
                    "vertex_order": "seeded random permutation" if relabel else "as generated (natural order)",
                    "n": g.m, "nnz": g.nnz, "d": w.d, "max_degree": int(deg.max()),
@@ -460,6 +470,8 @@ def main():
                     help="optional storage mode: gather Y from an IEEE half copy (not the headline configuration)")
     ap.add_argument("--y-bf16", action="store_true",
                     help="optional storage mode: gather Y from a bfloat16 copy (not the headline configuration)")
+    ap.add_argument("--f64", action="store_true",
+                    help="the whole step in double precision through fusedmm_execute_f64 (not the headline configuration)")
     ap.add_argument("--column-classes", type=int, default=0)
     ap.add_argument("--tile-row-min", type=int, default=0)
     args = ap.parse_args()
@@ -476,7 +488,7 @@ def main():
         options = {"small_row_max": args.small_row_max, "split_row_min": args.split_row_min,
                    "chunk_edges": args.chunk_edges, "column_classes": args.column_classes,
                    "tile_row_min": args.tile_row_min}
-    y_storage = "bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32")
+    y_storage = "f64" if args.f64 else ("bf16" if args.y_bf16 else ("f16" if args.y_f16 else "f32"))
     out = run(workload, args.steps, args.warmup, not args.no_cpu_baseline, options, args.d,
               args.copy_calibration_mib, args.autotune, y_storage, not args.no_context, not args.natural_order,
               aop=args.aop)

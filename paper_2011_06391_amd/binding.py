@@ -378,21 +378,23 @@ class Plan:
         fusedmm_execute(self._plan, ops, d, values, X, ldx, Y, Y.stride(0), Z, Z.stride(0), stream)
 
     def bind(self, ops, X, Y, Z, values=None, stream=None, y_format: str = "f32"):
-        """The same call as execute / execute_bf16y / execute_f16y with the arguments marshalled once: returns
+        """The same call as execute / execute_bf16y / execute_f16y / execute_f64 with the arguments marshalled once: returns
         a function of no arguments that issues it (for loops that repeat one call: per-call cost is the C
         call alone).  The stream is the one given, or the current stream at the time of binding; the tensors
         are kept alive by the returned function."""
         if isinstance(ops, str):
             ops = fusedmm_ops_preset(ops)
-        if y_format not in ("f32", "bf16", "f16"):
-            raise ValueError("y_format must be 'f32', 'bf16' or 'f16'")
-        for t in (X, Z, values) + ((Y,) if y_format == "f32" else ()):
-            if t is not None and not (t.is_cuda and str(t.dtype) == "torch.float32" and (t.dim() < 2 or t.stride(-1) == 1)):
-                raise TypeError("operands must be CUDA float32 tensors with unit stride along the feature dimension")
-        if y_format != "f32" and not (Y.is_cuda and Y.element_size() == 2 and Y.stride(-1) == 1):
+        if y_format not in ("f32", "bf16", "f16", "f64"):
+            raise ValueError("y_format must be 'f32', 'bf16', 'f16' or 'f64' (everything in double precision)")
+        want = "torch.float64" if y_format == "f64" else "torch.float32"
+        for t in (X, Z, values) + ((Y,) if y_format in ("f32", "f64") else ()):
+            if t is not None and not (t.is_cuda and str(t.dtype) == want and (t.dim() < 2 or t.stride(-1) == 1)):
+                raise TypeError(f"operands must be CUDA {want[6:]} tensors with unit stride along the feature dimension")
+        if y_format in ("bf16", "f16") and not (Y.is_cuda and Y.element_size() == 2 and Y.stride(-1) == 1):
             raise TypeError("Y must be a CUDA tensor of 2-byte elements with unit stride along the feature dimension")
         lib = load()
-        fn = {"f32": lib.fusedmm_execute, "bf16": lib.fusedmm_execute_bf16y, "f16": lib.fusedmm_execute_f16y}[y_format]
+        fn = {"f32": lib.fusedmm_execute, "bf16": lib.fusedmm_execute_bf16y, "f16": lib.fusedmm_execute_f16y,
+              "f64": lib.fusedmm_execute_f64}[y_format]
         args = (self._plan, ctypes.byref(ops), int(Z.shape[1]), _dptr(values), _dptr(X), 0 if X is None else X.stride(0),
                 _dptr(Y), Y.stride(0), _dptr(Z), Z.stride(0), _stream(stream))
         keep = (ops, X, Y, Z, values, self)

@@ -992,7 +992,15 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     a.values = reinterpret_cast<const float*>(d_values); a.X = reinterpret_cast<const float*>(d_X); a.Y = d_Y;
     a.Z = reinterpret_cast<float*>(d_Z);
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
+    if (plan->profiling && plan->events_used < plan->events.size()) {
+      ev0 = plan->events[plan->events_used].before;
+      ev1 = plan->events[plan->events_used].after;
+      ev2 = plan->events[plan->events_used].after2;
+    }
+    if (ev0) (void)hipEventRecord(ev0, stream);
     hipError_t e = launch_fast(pattern, D, kYF64, a, stream);
+    if (ev0) { (void)hipEventRecord(ev1, stream); (void)hipEventRecord(ev2, stream); ++plan->events_used; }
     if (e == hipSuccess)
       e = launch_merge(plan->d_merges, plan->n_merges, reinterpret_cast<const double*>(plan->d_partials), d, D, ops->aop,
                        plan->d_rowptr, d_Z, ldz, stream);

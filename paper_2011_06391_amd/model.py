@@ -36,18 +36,20 @@ class Traffic:
 
 
 def traffic(m: int, n: int, nnz: int, d: int, uses_x: bool, uses_values: bool,
-            x_is_y: bool, y_bytes: int = 4) -> Traffic:
-    """Algorithmic traffic with fp32 data, int32 colidx, int64 rowptr.
+            x_is_y: bool, y_bytes: int = 0, elem_bytes: int = 4) -> Traffic:
+    """Algorithmic traffic with fp32 data (elem_bytes = 8: fp64), int32 colidx, int64 rowptr.
 
     per stored entry : 4 (colidx) + 4d (row of Y; 2d when Y is stored as bfloat16) [+ 4 (edge value)]
     per row          : 8 (rowptr) + 4d (store z_u) [+ 4d (load x_u)]
     """
-    per_edge = 4 + y_bytes * d + (4 if uses_values else 0)
-    per_row = 8 + 4 * d + (4 * d if uses_x else 0)
+    e = elem_bytes
+    y_bytes = y_bytes or e
+    per_edge = 4 + y_bytes * d + (e if uses_values else 0)
+    per_row = 8 + e * d + (e * d if uses_x else 0)
     model = nnz * per_edge + m * per_row
-    mn = nnz * (4 + (4 if uses_values else 0)) + 8 * m + y_bytes * n * d + 4 * m * d
-    if uses_x and (not x_is_y or y_bytes != 4):
-        mn += 4 * m * d
+    mn = nnz * (4 + (e if uses_values else 0)) + 8 * m + y_bytes * n * d + e * m * d
+    if uses_x and (not x_is_y or y_bytes != e):
+        mn += e * m * d
     flops = nnz * (4 * d if uses_x else 2 * d)
     return Traffic(per_edge, per_row, model, mn, flops)
 
