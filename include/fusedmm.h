@@ -136,9 +136,11 @@ typedef struct fusedmm_plan_options {
                               within the long rows, else it is skipped. */
   int32_t tile_row_min;    /* rows with >= this many entries are cut into 8 classes, with twice as many
                               into 16, and so on; 0 = 128 (16 entries per class) */
-  int32_t feature_dim_hint;/* feature dimension the plan will mostly run with: used by the automatic
-                              choice of column_classes, and fusedmm_plan_create reserves the scratch
-                              for it (as fusedmm_plan_reserve does); 0 = 128 */
+  int32_t feature_dim_hint;/* feature dimension the plan will mostly run with, in 4-byte elements (a plan
+                              for fusedmm_execute_f64 passes twice its dimension; for 2-byte storage of Y
+                              the fp32 dimension still does well): used by the automatic choice of
+                              column_classes, and fusedmm_plan_create reserves the scratch for it (as
+                              fusedmm_plan_reserve does); 0 = 128 */
   int32_t reserved[2];
 } fusedmm_plan_options_t;
 
