@@ -135,7 +135,8 @@ typedef struct fusedmm_plan_options {
                               0 = automatic (off while Y is small), 1 = off.  Needs column indices sorted
                               within the long rows, else it is skipped. */
   int32_t tile_row_min;    /* rows with >= this many entries are cut into 8 classes, with twice as many
-                              into 16, and so on; 0 = 128 (16 entries per class) */
+                              into 16, and so on; 0 = 128 (16 entries per class), 64 on patterns with
+                              128 or more stored entries per row on average */
   int32_t feature_dim_hint;/* feature dimension the plan will mostly run with, in 4-byte elements (a plan
                               for fusedmm_execute_f64 passes twice its dimension; for 2-byte storage of Y
                               the fp32 dimension still does well): used by the automatic choice of

@@ -68,7 +68,7 @@ def test_offsets_beyond_2_to_31(B):
     ci = (torch.from_numpy(first).cuda()[rows.long()] + k * torch.from_numpy(step).cuda()[rows.long()]).to(torch.int32)
     del rows, k
     assert int(ci.max()) < n and int(ci.min()) >= 0
-    plan = B.Plan(m, n, rp, ci)
+    plan = B.Plan(m, n, rp, ci, {"tile_row_min": 128})   # (a pattern this dense would tile from 64 entries: no wave rows)
     st = plan.stats()
     assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0 and st["column_classes"] > 1
 
