@@ -15,7 +15,7 @@ struct fusedmm_plan {
   int64_t m = 0, n = 0, nnz = 0;
   const int64_t* d_rowptr = nullptr;
   const int32_t* d_colidx = nullptr;
-  int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0;
+  int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0, tile_row_min = 0;  // as resolved
   int32_t n_wave = 0, n_packed = 0, n_empty = 0, n_chunks = 0, n_merges = 0, n_parts = 0;  // n_packed: non-empty
   int32_t n_items = 0, n_tile_descs = 0, n_tiled_rows = 0, n_classes = 1;
   int32_t* d_order = nullptr;
@@ -427,7 +427,7 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   if (!p) return FUSEDMM_ERR_ALLOC;
   p->m = m; p->n = n; p->nnz = nnz;
   p->d_rowptr = d_rowptr; p->d_colidx = d_colidx;
-  p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk;
+  p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk; p->tile_row_min = tile_min;
 
   std::vector<int32_t> order;
   std::vector<ChunkDesc> chunks, tile_descs;
@@ -1230,6 +1230,7 @@ int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_
     chosen->split_row_min = best->split_row_min;
     chosen->chunk_edges = best->chunk_edges;
     chosen->column_classes = best->n_classes;
+    chosen->tile_row_min = best->tile_row_min;
   }
   if (best_ms) *best_ms = best_time;
   return FUSEDMM_OK;

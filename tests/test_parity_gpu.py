@@ -541,6 +541,7 @@ def test_tuned_plan_is_a_valid_plan(B):
     plan = B.Plan.tuned(g.m, g.n, rp, ci, "one_minus_sigmoid", Xd, Xd, Z)
     assert plan.tuned_ms > 0 and plan.tuned_options["column_classes"] in (1, 8, 16, 32, 64, 128)
     assert plan.tuned_options["chunk_edges"] in (512, 1024, 2048) and plan.tuned_options["split_row_min"] in (256, 512, 1024)
+    assert plan.tuned_options["tile_row_min"] in (64, 128, 256)     # reported as resolved, never as the 0 that asks for the default
     Z.fill_(float("nan"))
     plan.execute("one_minus_sigmoid", Xd, Xd, Z)
     torch.cuda.synchronize()
