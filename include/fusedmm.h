@@ -263,8 +263,8 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic (the sigmoid's exponential, reciprocals and square
  * roots are the correctly rounded library ones, not the fp32 hardware approximations).  Multiples of 4
- * up to d = 256 with 32-byte aligned X, Y, Z and leading dimensions that are multiples of 4 run the
- * specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256; a dimension
+ * up to d = 512 with 32-byte aligned X, Y, Z and leading dimensions that are multiples of 4 run the
+ * specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; a dimension
  * in between runs on the next larger one); everything else -- any 1 <= d <= FUSEDMM_MAX_D, any alignment
  * -- runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
  * way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan

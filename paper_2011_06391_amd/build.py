@@ -29,6 +29,7 @@ SOURCES = [
     "fusedmm_fast_f64_d64.hip",
     "fusedmm_fast_f64_d128.hip",
     "fusedmm_fast_f64_d256.hip",
+    "fusedmm_fast_f64_d512.hip",
 ]
 
 # packed FP32 instructions are switched off for all device code

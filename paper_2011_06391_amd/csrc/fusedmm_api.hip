@@ -106,19 +106,16 @@ int32_t instance_dim(int32_t d) {
   return D;
 }
 
-// The same for double precision: instances of 32, 64, 128 and 256 elements.
-int32_t instance_dim_f64(int32_t d) {
-  const int32_t D = instance_dim(d);
-  return D > 256 ? 0 : D;
-}
+// The same for double precision: the same five sizes.
+int32_t instance_dim_f64(int32_t d) { return instance_dim(d); }
 
 // How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
 // fp32 (the largest instance size among them, and the short-vector kernels' fixed stride) ...
 int32_t partial_floats_f32(int32_t d) {
   return std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
 }
-// ... and in fp64 (two floats per element; nothing above 256 runs on the specialised schedule)
-int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 256 ? 256 : instance_dim_f64(d / 4 * 4)); }
+// ... and in fp64 (two floats per element)
+int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 512 ? 512 : instance_dim_f64(d / 4 * 4)); }
 
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value

@@ -412,7 +412,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
   hipError_t launch_fast##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
   int packed_rows_per_block##D(int y_format);
 FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512)
-FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256)
+FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256) FMM_DECL(_f64_d512)
 #undef FMM_DECL
 
 int packed_rows_per_block(int d, int y_format) {
@@ -422,6 +422,7 @@ int packed_rows_per_block(int d, int y_format) {
       case 64: return packed_rows_per_block_f64_d64(kYF32);
       case 128: return packed_rows_per_block_f64_d128(kYF32);
       case 256: return packed_rows_per_block_f64_d256(kYF32);
+      case 512: return packed_rows_per_block_f64_d512(kYF32);
       default: return 0;
     }
   }
@@ -442,6 +443,7 @@ hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hi
       case 64: return launch_fast_f64_d64(pattern, kYF32, a, stream);
       case 128: return launch_fast_f64_d128(pattern, kYF32, a, stream);
       case 256: return launch_fast_f64_d256(pattern, kYF32, a, stream);
+      case 512: return launch_fast_f64_d512(pattern, kYF32, a, stream);
       default: return hipErrorInvalidValue;
     }
   }
