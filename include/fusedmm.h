@@ -52,10 +52,13 @@ extern "C" {
 #define FUSEDMM_VERSION 100 /* 0.1.0 */
 
 /* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
- * paper's sweep, Table VI) with 16-byte aligned rows runs the specialised
- * kernels, every other multiple of 4 up to 512 the same schedule on the next
- * larger of them; any other 1 <= d <= FUSEDMM_MAX_D runs the general kernel
- * (see fusedmm_ops_t below). */
+ * paper's sweep, Table VI) runs the specialised kernels, every other d from 9
+ * to 512 the same schedule on the next larger of them, d = 2, 3, 4, 8, 16
+ * kernels of their own; any other 1 <= d <= FUSEDMM_MAX_D runs the general
+ * kernel (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
+ * element: no alignment beyond that of a float is asked of the fp32 entry
+ * points (aligned rows are read fastest: a row that straddles cache lines
+ * costs up to a quarter more). */
 #define FUSEDMM_MAX_D 2048
 
 typedef enum fusedmm_status {
@@ -99,10 +102,12 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
  * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
  * The five application patterns below, and the GCN pattern with MAX, MIN or MEAN pooling instead of
- * the sum, run the specialised kernels when d is 32, 64, 128, 256 or 512; every other tuple, and
- * every other d that is a multiple of 4 up to 512, runs the same
- * schedule with the ops read at run time (on the next larger kernel size, skipping the columns
- * beyond d); any other d up to FUSEDMM_MAX_D, or operands that are not 16-byte aligned, run the
+ * the sum, run kernels of their own when d is 32, 64, 128, 256 or 512, and masked forms of them
+ * (on the next larger size, skipping what lies beyond d) at the other multiples of 4; tuples with a
+ * scalar message from a dot product or from the sum / difference of the operands run two families of
+ * kernels with their vector loops fixed; every other tuple runs the same schedule with the ops read at
+ * run time.  A d from 9 to 512 that is not a multiple of 4 runs the families, the GCN kernels or the
+ * run-time-ops kernel in a form that masks down to the element.  d above 512 (and 1, 5, 6, 7) runs the
  * general kernel (one wavefront per row or per 256-entry segment of a long row: a correctness path,
  * an order of magnitude slower). */
 typedef struct fusedmm_ops {
@@ -142,7 +147,10 @@ typedef struct fusedmm_plan_options {
                               the fp32 dimension still does well): used by the automatic choice of
                               column_classes, and fusedmm_plan_create reserves the scratch for it (as
                               fusedmm_plan_reserve does); 0 = 128 */
-  int32_t reserved[2];
+  int32_t general_kernel_only; /* non-zero: every fp32 / fp64 execute of this plan runs the general kernel
+                              (one wavefront per row or 256-entry segment, any d), whatever the dimension
+                              and alignment: the slow, simple path, kept selectable for cross-checks */
+  int32_t reserved[1];
 } fusedmm_plan_options_t;
 
 typedef struct fusedmm_plan fusedmm_plan_t;
@@ -262,11 +270,10 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic (the sigmoid's exponential, reciprocals and square
- * roots are the correctly rounded library ones, not the fp32 hardware approximations).  Multiples of 4
- * up to d = 512 with 32-byte aligned X, Y, Z and leading dimensions that are multiples of 4 run the
- * specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; a dimension
- * in between runs on the next larger one); everything else -- any 1 <= d <= FUSEDMM_MAX_D, any alignment
- * -- runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
+ * roots are the correctly rounded library ones, not the fp32 hardware approximations).  d from 9 to 512
+ * runs the specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; a
+ * dimension in between runs on the next larger one; rows may start at any element); every other
+ * 1 <= d <= FUSEDMM_MAX_D runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
  * way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan
  * with split rows needs fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise):
  * fusedmm_plan_create reserves for fp32 rows only. */
@@ -333,8 +340,7 @@ int fusedmm_plan_destroy(fusedmm_plan_t* plan);
  *          required before the first epoch with a dimension above any reserved so far
  *          (fusedmm_minibatch_epoch never allocates: FUSEDMM_ERR_NOT_RESERVED otherwise).
  * epoch  : one pass over all batches, asynchronous on `stream`, in place on d_X (n rows, leading
- *          dimension ldx >= d).  Any 1 <= d <= FUSEDMM_MAX_D; d in {32,...,512} with 16-byte aligned
- *          rows runs the specialised kernels.  Overlapping epochs on one handle must be on one stream.
+ *          dimension ldx >= d).  Any 1 <= d <= FUSEDMM_MAX_D; dispatch as for fusedmm_execute.  Overlapping epochs on one handle must be on one stream.
  * info   : number of batches and of kernel launches one epoch issues (host pointers, may be NULL).
  * Errors as elsewhere: a status is returned and nothing is launched for the failing batch. */
 typedef struct fusedmm_minibatch fusedmm_minibatch_t;

@@ -18,6 +18,7 @@ struct fusedmm_plan {
   int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0, tile_row_min = 0;  // as resolved
   int32_t n_wave = 0, n_packed = 0, n_empty = 0, n_chunks = 0, n_merges = 0, n_parts = 0;  // n_packed: non-empty
   int32_t n_items = 0, n_tile_descs = 0, n_tiled_rows = 0, n_classes = 1;
+  bool general_only = false;  // every execute runs the general kernel
   int32_t* d_order = nullptr;
   ChunkDesc* d_chunks = nullptr;
   BlockItem* d_items = nullptr;
@@ -96,11 +97,13 @@ constexpr size_t kMaxProfiledCalls = 4096;
 
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
 
-// The instance size a dimension runs on: itself if it has instances of its own, else the next larger
-// one (multiples of 4 up to 512: the run-time-ops instance then skips the pieces beyond d), else 0.
+// The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
+// dimension from kMinWideDim up to 512: the masked instances skip what lies beyond d, element by element in the
+// last piece when d is not a multiple of 4), else 0.
+constexpr int32_t kMinWideDim = 9;
 int32_t instance_dim(int32_t d) {
   if (is_fast_dim(d)) return d;
-  if (d < 4 || d > 512 || d % 4 != 0) return 0;
+  if (d < kMinWideDim || d > 512) return 0;
   int32_t D = 32;
   while (D < d) D *= 2;
   return D;
@@ -112,10 +115,10 @@ int32_t instance_dim_f64(int32_t d) { return instance_dim(d); }
 // How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
 // fp32 (the largest instance size among them, and the short-vector kernels' fixed stride) ...
 int32_t partial_floats_f32(int32_t d) {
-  return std::max<int32_t>(d >= 512 ? 512 : instance_dim(d / 4 * 4), kSmallPartialStride);
+  return std::max<int32_t>(d >= 512 ? 512 : instance_dim(d), kSmallPartialStride);
 }
 // ... and in fp64 (two floats per element)
-int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 512 ? 512 : instance_dim_f64(d / 4 * 4)); }
+int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 512 ? 512 : instance_dim_f64(d)); }
 
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value
@@ -167,13 +170,18 @@ int recognise_family(const fusedmm_ops_t& o) {
 // Which instance of the specialised kernel an op tuple runs on: a recognised pattern its own (the masked form of
 // it when the dimension lies between two instance sizes), else the tuple family it belongs to, else the one that
 // reads its ops at run time.
-int choose_pattern(int recognised, int family, bool exact_dim) {
-  if (recognised >= 0) return exact_dim ? recognised : (recognised | kPatMasked);
+int choose_pattern(int recognised, int family, int32_t d, int32_t D) {
+  if (d % 4 != 0) {
+    // rows that end inside a 16-byte piece: the GCN messages, the two tuple families (which hold the other
+    // application patterns) and the run-time-ops instance exist in a form that masks down to the element
+    if (recognised == PAT_GCN || recognised == PAT_GCN_MAX || recognised == PAT_GCN_MIN) return recognised | kPatRagged;
+    return (family >= 0 ? family : PAT_RUNTIME) | kPatRagged;
+  }
+  if (recognised >= 0) return D == d ? recognised : (recognised | kPatMasked);
   return family >= 0 ? family : PAT_RUNTIME;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-bool aligned32(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 31u) == 0; }
 
 bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int64_t rows_b, int64_t ld_b, int32_t d) {
   if (!a || !b || rows_a <= 0 || rows_b <= 0) return false;
@@ -425,6 +433,7 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
   p->m = m; p->n = n; p->nnz = nnz;
   p->d_rowptr = d_rowptr; p->d_colidx = d_colidx;
   p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk; p->tile_row_min = tile_min;
+  p->general_only = options && options->general_kernel_only != 0;
 
   std::vector<int32_t> order;
   std::vector<ChunkDesc> chunks, tile_descs;
@@ -816,16 +825,16 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
   // structure with the ops decided at run time; odd shapes fall back to the general kernel
   // a dimension between two instance sizes runs the run-time-ops instance of the next larger size (fp32 storage only)
-  const bool small = !y_bf16 && is_small_dim(d);  // one lane per stored entry; rows need no alignment beyond 4 bytes
+  const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry
   const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);
   const int family = recognise_family(*ops);
-  const int pattern = choose_pattern(recognised, family, D == d);
-  const bool y_ok = plan->nnz == 0 || (y_bf16 ? (aligned16(d_Y) && ldy % 8 == 0)
-                                              : (aligned16(d_Y) && ldy % 4 == 0));
+  const int pattern = choose_pattern(recognised, family, d, D);
+  // fp32 rows may start anywhere (the kernels read and write them as element-aligned vectors); rows of 2-byte
+  // elements are read 16 bytes at a time and have to be aligned to that
+  const bool y_ok = plan->nnz == 0 || !y_bf16 || (aligned16(d_Y) && ldy % 8 == 0);
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
-  const bool fast = D != 0 && ldy < (int64_t(1) << 29) && aligned16(d_Z) && (ldz % 4 == 0) && y_ok &&
-                    (!uses_x || (aligned16(d_X) && ldx % 4 == 0));
+  const bool fast = D != 0 && ldy < (int64_t(1) << 29) && y_ok && (y_bf16 || !plan->general_only);
   if (y_bf16 && !fast) return is_fast_dim(d) ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
@@ -846,7 +855,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     KernelArgs a;
     fill_schedule_args(plan, d, kYF32, &a);
     a.partials = partials;
-    a.d_pieces = 0;
+    a.d_pieces = a.d_full = a.d_tail = 0;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
@@ -868,7 +877,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     KernelArgs a;
     fill_schedule_args(plan, D, y_format, &a);
     a.partials = partials;
-    a.d_pieces = d / 4;
+    a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     fill_op_args(*ops, &a);
@@ -978,17 +987,16 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
   // the specialised schedule in double precision: the same dispatch as fp32 (a recognised pattern at an instance
   // size, else its tuple family, else the ops at run time) on row registers of four doubles
   const int32_t D = instance_dim_f64(d);
-  const bool fast = D != 0 && ldy < (int64_t(1) << 28) && aligned32(d_Z) && ldz % 4 == 0 &&
-                    (plan->nnz == 0 || (aligned32(d_Y) && ldy % 4 == 0)) && (!uses_x || (aligned32(d_X) && ldx % 4 == 0));
+  const bool fast = D != 0 && ldy < (int64_t(1) << 28) && !plan->general_only;
   if (fast) {
     if (plan->n_parts > 0 && 2 * D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
     const int recognised = recognise(*ops);
     const int family = recognise_family(*ops);
-    const int pattern = choose_pattern(recognised, family, D == d);
+    const int pattern = choose_pattern(recognised, family, d, D);
     KernelArgs a;
     fill_schedule_args(plan, D, kYF64, &a);
     fill_op_args(*ops, &a);
-    a.d_pieces = d / 4;
+    a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     // the pointers travel under their fp32 names; the double-precision instances read them as doubles
     a.values = reinterpret_cast<const float*>(d_values); a.X = reinterpret_cast<const float*>(d_X); a.Y = d_Y;
     a.Z = reinterpret_cast<float*>(d_Z);
@@ -1051,7 +1059,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
-    a.d_pieces = d / 4;
+    a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     a.visit_counts = d_counts;
     e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(PAT_VISIT, D, fmt, a, stream);
   } else {

@@ -27,6 +27,10 @@ typedef double real;
 typedef float real;
 #endif
 typedef real vec4 __attribute__((ext_vector_type(4)));
+// The same four elements where they lie in global memory: rows of X, Y and Z only have to be aligned to one
+// element (any leading dimension, any column offset).  The hardware takes a 16-byte access at any 4-byte address,
+// so this costs nothing where the rows are aligned; in LDS and registers the natural alignment stays.
+typedef real vec4g __attribute__((ext_vector_type(4), aligned(sizeof(real))));
 
 // the typed views of the untyped-by-precision pointers of KernelArgs
 __device__ __forceinline__ const real* values_of(const KernelArgs& a) { return reinterpret_cast<const real*>(a.values); }
@@ -137,6 +141,14 @@ struct PatTraits {
   static constexpr int aop = (P == PAT_GCN_MAX || flips) ? FUSEDMM_AOP_MAX : (P == PAT_GCN_MIN ? FUSEDMM_AOP_MIN : FUSEDMM_AOP_SUM);
   static constexpr bool means = (P == PAT_RUNTIME || P == PAT_GCN || P == PAT_DOT || P == PAT_DIST);
 };
+// How an instance treats rows narrower than its size: not at all, by whole 4-element pieces, or down to the
+// element.
+enum : int { kMaskNone = 0, kMaskPieces = 1, kMaskRagged = 2 };
+template <int PM>
+constexpr int mask_mode() {
+  if ((PM & kPatRagged) != 0) return kMaskRagged;
+  return (PatTraits<(PM & ~(kPatMasked | kPatRagged))>::masked || (PM & kPatMasked) != 0) ? kMaskPieces : kMaskNone;
+}
 // Sum of the same lane-in-group position over all S = 64/G groups of the wavefront.
 template <int G>
 __device__ __forceinline__ real cross_group_allreduce(real v) {
@@ -178,7 +190,25 @@ __device__ __forceinline__ void combine_groups(const KernelArgs& a, vec4 (&z)[V]
   }
 }
 
-__device__ __forceinline__ vec4 ld4(const real* p) { return *reinterpret_cast<const vec4*>(p); }
+__device__ __forceinline__ vec4 ld4(const real* p) { return *reinterpret_cast<const vec4g*>(p); }
+
+// The last piece of a row whose length is not a multiple of 4: its first `tail` (1..3) elements, the rest zero /
+// untouched.  Element by element, so that nothing beyond the end of the row (and of the matrix) is touched.
+__device__ __forceinline__ vec4 ld_tail(const real* p, int tail) {
+  vec4 v = {0.f, 0.f, 0.f, 0.f};
+  v.x = p[0];
+  if (tail > 1) v.y = p[1];
+  if (tail > 2) v.z = p[2];
+  return v;
+}
+__device__ __forceinline__ void st_tail(real* p, const vec4& v, int tail) {
+  __builtin_nontemporal_store(v.x, p);
+  if (tail > 1) __builtin_nontemporal_store(v.y, p + 1);
+  if (tail > 2) __builtin_nontemporal_store(v.z, p + 2);
+}
+__device__ __forceinline__ void st4(real* p, const vec4& v) {
+  __builtin_nontemporal_store(static_cast<vec4g>(v), reinterpret_cast<vec4g*>(p));
+}
 
 // Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YF = kYF32: Y is fp32, one
 // 16-byte load.  YF = kYBf16: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
@@ -200,7 +230,7 @@ __device__ __forceinline__ vec4 gather4(const void* Y, int col, int64_t ldy, int
     const v4h raw = *reinterpret_cast<const v4h*>(p);
     return vec4{(float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w};
   } else {
-    return *reinterpret_cast<const vec4*>(p);
+    return *reinterpret_cast<const vec4g*>(p);
   }
 }
 
@@ -217,13 +247,21 @@ __device__ __forceinline__ int piece_index(int g, int i) {
 // 8-byte loads need, and it is the number of load instructions that occupies the return path.
 // M: pieces at or beyond a.d_pieces are left at zero instead of being loaded (the run-time-ops instance
 // on a dimension below its own).
-template <int YF, int G, int V, int C, bool M>
+template <int YF, int G, int V, int C, int M>
 __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, vec4 (&y)[V]) {
   if constexpr (C == 1) {
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-      if (!M || g + G * i < a.d_pieces) y[i] = gather4<YF>(a.Y, col, a.ldy, g + G * i);
-      else y[i] = vec4{0.f, 0.f, 0.f, 0.f};
+      const int piece = g + G * i;
+      if (M == kMaskNone || piece < (M == kMaskRagged ? a.d_full : a.d_pieces)) {
+        y[i] = gather4<YF>(a.Y, col, a.ldy, piece);
+      } else if (M == kMaskRagged && YF == kYF32 && piece < a.d_pieces) {  // the row ends inside this piece
+        const uint32_t pitch = (uint32_t)a.ldy * (uint32_t)sizeof(real);
+        y[i] = ld_tail(reinterpret_cast<const real*>(static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch) + 4 * piece,
+                       a.d_tail);
+      } else {
+        y[i] = vec4{0.f, 0.f, 0.f, 0.f};
+      }
     }
   } else {
     static_assert(YF != kYF32 && V % 2 == 0, "16-byte chunks of 2-byte elements");
@@ -231,7 +269,7 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
     const char* base = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
 #pragma unroll
     for (int j = 0; j < V / 2; ++j) {
-      if (M && 2 * (g + G * j) + 1 >= a.d_pieces) {
+      if (M != kMaskNone && 2 * (g + G * j) + 1 >= a.d_pieces) {
         y[2 * j] = y[2 * j + 1] = vec4{0.f, 0.f, 0.f, 0.f};
         continue;
       }
@@ -259,7 +297,8 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
 // the plan from the entry counts of the columns) raised the L2 hit rate by 3.5 points and cost 15-100 %.
 template <class T>
 __device__ __forceinline__ T ld_stream(const T* p) { return *p; }
-__device__ __forceinline__ vec4 ld4_stream(const real* p) { return *reinterpret_cast<const vec4*>(p); }
+__device__ __forceinline__ vec4 ld4_stream(const real* p) { return *reinterpret_cast<const vec4g*>(p); }
+
 
 // ---------------------------------------------------------------------------------------
 // per-entry arithmetic: VOP, ROP, SOP, MOP, AOP for one stored entry, on one lane group
@@ -305,7 +344,7 @@ __device__ __forceinline__ real sop_scale(const KernelArgs& a) {
 
 template <int P, int G, int V, bool CHECK>
 __device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[V], real aval, const KernelArgs& a,
-                                            bool valid, vec4 (&z)[V], int nv = V) {
+                                            bool valid, vec4 (&z)[V], int nv = V, int lane_tail = 0) {
   const real alpha = a.alpha;
   if constexpr (P == PAT_RUNTIME) {
     // Every op of the selector, the five steps in order.  The selectors are wave-uniform, so each
@@ -335,7 +374,12 @@ __device__ __forceinline__ void edge_update(const vec4 (&x)[V], const vec4 (&y)[
       if (a.rop == FUSEDMM_ROP_RMUL) {
         real p = 1.f;  // registers beyond the row's width hold padding, not factors
 #pragma unroll
-        for (int i = 0; i < V; ++i) p *= i < nv ? t[i].x * t[i].y * t[i].z * t[i].w : 1.f;
+        for (int i = 0; i < V; ++i) {
+          if (i >= nv) continue;
+          if (i == nv - 1 && lane_tail > 0)  // the row ends inside this lane's last piece
+            p *= t[i].x * (lane_tail > 1 ? t[i].y : (real)1) * (lane_tail > 2 ? t[i].z : (real)1);
+          else p *= t[i].x * t[i].y * t[i].z * t[i].w;
+        }
         s = group_allreduce_mul<G>(p);
       } else if (a.rop == FUSEDMM_ROP_RSUM) {
         real p = 0.f;
@@ -544,17 +588,21 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
   constexpr int V = D / (4 * G);
   constexpr int S = 64 / G;
   static_assert(S * U <= 64 && 64 % (S * U) == 0, "unroll must tile a batch of 64 entries");
-  constexpr int P = PM & ~kPatMasked;
-  constexpr bool kMasked = PatTraits<P>::masked || (PM & kPatMasked) != 0;
+  constexpr int P = PM & ~(kPatMasked | kPatRagged);
+  constexpr int kMask = mask_mode<PM>();
   using T = PatTraits<P>;
   const int slot = lane / G;
   const int g = lane % G;
   const bool use_val = reads_values<P>(a);
   int nv = V;  // registers of this lane that hold elements of the row (all of them unless the row is narrower)
+  int lane_tail = 0;  // elements in this lane's last such register if the row ends inside it, else 0
   if constexpr (P == PAT_RUNTIME) {
     nv = 0;
 #pragma unroll
     for (int i = 0; i < V; ++i) nv += piece_index<G, C>(g, i) < a.d_pieces ? 1 : 0;
+    if constexpr (kMask == kMaskRagged) {
+      if (a.d_tail > 0 && g == a.d_full % G) lane_tail = a.d_tail;
+    }
   }
 
   for (int64_t base = e0; base < e1; base += 64) {
@@ -579,9 +627,9 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv, lane_tail);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -601,10 +649,10 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
           for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
+            if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
+          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -623,10 +671,10 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 template <int PM, int D, int G, int U, int YF, int C>
 __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0, int deg, int maxdeg,
                                                  const vec4 (&x)[D / (4 * G)], vec4 (&z)[D / (4 * G)], int slot, int g, int nv,
-                                                 bool use_val) {
+                                                 int lane_tail, bool use_val) {
   constexpr int V = D / (4 * G);
-  constexpr int P = PM & ~kPatMasked;
-  constexpr bool kMasked = PatTraits<P>::masked || (PM & kPatMasked) != 0;
+  constexpr int P = PM & ~(kPatMasked | kPatRagged);
+  constexpr int kMask = mask_mode<PM>();
   using T = PatTraits<P>;
   for (int bb = 0; bb < maxdeg; bb += G) {
     int colb = 0;
@@ -652,10 +700,10 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
         for (int u = 0; u < U; ++u) {
 #pragma unroll
           for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-          if (ok[u]) gather_row<YF, G, V, C, kMasked>(a, c[u], g, y[u]);
+          if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv);
+        for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
       } else {
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -665,13 +713,15 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
   }
 }
 
-template <int D, int G, int C, bool M>
+template <int D, int G, int C, int M>
 __device__ __forceinline__ void load_x(const KernelArgs& a, int64_t row, int g, vec4 (&x)[D / (4 * G)]) {
   const real* xr = X_of(a) + row * a.ldx;
 #pragma unroll
   for (int i = 0; i < D / (4 * G); ++i) {
     const int p = piece_index<G, C>(g, i);
-    if (!M || p < a.d_pieces) x[i] = ld4_stream(xr + 4 * p); else x[i] = vec4{0.f, 0.f, 0.f, 0.f};
+    if (M == kMaskNone || p < (M == kMaskRagged ? a.d_full : a.d_pieces)) x[i] = ld4_stream(xr + 4 * p);
+    else if (M == kMaskRagged && p < a.d_pieces) x[i] = ld_tail(xr + 4 * p, a.d_tail);
+    else x[i] = vec4{0.f, 0.f, 0.f, 0.f};
   }
 }
 
@@ -687,12 +737,13 @@ __device__ __forceinline__ void scale(vec4 (&z)[V], real f) {
   for (int i = 0; i < V; ++i) z[i] *= f;
 }
 
-template <int D, int G, int C, bool M>
+template <int D, int G, int C, int M>
 __device__ __forceinline__ void store_row(const KernelArgs& a, real* dst, int g, const vec4 (&z)[D / (4 * G)]) {
 #pragma unroll
   for (int i = 0; i < D / (4 * G); ++i) {
     const int p = piece_index<G, C>(g, i);
-    if (!M || p < a.d_pieces) __builtin_nontemporal_store(z[i], reinterpret_cast<vec4*>(dst + 4 * p));
+    if (M == kMaskNone || p < (M == kMaskRagged ? a.d_full : a.d_pieces)) st4(dst + 4 * p, z[i]);
+    else if (M == kMaskRagged && p < a.d_pieces) st_tail(dst + 4 * p, z[i], a.d_tail);
   }
 }
 
@@ -719,9 +770,10 @@ __device__ __forceinline__ void store_row(const KernelArgs& a, real* dst, int g,
 template <int PM, int D, int GW0, int UW0, int GP0, int UP0, int YF, class E = real>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   static_assert(sizeof(E) == sizeof(real), "the element type is fixed per translation unit");
-  constexpr int P = PM & ~kPatMasked;
+  constexpr int P = PM & ~(kPatMasked | kPatRagged);
   using T = PatTraits<P>;
-  constexpr bool kMasked = T::masked || (PM & kPatMasked) != 0;
+  constexpr int kMask = mask_mode<PM>();
+  constexpr bool kMasked = kMask != kMaskNone;
   // Rows of 2-byte elements are read 16 bytes per lane where the lane group can be halved (it must
   // keep 8 lanes): same bytes in flight per wavefront, half as many load instructions.
   constexpr bool kWideW = YF != kYF32 && GW0 >= 16, kWideP = YF != kYF32 && GP0 >= 16;
@@ -761,7 +813,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     vec4 x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, kMasked>(a, ch.row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, kMask>(a, ch.row, g, x); else zero(x);
     wave_accumulate<PM, D, GW, UW, YF, CW>(a, ch.e_begin + lo, ch.e_begin + hi, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
@@ -790,7 +842,8 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
           if (a.mean && ch.part < 0) s *= (real)1 / (real)ch.e_count;  // the chunk is the whole row
         }
         real* dst = ch.part < 0 ? Z_of(a) + (int64_t)ch.row * a.ldz : partials_of(a) + (int64_t)ch.part * D;
-        __builtin_nontemporal_store(s, reinterpret_cast<vec4*>(dst + 4 * threadIdx.x));
+        if (kMask != kMaskRagged || (int)threadIdx.x < a.d_full) st4(dst + 4 * threadIdx.x, s);
+        else st_tail(dst + 4 * threadIdx.x, s, a.d_tail);
       }
     }
   } else if (kind == kItemWave) {
@@ -812,7 +865,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int g = lane % GW;
     vec4 x[V], z[V];
     zero(z);
-    if (reads_x<P>(a)) load_x<D, GW, CW, kMasked>(a, row, g, x); else zero(x);
+    if (reads_x<P>(a)) load_x<D, GW, CW, kMask>(a, row, g, x); else zero(x);
     wave_accumulate<PM, D, GW, UW, YF, CW>(a, e0, e1, x, z, lane);
     if constexpr (T::loads_y) {
       combine_groups<P, GW, V>(a, z);
@@ -820,7 +873,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       if constexpr (T::means) {
         if (a.mean && !from_desc) scale(z, (real)1 / (real)(e1 - e0));
       }
-      if (lane < GW) store_row<D, GW, CW, kMasked>(a, dst, g, z);
+      if (lane < GW) store_row<D, GW, CW, kMask>(a, dst, g, z);
     }
   } else if (kind == kItemPacked) {
     // ---- one short segment per lane group ----------------------------------------------
@@ -830,11 +883,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
     const int slot = lane / GP;
     const int g = lane % GP;
     const bool use_val = reads_values<P>(a);
-    int nv = V;
+    int nv = V, lane_tail = 0;
     if constexpr (P == PAT_RUNTIME) {
       nv = 0;
 #pragma unroll
       for (int i = 0; i < V; ++i) nv += piece_index<GP, CP>(g, i) < a.d_pieces ? 1 : 0;
+      if constexpr (kMask == kMaskRagged) {
+        if (a.d_tail > 0 && g == a.d_full % GP) lane_tail = a.d_tail;
+      }
     }
     for (int round = 0; round < count; round += kWavesPerBlock * S) {
       const int idx = round + wave * S + slot;
@@ -858,20 +914,20 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       zero(z);
       zero(x);
       if (reads_x<P>(a)) {
-        if (deg > 0) load_x<D, GP, CP, kMasked>(a, row, g, x);
+        if (deg > 0) load_x<D, GP, CP, kMask>(a, row, g, x);
       }
       int maxdeg = deg;  // wave-uniform upper bound of the trip count
       if constexpr (GP <= 8) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 8));
       if constexpr (GP <= 16) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 16));
       if constexpr (GP <= 32) maxdeg = max(maxdeg, __shfl_xor(maxdeg, 32));
       maxdeg = __builtin_amdgcn_readfirstlane(maxdeg);
-      group_accumulate<PM, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, use_val);
+      group_accumulate<PM, D, GP, UP, YF, CP>(a, e0, deg, maxdeg, x, z, slot, g, nv, lane_tail, use_val);
       if constexpr (T::loads_y) {
         if constexpr (T::flips) scale(z, a.sign);
         if constexpr (T::means) {
           if (a.mean && !from_desc && deg > 0) scale(z, (real)1 / (real)deg);
         }
-        if (has_seg) store_row<D, GP, CP, kMasked>(a, dst, g, z);
+        if (has_seg) store_row<D, GP, CP, kMask>(a, dst, g, z);
       }
     }
   }
@@ -882,7 +938,9 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
       for (int i = threadIdx.x; i < count * kPieces; i += kBlockThreads) {
         const int64_t row = rows[i / kPieces];
-        __builtin_nontemporal_store(vec4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<vec4*>(Z_of(a) + row * a.ldz + 4 * (i % kPieces)));
+        real* dst = Z_of(a) + row * a.ldz + 4 * (i % kPieces);
+        if (kMask != kMaskRagged || i % kPieces < a.d_full) st4(dst, vec4{0.f, 0.f, 0.f, 0.f});
+        else st_tail(dst, vec4{0.f, 0.f, 0.f, 0.f}, a.d_tail);
       }
     }
   }

@@ -40,6 +40,22 @@ static hipError_t launch_masked(const KernelArgs& a, hipStream_t stream) {
 
 template <int YF>
 static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t stream) {
+  if ((pattern & kPatRagged) != 0) {  // rows that end inside a 16-byte piece: fp32 / fp64 storage only
+    if constexpr (YF == kYF32) {
+      switch (pattern & ~kPatRagged) {
+        case PAT_RUNTIME: return launch_one<PAT_RUNTIME | kPatRagged, kYF32>(a, stream);
+        case PAT_DOT: return launch_one<PAT_DOT | kPatRagged, kYF32>(a, stream);
+        case PAT_DOT_MM: return launch_one<PAT_DOT_MM | kPatRagged, kYF32>(a, stream);
+        case PAT_DIST: return launch_one<PAT_DIST | kPatRagged, kYF32>(a, stream);
+        case PAT_DIST_MM: return launch_one<PAT_DIST_MM | kPatRagged, kYF32>(a, stream);
+        case PAT_GCN: return launch_one<PAT_GCN | kPatRagged, kYF32>(a, stream);
+        case PAT_GCN_MAX: return launch_one<PAT_GCN_MAX | kPatRagged, kYF32>(a, stream);
+        case PAT_GCN_MIN: return launch_one<PAT_GCN_MIN | kPatRagged, kYF32>(a, stream);
+        default: return hipErrorInvalidValue;
+      }
+    }
+    return hipErrorInvalidValue;
+  }
   const bool m = (pattern & kPatMasked) != 0;
   switch (pattern & ~kPatMasked) {
     case PAT_SIGMOID: return m ? launch_masked<PAT_SIGMOID, YF>(a, stream) : launch_one<PAT_SIGMOID, YF>(a, stream);

@@ -266,19 +266,21 @@ __device__ __forceinline__ V4 merge_two(int aop, V4 s, V4 t) {
   return V4{fmin(s.x, t.x), fmin(s.y, t.y), fmin(s.z, t.z), fmin(s.w, t.w)};
 }
 
-// E: float, or double (a thread then owns a 32-byte column)
+// E: float, or double (a thread then owns a 32-byte column).  d need not be a multiple of 4 (the last column of
+// a row then holds d % 4 elements, stored one by one) and the rows of Z may start at any element.
 template <class E>
 __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* merges, int32_t n_merges,
                                                            const E* partials, int32_t d, int32_t pstride,
                                                            int32_t aop, const int64_t* rowptr, E* Z, int64_t ldz) {
   typedef E V4 __attribute__((ext_vector_type(4)));
-  const int cols = d >> 2;
+  typedef E V4G __attribute__((ext_vector_type(4), aligned(sizeof(E))));
+  const int cols = (d + 3) >> 2;
   const int rows_per_block = 256 / cols;
   const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
   const int64_t mi = (int64_t)blockIdx.x * rows_per_block + r;
   if (r >= rows_per_block || mi >= n_merges) return;
   const MergeDesc md = merges[mi];
-  const E* src = partials + (int64_t)md.first_part * pstride + 4 * c;
+  const E* src = partials + (int64_t)md.first_part * pstride + 4 * c;  // partial rows are pstride >= 4 * cols apart
   V4 s = {0, 0, 0, 0};
   int p = 0;
   for (; p + 8 <= md.n_parts; p += 8) {
@@ -291,14 +293,22 @@ __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* mer
   for (; p < md.n_parts; ++p)
     s = merge_two(aop, s, __builtin_nontemporal_load(reinterpret_cast<const V4*>(src + (int64_t)p * pstride)));
   if (aop == FUSEDMM_AOP_MEAN) s *= (E)1 / (E)(rowptr[md.row + 1] - rowptr[md.row]);  // split rows are never empty
-  __builtin_nontemporal_store(s, reinterpret_cast<V4*>(Z + (int64_t)md.row * ldz + 4 * c));
+  E* dst = Z + (int64_t)md.row * ldz + 4 * c;
+  const int left = d - 4 * c;
+  if (left >= 4) {
+    __builtin_nontemporal_store(static_cast<V4G>(s), reinterpret_cast<V4G*>(dst));
+  } else {  // the row ends inside this column (what the partial rows hold beyond it was never written)
+    __builtin_nontemporal_store(s.x, dst);
+    if (left > 1) __builtin_nontemporal_store(s.y, dst + 1);
+    if (left > 2) __builtin_nontemporal_store(s.z, dst + 2);
+  }
 }
 
 template <class E>
 static hipError_t launch_merge_t(const MergeDesc* merges, int32_t n_merges, const E* partials, int32_t d, int32_t pstride,
                                  int32_t aop, const int64_t* rowptr, E* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
-  const int rows_per_block = 256 / (d >> 2);
+  const int rows_per_block = 256 / ((d + 3) >> 2);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
   hipLaunchKernelGGL(fusedmm_merge_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
                      pstride, aop, rowptr, Z, ldz);

@@ -21,6 +21,10 @@ enum : int { PAT_SIGMOID = 0, PAT_ONE_MINUS_SIGMOID = 1, PAT_GCN = 2, PAT_TDIST 
 // pattern | kPatMasked: the instance of that pattern for a dimension between two instance sizes (pieces of a row
 // at or beyond KernelArgs::d_pieces are neither loaded nor stored); fp32 / fp64 storage only
 constexpr int kPatMasked = 32;
+// pattern | kPatRagged: the instance for a dimension that is not a multiple of 4 (the last piece of a row holds
+// KernelArgs::d_tail elements, read and written one by one); built for the GCN messages, the tuple families and
+// the run-time-ops instance
+constexpr int kPatRagged = 64;
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockThreads = 64 * kWavesPerBlock;
@@ -75,9 +79,10 @@ struct KernelArgs {
   int32_t sop_exp, sop_rcp;
   int32_t vop, rop, sop, mop, aop;  // read by the run-time-ops and family instances; aop is SUM, MAX or MIN here
   int32_t mean;                     // PAT_RUNTIME: a row stored whole is divided by its length (mean pooling)
-  // PAT_RUNTIME: rows have this many 4-float pieces; below D/4 when a dimension between two instance
-  // sizes runs on the next larger instance (pieces beyond it are neither loaded nor stored)
-  int32_t d_pieces;
+  // Masked instances: the rows have d_pieces 4-element pieces, fewer than D/4 when a dimension below the
+  // instance size runs on it (pieces beyond are neither loaded nor stored); the first d_full of them are whole,
+  // and when the dimension is not a multiple of 4 the last one holds d_tail (1..3) elements.
+  int32_t d_pieces, d_full, d_tail;
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
   // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed), rows without entries
   // (zero fill only) from order[n_wave+n_packed .. n_wave+n_packed+n_empty).

@@ -1,9 +1,10 @@
 """Every valid op tuple of the selector (4 VOP x 26 valid ROP/SOP pairs x 3 MOP x 4 AOP = 1248) against the
 oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
-(32, 128), one between instance sizes (20, masked), two of the one-lane-per-entry kernels (2, 3) and those only
-the general kernel takes (6, 13, 27, 97, 301, 700: its lane-group widths and register counts), and with Y
-stored as bfloat16 / half (narrow loads at 32, wide ones at 64 and 128), and in double precision on the
-specialised schedule (32, 256, and 20 on the masked instance; bound 1e-12).  A dispatch slip -- a tuple
+(32, 128), between instance sizes on the masked instances (20; 6, 13, 27, 97, 301: rows that end inside a
+16-byte piece), two of the one-lane-per-entry kernels (2, 3), on the general kernel (700, and 6, 27, 97, 128 with
+the plan told to use nothing else: its lane-group widths and register counts), with Y stored as bfloat16 / half
+(narrow loads at 32, wide ones at 64 and 128), and in double precision on the specialised schedule (32, 256, and
+20 on the masked instance; bound 1e-12).  A dispatch slip -- a tuple
 recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
 import itertools
 
@@ -51,9 +52,11 @@ def rounded(Y, fmt):
 
 @pytest.mark.parametrize("d,fmt", [(32, "f32"), (20, "f32"), (6, "f32"), (128, "f32"), (32, "bf16"), (64, "f16"),
                                    (128, "bf16"), (128, "f16"),
-                                   # the general kernel's other lane-group widths and register counts
+                                   # rows that end inside a 16-byte piece (masked instances), the general kernel at 700
                                    (2, "f32"), (3, "f32"), (13, "f32"), (27, "f32"), (97, "f32"), (301, "f32"),
-                                   (700, "f32"), (32, "f64"), (20, "f64"), (256, "f64")])
+                                   (700, "f32"), (32, "f64"), (20, "f64"), (256, "f64"),
+                                   # the general kernel at dimensions the wide kernels would take
+                                   (6, "general"), (27, "general"), (97, "general"), (128, "general")])
 def test_every_valid_tuple(B, d, fmt):
     rng = np.random.default_rng(2024 + d)
     m, n = 48, 90
@@ -90,8 +93,11 @@ def test_every_valid_tuple(B, d, fmt):
         mats[k] = rounded(mats[k], fmt)      # what the kernels see when Y is stored in 2 bytes
     rp, ci, vd = (torch.from_numpy(a).cuda() for a in (rowptr, colidx, vals))
     dev = {k: torch.from_numpy(v).cuda() for k, v in mats.items()}
+    general = fmt == "general"
+    if general:
+        fmt = "f32"
     plan = B.Plan(m, n, rp, ci, {"small_row_max": 4, "split_row_min": 32, "chunk_edges": 256, "column_classes": 8,
-                                 "tile_row_min": 64, "feature_dim_hint": d})
+                                 "tile_row_min": 64, "feature_dim_hint": d, "general_kernel_only": int(general)})
     plan.reserve(d)
     st = plan.stats()
     assert st["tiled_rows"] > 0 and st["wave_rows"] > 0 and st["packed_rows"] > 0

@@ -78,7 +78,7 @@ def test_f64_matches_oracle(B, case, d):
 
 # the specialised schedule's double-precision instances: instance sizes and dimensions between them, on a plan
 # whose options put rows into every bin (packed, wave, chunks, column-class tiles with partial rows)
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300, 13, 30, 97, 301))
 @pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
 def test_f64_specialised_schedule_all_bins(B, case, d):
     gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
@@ -126,19 +126,19 @@ def test_f64_specialised_schedule_all_bins(B, case, d):
 
 
 def test_f64_specialised_schedule_is_the_one_that_runs(B):
-    """At an instance size with aligned operands fusedmm_execute_f64 must be several times faster than on the
-    same rows shifted by one element (unaligned: the general kernel) -- a silent fall-back would show here."""
+    """fusedmm_execute_f64 at d = 128 must be several times faster than at d = 520, which only the general kernel
+    takes, per element of work -- a silent fall-back of the instance sizes to the general kernel would show here.
+    Rows that start at an odd element run the same instances (the kernels read element-aligned vectors)."""
     g = synth.rmat(14, (1 << 14) * 32, seed=77)
     m = n = g.m
-    d = 128
     rng = np.random.default_rng(3)
-    Xw = torch.from_numpy(rng.uniform(-0.5, 0.5, (m, d + 4))).cuda()
-    Zw = torch.empty((m, d + 4), dtype=torch.float64, device="cuda")
     plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx))
-    plan.reserve_f64(d)
+    plan.reserve_f64(520)
     ops = B.fusedmm_ops_preset("sigmoid")
 
-    def timed(off):
+    def timed(d, off):
+        Xw = torch.from_numpy(rng.uniform(-0.5, 0.5, (m, d + 4))).cuda()
+        Zw = torch.empty((m, d + 4), dtype=torch.float64, device="cuda")
         X, Z = Xw[:, off:off + d], Zw[:, off:off + d]
         for _ in range(3):
             plan.execute_f64(ops, X, X, Z)
@@ -149,10 +149,10 @@ def test_f64_specialised_schedule_is_the_one_that_runs(B):
             plan.execute_f64(ops, X, X, Z)
         t1.record()
         torch.cuda.synchronize()
-        return t0.elapsed_time(t1) / 10
+        return t0.elapsed_time(t1) / 10 / d
 
-    t_fast, t_gen = timed(0), timed(1)
-    assert t_fast * 2 < t_gen, (t_fast, t_gen)
+    t_fast, t_odd, t_gen = timed(128, 0), timed(128, 1), timed(520, 0)
+    assert t_fast * 2 < t_gen and t_odd * 2 < t_gen, (t_fast, t_odd, t_gen)
     plan.close()
 
 

@@ -372,6 +372,52 @@ def test_general_kernel_long_rows(B, case, d):
     plan.close()
 
 
+@pytest.mark.parametrize("d", (32, 128, 100, 50, 97, 127, 13, 301))
+@pytest.mark.parametrize("case", SMALL_CASES, ids=[str(c[0]) + "-" + c[1] for c in SMALL_CASES])
+def test_element_aligned_rows_all_bins(B, case, d):
+    """The wide kernels on rows that are only aligned to one float: views that start one column in, odd leading
+    dimensions, dimensions with instances of their own (32, 128), between them (100) and not a multiple of 4 (the
+    row ends 1, 2 or 3 elements into a 16-byte piece), on every bin of the schedule.  The columns on either side
+    of the views hold poison in X and Y (never to be read) and a guard value in Z (never to be written)."""
+    gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
+    rng = np.random.default_rng(7000 + d)
+    m, n = 301, 4000
+    long_rows = {3: 64, 4: 65, 5: 120, 10: 127, 11: 257, 57: 700, 200: 1024, 201: 1025, 299: 3001, 300: 9000}
+    rowptr, colidx = skewed_csr(rng, m, n, long_rows, sort_cols=True)
+    pad = 3
+    rmul = not isinstance(oracle_ops, str) and oracle_ops[1] == "RMUL"
+    # RMUL: x + y near 1, so that a product of d such factors stays a normal number; else dot products of a few units
+    # (the complement of a sigmoid of 90 would be below fp32's range)
+    lo, hi = (0.49, 0.51) if rmul else (0.2 * min(1.0, 4 / d ** 0.5), 0.9 * min(1.0, 4 / d ** 0.5))
+    Xw = rng.uniform(lo, hi, (m, d + pad)).astype(np.float32)
+    Yw = rng.uniform(lo, hi, (n, d + pad)).astype(np.float32)
+    for W in (Xw, Yw):
+        W[:, 0] = 1e30
+        W[:, d + 1:] = 1e30
+    vals = rng.uniform(-1.0, 1.0, len(colidx)).astype(np.float32)
+    names = oracle.PATTERNS[oracle_ops] if isinstance(oracle_ops, str) else oracle_ops
+    Zr, S, _ = oracle.unfused_general(rowptr, colidx, vals, Xw[:, 1:d + 1], Yw[:, 1:d + 1], names, oracle_aop, alpha=ALPHA)
+    ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
+    ops.alpha = ALPHA
+    uses_x = ops.vop != B.VOP["SEL2ND"]
+    rp, ci = dev(rowptr), dev(colidx)
+    Xd, Yd, vd = dev(Xw), dev(Yw), dev(vals)
+    for options in (None, {"small_row_max": 8, "split_row_min": 96, "chunk_edges": 512}, TILED,
+                    dict(TILED, column_classes=64, tile_row_min=64, small_row_max=2, split_row_min=40)):
+        plan = B.Plan(m, n, rp, ci, dict(options or {}, feature_dim_hint=d))
+        Zb = torch.full((m, d + pad), 7.0, dtype=torch.float32, device="cuda")
+        plan.execute(ops, Xd[:, 1:d + 1] if uses_x else None, Yd[:, 1:d + 1], Zb[:, 1:d + 1], vd)
+        torch.cuda.synchronize()
+        out = Zb.cpu().numpy()
+        check(out[:, 1:d + 1], Zr, S, f"{gpu_ops} {gpu_aop} d={d} {options}")
+        assert (out[:, 0] == 7.0).all() and (out[:, d + 1:] == 7.0).all()
+        counts = torch.zeros(len(colidx), dtype=torch.int32, device="cuda")
+        plan.edge_visits(d, True, counts)
+        torch.cuda.synchronize()
+        assert (counts == 1).all()
+        plan.close()
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
@@ -389,7 +435,7 @@ def test_leading_dimensions_and_rectangular(B):
     out = Zb.cpu().numpy()
     check(out[:, :d], Zr, S, "strided")
     assert (out[:, d:] == 7.0).all()
-    # an unaligned view (offset by one float) must take the general kernel and still be right
+    # a view that starts one float in runs the same instance on element-aligned rows
     Zr2, S2, _ = oracle.unfused(rowptr, colidx, None, Xb[:, 1:d + 1], Yb[:, 1:d + 1], "tdist")
     Zc = torch.full((m, d), np.nan, dtype=torch.float32, device="cuda")
     plan.execute("tdist", Xd[:, 1:d + 1], Yd[:, 1:d + 1], Zc)
