@@ -52,7 +52,7 @@ def graph_with_hub(n, seed, hub_degree):
 
 
 @pytest.mark.parametrize("n,d,batch_rows,s", [(1000, 64, 256, 5), (2708, 128, 256, 5), (300, 20, 64, 0), (517, 32, 517, 3),
-                                              (130, 256, 1000, 2)])
+                                              (130, 256, 1000, 2), (400, 50, 128, 4), (400, 3, 128, 4)])
 def test_epoch_matches_oracle(B, n, d, batch_rows, s):
     g, hub = graph_with_hub(n, 11 + n, min(n - 1, 700))
     assert g.degrees()[hub] >= min(n - 3, 700)   # a long row inside one batch (the hub may draw itself: dropped)
