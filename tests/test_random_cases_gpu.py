@@ -62,9 +62,9 @@ def make_case(seed):
     if sorted_cols:
         for u in range(m):
             colidx[rowptr[u]:rowptr[u + 1]].sort()
-    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508]))
+    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511]))
     share = rng.random() < 0.3 and m <= n
-    ld = d + int(rng.choice([0, 0, 4, 12]))
+    ld = d + int(rng.choice([0, 0, 4, 12, 1, 3]))     # rows need no alignment beyond one float
     Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
     Xb = Yb[:m] if share else rng.uniform(-0.7, 0.7, (m, ld)).astype(np.float32)
     vals = rng.uniform(-1, 1, max(1, nnz)).astype(np.float32)[:nnz]
