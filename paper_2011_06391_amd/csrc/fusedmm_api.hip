@@ -76,12 +76,14 @@ constexpr int32_t kShortDimSmallRowMax = 128;
 constexpr int32_t kShortDimSplitRowMin = 2048;
 constexpr int32_t kShortDimChunkEdges = 8192;
 // Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
-// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB).  The finest level
+// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB; >= 16 MiB on dense patterns,
+// where every row of Y is gathered hundreds of times and an eighth of it fits one L2).  The finest level
 // keeps a class slice of Y at about 64 MiB on sparse patterns -- there only the often-gathered rows of
 // a slice are reused, and they fit an L2 from that size down; finer classes only add partial rows --
 // and at about 8 MiB on dense ones (128 stored entries per row on average: every row of the slice is
 // reused many times, so the slice itself should come near an L2); it stops at 64 classes.
 constexpr int64_t kTilingMinYBytes = 48ll << 20;
+constexpr int64_t kTilingMinYBytesDense = 16ll << 20;  // c3's graph at d = 32 (Y = 30 MB): 1.69 -> 1.07 ms with 8 classes
 constexpr int64_t kTilingSliceBytesSparse = 64ll << 20;
 constexpr int64_t kTilingSliceBytesDense = 8ll << 20;
 constexpr int64_t kDenseEntriesPerRow = 128;
@@ -378,10 +380,11 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     // automatic: off while Y (n rows of the hinted dimension) is small; else as many finest classes as
     // bring a class slice of Y down to the size that pays for the pattern's density, at most 64
     const int64_t y_bytes = n * (int64_t)d_hint * (int64_t)sizeof(float);
+    const bool dense = m > 0 && nnz / m >= kDenseEntriesPerRow;
     n_classes = 1;
-    if (y_bytes >= kTilingMinYBytes) {
+    if (y_bytes >= (dense ? kTilingMinYBytesDense : kTilingMinYBytes)) {
       n_classes = kNumXcd;
-      const int64_t slice = (m > 0 && nnz / m >= kDenseEntriesPerRow) ? kTilingSliceBytesDense : kTilingSliceBytesSparse;
+      const int64_t slice = dense ? kTilingSliceBytesDense : kTilingSliceBytesSparse;
       while (n_classes < kAutoMaxColumnClasses && y_bytes / n_classes > slice) n_classes *= 2;
     }
   }
