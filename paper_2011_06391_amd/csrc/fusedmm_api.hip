@@ -825,9 +825,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-  // a recognised pattern runs its specialised instance; any other tuple runs the same kernel
-  // structure with the ops decided at run time; odd shapes fall back to the general kernel
-  // a dimension between two instance sizes runs the run-time-ops instance of the next larger size (fp32 storage only)
+  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; 9 ... 512: the wide kernels, on the instance of d itself
+  // or the next larger one (choose_pattern says in which form); everything else, and every call of a plan that
+  // asks for it: the general kernel.  2-byte storage of Y exists at the five instance sizes only.
   const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry
   const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
   const int recognised = recognise(*ops);

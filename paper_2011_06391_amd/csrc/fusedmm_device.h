@@ -245,8 +245,8 @@ __device__ __forceinline__ int piece_index(int g, int i) {
 // One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>.  With C = 2 a
 // lane fetches 16 bytes of 2-byte elements per load: half as many load instructions per row as
 // 8-byte loads need, and it is the number of load instructions that occupies the return path.
-// M: pieces at or beyond a.d_pieces are left at zero instead of being loaded (the run-time-ops instance
-// on a dimension below its own).
+// M = kMaskPieces: pieces at or beyond a.d_pieces read as zero (a dimension below the instance's own);
+// M = kMaskRagged: and the row may end inside its last piece (a dimension that is not a multiple of 4).
 template <int YF, int G, int V, int C, int M>
 __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, vec4 (&y)[V]) {
   if constexpr (C == 1) {
@@ -766,7 +766,8 @@ __device__ __forceinline__ void store_row(const KernelArgs& a, real* dst, int g,
 // ---------------------------------------------------------------------------------------
 // E (always `real`) only makes the single- and double-precision instances of one shape different symbols.
 // PM: the pattern, with kPatMasked set when the rows are narrower than D (pieces at or beyond a.d_pieces are
-// neither loaded nor stored; the run-time-ops and family instances always work that way).
+// neither loaded nor stored; the run-time-ops and family instances always work that way) or kPatRagged when
+// they also end inside a piece.
 template <int PM, int D, int GW0, int UW0, int GP0, int UP0, int YF, class E = real>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const KernelArgs a) {
   static_assert(sizeof(E) == sizeof(real), "the element type is fixed per translation unit");
