@@ -45,3 +45,20 @@ def test_traffic_table_rows_are_well_formed():
             assert len(f[1]) == 16 and all(int(x) >= 0 for x in f[2:7]) and 0.0 <= float(f[7]) <= 1.0
     t, hit, why = bench.measured_traffic("no-such-workload", {"partials": 0, "tile_segments": 0, "column_classes": 1})
     assert t is None and hit is None and why
+
+
+def test_traffic_table_belongs_to_the_current_kernel_sources():
+    """bench.py prices roofline.frac on the measured bytes only when the table was written for the kernel sources
+    in the tree; after a change to csrc/ the table has to be regenerated (profile_summary.py says how).  The
+    headline workload and the three others bench.py reports must all be there."""
+    sys.path.insert(0, ROOT)
+    import bench
+    sha = bench.kernel_sources_sha16()
+    rows = {}
+    for line in open(bench.TRAFFIC_TABLE):
+        f = line.split("#")[0].split()
+        if f:
+            rows[f[0]] = f[1]
+    for w in ("c2", "c3", "c4", "c5"):
+        assert rows.get(w) == sha, f"profiles/hbm_traffic_per_launch.txt: the row of {w} is for other kernel sources"
+
