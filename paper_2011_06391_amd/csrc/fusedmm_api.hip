@@ -97,30 +97,32 @@ constexpr int32_t kDefaultTileEdgesPerClass = 16;
 constexpr int32_t kDenseTileEdgesPerClass = 8;
 constexpr size_t kMaxProfiledCalls = 4096;
 
+// the sizes that also exist with Y stored in 2-byte elements
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
 
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
-// dimension from kMinWideDim up to 512: the masked instances skip what lies beyond d, element by element in the
-// last piece when d is not a multiple of 4), else 0.
+// dimension from kMinWideDim up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in
+// the last piece when d is not a multiple of 4), else 0.  The largest size, 1024, exists for fp32 only.
 constexpr int32_t kMinWideDim = 9;
+constexpr int32_t kMaxWideDim = 1024;
+constexpr int32_t kMaxWideDimF64 = 512;
 int32_t instance_dim(int32_t d) {
-  if (is_fast_dim(d)) return d;
-  if (d < kMinWideDim || d > 512) return 0;
+  if (d < kMinWideDim || d > kMaxWideDim) return 0;
   int32_t D = 32;
   while (D < d) D *= 2;
   return D;
 }
 
-// The same for double precision: the same five sizes.
-int32_t instance_dim_f64(int32_t d) { return instance_dim(d); }
+// The same for double precision: the five sizes up to 512.
+int32_t instance_dim_f64(int32_t d) { return d > kMaxWideDimF64 ? 0 : instance_dim(d); }
 
 // How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
 // fp32 (the largest instance size among them, and the short-vector kernels' fixed stride) ...
 int32_t partial_floats_f32(int32_t d) {
-  return std::max<int32_t>(d >= 512 ? 512 : instance_dim(d), kSmallPartialStride);
+  return std::max<int32_t>(d >= kMaxWideDim ? kMaxWideDim : instance_dim(d), kSmallPartialStride);
 }
 // ... and in fp64 (two floats per element)
-int32_t partial_floats_f64(int32_t d) { return 2 * (d >= 512 ? 512 : instance_dim_f64(d)); }
+int32_t partial_floats_f64(int32_t d) { return 2 * (d >= kMaxWideDimF64 ? kMaxWideDimF64 : instance_dim_f64(d)); }
 
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value
@@ -825,7 +827,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; 9 ... 512: the wide kernels, on the instance of d itself
+  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; 9 ... 1024: the wide kernels, on the instance of d itself
   // or the next larger one (choose_pattern says in which form); everything else, and every call of a plan that
   // asks for it: the general kernel.  2-byte storage of Y exists at the five instance sizes only.
   const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry

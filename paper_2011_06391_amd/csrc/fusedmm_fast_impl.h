@@ -14,6 +14,12 @@ constexpr bool kDouble = true;
 #define FMM_FN(name) FMM_CAT(FMM_CAT(name, _d), FMM_D)
 constexpr bool kDouble = false;
 #endif
+// sizes that exist for Y in the build's own element type only (no bfloat16 / half storage)
+#if defined(FMM_F64) || defined(FMM_NATIVE_Y_ONLY)
+constexpr bool kNativeYOnly = true;
+#else
+constexpr bool kNativeYOnly = false;
+#endif
 
 template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
@@ -84,7 +90,7 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
 
 // y_format kYF32 stands for "Y in the element type of the build"; the 2-byte formats exist for fp32 arithmetic only
 hipError_t FMM_FN(launch_fast)(int pattern, int y_format, const KernelArgs& a, hipStream_t stream) {
-  if constexpr (kDouble) {
+  if constexpr (kNativeYOnly) {
     return y_format == kYF32 ? launch_format<kYF32>(pattern, a, stream) : hipErrorInvalidValue;
   } else {
     switch (y_format) {

@@ -421,7 +421,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 #define FMM_DECL(D)                                                                   \
   hipError_t launch_fast##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
   int packed_rows_per_block##D(int y_format);
-FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512)
+FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512) FMM_DECL(_d1024)
 FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256) FMM_DECL(_f64_d512)
 #undef FMM_DECL
 
@@ -442,6 +442,7 @@ int packed_rows_per_block(int d, int y_format) {
     case 128: return packed_rows_per_block_d128(y_format);
     case 256: return packed_rows_per_block_d256(y_format);
     case 512: return packed_rows_per_block_d512(y_format);
+    case 1024: return packed_rows_per_block_d1024(y_format);
     default: return 0;
   }
 }
@@ -463,6 +464,7 @@ hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hi
     case 128: return launch_fast_d128(pattern, y_format, a, stream);
     case 256: return launch_fast_d256(pattern, y_format, a, stream);
     case 512: return launch_fast_d512(pattern, y_format, a, stream);
+    case 1024: return launch_fast_d1024(pattern, y_format, a, stream);
     default: return hipErrorInvalidValue;
   }
 }

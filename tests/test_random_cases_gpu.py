@@ -65,7 +65,7 @@ def make_case(seed):
     if sorted_cols:
         for u in range(m):
             colidx[rowptr[u]:rowptr[u + 1]].sort()
-    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511]))
+    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511, 768, 1024, 1433]))
     share = rng.random() < 0.3 and m <= n
     ld = d + int(rng.choice([0, 0, 4, 12, 1, 3]))     # rows need no alignment beyond one float
     Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
@@ -134,7 +134,7 @@ def test_random_case(B, seed):
     assert err <= (1e-12 if fmt == "f64" else TOL), f"{info}: max rel err {err:.3e} at {am}"
     assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
     counts = torch.zeros(max(1, len(colidx)), dtype=torch.int32, device="cuda")
-    plan.edge_visits(d, True, counts)
+    plan.edge_visits(d, d <= 1024, counts)     # the indexing of the kernel that ran: the general one above 1024
     torch.cuda.synchronize()
     if len(colidx):
         c = counts[:len(colidx)].cpu().numpy()

@@ -41,7 +41,7 @@ def one_case(B, scale, pairs, d, pattern, seed):
     Z_ref = torch.full((g.m, d), float("nan"), dtype=torch.float32, device="cuda")
     plan_ref.execute(ops, Xd, Xd, Z_ref)
     Z = torch.full((g.m, d), float("nan"), dtype=torch.float32, device="cuda")
-    if 32 < d <= 512:
+    if 32 < d <= 1024:
         with pytest.raises(B.FusedMMError) as ei:   # the ordinary entry point refuses: nothing reserved for d
             plan.execute(ops, Xd, Xd, Z)
         assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED
@@ -58,10 +58,10 @@ def test_two_calls_in_a_row_second_one_smaller(B):
     big = one_case(B, 13, (1 << 12) * 16, 128, "tdist", 601)
     small = one_case(B, 10, (1 << 9) * 16, 64, "one_minus_sigmoid", 602)
     assert small["partials"] < big["partials"]
-    # and once more through a ragged instance (d not a multiple of 4), through the general kernel (d above 512),
+    # and once more through a ragged instance (d not a multiple of 4), through the general kernel (d above 1024),
     # whose segments use the same array, and through the one-lane-per-entry kernels (partial rows 16 floats apart)
     one_case(B, 11, (1 << 10) * 16, 50, "fr", 603)
-    one_case(B, 11, (1 << 10) * 16, 600, "fr", 606)
+    one_case(B, 11, (1 << 10) * 16, 1100, "fr", 606)
     one_case(B, 11, (1 << 10) * 16, 3, "fr", 604)
     one_case(B, 12, (1 << 11) * 16, 16, "sigmoid", 605)
 
