@@ -1002,9 +1002,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     fill_schedule_args(plan, D, kYF64, &a);
     fill_op_args(*ops, &a);
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
-    // the pointers travel under their fp32 names; the double-precision instances read them as doubles
-    a.values = reinterpret_cast<const float*>(d_values); a.X = reinterpret_cast<const float*>(d_X); a.Y = d_Y;
-    a.Z = reinterpret_cast<float*>(d_Z);
+    a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
     if (plan->profiling && plan->events_used < plan->events.size()) {

@@ -65,10 +65,13 @@ struct MergeDesc {
 struct KernelArgs {
   const int64_t* rowptr;
   const int32_t* colidx;
-  const float* values;
-  const float* X;
-  const void* Y;  // fp32, or bfloat16 / half when the launch says so; ldy counts elements of that type
-  float* Z;
+  // values, X, Z and the partial rows are fp32, or fp64 in the double-precision instances (the kernels read them
+  // through typed views); Y likewise, or bfloat16 / half when the launch says so; the leading dimensions count
+  // elements of the type in use
+  const void* values;
+  const void* X;
+  const void* Y;
+  void* Z;
   int64_t ldx, ldy, ldz;
   float alpha;
   float sign;   // PAT_DOT_MM / PAT_DIST_MM: -1 when the messages are pooled by MIN (run as MAX of the negated messages), else 1
@@ -90,7 +93,7 @@ struct KernelArgs {
   const ChunkDesc* chunks;
   const BlockItem* items;       // tiled region, nb_tiled entries
   const ChunkDesc* tile_descs;  // segments of tiled rows; part is always a partial row
-  float* partials;
+  void* partials;
   uint32_t* visit_counts;
   int32_t n_chunks, n_wave, n_packed, n_empty;
   int32_t nb_tiled, nb_chunk, nb_wave, nb_packed, nb_zero;

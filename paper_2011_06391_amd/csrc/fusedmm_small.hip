@@ -114,7 +114,7 @@ __device__ __forceinline__ void small_accumulate(const KernelArgs& a, int64_t e0
     for (int u = 0; u < U; ++u) {
       ok[u] = k + u * W < cnt;
       c[u] = ok[u] ? a.colidx[e0 + k + u * W] : 0;
-      av[u] = (ok[u] && use_val) ? a.values[e0 + k + u * W] : 0.f;
+      av[u] = (ok[u] && use_val) ? values_of(a)[e0 + k + u * W] : 0.f;
     }
     if constexpr (T::loads_y) {
 #pragma unroll
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_small_kernel(const Kern
     const int per = ((ch.e_count + kWavesPerBlock * 64 - 1) / (kWavesPerBlock * 64)) * 64;
     const int lo = wave * per < ch.e_count ? wave * per : ch.e_count;
     const int hi = (wave + 1) * per < ch.e_count ? (wave + 1) * per : ch.e_count;
-    if (reads_x<P>(a)) load_vec<D>(a.X + (int64_t)ch.row * a.ldx, x);
+    if (reads_x<P>(a)) load_vec<D>(X_of(a) + (int64_t)ch.row * a.ldx, x);
     small_accumulate<P, D, 64, UW>(a, ch.e_begin + lo, hi - lo, lane, x, acc);
     if constexpr (T::loads_y) {
       small_reduce<P, D, 64>(a, acc);
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_small_kernel(const Kern
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) s = small_aop<P>(a, s, stage[w][threadIdx.x]);
         if (a.mean && ch.part < 0) s *= 1.0f / (float)ch.e_count;  // the chunk is the whole row
-        float* dst = ch.part < 0 ? a.Z + (int64_t)ch.row * a.ldz : a.partials + (int64_t)ch.part * kSmallPartialStride;
+        float* dst = ch.part < 0 ? Z_of(a) + (int64_t)ch.row * a.ldz : partials_of(a) + (int64_t)ch.part * kSmallPartialStride;
         dst[threadIdx.x] = s;
       }
     }
@@ -223,13 +223,13 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_small_kernel(const Kern
     if (from_desc) {
       const ChunkDesc td = a.tile_descs[first + wave];
       row = td.row; e0 = td.e_begin; e1 = td.e_begin + td.e_count;
-      dst = a.partials + (int64_t)td.part * kSmallPartialStride;
+      dst = partials_of(a) + (int64_t)td.part * kSmallPartialStride;
     } else {
       row = __builtin_amdgcn_readfirstlane(a.order[first + wave]);
       e0 = a.rowptr[row]; e1 = a.rowptr[row + 1];
-      dst = a.Z + (int64_t)row * a.ldz;
+      dst = Z_of(a) + (int64_t)row * a.ldz;
     }
-    if (reads_x<P>(a)) load_vec<D>(a.X + (int64_t)row * a.ldx, x);
+    if (reads_x<P>(a)) load_vec<D>(X_of(a) + (int64_t)row * a.ldx, x);
     small_accumulate<P, D, 64, UW>(a, e0, (int)(e1 - e0), lane, x, acc);
     if constexpr (T::loads_y) {
       small_reduce<P, D, 64>(a, acc);
@@ -248,18 +248,18 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_small_kernel(const Kern
         if (from_desc) {
           const ChunkDesc td = a.tile_descs[first + idx];
           row = td.row; e0 = td.e_begin; deg = td.e_count;
-          dst = a.partials + (int64_t)td.part * kSmallPartialStride;
+          dst = partials_of(a) + (int64_t)td.part * kSmallPartialStride;
         } else {
           row = a.order[a.n_wave + first + idx];
           e0 = a.rowptr[row];
           deg = (int)(a.rowptr[row + 1] - e0);
-          dst = a.Z + row * a.ldz;
+          dst = Z_of(a) + row * a.ldz;
         }
       }
 #pragma unroll
       for (int i = 0; i < D; ++i) { x[i] = 0.f; acc[i] = 0.f; }
       if (reads_x<P>(a)) {
-        if (deg > 0) load_vec<D>(a.X + row * a.ldx, x);
+        if (deg > 0) load_vec<D>(X_of(a) + row * a.ldx, x);
       }
       // rows come sorted by length, so the lane groups of a wavefront hold rows of about the same length:
       // the number of entries per lane taken at once follows the longest of them (wave-uniform)
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_small_kernel(const Kern
   } else if (kind == kItemZero) {
     if constexpr (T::loads_y) {
       const int32_t* rows = a.order + a.n_wave + a.n_packed + first;
-      for (int i = threadIdx.x; i < count * D; i += kBlockThreads) a.Z[(int64_t)rows[i / D] * a.ldz + (i % D)] = 0.f;
+      for (int i = threadIdx.x; i < count * D; i += kBlockThreads) Z_of(a)[(int64_t)rows[i / D] * a.ldz + (i % D)] = 0.f;
     }
   }
 }
