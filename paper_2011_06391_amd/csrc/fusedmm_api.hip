@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <mutex>
 #include <new>
+#include <thread>
 #include <utility>
 #include <vector>
 
@@ -96,6 +97,9 @@ constexpr int32_t kMaxColumnClasses = 512;
 constexpr int32_t kDefaultTileEdgesPerClass = 16;
 constexpr int32_t kDenseTileEdgesPerClass = 8;
 constexpr size_t kMaxProfiledCalls = 4096;
+// the plan's passes over the rows run on up to this many host threads, each on at least this many rows
+constexpr int kPlanThreads = 16;
+constexpr int64_t kPlanRowsPerThread = 1 << 16;
 
 // the sizes that also exist with Y stored in 2-byte elements
 bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
@@ -559,20 +563,6 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     const bool tiling = !tiled_rows.empty();
     const int64_t tiled_from = tiling ? tile_min : INT64_MAX;
 
-    // ---- counting sort of the short rows by length, longest first, row order kept among equals
-    std::vector<int64_t> bucket((size_t)split_min + 2, 0);
-    int64_t n_long = 0;
-    for (int64_t u = 0; u < m; ++u) {
-      const int64_t deg = rp[u + 1] - rp[u];
-      if (deg > split_min || deg >= tiled_from) ++n_long; else ++bucket[(size_t)deg];
-    }
-    std::vector<int64_t> start((size_t)split_min + 1, 0);
-    int64_t pos = 0;
-    for (int64_t deg = split_min; deg >= 0; --deg) { start[(size_t)deg] = pos; pos += bucket[(size_t)deg]; }
-    order.resize((size_t)(m - n_long));
-    int64_t n_wave = 0;
-    for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
-
     // length of a workgroup chunk when `count` entries are cut into chunks of at most chunk_edges:
     // equal shares, rounded up to whole batches of 64 entries for each of the 4 wavefronts
     auto chunk_len = [&](int64_t count) {
@@ -580,26 +570,90 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
       return ((count + nc - 1) / nc + 255) / 256 * 256;
     };
 
-    // ---- pass 1 over the tiles: per class, the number of chunk descriptors and of shorter
-    // segments of each length (all segments of a class are laid out longest first) -----------
+    // ---- the rows are walked twice, by T host threads over contiguous row ranges: first counted, then placed.
+    // What a thread counts in the first pass becomes, by prefix sums over the threads in row order, the positions
+    // it writes to in the second, so the lists are the ones a single thread walking the rows in order produces:
+    // short rows sorted by length (longest first, row order kept among equals); the segments of the tiled rows
+    // class by class ([chunks][wavefront segments][lane-group segments], longest first within each); partial-row
+    // slots handed out in row order, so the merge order of a row is fixed by (class, chunk) and does not depend
+    // on how the descriptors are arranged.  All memory is allocated here, before the threads start.
     const size_t ncls = tiling ? (size_t)n_classes : 0;
     const size_t hw = (size_t)split_min + 1;
-    std::vector<int64_t> cls_nchunk(ncls, 0), cls_hist(ncls * hw, 0);
-    for (size_t ti = 0; tiling && ti < tiled_rows.size(); ++ti) {
-      const int32_t* bnd = bounds.data() + bnd_off[ti];
-      const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
-      for (size_t t = 0; t < level; ++t) {
-        const int64_t cnt = (int64_t)bnd[t + 1] - bnd[t];
-        if (cnt <= 0) continue;
-        const size_t c = t * stride;  // the tile is filed under the first finest class it covers
-        if (cnt > split_min) {
-          const int64_t per = chunk_len(cnt);
-          cls_nchunk[c] += (cnt + per - 1) / per;
+    const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)kPlanThreads, (int64_t)std::thread::hardware_concurrency(),
+                                                                 m / kPlanRowsPerThread}));
+    struct ThreadCounts {
+      std::vector<int64_t> bucket;                // short rows by length; after the prefix sums: where the next one goes
+      std::vector<int64_t> cls_nchunk, cls_hist;  // tile chunks per class, shorter segments per (class, length); likewise
+      int64_t n_long = 0, n_chunk_descs = 0, n_merges = 0, n_parts = 0, n_tiled = 0;
+      size_t ti0 = 0;  // index in tiled_rows of the thread's first tiled row
+    };
+    std::vector<ThreadCounts> tc((size_t)T);
+    for (int t = 0; t < T; ++t) {
+      tc[(size_t)t].bucket.assign((size_t)split_min + 1, 0);
+      tc[(size_t)t].cls_nchunk.assign(ncls, 0);
+      tc[(size_t)t].cls_hist.assign(ncls * hw, 0);
+      tc[(size_t)t].ti0 = (size_t)(std::lower_bound(tiled_rows.begin(), tiled_rows.end(), (int32_t)(m * t / T)) - tiled_rows.begin());
+    }
+    auto on_threads = [&](auto&& body) {
+      if (T == 1) { body(0); return; }
+      std::vector<std::thread> workers;
+      workers.reserve((size_t)T);
+      for (int t = 0; t < T; ++t) workers.emplace_back([&body, t]() { body(t); });
+      for (auto& w : workers) w.join();
+    };
+
+    // first pass: count
+    on_threads([&](int t) {
+      ThreadCounts& c = tc[(size_t)t];
+      size_t ti = c.ti0;
+      for (int64_t u = m * t / T; u < m * (t + 1) / T; ++u) {
+        const int64_t deg = rp[u + 1] - rp[u];
+        if (deg >= tiled_from) {
+          const int32_t* bnd = bounds.data() + bnd_off[ti];
+          const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
+          ++ti;
+          for (size_t k = 0; k < level; ++k) {
+            const int64_t cnt = (int64_t)bnd[k + 1] - bnd[k];
+            if (cnt <= 0) continue;
+            const size_t cl = k * stride;  // the tile is filed under the first finest class it covers
+            if (cnt > split_min) {
+              const int64_t per = chunk_len(cnt);
+              c.cls_nchunk[cl] += (cnt + per - 1) / per;
+              c.n_parts += (cnt + per - 1) / per;
+            } else {
+              ++c.cls_hist[cl * hw + (size_t)cnt];
+              ++c.n_parts;
+            }
+          }
+          ++c.n_long; ++c.n_tiled; ++c.n_merges;
+        } else if (deg <= split_min) {
+          ++c.bucket[(size_t)deg];
         } else {
-          ++cls_hist[c * hw + (size_t)cnt];
+          const int64_t per = chunk_len(deg);
+          const int64_t nc = (deg + per - 1) / per;
+          ++c.n_long;
+          c.n_chunk_descs += nc;
+          if (nc > 1) { ++c.n_merges; c.n_parts += nc; }
         }
       }
+    });
+
+    // totals, the layout of the lists, and every thread's starting positions in them
+    std::vector<int64_t> bucket((size_t)split_min + 1, 0), cls_nchunk(ncls, 0), cls_hist(ncls * hw, 0);
+    int64_t n_long = 0, n_chunk_descs = 0, n_merge_descs = 0, n_part_slots = 0;
+    for (const ThreadCounts& c : tc) {
+      for (size_t i = 0; i < bucket.size(); ++i) bucket[i] += c.bucket[i];
+      for (size_t i = 0; i < cls_nchunk.size(); ++i) cls_nchunk[i] += c.cls_nchunk[i];
+      for (size_t i = 0; i < cls_hist.size(); ++i) cls_hist[i] += c.cls_hist[i];
+      n_long += c.n_long; n_chunk_descs += c.n_chunk_descs; n_merge_descs += c.n_merges; n_part_slots += c.n_parts;
+      p->n_tiled_rows += (int32_t)c.n_tiled;
     }
+    if (n_part_slots >= (int64_t)INT32_MAX || n_chunk_descs >= (int64_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
+    std::vector<int64_t> start((size_t)split_min + 1, 0);
+    int64_t pos = 0;
+    for (int64_t deg = split_min; deg >= 0; --deg) { start[(size_t)deg] = pos; pos += bucket[(size_t)deg]; }
+    int64_t n_wave = 0;
+    for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
     // descriptor layout: class by class, [chunks][wavefront segments][lane-group segments]
     std::vector<int64_t> cls_base(ncls + 1, 0), cls_nwave(ncls, 0), cls_nshort(ncls, 0), cls_chunk_cursor(ncls, 0);
     for (size_t c = 0; c < ncls; ++c) {
@@ -607,53 +661,74 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
       cls_chunk_cursor[c] = cls_base[c];
       for (int64_t len = split_min; len >= 1; --len) {
         const int64_t h = cls_hist[c * hw + (size_t)len];
-        cls_hist[c * hw + (size_t)len] = at;  // from now on: where the next segment of this length goes
+        cls_hist[c * hw + (size_t)len] = at;  // from now on: where the first segment of this length goes
         at += h;
         (len > small_max ? cls_nwave : cls_nshort)[c] += h;
       }
       cls_base[c + 1] = at;
     }
     if (ncls > 0 && cls_base[ncls] >= (int64_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
-    tile_descs.resize(ncls > 0 ? (size_t)cls_base[ncls] : 0);
-
-    // ---- pass 2: rows in order; partial-row slots are handed out here, so the merge order of a
-    // row is fixed by (class, chunk) and does not depend on how the descriptors were arranged ---
-    int32_t next_part = 0;
-    size_t ti = 0;
-    for (int64_t u = 0; u < m; ++u) {
-      const int64_t deg = rp[u + 1] - rp[u];
-      if (deg >= tiled_from) {
-        const int32_t* bnd = bounds.data() + bnd_off[ti];
-        const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
-        ++ti;
-        const int32_t first_part = next_part;
-        for (size_t t = 0; t < level; ++t) {
-          const int64_t cnt = (int64_t)bnd[t + 1] - bnd[t];
-          if (cnt <= 0) continue;
-          const size_t c = t * stride;
-          const int64_t e_begin = rp[u] + bnd[t];
-          if (cnt > split_min) {
-            const int64_t per = chunk_len(cnt);
-            for (int64_t off = 0; off < cnt; off += per)
-              tile_descs[(size_t)cls_chunk_cursor[c]++] =
-                  ChunkDesc{e_begin + off, (int32_t)std::min<int64_t>(per, cnt - off), (int32_t)u, next_part++, 0};
-          } else {
-            tile_descs[(size_t)cls_hist[c * hw + (size_t)cnt]++] = ChunkDesc{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
-          }
+    std::vector<int64_t> part0((size_t)T, 0), merge0((size_t)T, 0), chunk0((size_t)T, 0);
+    {
+      int64_t parts = 0, mrg = 0, chk = 0;
+      for (int t = 0; t < T; ++t) {
+        ThreadCounts& c = tc[(size_t)t];
+        part0[(size_t)t] = parts; merge0[(size_t)t] = mrg; chunk0[(size_t)t] = chk;
+        parts += c.n_parts; mrg += c.n_merges; chk += c.n_chunk_descs;
+        // counts -> positions: what the earlier threads' rows take comes first
+        for (size_t i = 0; i < start.size(); ++i) { const int64_t k = c.bucket[i]; c.bucket[i] = start[i]; start[i] += k; }
+        for (size_t i = 0; i < cls_chunk_cursor.size(); ++i) {
+          const int64_t k = c.cls_nchunk[i]; c.cls_nchunk[i] = cls_chunk_cursor[i]; cls_chunk_cursor[i] += k;
         }
-        merges.push_back(MergeDesc{(int32_t)u, first_part, next_part - first_part, 0});
-        ++p->n_tiled_rows;
-      } else if (deg <= split_min) {
-        order[(size_t)start[(size_t)deg]++] = (int32_t)u;
-      } else {
-        const int64_t per = chunk_len(deg);
-        const int32_t nc = (int32_t)((deg + per - 1) / per);
-        if (nc > 1) merges.push_back(MergeDesc{(int32_t)u, next_part, nc, 0});
-        for (int64_t off = 0; off < deg; off += per)
-          chunks.push_back(ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(per, deg - off), (int32_t)u,
-                                     nc > 1 ? next_part++ : -1, 0});
+        for (size_t i = 0; i < cls_hist.size(); ++i) { const int64_t k = c.cls_hist[i]; c.cls_hist[i] = cls_hist[i]; cls_hist[i] += k; }
       }
     }
+    order.resize((size_t)(m - n_long));
+    chunks.resize((size_t)n_chunk_descs);
+    merges.resize((size_t)n_merge_descs);
+    tile_descs.resize(ncls > 0 ? (size_t)cls_base[ncls] : 0);
+
+    // second pass: place
+    on_threads([&](int t) {
+      ThreadCounts& c = tc[(size_t)t];
+      size_t ti = c.ti0;
+      int32_t next_part = (int32_t)part0[(size_t)t];
+      int64_t next_merge = merge0[(size_t)t], next_chunk = chunk0[(size_t)t];
+      for (int64_t u = m * t / T; u < m * (t + 1) / T; ++u) {
+        const int64_t deg = rp[u + 1] - rp[u];
+        if (deg >= tiled_from) {
+          const int32_t* bnd = bounds.data() + bnd_off[ti];
+          const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
+          ++ti;
+          const int32_t first_part = next_part;
+          for (size_t k = 0; k < level; ++k) {
+            const int64_t cnt = (int64_t)bnd[k + 1] - bnd[k];
+            if (cnt <= 0) continue;
+            const size_t cl = k * stride;
+            const int64_t e_begin = rp[u] + bnd[k];
+            if (cnt > split_min) {
+              const int64_t per = chunk_len(cnt);
+              for (int64_t off = 0; off < cnt; off += per)
+                tile_descs[(size_t)c.cls_nchunk[cl]++] =
+                    ChunkDesc{e_begin + off, (int32_t)std::min<int64_t>(per, cnt - off), (int32_t)u, next_part++, 0};
+            } else {
+              tile_descs[(size_t)c.cls_hist[cl * hw + (size_t)cnt]++] = ChunkDesc{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
+            }
+          }
+          merges[(size_t)next_merge++] = MergeDesc{(int32_t)u, first_part, next_part - first_part, 0};
+        } else if (deg <= split_min) {
+          order[(size_t)c.bucket[(size_t)deg]++] = (int32_t)u;
+        } else {
+          const int64_t per = chunk_len(deg);
+          const int32_t nc = (int32_t)((deg + per - 1) / per);
+          if (nc > 1) merges[(size_t)next_merge++] = MergeDesc{(int32_t)u, next_part, nc, 0};
+          for (int64_t off = 0; off < deg; off += per)
+            chunks[(size_t)next_chunk++] = ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(per, deg - off), (int32_t)u,
+                                                     nc > 1 ? next_part++ : -1, 0};
+        }
+      }
+    });
+    const int32_t next_part = (int32_t)n_part_slots;
 
     // ---- deal the classes to the XCDs: XCD k owns the k-th eighth of the column range and works
     // through its finest classes in order; coarser tiles sit where their first finest class is ----
