@@ -150,7 +150,9 @@ typedef struct fusedmm_plan_options {
   int32_t general_kernel_only; /* non-zero: every fp32 / fp64 execute of this plan runs the general kernel
                               (one wavefront per row or 256-entry segment, any d), whatever the dimension
                               and alignment: the slow, simple path, kept selectable for cross-checks */
-  int32_t reserved[1];
+  int32_t host_threads;    /* host threads that build the plan's work lists: 0 = automatic (one per 65 536
+                              rows, at most 16 and at most the machine's), k > 0 = exactly min(k, 64); the
+                              plan does not depend on it */
 } fusedmm_plan_options_t;
 
 typedef struct fusedmm_plan fusedmm_plan_t;

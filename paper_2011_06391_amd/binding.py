@@ -55,7 +55,7 @@ class fusedmm_plan_options_t(ctypes.Structure):
     _fields_ = [("small_row_max", ctypes.c_int32), ("split_row_min", ctypes.c_int32),
                 ("chunk_edges", ctypes.c_int32), ("column_classes", ctypes.c_int32),
                 ("tile_row_min", ctypes.c_int32), ("feature_dim_hint", ctypes.c_int32),
-                ("general_kernel_only", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
+                ("general_kernel_only", ctypes.c_int32), ("host_threads", ctypes.c_int32)]
 
 
 class FusedMMError(RuntimeError):
@@ -185,7 +185,7 @@ def fusedmm_plan_create(m: int, n: int, nnz: int, d_rowptr, d_colidx, options=No
         opt = ctypes.byref(fusedmm_plan_options_t(options.get("small_row_max", 0), options.get("split_row_min", 0),
                                                   options.get("chunk_edges", 0), options.get("column_classes", 0),
                                                   options.get("tile_row_min", 0), options.get("feature_dim_hint", 0),
-                                                  options.get("general_kernel_only", 0)))
+                                                  options.get("general_kernel_only", 0), options.get("host_threads", 0)))
     st = load().fusedmm_plan_create(ctypes.byref(plan), m, n, nnz, _dptr(d_rowptr), _dptr(d_colidx), opt,
                                     _stream(stream))
     _check(st, "fusedmm_plan_create")

@@ -99,6 +99,7 @@ constexpr int32_t kDenseTileEdgesPerClass = 8;
 constexpr size_t kMaxProfiledCalls = 4096;
 // the plan's passes over the rows run on up to this many host threads, each on at least this many rows
 constexpr int kPlanThreads = 16;
+constexpr int kPlanThreadsLimit = 64;   // for an explicit fusedmm_plan_options_t::host_threads
 constexpr int64_t kPlanRowsPerThread = 1 << 16;
 
 // the sizes that also exist with Y stored in 2-byte elements
@@ -579,8 +580,11 @@ int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz,
     // on how the descriptors are arranged.  All memory is allocated here, before the threads start.
     const size_t ncls = tiling ? (size_t)n_classes : 0;
     const size_t hw = (size_t)split_min + 1;
-    const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)kPlanThreads, (int64_t)std::thread::hardware_concurrency(),
-                                                                 m / kPlanRowsPerThread}));
+    const int asked_threads = options ? options->host_threads : 0;
+    const int T = asked_threads > 0
+                      ? std::min(asked_threads, kPlanThreadsLimit)
+                      : (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)kPlanThreads, (int64_t)std::thread::hardware_concurrency(),
+                                                                      m / kPlanRowsPerThread}));
     struct ThreadCounts {
       std::vector<int64_t> bucket;                // short rows by length; after the prefix sums: where the next one goes
       std::vector<int64_t> cls_nchunk, cls_hist;  // tile chunks per class, shorter segments per (class, length); likewise

@@ -535,6 +535,48 @@ def test_run_to_run_determinism(B):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("threads", (2, 7, 64))
+def test_plan_does_not_depend_on_the_host_threads_that_build_it(B, threads):
+    """The work lists are built by host threads over contiguous row ranges (counts, prefix sums, places).
+    Whatever their number -- also more threads than some ranges have rows, so that ranges are empty or hold a
+    single long row -- the plan is the one a single thread builds: same statistics, every stored entry visited
+    once, and results equal bit for bit (the order of each row's partial sums is part of the plan)."""
+    for m, scale_pairs, options in ((1 << 12, (12, (1 << 12) * 12), {"small_row_max": 4, "split_row_min": 32,
+                                                                     "chunk_edges": 256, "column_classes": 16,
+                                                                     "tile_row_min": 24}),
+                                    (1 << 12, (12, (1 << 12) * 12), {"small_row_max": 8, "split_row_min": 64,
+                                                                     "chunk_edges": 256, "column_classes": 1}),
+                                    (40, None, {"small_row_max": 2, "split_row_min": 16, "chunk_edges": 256,
+                                                "column_classes": 8, "tile_row_min": 8})):
+        if scale_pairs is None:
+            rng = np.random.default_rng(77)
+            rowptr, colidx = skewed_csr(rng, m, 4096, {3: 900, 17: 300, 39: 1500}, sort_cols=True)
+            n = 4096
+        else:
+            g = synth.rmat(*scale_pairs, seed=81)
+            rowptr, colidx, n = g.rowptr, g.colidx, g.n
+        nnz = int(rowptr[-1])
+        d = 64
+        X = synth.fill_uniform((m, d), 5, -0.5, 0.5)
+        Y = synth.fill_uniform((n, d), 6, -0.5, 0.5)
+        rp, ci, Xd, Yd = dev(rowptr), dev(colidx), dev(X), dev(Y)
+        results = []
+        for T in (1, threads):
+            plan = B.Plan(m, n, rp, ci, dict(options, host_threads=T))
+            plan.reserve(d)
+            Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+            plan.execute("sigmoid", Xd, Yd, Z)
+            counts = torch.zeros(nnz, dtype=torch.int32, device="cuda")
+            plan.edge_visits(d, True, counts)
+            torch.cuda.synchronize()
+            c = counts.cpu().numpy()
+            assert c.min() == 1 and c.max() == 1, f"{T} threads: visit counts in [{c.min()}, {c.max()}]"
+            results.append((plan.stats(), Z.cpu().numpy()))
+            plan.close()
+        assert results[0][0] == results[1][0], f"{threads} threads: {results[1][0]} != {results[0][0]}"
+        assert np.array_equal(results[0][1], results[1][1]), f"{threads} threads, m={m}: results differ"
+
+
 def test_execute_can_be_captured_in_a_hip_graph(B):
     """fusedmm_execute neither allocates nor synchronises, so a caller can record it into a HIP graph:
     one plan, reserved once for the largest dimension, captured at two different dimensions.  Each
