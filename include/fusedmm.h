@@ -247,9 +247,10 @@ int fusedmm_execute_static_scratch(fusedmm_plan_t* plan, const fusedmm_ops_t* op
 /* The same operation with Y stored as bfloat16 (the upper 16 bits of each fp32 value): the
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
  * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
- * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes per lane).  Only d in
- * {32, 64, 128, 256, 512} with aligned operands (FUSEDMM_ERR_UNSUPPORTED_DIM /
- * FUSEDMM_ERR_INVALID_ARG otherwise).  The result is that of
+ * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes = 8 elements per lane).  d is a
+ * multiple of 8 from 8 to 512 (32, 64, 128, 256, 512 on their own instances, the others on the next larger
+ * one; FUSEDMM_ERR_UNSUPPORTED_DIM for any other d, FUSEDMM_ERR_INVALID_ARG for rows that are not
+ * aligned).  Any valid op tuple.  The result is that of
  * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back, up to the
  * order of the fp32 sums (the lane groups are half as wide). */
 int fusedmm_execute_bf16y(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,

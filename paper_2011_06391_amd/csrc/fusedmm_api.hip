@@ -102,9 +102,6 @@ constexpr int kPlanThreads = 16;
 constexpr int kPlanThreadsLimit = 64;   // for an explicit fusedmm_plan_options_t::host_threads
 constexpr int64_t kPlanRowsPerThread = 1 << 16;
 
-// the sizes that also exist with Y stored in 2-byte elements
-bool is_fast_dim(int32_t d) { return d == 32 || d == 64 || d == 128 || d == 256 || d == 512; }
-
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
 // dimension from kMinWideDim up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in
 // the last piece when d is not a multiple of 4), else 0.  The largest size, 1024, exists for fp32 only.
@@ -120,6 +117,14 @@ int32_t instance_dim(int32_t d) {
 
 // The same for double precision: the five sizes up to 512.
 int32_t instance_dim_f64(int32_t d) { return d > kMaxWideDimF64 ? 0 : instance_dim(d); }
+
+// The same for Y stored in 2-byte elements: rows are read 16 bytes = 8 elements at a time, so d is a multiple
+// of 8, from 8 up to 512.
+constexpr int32_t kMaxWideDim2Byte = 512;
+int32_t instance_dim_2byte(int32_t d) {
+  if (d < 8 || d % 8 != 0 || d > kMaxWideDim2Byte) return 0;
+  return std::max<int32_t>(32, instance_dim(d));
+}
 
 // How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
 // fp32 (the largest instance size among them, and the short-vector kernels' fixed stride) ...
@@ -908,9 +913,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
 
   // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; 9 ... 1024: the wide kernels, on the instance of d itself
   // or the next larger one (choose_pattern says in which form); everything else, and every call of a plan that
-  // asks for it: the general kernel.  2-byte storage of Y exists at the five instance sizes only.
+  // asks for it: the general kernel.  2-byte storage of Y exists on the wide kernels only (d = 8, 16, 24 ... 512).
   const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry
-  const int32_t D = y_bf16 ? (is_fast_dim(d) ? d : 0) : instance_dim(d);
+  const int32_t D = y_bf16 ? instance_dim_2byte(d) : instance_dim(d);
   const int recognised = recognise(*ops);
   const int family = recognise_family(*ops);
   const int pattern = choose_pattern(recognised, family, d, D);
@@ -919,7 +924,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   const bool y_ok = plan->nnz == 0 || !y_bf16 || (aligned16(d_Y) && ldy % 8 == 0);
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
   const bool fast = D != 0 && ldy < (int64_t(1) << 29) && y_ok && (y_bf16 || !plan->general_only);
-  if (y_bf16 && !fast) return is_fast_dim(d) ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
+  if (y_bf16 && !fast) return D != 0 ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
   if (plan->profiling && plan->events_used < plan->events.size()) {

@@ -36,12 +36,11 @@ int FMM_FN(packed_rows_per_block)(int y_format) {
   return kWavesPerBlock * (64 / gp);
 }
 
-// the instance for rows narrower than FMM_D: in the build's own element type only (2-byte storage of Y is
-// offered at the instance sizes), and only for the patterns that do not mask by themselves
+// the instance for rows narrower than FMM_D (whole 4-element pieces; rows of 2-byte elements: whole 16-byte
+// chunks of 8), for the patterns that do not mask by themselves
 template <int P, int YF>
 static hipError_t launch_masked(const KernelArgs& a, hipStream_t stream) {
-  if constexpr (YF == kYF32) return launch_one<P | kPatMasked, kYF32>(a, stream);
-  return hipErrorInvalidValue;
+  return launch_one<P | kPatMasked, YF>(a, stream);
 }
 
 template <int YF>
@@ -82,7 +81,7 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
       return hipErrorInvalidValue;
     case PAT_SIGNED_SIGMOID:  // used by the minibatch layer on fp32 embeddings only
       if constexpr (YF == kYF32 && !kDouble)
-        return m ? launch_masked<PAT_SIGNED_SIGMOID, YF>(a, stream) : launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
+        return m ? launch_masked<PAT_SIGNED_SIGMOID, kYF32>(a, stream) : launch_one<PAT_SIGNED_SIGMOID, kYF32>(a, stream);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }

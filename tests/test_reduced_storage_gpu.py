@@ -79,7 +79,7 @@ def test_half_rounding_kernel_bit_exact(B):
     assert np.isnan(out.cpu().numpy().view(np.float16))[0]
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 16, 72, 136, 392))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "general"))
 def test_half_storage_parity(B, pattern, d):
     rng = np.random.default_rng(41 + d)
@@ -127,7 +127,7 @@ def test_half_storage_parity(B, pattern, d):
         plan.close()
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 8, 16, 24, 40, 96, 200, 264, 504))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "fr", "general"))
 def test_bf16_storage_parity(B, pattern, d):
     rng = np.random.default_rng(31 + d)
@@ -170,12 +170,50 @@ def test_bf16_storage_parity(B, pattern, d):
         plan.close()
 
 
+@pytest.mark.parametrize("d,ld", ((40, 48), (8, 16), (200, 256), (264, 272)))
+def test_two_byte_rows_narrower_than_their_pitch(B, d, ld):
+    """Rows of Y that are d elements wide in a matrix ld apart, with NaN in every element beyond d (and X, Z
+    likewise wider than d): nothing beyond d may be read into the result or written."""
+    rng = np.random.default_rng(7 + d)
+    g = synth.rmat(11, (1 << 10) * 24, seed=400 + d)
+    m = n = g.m
+    X = rng.uniform(-0.6, 0.6, (m, d)).astype(np.float32)
+    Y = (rng.uniform(0.05, 0.6, (n, d)) * rng.choice((-1.0, 1.0), (n, d))).astype(np.float32)
+    Y = widen(bf16_bits_rne(Y))   # exactly representable in bfloat16, and (away from zero) in half as well
+    Zr, S, _ = oracle.unfused(g.rowptr, g.colidx, None, X, Y, "sigmoid")
+    rp, ci = torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda()
+    Xw = torch.full((m, ld), float("nan"), dtype=torch.float32, device="cuda")
+    Xw[:, :d] = torch.from_numpy(X).cuda()
+    Zw = torch.full((m, ld), 7.0, dtype=torch.float32, device="cuda")
+    ops = B.fusedmm_ops_preset("sigmoid")
+    for fmt, entry in (("bf16", B.fusedmm_execute_bf16y), ("f16", B.fusedmm_execute_f16y)):
+        if fmt == "bf16":
+            Yw = torch.full((n, ld), 0x7FC0, dtype=torch.int16, device="cuda")          # bfloat16 NaN
+            Yw[:, :d] = torch.from_numpy(bf16_bits_rne(Y).view(np.int16)).cuda()
+        else:
+            Yw = torch.full((n, ld), 0x7E00, dtype=torch.int16, device="cuda")          # half NaN
+            Yw[:, :d] = torch.from_numpy(Y.astype(np.float16).view(np.int16)).cuda()   # bfloat16 values fit half here
+            assert np.array_equal(Y.astype(np.float16).astype(np.float32), Y)
+        for options in ({"column_classes": 1}, {"column_classes": 16, "tile_row_min": 64, "split_row_min": 128}):
+            plan = B.Plan(m, n, rp, ci, options)
+            plan.reserve(d)
+            Zw.fill_(7.0)
+            entry(plan._plan, ops, d, None, Xw, ld, Yw, ld, Zw, ld)
+            torch.cuda.synchronize()
+            out = Zw.cpu().numpy()
+            assert (out[:, d:] == 7.0).all(), f"{fmt} d={d}: written beyond d"
+            err, am, viol = oracle.compare(out[:, :d].copy(), Zr, S)
+            assert viol == 0 and err <= TOL, f"{fmt} d={d} ld={ld} {options}: err {err:.3e} at {am}, viol {viol}"
+            plan.close()
+
+
 def test_bf16_argument_checks(B):
     g = synth.rmat(8, 1024, seed=3)
     rp, ci = torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda()
     plan = B.Plan(g.m, g.n, rp, ci)
     ops = B.fusedmm_ops_preset("sigmoid")
-    for d, ld, expect in ((48, 48, B.FUSEDMM_ERR_UNSUPPORTED_DIM), (64, 66, B.FUSEDMM_ERR_INVALID_ARG)):
+    for d, ld, expect in ((44, 48, B.FUSEDMM_ERR_UNSUPPORTED_DIM), (520, 520, B.FUSEDMM_ERR_UNSUPPORTED_DIM),
+                          (64, 66, B.FUSEDMM_ERR_INVALID_ARG), (48, 52, B.FUSEDMM_ERR_INVALID_ARG)):
         X = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
         Yb = torch.zeros((g.n, ld), dtype=torch.int16, device="cuda")
         Z = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
