@@ -17,6 +17,7 @@ LIB = os.path.join(HERE, "libfusedmm.so")
 
 SOURCES = [
     "fusedmm_api.hip",
+    "fusedmm_plan.hip",
     "fusedmm_generic.hip",
     "fusedmm_minibatch.hip",
     "fusedmm_small.hip",

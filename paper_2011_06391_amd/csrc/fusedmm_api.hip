@@ -1,43 +1,14 @@
-// Host side of libfusedmm.so: the C ABI of include/fusedmm.h, argument validation,
-// the degree-binned plan (the GPU counterpart of Part1D in Algorithm 1) and dispatch.
-#include "../../include/fusedmm.h"
-#include "fusedmm_internal.h"
+// Host side of libfusedmm.so: the C ABI of include/fusedmm.h apart from fusedmm_plan_create (fusedmm_plan.hip) --
+// argument validation, pattern recognition, dispatch to the kernels, scratch, profiling, the tuned plan.
+#include "fusedmm_plan.h"
 
 #include <algorithm>
 #include <mutex>
 #include <new>
-#include <thread>
 #include <utility>
 #include <vector>
 
 using namespace fmm;
-
-struct fusedmm_plan {
-  int64_t m = 0, n = 0, nnz = 0;
-  const int64_t* d_rowptr = nullptr;
-  const int32_t* d_colidx = nullptr;
-  int32_t small_row_max = 0, split_row_min = 0, chunk_edges = 0, tile_row_min = 0;  // as resolved
-  int32_t n_wave = 0, n_packed = 0, n_empty = 0, n_chunks = 0, n_merges = 0, n_parts = 0;  // n_packed: non-empty
-  int32_t n_items = 0, n_tile_descs = 0, n_tiled_rows = 0, n_classes = 1;
-  bool general_only = false;  // every execute runs the general kernel
-  int32_t* d_order = nullptr;
-  ChunkDesc* d_chunks = nullptr;
-  BlockItem* d_items = nullptr;
-  ChunkDesc* d_tile_descs = nullptr;
-  MergeDesc* d_merges = nullptr;
-  float* d_partials = nullptr;
-  int32_t partials_d = 0;  // scratch holds n_parts rows of this many floats
-  // the general kernel's own cut of the rows longer than kGenericSplit (any d, fp32 or fp64)
-  ChunkDesc* d_gen_segs = nullptr;
-  MergeDesc* d_gen_merges = nullptr;
-  int32_t n_gen_segs = 0, n_gen_merges = 0;
-  void* d_gen_partials = nullptr;
-  size_t gen_partials_bytes = 0;
-  bool profiling = false;
-  struct EventTriple { hipEvent_t before, after, after2; };
-  std::vector<EventTriple> events;  // main kernel between before/after; nothing between after/after2
-  size_t events_used = 0;
-};
 
 // Fixed scratch of fusedmm_execute_static_scratch: partial rows of split rows, for callers that cannot
 // allocate.  One copy per GPU the library runs on, held until the process ends.  In host code the array's
@@ -51,8 +22,10 @@ constexpr int kMaxScratchDevices = 64;
 void* g_scratch_ptr[kMaxScratchDevices] = {};
 std::mutex g_scratch_mutex;
 
+}  // namespace
+
 // The address of `scratch` on the current device (every GPU holds its own copy at its own address).
-int static_scratch_for_current_device(void** out) {
+int fmm::static_scratch_for_current_device(void** out) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return FUSEDMM_ERR_HIP;
   if (dev < 0 || dev >= kMaxScratchDevices) return FUSEDMM_ERR_INVALID_ARG;
@@ -69,38 +42,9 @@ int static_scratch_for_current_device(void** out) {
   return FUSEDMM_OK;
 }
 
-constexpr int32_t kDefaultSmallRowMax = 64;
-constexpr int32_t kDefaultSplitRowMin = 512;
-constexpr int32_t kDefaultChunkEdges = 1024;
-// the same three when the plan is hinted a feature dimension of at most 16
-constexpr int32_t kShortDimSmallRowMax = 128;
-constexpr int32_t kShortDimSplitRowMin = 2048;
-constexpr int32_t kShortDimChunkEdges = 8192;
-// Column-class tiling defaults, from sweeps on MI355X: it pays once Y (n rows of the hinted
-// dimension) is beyond what the eight 4 MB L2s keep resident anyway (>= 48 MiB; >= 16 MiB on dense patterns,
-// where every row of Y is gathered hundreds of times and an eighth of it fits one L2).  The finest level
-// keeps a class slice of Y at about 64 MiB on sparse patterns -- there only the often-gathered rows of
-// a slice are reused, and they fit an L2 from that size down; finer classes only add partial rows --
-// and at about 8 MiB on dense ones (128 stored entries per row on average: every row of the slice is
-// reused many times, so the slice itself should come near an L2); it stops at 64 classes.
-constexpr int64_t kTilingMinYBytes = 48ll << 20;
-constexpr int64_t kTilingMinYBytesDense = 16ll << 20;  // c3's graph at d = 32 (Y = 30 MB): 1.69 -> 1.07 ms with 8 classes
-constexpr int64_t kTilingSliceBytesSparse = 64ll << 20;
-constexpr int64_t kTilingSliceBytesDense = 8ll << 20;
-constexpr int64_t kDenseEntriesPerRow = 128;
-constexpr int32_t kAutoMaxColumnClasses = 64;
-// class boundaries come from a histogram of the column indices: this many buckets, about this many sampled entries
-constexpr int64_t kClassBuckets = 1 << 16;
-constexpr int64_t kClassSamples = 1 << 24;
-constexpr double kClassWidthWeight = 0.25;
-constexpr int32_t kMaxColumnClasses = 512;
-constexpr int32_t kDefaultTileEdgesPerClass = 16;
-constexpr int32_t kDenseTileEdgesPerClass = 8;
+namespace {
+
 constexpr size_t kMaxProfiledCalls = 4096;
-// the plan's passes over the rows run on up to this many host threads, each on at least this many rows
-constexpr int kPlanThreads = 16;
-constexpr int kPlanThreadsLimit = 64;   // for an explicit fusedmm_plan_options_t::host_threads
-constexpr int64_t kPlanRowsPerThread = 1 << 16;
 
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
 // dimension from kMinWideDim up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in
@@ -203,37 +147,6 @@ bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int6
   const uintptr_t a1 = a0 + (uintptr_t)((rows_a - 1) * ld_a + d) * sizeof(float);
   const uintptr_t b1 = b0 + (uintptr_t)((rows_b - 1) * ld_b + d) * sizeof(float);
   return a0 < b1 && b0 < a1;
-}
-
-void free_plan_device(fusedmm_plan* p) {
-  if (p->d_order) (void)hipFree(p->d_order);
-  if (p->d_chunks) (void)hipFree(p->d_chunks);
-  if (p->d_merges) (void)hipFree(p->d_merges);
-  if (p->d_items) (void)hipFree(p->d_items);
-  if (p->d_tile_descs) (void)hipFree(p->d_tile_descs);
-  if (p->d_partials) (void)hipFree(p->d_partials);
-  if (p->d_gen_segs) (void)hipFree(p->d_gen_segs);
-  if (p->d_gen_merges) (void)hipFree(p->d_gen_merges);
-  if (p->d_gen_partials) (void)hipFree(p->d_gen_partials);
-  for (auto& ev : p->events) {
-    (void)hipEventDestroy(ev.before);
-    (void)hipEventDestroy(ev.after);
-    (void)hipEventDestroy(ev.after2);
-  }
-  p->events.clear();
-}
-
-template <class T>
-int upload(T** dst, const std::vector<T>& src, hipStream_t stream) {
-  *dst = nullptr;
-  if (src.empty()) return FUSEDMM_OK;
-  if (hipMalloc(reinterpret_cast<void**>(dst), src.size() * sizeof(T)) != hipSuccess) {
-    (void)hipGetLastError();
-    return FUSEDMM_ERR_ALLOC;
-  }
-  if (hipMemcpyAsync(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, stream) != hipSuccess)
-    return FUSEDMM_ERR_HIP;
-  return FUSEDMM_OK;
 }
 
 // Reserve-time only (fusedmm_plan_create, fusedmm_plan_reserve*): may synchronise the device, free and
@@ -358,471 +271,6 @@ int fusedmm_ops_preset(int pattern, fusedmm_ops_t* out) {
     default: return FUSEDMM_ERR_INVALID_ARG;
   }
   *out = o;
-  return FUSEDMM_OK;
-}
-
-int fusedmm_plan_create(fusedmm_plan_t** out, int64_t m, int64_t n, int64_t nnz, const int64_t* d_rowptr,
-                        const int32_t* d_colidx, const fusedmm_plan_options_t* options, void* stream_) {
-  if (!out) return FUSEDMM_ERR_INVALID_ARG;
-  *out = nullptr;
-  if (m < 0 || n < 0 || nnz < 0 || m >= INT32_MAX || n >= INT32_MAX) return FUSEDMM_ERR_INVALID_ARG;
-  if (!d_rowptr || (nnz > 0 && (!d_colidx || n == 0 || m == 0))) return FUSEDMM_ERR_INVALID_ARG;
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-
-  int32_t small_max = kDefaultSmallRowMax, split_min = kDefaultSplitRowMin, chunk = kDefaultChunkEdges;
-  if (options && options->feature_dim_hint > 0 && options->feature_dim_hint <= 16) {
-    // very short feature vectors (one lane per stored entry): a work item's fixed cost -- its descriptor, the
-    // reduction across lanes, the store -- is spread over more entries
-    small_max = kShortDimSmallRowMax; split_min = kShortDimSplitRowMin; chunk = kShortDimChunkEdges;
-  }
-  if (options) {
-    if (options->small_row_max < 0 || options->split_row_min < 0 || options->chunk_edges < 0) return FUSEDMM_ERR_INVALID_ARG;
-    if (options->small_row_max > 0) small_max = options->small_row_max;
-    if (options->split_row_min > 0) split_min = options->split_row_min;
-    if (options->chunk_edges > 0) chunk = options->chunk_edges;
-  }
-  int32_t n_classes = 0, tile_min = 0, d_hint = 128;
-  if (options) {
-    if (options->column_classes < 0 || options->tile_row_min < 0 || options->feature_dim_hint < 0) return FUSEDMM_ERR_INVALID_ARG;
-    n_classes = options->column_classes;
-    tile_min = options->tile_row_min;
-    if (options->feature_dim_hint > 0) d_hint = options->feature_dim_hint;
-  }
-  if (n_classes == 0) {
-    // automatic: off while Y (n rows of the hinted dimension) is small; else as many finest classes as
-    // bring a class slice of Y down to the size that pays for the pattern's density, at most 64
-    const int64_t y_bytes = n * (int64_t)d_hint * (int64_t)sizeof(float);
-    const bool dense = m > 0 && nnz / m >= kDenseEntriesPerRow;
-    n_classes = 1;
-    if (y_bytes >= (dense ? kTilingMinYBytesDense : kTilingMinYBytes)) {
-      n_classes = kNumXcd;
-      const int64_t slice = dense ? kTilingSliceBytesDense : kTilingSliceBytesSparse;
-      while (n_classes < kAutoMaxColumnClasses && y_bytes / n_classes > slice) n_classes *= 2;
-    }
-  }
-  if (n_classes > 1) {  // levels are nested: 8, 16, 32, ... classes
-    int32_t c = kNumXcd;
-    while (c < n_classes && c < kMaxColumnClasses) c *= 2;
-    n_classes = c;
-  }
-  // a row needs 16 entries per class on average for a partial row per class to be worth it; 8 on dense patterns,
-  // where nearly every row is tiled anyway and the shorter ones gain more from their classes' L2 than their partial
-  // rows cost (c3: 3.99 -> 3.90 ms; the sparse workloads lose 1-6 % with it)
-  if (tile_min <= 0)
-    tile_min = ((m > 0 && nnz / m >= kDenseEntriesPerRow) ? kDenseTileEdgesPerClass : kDefaultTileEdgesPerClass) * kNumXcd;
-  const int64_t tile_edges_per_class = std::max<int64_t>(1, tile_min / kNumXcd);
-  small_max = std::min(small_max, 1 << 16);
-  split_min = std::min(std::max(split_min, small_max), 1 << 20);
-  chunk = std::min(std::max((chunk + 255) / 256 * 256, 256), 1 << 24);
-
-  // row pointers to the host: O(m) scan, like Part1D
-  std::vector<int64_t> rp;
-  try {
-    rp.resize((size_t)m + 1);
-  } catch (const std::bad_alloc&) {
-    return FUSEDMM_ERR_ALLOC;
-  }
-  if (hipStreamSynchronize(stream) != hipSuccess) return FUSEDMM_ERR_HIP;
-  if (hipMemcpy(rp.data(), d_rowptr, ((size_t)m + 1) * sizeof(int64_t), hipMemcpyDeviceToHost) != hipSuccess)
-    return FUSEDMM_ERR_HIP;
-  if (rp[0] != 0 || rp[m] != nnz) return FUSEDMM_ERR_INVALID_ARG;
-  for (int64_t u = 0; u < m; ++u)
-    if (rp[u + 1] < rp[u]) return FUSEDMM_ERR_INVALID_ARG;
-
-  // column indices must address rows of Y: checked on the device, once
-  if (nnz > 0) {
-    int32_t* d_flag = nullptr;
-    if (hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t)) != hipSuccess) return FUSEDMM_ERR_ALLOC;
-    int32_t flag = 0;
-    hipError_t e = hipMemcpy(d_flag, &flag, sizeof(flag), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = launch_validate_colidx(d_colidx, nnz, n, d_flag, stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(stream);
-    if (e == hipSuccess) e = hipMemcpy(&flag, d_flag, sizeof(flag), hipMemcpyDeviceToHost);
-    (void)hipFree(d_flag);
-    if (e != hipSuccess) return FUSEDMM_ERR_HIP;
-    if (flag != 0) return FUSEDMM_ERR_INVALID_ARG;
-  }
-
-  fusedmm_plan* p = new (std::nothrow) fusedmm_plan();
-  if (!p) return FUSEDMM_ERR_ALLOC;
-  p->m = m; p->n = n; p->nnz = nnz;
-  p->d_rowptr = d_rowptr; p->d_colidx = d_colidx;
-  p->small_row_max = small_max; p->split_row_min = split_min; p->chunk_edges = chunk; p->tile_row_min = tile_min;
-  p->general_only = options && options->general_kernel_only != 0;
-
-  std::vector<int32_t> order;
-  std::vector<ChunkDesc> chunks, tile_descs;
-  std::vector<MergeDesc> merges;
-  std::vector<BlockItem> items;
-  int st = FUSEDMM_OK;
-  int32_t* d_class_start = nullptr;  // column-class boundaries on the device while the tile bounds are computed
-  try {
-    // ---- which rows are cut into column-class tiles, and how finely ---------------------
-    // Level of a row = number of classes it is cut into: the largest of 8, 16, ..., n_classes
-    // that leaves it tile_edges_per_class entries per class on average.  Classes are nested
-    // contiguous column ranges: a class of level L is n_classes / L finest classes.
-    std::vector<int32_t> tiled_rows, tiled_level;
-    std::vector<int64_t> bnd_off;  // per tiled row: where its level + 1 boundaries start in bounds[]
-    std::vector<int32_t> bounds;
-    // The finest classes are contiguous column ranges that hold about the same number of stored entries each
-    // (from a histogram of the column indices over kClassBuckets buckets, every stride-th entry), not the same
-    // number of columns: where the often-gathered columns sit side by side -- vertex orders that keep hubs
-    // together -- equal widths would give one XCD most of the work.
-    std::vector<int32_t> class_start;
-    if (n_classes > 1 && nnz > 0) {
-      const int32_t nbk = (int32_t)std::min<int64_t>(kClassBuckets, n);
-      const int64_t stride = std::max<int64_t>(1, nnz / kClassSamples);
-      std::vector<uint32_t> hist((size_t)nbk);
-      uint32_t* d_hist = nullptr;
-      hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_hist), (size_t)nbk * sizeof(uint32_t));
-      if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_class_start), ((size_t)n_classes + 1) * sizeof(int32_t));
-      if (e != hipSuccess) {
-        (void)hipGetLastError();
-        st = FUSEDMM_ERR_ALLOC;
-      } else {
-        e = hipMemsetAsync(d_hist, 0, (size_t)nbk * sizeof(uint32_t), stream);
-        if (e == hipSuccess) e = launch_column_histogram(d_colidx, nnz, stride, n, nbk, d_hist, stream);
-        if (e == hipSuccess) e = hipStreamSynchronize(stream);
-        if (e == hipSuccess) e = hipMemcpy(hist.data(), d_hist, (size_t)nbk * sizeof(uint32_t), hipMemcpyDeviceToHost);
-        if (e == hipSuccess) {
-          uint64_t total = 0;
-          for (uint32_t h : hist) total += h;
-          class_start.assign((size_t)n_classes + 1, 0);
-          class_start[(size_t)n_classes] = (int32_t)n;
-          // A class's weight is 3/4 its share of the stored entries + 1/4 its share of the columns: a class of
-          // often-gathered columns is served from the L2 and can take more entries than a wide class of rarely
-          // gathered ones, whose rows of Y mostly come from memory.  (Where entries are spread evenly over the
-          // columns both shares are the same.)  Measured on the workloads in their as-generated vertex order,
-          // weights of the width 0 / 0.25 / 0.5 / 1: c3 5.5 / 4.9 / 5.0 / 8.8 ms, c5 15.3 / 14.6 / 15.7 / 26.7 ms.
-          const double wfrac = kClassWidthWeight;
-          double acc = 0.0;
-          int32_t c = 1;
-          for (int32_t b = 0; b < nbk && c < n_classes; ++b) {
-            acc += (1.0 - wfrac) * (total ? (double)hist[(size_t)b] / (double)total : 0.0) + wfrac / (double)nbk;
-            // bucket b ends class c - 1 (and any class it fills on its own) once the classes before c hold their share
-            while (c < n_classes && acc * (double)n_classes >= (double)c * (1.0 - 1e-12)) {
-              const int64_t first_col_after = ((int64_t)(b + 1) * n + nbk - 1) / nbk;  // first column of bucket b + 1
-              class_start[(size_t)c++] = (int32_t)std::min<int64_t>(first_col_after, n);
-            }
-          }
-          for (; c < n_classes; ++c) class_start[(size_t)c] = (int32_t)n;
-          e = hipMemcpy(d_class_start, class_start.data(), class_start.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-        }
-        if (e != hipSuccess) st = FUSEDMM_ERR_HIP;
-      }
-      if (d_hist) (void)hipFree(d_hist);
-      if (st != FUSEDMM_OK) {
-        if (d_class_start) (void)hipFree(d_class_start);
-        delete p;
-        return st;
-      }
-    }
-    if (n_classes > 1 && nnz > 0) {
-      int64_t nb = 0;
-      for (int64_t u = 0; u < m; ++u) {
-        const int64_t deg = rp[u + 1] - rp[u];
-        if (deg < tile_min) continue;
-        int32_t level = kNumXcd;
-        while (level < n_classes && deg >= tile_edges_per_class * 2 * level) level *= 2;
-        tiled_rows.push_back((int32_t)u);
-        tiled_level.push_back(level);
-        bnd_off.push_back(nb);
-        nb += level + 1;
-      }
-      if (!tiled_rows.empty()) {
-        int32_t *d_rows = nullptr, *d_level = nullptr, *d_bounds = nullptr, *d_flag = nullptr;
-        int64_t* d_off = nullptr;
-        const size_t nt = tiled_rows.size();
-        bounds.resize((size_t)nb);
-        int32_t flag = 0;
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_rows), nt * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_level), nt * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_off), nt * sizeof(int64_t));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_bounds), (size_t)nb * sizeof(int32_t));
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t));
-        if (e != hipSuccess) {
-          (void)hipGetLastError();
-          st = FUSEDMM_ERR_ALLOC;
-        } else {
-          e = hipMemcpy(d_rows, tiled_rows.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice);
-          if (e == hipSuccess) e = hipMemcpy(d_level, tiled_level.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice);
-          if (e == hipSuccess) e = hipMemcpy(d_off, bnd_off.data(), nt * sizeof(int64_t), hipMemcpyHostToDevice);
-          if (e == hipSuccess) e = hipMemcpy(d_flag, &flag, sizeof(flag), hipMemcpyHostToDevice);
-          if (e == hipSuccess)
-            e = launch_tile_bounds(d_rowptr, d_colidx, d_rows, d_level, d_off, (int32_t)nt, n_classes, d_class_start,
-                                   d_bounds, d_flag, stream);
-          if (e == hipSuccess) e = hipStreamSynchronize(stream);
-          if (e == hipSuccess) e = hipMemcpy(bounds.data(), d_bounds, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToHost);
-          if (e == hipSuccess) e = hipMemcpy(&flag, d_flag, sizeof(flag), hipMemcpyDeviceToHost);
-          if (e != hipSuccess) st = FUSEDMM_ERR_HIP;
-        }
-        if (d_rows) (void)hipFree(d_rows);
-        if (d_level) (void)hipFree(d_level);
-        if (d_off) (void)hipFree(d_off);
-        if (d_bounds) (void)hipFree(d_bounds);
-        if (d_flag) (void)hipFree(d_flag);
-        if (st != FUSEDMM_OK) { (void)hipFree(d_class_start); delete p; return st; }
-        if (flag != 0) tiled_rows.clear();  // some long row has unsorted columns: no tiling for this pattern
-      }
-    }
-    if (d_class_start) { (void)hipFree(d_class_start); d_class_start = nullptr; }
-    const bool tiling = !tiled_rows.empty();
-    const int64_t tiled_from = tiling ? tile_min : INT64_MAX;
-
-    // length of a workgroup chunk when `count` entries are cut into chunks of at most chunk_edges:
-    // equal shares, rounded up to whole batches of 64 entries for each of the 4 wavefronts
-    auto chunk_len = [&](int64_t count) {
-      const int64_t nc = (count + chunk - 1) / chunk;
-      return ((count + nc - 1) / nc + 255) / 256 * 256;
-    };
-
-    // ---- the rows are walked twice, by T host threads over contiguous row ranges: first counted, then placed.
-    // What a thread counts in the first pass becomes, by prefix sums over the threads in row order, the positions
-    // it writes to in the second, so the lists are the ones a single thread walking the rows in order produces:
-    // short rows sorted by length (longest first, row order kept among equals); the segments of the tiled rows
-    // class by class ([chunks][wavefront segments][lane-group segments], longest first within each); partial-row
-    // slots handed out in row order, so the merge order of a row is fixed by (class, chunk) and does not depend
-    // on how the descriptors are arranged.  All memory is allocated here, before the threads start.
-    const size_t ncls = tiling ? (size_t)n_classes : 0;
-    const size_t hw = (size_t)split_min + 1;
-    const int asked_threads = options ? options->host_threads : 0;
-    const int T = asked_threads > 0
-                      ? std::min(asked_threads, kPlanThreadsLimit)
-                      : (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)kPlanThreads, (int64_t)std::thread::hardware_concurrency(),
-                                                                      m / kPlanRowsPerThread}));
-    struct ThreadCounts {
-      std::vector<int64_t> bucket;                // short rows by length; after the prefix sums: where the next one goes
-      std::vector<int64_t> cls_nchunk, cls_hist;  // tile chunks per class, shorter segments per (class, length); likewise
-      int64_t n_long = 0, n_chunk_descs = 0, n_merges = 0, n_parts = 0, n_tiled = 0;
-      size_t ti0 = 0;  // index in tiled_rows of the thread's first tiled row
-    };
-    std::vector<ThreadCounts> tc((size_t)T);
-    for (int t = 0; t < T; ++t) {
-      tc[(size_t)t].bucket.assign((size_t)split_min + 1, 0);
-      tc[(size_t)t].cls_nchunk.assign(ncls, 0);
-      tc[(size_t)t].cls_hist.assign(ncls * hw, 0);
-      tc[(size_t)t].ti0 = (size_t)(std::lower_bound(tiled_rows.begin(), tiled_rows.end(), (int32_t)(m * t / T)) - tiled_rows.begin());
-    }
-    auto on_threads = [&](auto&& body) {
-      if (T == 1) { body(0); return; }
-      std::vector<std::thread> workers;
-      workers.reserve((size_t)T);
-      for (int t = 0; t < T; ++t) workers.emplace_back([&body, t]() { body(t); });
-      for (auto& w : workers) w.join();
-    };
-
-    // first pass: count
-    on_threads([&](int t) {
-      ThreadCounts& c = tc[(size_t)t];
-      size_t ti = c.ti0;
-      for (int64_t u = m * t / T; u < m * (t + 1) / T; ++u) {
-        const int64_t deg = rp[u + 1] - rp[u];
-        if (deg >= tiled_from) {
-          const int32_t* bnd = bounds.data() + bnd_off[ti];
-          const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
-          ++ti;
-          for (size_t k = 0; k < level; ++k) {
-            const int64_t cnt = (int64_t)bnd[k + 1] - bnd[k];
-            if (cnt <= 0) continue;
-            const size_t cl = k * stride;  // the tile is filed under the first finest class it covers
-            if (cnt > split_min) {
-              const int64_t per = chunk_len(cnt);
-              c.cls_nchunk[cl] += (cnt + per - 1) / per;
-              c.n_parts += (cnt + per - 1) / per;
-            } else {
-              ++c.cls_hist[cl * hw + (size_t)cnt];
-              ++c.n_parts;
-            }
-          }
-          ++c.n_long; ++c.n_tiled; ++c.n_merges;
-        } else if (deg <= split_min) {
-          ++c.bucket[(size_t)deg];
-        } else {
-          const int64_t per = chunk_len(deg);
-          const int64_t nc = (deg + per - 1) / per;
-          ++c.n_long;
-          c.n_chunk_descs += nc;
-          if (nc > 1) { ++c.n_merges; c.n_parts += nc; }
-        }
-      }
-    });
-
-    // totals, the layout of the lists, and every thread's starting positions in them
-    std::vector<int64_t> bucket((size_t)split_min + 1, 0), cls_nchunk(ncls, 0), cls_hist(ncls * hw, 0);
-    int64_t n_long = 0, n_chunk_descs = 0, n_merge_descs = 0, n_part_slots = 0;
-    for (const ThreadCounts& c : tc) {
-      for (size_t i = 0; i < bucket.size(); ++i) bucket[i] += c.bucket[i];
-      for (size_t i = 0; i < cls_nchunk.size(); ++i) cls_nchunk[i] += c.cls_nchunk[i];
-      for (size_t i = 0; i < cls_hist.size(); ++i) cls_hist[i] += c.cls_hist[i];
-      n_long += c.n_long; n_chunk_descs += c.n_chunk_descs; n_merge_descs += c.n_merges; n_part_slots += c.n_parts;
-      p->n_tiled_rows += (int32_t)c.n_tiled;
-    }
-    if (n_part_slots >= (int64_t)INT32_MAX || n_chunk_descs >= (int64_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
-    std::vector<int64_t> start((size_t)split_min + 1, 0);
-    int64_t pos = 0;
-    for (int64_t deg = split_min; deg >= 0; --deg) { start[(size_t)deg] = pos; pos += bucket[(size_t)deg]; }
-    int64_t n_wave = 0;
-    for (int64_t deg = split_min; deg > small_max; --deg) n_wave += bucket[(size_t)deg];
-    // descriptor layout: class by class, [chunks][wavefront segments][lane-group segments]
-    std::vector<int64_t> cls_base(ncls + 1, 0), cls_nwave(ncls, 0), cls_nshort(ncls, 0), cls_chunk_cursor(ncls, 0);
-    for (size_t c = 0; c < ncls; ++c) {
-      int64_t at = cls_base[c] + cls_nchunk[c];
-      cls_chunk_cursor[c] = cls_base[c];
-      for (int64_t len = split_min; len >= 1; --len) {
-        const int64_t h = cls_hist[c * hw + (size_t)len];
-        cls_hist[c * hw + (size_t)len] = at;  // from now on: where the first segment of this length goes
-        at += h;
-        (len > small_max ? cls_nwave : cls_nshort)[c] += h;
-      }
-      cls_base[c + 1] = at;
-    }
-    if (ncls > 0 && cls_base[ncls] >= (int64_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
-    std::vector<int64_t> part0((size_t)T, 0), merge0((size_t)T, 0), chunk0((size_t)T, 0);
-    {
-      int64_t parts = 0, mrg = 0, chk = 0;
-      for (int t = 0; t < T; ++t) {
-        ThreadCounts& c = tc[(size_t)t];
-        part0[(size_t)t] = parts; merge0[(size_t)t] = mrg; chunk0[(size_t)t] = chk;
-        parts += c.n_parts; mrg += c.n_merges; chk += c.n_chunk_descs;
-        // counts -> positions: what the earlier threads' rows take comes first
-        for (size_t i = 0; i < start.size(); ++i) { const int64_t k = c.bucket[i]; c.bucket[i] = start[i]; start[i] += k; }
-        for (size_t i = 0; i < cls_chunk_cursor.size(); ++i) {
-          const int64_t k = c.cls_nchunk[i]; c.cls_nchunk[i] = cls_chunk_cursor[i]; cls_chunk_cursor[i] += k;
-        }
-        for (size_t i = 0; i < cls_hist.size(); ++i) { const int64_t k = c.cls_hist[i]; c.cls_hist[i] = cls_hist[i]; cls_hist[i] += k; }
-      }
-    }
-    order.resize((size_t)(m - n_long));
-    chunks.resize((size_t)n_chunk_descs);
-    merges.resize((size_t)n_merge_descs);
-    tile_descs.resize(ncls > 0 ? (size_t)cls_base[ncls] : 0);
-
-    // second pass: place
-    on_threads([&](int t) {
-      ThreadCounts& c = tc[(size_t)t];
-      size_t ti = c.ti0;
-      int32_t next_part = (int32_t)part0[(size_t)t];
-      int64_t next_merge = merge0[(size_t)t], next_chunk = chunk0[(size_t)t];
-      for (int64_t u = m * t / T; u < m * (t + 1) / T; ++u) {
-        const int64_t deg = rp[u + 1] - rp[u];
-        if (deg >= tiled_from) {
-          const int32_t* bnd = bounds.data() + bnd_off[ti];
-          const size_t level = (size_t)tiled_level[ti], stride = ncls / level;
-          ++ti;
-          const int32_t first_part = next_part;
-          for (size_t k = 0; k < level; ++k) {
-            const int64_t cnt = (int64_t)bnd[k + 1] - bnd[k];
-            if (cnt <= 0) continue;
-            const size_t cl = k * stride;
-            const int64_t e_begin = rp[u] + bnd[k];
-            if (cnt > split_min) {
-              const int64_t per = chunk_len(cnt);
-              for (int64_t off = 0; off < cnt; off += per)
-                tile_descs[(size_t)c.cls_nchunk[cl]++] =
-                    ChunkDesc{e_begin + off, (int32_t)std::min<int64_t>(per, cnt - off), (int32_t)u, next_part++, 0};
-            } else {
-              tile_descs[(size_t)c.cls_hist[cl * hw + (size_t)cnt]++] = ChunkDesc{e_begin, (int32_t)cnt, (int32_t)u, next_part++, 0};
-            }
-          }
-          merges[(size_t)next_merge++] = MergeDesc{(int32_t)u, first_part, next_part - first_part, 0};
-        } else if (deg <= split_min) {
-          order[(size_t)c.bucket[(size_t)deg]++] = (int32_t)u;
-        } else {
-          const int64_t per = chunk_len(deg);
-          const int32_t nc = (int32_t)((deg + per - 1) / per);
-          if (nc > 1) merges[(size_t)next_merge++] = MergeDesc{(int32_t)u, next_part, nc, 0};
-          for (int64_t off = 0; off < deg; off += per)
-            chunks[(size_t)next_chunk++] = ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(per, deg - off), (int32_t)u,
-                                                     nc > 1 ? next_part++ : -1, 0};
-        }
-      }
-    });
-    const int32_t next_part = (int32_t)n_part_slots;
-
-    // ---- deal the classes to the XCDs: XCD k owns the k-th eighth of the column range and works
-    // through its finest classes in order; coarser tiles sit where their first finest class is ----
-    if (tiling) {
-      std::vector<std::vector<BlockItem>> xcd_items(kNumXcd);
-      for (size_t c = 0; c < ncls; ++c) {
-        auto& lst = xcd_items[c / (ncls / kNumXcd)];
-        int64_t at = cls_base[c];
-        for (int64_t k = 0; k < cls_nchunk[c]; ++k) lst.push_back(BlockItem{kItemChunk, (int32_t)(at++), 1, 0});
-        for (int64_t k = 0; k < cls_nwave[c]; k += kWavesPerBlock) {
-          const int32_t cnt = (int32_t)std::min<int64_t>(kWavesPerBlock, cls_nwave[c] - k);
-          lst.push_back(BlockItem{kItemWave, (int32_t)at, cnt, 0});
-          at += cnt;
-        }
-        for (int64_t k = 0; k < cls_nshort[c]; k += kPackedSegsPerItem) {
-          const int32_t cnt = (int32_t)std::min<int64_t>(kPackedSegsPerItem, cls_nshort[c] - k);
-          lst.push_back(BlockItem{kItemPacked, (int32_t)at, cnt, 0});
-          at += cnt;
-        }
-      }
-      size_t longest = 0;
-      for (const auto& lst : xcd_items) longest = std::max(longest, lst.size());
-      items.assign(longest * kNumXcd, BlockItem{kItemNone, 0, 0, 0});
-      for (int k = 0; k < kNumXcd; ++k)
-        for (size_t j = 0; j < xcd_items[(size_t)k].size(); ++j) items[j * kNumXcd + (size_t)k] = xcd_items[(size_t)k][j];
-      p->n_classes = n_classes;
-    }
-    if (tile_descs.size() >= (size_t)INT32_MAX || items.size() >= (size_t)INT32_MAX) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
-    p->n_wave = (int32_t)n_wave;
-    p->n_empty = (int32_t)bucket[0];  // they sort last: zero-filled by workgroups of their own
-    p->n_packed = (int32_t)((m - n_long) - n_wave - bucket[0]);
-    p->n_chunks = (int32_t)chunks.size();
-    p->n_merges = (int32_t)merges.size();
-    p->n_parts = next_part;
-    p->n_items = (int32_t)items.size();
-    p->n_tile_descs = (int32_t)tile_descs.size();
-  } catch (const std::bad_alloc&) {
-    if (d_class_start) (void)hipFree(d_class_start);
-    delete p;
-    return FUSEDMM_ERR_ALLOC;
-  }
-
-  // ---- the general kernel's segments: rows longer than kGenericSplit, cut into runs of that length
-  std::vector<ChunkDesc> gen_segs;
-  std::vector<MergeDesc> gen_merges;
-  try {
-    for (int64_t u = 0; u < m; ++u) {
-      const int64_t deg = rp[u + 1] - rp[u];
-      if (deg <= kGenericSplit) continue;
-      const int32_t first = (int32_t)gen_segs.size();
-      for (int64_t off = 0; off < deg; off += kGenericSplit)
-        gen_segs.push_back(ChunkDesc{rp[u] + off, (int32_t)std::min<int64_t>(kGenericSplit, deg - off), (int32_t)u,
-                                     (int32_t)gen_segs.size(), 0});
-      gen_merges.push_back(MergeDesc{(int32_t)u, first, (int32_t)gen_segs.size() - first, 0});
-      if (gen_segs.size() >= (size_t)INT32_MAX / 2) { delete p; return FUSEDMM_ERR_INVALID_ARG; }
-    }
-  } catch (const std::bad_alloc&) {
-    delete p;
-    return FUSEDMM_ERR_ALLOC;
-  }
-  p->n_gen_segs = (int32_t)gen_segs.size();
-  p->n_gen_merges = (int32_t)gen_merges.size();
-
-  st = upload(&p->d_order, order, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_gen_segs, gen_segs, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_gen_merges, gen_merges, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_chunks, chunks, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_merges, merges, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_items, items, stream);
-  if (st == FUSEDMM_OK) st = upload(&p->d_tile_descs, tile_descs, stream);
-  if (st == FUSEDMM_OK && hipStreamSynchronize(stream) != hipSuccess) st = FUSEDMM_ERR_HIP;
-  // the address of the static scratch on this device is looked up here, once, so that
-  // fusedmm_execute_static_scratch finds it in place (its own first call would look it up otherwise)
-  if (st == FUSEDMM_OK) {
-    void* unused = nullptr;
-    (void)static_scratch_for_current_device(&unused);  // a failure is reported by that entry point, not here
-  }
-  // the scratch of the hinted dimension, so that execute never has to allocate
-  if (st == FUSEDMM_OK) st = fusedmm_plan_reserve(p, std::min<int32_t>(d_hint, FUSEDMM_MAX_D));
-  if (st != FUSEDMM_OK) {
-    free_plan_device(p);
-    delete p;
-    return st;
-  }
-  *out = p;
   return FUSEDMM_OK;
 }
 
