@@ -248,7 +248,7 @@ int fusedmm_execute_static_scratch(fusedmm_plan_t* plan, const fusedmm_ops_t* op
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
  * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
  * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes = 8 elements per lane).  d is a
- * multiple of 8 from 8 to 512 (32, 64, 128, 256, 512 on their own instances, the others on the next larger
+ * multiple of 8 from 8 to 1024 (32, 64, 128, 256, 512, 1024 on their own instances, the others on the next larger
  * one; FUSEDMM_ERR_UNSUPPORTED_DIM for any other d, FUSEDMM_ERR_INVALID_ARG for rows that are not
  * aligned).  Any valid op tuple.  The result is that of
  * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back, up to the

@@ -210,27 +210,20 @@ __device__ __forceinline__ void st4(real* p, const vec4& v) {
   __builtin_nontemporal_store(static_cast<vec4g>(v), reinterpret_cast<vec4g*>(p));
 }
 
-// Elements [4*piece, 4*piece + 4) of row `col` of Y as four floats.  YF = kYF32: Y is fp32, one
-// 16-byte load.  YF = kYBf16: Y is stored as bfloat16 (the upper 16 bits of the float), one 8-byte
-// load widened by shifts.  YF = kYF16: IEEE half precision, one 8-byte load and four conversions.
-// The arithmetic stays fp32 in every case.
-// The address is one 32 x 32 -> 64-bit multiply-add: column index (validated, non-negative) times
-// the row pitch in bytes (below 2^32, checked by the host) plus the lane's own base.
+// Four elements of a row of Y stored in 2-byte elements (8 bytes as two 32-bit words) as four floats: bfloat16
+// is the upper 16 bits of the float and is widened by shifts, IEEE half by the hardware conversion.  The
+// arithmetic stays fp32 in every case.
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 template <int YF>
-__device__ __forceinline__ vec4 gather4(const void* Y, int col, int64_t ldy, int piece) {
-  const uint32_t pitch = (uint32_t)ldy * (YF == kYF32 ? (uint32_t)sizeof(real) : 2u);
-  const char* p = static_cast<const char*>(Y) + (size_t)piece * (YF == kYF32 ? (uint32_t)sizeof(vec4) : 8u) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+__device__ __forceinline__ vec4 widen4(v2u raw) {
   if constexpr (YF == kYBf16) {
-    typedef unsigned int v2u __attribute__((ext_vector_type(2)));
-    const v2u raw = *reinterpret_cast<const v2u*>(p);
     return vec4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
                __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
-  } else if constexpr (YF == kYF16) {
-    typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-    const v4h raw = *reinterpret_cast<const v4h*>(p);
-    return vec4{(float)raw.x, (float)raw.y, (float)raw.z, (float)raw.w};
   } else {
-    return *reinterpret_cast<const vec4g*>(p);
+    typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+    const v4h h = __builtin_bit_cast(v4h, raw);
+    return vec4{(float)h.x, (float)h.y, (float)h.z, (float)h.w};
   }
 }
 
@@ -242,51 +235,56 @@ __device__ __forceinline__ int piece_index(int g, int i) {
   if constexpr (C == 1) return g + G * i; else return 2 * (g + G * (i / 2)) + (i & 1);
 }
 
-// One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>.  With C = 2 a
-// lane fetches 16 bytes of 2-byte elements per load: half as many load instructions per row as
-// 8-byte loads need, and it is the number of load instructions that occupies the return path.
+// One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>: fp32 (fp64 in the
+// double-precision build) rows by one 16-byte load per piece; rows of 2-byte elements by one 8-byte load per
+// piece (C = 1) or one 16-byte load per two pieces (C = 2: half as many load instructions per row, and it is
+// the number of load instructions that occupies the return path).
+// The address is one 32 x 32 -> 64-bit multiply-add: column index (validated, non-negative) times the row
+// pitch in bytes (below 2^32, checked by the host) plus the lane's own offset.
 // M = kMaskPieces: pieces at or beyond a.d_pieces read as zero (a dimension below the instance's own);
 // M = kMaskRagged: and the row may end inside its last piece (a dimension that is not a multiple of 4).
+// Rows of 2-byte elements are loaded first, all of them, and widened afterwards: a conversion next to its
+// load inside the mask's branch would make every load wait for the one before.
 template <int YF, int G, int V, int C, int M>
 __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, vec4 (&y)[V]) {
-  if constexpr (C == 1) {
+  const uint32_t pitch = (uint32_t)a.ldy * (YF == kYF32 ? (uint32_t)sizeof(real) : 2u);
+  const char* row = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+  if constexpr (YF == kYF32) {
+    static_assert(C == 1, "one 16-byte load per piece");
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       const int piece = g + G * i;
       if (M == kMaskNone || piece < (M == kMaskRagged ? a.d_full : a.d_pieces)) {
-        y[i] = gather4<YF>(a.Y, col, a.ldy, piece);
-      } else if (M == kMaskRagged && YF == kYF32 && piece < a.d_pieces) {  // the row ends inside this piece
-        const uint32_t pitch = (uint32_t)a.ldy * (uint32_t)sizeof(real);
-        y[i] = ld_tail(reinterpret_cast<const real*>(static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch) + 4 * piece,
-                       a.d_tail);
+        y[i] = *reinterpret_cast<const vec4g*>(row + (size_t)piece * sizeof(vec4));
+      } else if (M == kMaskRagged && piece < a.d_pieces) {  // the row ends inside this piece
+        y[i] = ld_tail(reinterpret_cast<const real*>(row) + 4 * piece, a.d_tail);
       } else {
         y[i] = vec4{0.f, 0.f, 0.f, 0.f};
       }
     }
+  } else if constexpr (C == 1) {
+    v2u raw[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const int piece = g + G * i;
+      if (M == kMaskNone || piece < a.d_pieces) raw[i] = *reinterpret_cast<const v2u*>(row + (size_t)piece * 8u);
+      else raw[i] = v2u{0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) y[i] = widen4<YF>(raw[i]);
   } else {
-    static_assert(YF != kYF32 && V % 2 == 0, "16-byte chunks of 2-byte elements");
-    const uint32_t pitch = (uint32_t)a.ldy * 2u;
-    const char* base = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
+    static_assert(V % 2 == 0, "16-byte chunks of 2-byte elements");
+    v4u raw[V / 2];
 #pragma unroll
     for (int j = 0; j < V / 2; ++j) {
-      if (M != kMaskNone && 2 * (g + G * j) + 1 >= a.d_pieces) {
-        y[2 * j] = y[2 * j + 1] = vec4{0.f, 0.f, 0.f, 0.f};
-        continue;
-      }
-      const char* p = base + (size_t)(g + G * j) * 16u;
-      if constexpr (YF == kYBf16) {
-        typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-        const v4u raw = *reinterpret_cast<const v4u*>(p);
-        y[2 * j] = vec4{__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
-                       __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u)};
-        y[2 * j + 1] = vec4{__builtin_bit_cast(float, raw.z << 16), __builtin_bit_cast(float, raw.z & 0xffff0000u),
-                           __builtin_bit_cast(float, raw.w << 16), __builtin_bit_cast(float, raw.w & 0xffff0000u)};
-      } else {
-        typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-        const v8h raw = *reinterpret_cast<const v8h*>(p);
-        y[2 * j] = vec4{(float)raw.s0, (float)raw.s1, (float)raw.s2, (float)raw.s3};
-        y[2 * j + 1] = vec4{(float)raw.s4, (float)raw.s5, (float)raw.s6, (float)raw.s7};
-      }
+      const int chunk = g + G * j;
+      if (M == kMaskNone || 2 * chunk + 1 < a.d_pieces) raw[j] = *reinterpret_cast<const v4u*>(row + (size_t)chunk * 16u);
+      else raw[j] = v4u{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int j = 0; j < V / 2; ++j) {
+      y[2 * j] = widen4<YF>(v2u{raw[j].x, raw[j].y});
+      y[2 * j + 1] = widen4<YF>(v2u{raw[j].z, raw[j].w});
     }
   }
 }

@@ -1,8 +1,7 @@
 // Specialised FusedMM kernels for d = 1024 (and, masked, for everything between 513 and 1023): lane groups of 64
-// lanes (unroll 2) for wave rows and chunks and for packed short rows.  fp32 storage of Y only.  The four tuning
+// lanes (unroll 2) for wave rows and chunks and for packed short rows.  The four tuning
 // values can be overridden on the compiler command line when sweeping.
 #define FMM_D 1024
-#define FMM_NATIVE_Y_ONLY 1
 #ifndef FMM_GW
 #define FMM_GW 64
 #define FMM_UW 2

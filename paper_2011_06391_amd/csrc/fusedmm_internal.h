@@ -122,8 +122,8 @@ constexpr int kSopValueMinusSigmoid = 100;
 // (the leading dimensions count doubles) and the arithmetic is fp64.
 enum : int { kYF32 = 0, kYBf16 = 1, kYF16 = 2, kYF64 = 3 };
 
-// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512, or 1024 (fp32 storage only).  kYBf16 /
-// kYF16: a.Y holds 2-byte elements (the five sum patterns and the run-time-ops instance exist in that form).
+// Launch the specialised kernel for (pattern, d).  d must be 32/64/128/256/512/1024.  kYBf16 /
+// kYF16: a.Y holds 2-byte elements (every instance except the ragged ones exists in that form).
 hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hipStream_t stream);
 
 // The kernels for very short feature vectors (one lane per stored entry): d must be 2, 3, 4, 8 or 16, fp32,

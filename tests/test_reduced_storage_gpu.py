@@ -79,7 +79,7 @@ def test_half_rounding_kernel_bit_exact(B):
     assert np.isnan(out.cpu().numpy().view(np.float16))[0]
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 16, 72, 136, 392))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 1024, 16, 72, 136, 392, 600))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "general"))
 def test_half_storage_parity(B, pattern, d):
     rng = np.random.default_rng(41 + d)
@@ -127,7 +127,7 @@ def test_half_storage_parity(B, pattern, d):
         plan.close()
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 8, 16, 24, 40, 96, 200, 264, 504))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 1024, 8, 16, 24, 40, 96, 200, 264, 504, 768))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "fr", "general"))
 def test_bf16_storage_parity(B, pattern, d):
     rng = np.random.default_rng(31 + d)
@@ -212,7 +212,7 @@ def test_bf16_argument_checks(B):
     rp, ci = torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda()
     plan = B.Plan(g.m, g.n, rp, ci)
     ops = B.fusedmm_ops_preset("sigmoid")
-    for d, ld, expect in ((44, 48, B.FUSEDMM_ERR_UNSUPPORTED_DIM), (520, 520, B.FUSEDMM_ERR_UNSUPPORTED_DIM),
+    for d, ld, expect in ((44, 48, B.FUSEDMM_ERR_UNSUPPORTED_DIM), (1032, 1032, B.FUSEDMM_ERR_UNSUPPORTED_DIM),
                           (64, 66, B.FUSEDMM_ERR_INVALID_ARG), (48, 52, B.FUSEDMM_ERR_INVALID_ARG)):
         X = torch.zeros((g.m, d), dtype=torch.float32, device="cuda")
         Yb = torch.zeros((g.n, ld), dtype=torch.int16, device="cuda")
