@@ -64,3 +64,31 @@ def test_enum_values_match_header():
             m = re.search(prefix + name + r"\s*=\s*(\d+)", text)
             assert m and int(m.group(1)) == val, (prefix + name)
     assert int(re.search(r"#define FUSEDMM_MAX_D (\d+)", text).group(1)) == binding.FUSEDMM_MAX_D
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_structs(tmp_path):
+    """include/fusedmm.h compiles as C99 on its own (the boundary has no C++ or torch types), and the
+    structures the ctypes binding passes have the header's size and field offsets."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    fields = {"fusedmm_plan_options_t": [f[0] for f in binding.fusedmm_plan_options_t._fields_],
+              "fusedmm_ops_t": [f[0] for f in binding.fusedmm_ops_t._fields_]}
+    lines = ['#include "fusedmm.h"', "#include <stddef.h>", "#include <stdio.h>", "int main(void) {"]
+    for struct, names in fields.items():
+        lines.append(f'  printf("{struct} %zu\\n", sizeof({struct}));')
+        for name in names:
+            lines.append(f'  printf("{struct}.{name} %zu\\n", offsetof({struct}, {name}));')
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for struct, names in fields.items():
+        cls = getattr(binding, struct)
+        assert int(out[struct]) == ctypes.sizeof(cls), struct
+        for name in names:
+            assert int(out[f"{struct}.{name}"]) == getattr(cls, name).offset, f"{struct}.{name}"
