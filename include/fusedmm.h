@@ -53,8 +53,8 @@ extern "C" {
 
 /* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
  * paper's sweep, Table VI) and 1024 run the specialised kernels, every other
- * d from 9 to 1024 the same schedule on the next larger of them, d = 2, 3, 4,
- * 8, 16 kernels of their own; any other 1 <= d <= FUSEDMM_MAX_D runs the
+ * d up to 1024 the same schedule on the next larger of them, d = 2, 3, 4,
+ * 8, 16 kernels of their own; d from 1025 to FUSEDMM_MAX_D runs the
  * general kernel (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
  * element: no alignment beyond that of a float is asked of the fp32 entry
  * points (aligned rows are read fastest: a row that straddles cache lines
@@ -106,8 +106,8 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * (on the next larger size, skipping what lies beyond d) at the other multiples of 4; tuples with a
  * scalar message from a dot product or from the sum / difference of the operands run two families of
  * kernels with their vector loops fixed; every other tuple runs the same schedule with the ops read at
- * run time.  A d from 9 to 1024 that is not a multiple of 4 runs the families, the GCN kernels or the
- * run-time-ops kernel in a form that masks down to the element.  d above 1024 (and 1, 5, 6, 7) runs the
+ * run time.  A d up to 1024 that is not a multiple of 4 runs the families, the GCN kernels or the
+ * run-time-ops kernel in a form that masks down to the element.  d above 1024 runs the
  * general kernel (one wavefront per row or per 256-entry segment of a long row: a correctness path,
  * an order of magnitude slower). */
 typedef struct fusedmm_ops {
@@ -273,10 +273,10 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic (the sigmoid's exponential, reciprocals and square
- * roots are the correctly rounded library ones, not the fp32 hardware approximations).  d from 9 to 512
- * runs the specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; a
- * dimension in between runs on the next larger one; rows may start at any element); every other
- * 1 <= d <= FUSEDMM_MAX_D runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
+ * roots are the correctly rounded library ones, not the fp32 hardware approximations).  d up to 512
+ * runs the specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; any
+ * other dimension runs on the next larger one; rows may start at any element); d from 513 to
+ * FUSEDMM_MAX_D runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
  * way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan
  * with split rows needs fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise):
  * fusedmm_plan_create reserves for fp32 rows only. */

@@ -47,13 +47,12 @@ namespace {
 constexpr size_t kMaxProfiledCalls = 4096;
 
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
-// dimension from kMinWideDim up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in
-// the last piece when d is not a multiple of 4), else 0.  The largest size, 1024, does not exist in double precision.
-constexpr int32_t kMinWideDim = 9;
+// dimension up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in the last piece
+// when d is not a multiple of 4), else 0.  The largest size, 1024, does not exist in double precision.
 constexpr int32_t kMaxWideDim = 1024;
 constexpr int32_t kMaxWideDimF64 = 512;
 int32_t instance_dim(int32_t d) {
-  if (d < kMinWideDim || d > kMaxWideDim) return 0;
+  if (d < 1 || d > kMaxWideDim) return 0;
   int32_t D = 32;
   while (D < d) D *= 2;
   return D;
@@ -66,7 +65,7 @@ int32_t instance_dim_f64(int32_t d) { return d > kMaxWideDimF64 ? 0 : instance_d
 // of 8, from 8 up to 1024.
 int32_t instance_dim_2byte(int32_t d) {
   if (d < 8 || d % 8 != 0 || d > kMaxWideDim) return 0;
-  return std::max<int32_t>(32, instance_dim(d));
+  return instance_dim(d);
 }
 
 // How many floats a partial row of the specialised schedule takes when the plan serves dimensions up to d in
@@ -358,9 +357,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; 9 ... 1024: the wide kernels, on the instance of d itself
-  // or the next larger one (choose_pattern says in which form); everything else, and every call of a plan that
-  // asks for it: the general kernel.  2-byte storage of Y exists on the wide kernels only (d = 8, 16, 24 ... 1024).
+  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; every other d up to 1024: the wide kernels, on the instance
+  // of d itself or the next larger one (choose_pattern says in which form); d above 1024, and every call of a plan
+  // that asks for it: the general kernel.  2-byte storage of Y exists on the wide kernels only (d = 8, 16, 24 ... 1024).
   const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry
   const int32_t D = y_bf16 ? instance_dim_2byte(d) : instance_dim(d);
   const int recognised = recognise(*ops);

@@ -78,7 +78,7 @@ def test_f64_matches_oracle(B, case, d):
 
 # the specialised schedule's double-precision instances: instance sizes and dimensions between them, on a plan
 # whose options put rows into every bin (packed, wave, chunks, column-class tiles with partial rows)
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300, 13, 30, 97, 301))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300, 13, 30, 97, 301, 1, 2, 6, 8, 16))
 @pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
 def test_f64_specialised_schedule_all_bins(B, case, d):
     gpu_ops, gpu_aop, oracle_ops, oracle_aop = case

@@ -182,8 +182,9 @@ def test_general_kernel_odd_dims(B, pattern, d):
     Y = rng.uniform(-0.5, 0.5, (n, d)).astype(np.float32)
     vals = rng.uniform(0.05, 1.0, len(colidx)).astype(np.float32)
     Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
-    Zg, _ = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA)
-    check(Zg, Zr, S, f"{pattern} d={d}")
+    for options in ({"general_kernel_only": 1}, None):   # the general kernel; whatever kernel takes d by default
+        Zg, _ = run_gpu(B, rowptr, colidx, vals, X, Y, pattern, m, n, alpha=ALPHA, options=options)
+        check(Zg, Zr, S, f"{pattern} d={d} {options}")
 
 
 # op tuples outside the five presets: (binding names) -> (oracle names)
@@ -330,9 +331,9 @@ def test_dimensions_between_instance_sizes(B, case, d):
 @pytest.mark.parametrize("d", (5, 50, 130, 516, 1027))
 @pytest.mark.parametrize("case", IN_BETWEEN_CASES, ids=[str(c[0]) + "-" + c[1] for c in IN_BETWEEN_CASES])
 def test_general_kernel_long_rows(B, case, d):
-    """Dimensions the fast schedule cannot take (not a multiple of 4, or above 512) run the general
-    kernel, which cuts rows longer than 256 entries into segments and merges their partial rows:
-    rows of 256, 257, 700, 4000 and 12000 entries, every accumulation kind, visits counted once."""
+    """The general kernel (taken by d above 1024 and by plans that ask for it) cuts rows longer than 256
+    entries into segments and merges their partial rows: rows of 256, 257, 700, 4000 and 12000 entries,
+    every accumulation kind, visits counted once."""
     gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
     rng = np.random.default_rng(77 * d)
     m, n = 150, 900
@@ -348,7 +349,7 @@ def test_general_kernel_long_rows(B, case, d):
     ops = B.fusedmm_ops_preset(gpu_ops) if isinstance(gpu_ops, str) else B.make_ops(*gpu_ops, aop=gpu_aop)
     ops.alpha = ALPHA
     rp, ci = dev(rowptr), dev(colidx)
-    plan = B.Plan(m, n, rp, ci)
+    plan = B.Plan(m, n, rp, ci, {"general_kernel_only": 1})
     plan.reserve(d)
     uses_x = ops.vop != B.VOP["SEL2ND"]
     Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
@@ -372,7 +373,7 @@ def test_general_kernel_long_rows(B, case, d):
     plan.close()
 
 
-@pytest.mark.parametrize("d", (32, 128, 100, 50, 97, 127, 13, 301, 1024, 602))
+@pytest.mark.parametrize("d", (32, 128, 100, 50, 97, 127, 13, 301, 1024, 602, 1, 5, 7))
 @pytest.mark.parametrize("case", SMALL_CASES, ids=[str(c[0]) + "-" + c[1] for c in SMALL_CASES])
 def test_element_aligned_rows_all_bins(B, case, d):
     """The wide kernels on rows that are only aligned to one float: views that start one column in, odd leading
