@@ -47,6 +47,7 @@ def make_case(seed):
         "chunk_edges": int(rng.choice([256, 512, 1024])),
         "column_classes": int(rng.choice([1, 8, 16, 64, 512])),
         "tile_row_min": int(rng.choice([8, 17, 64, 128])),
+        "host_threads": int(rng.choice([0, 1, 3, 64])),
     }
     specials = [0, 1, opts["small_row_max"], opts["small_row_max"] + 1, opts["split_row_min"], opts["split_row_min"] + 1,
                 opts["tile_row_min"] - 1, opts["tile_row_min"], 63, 64, 65, 255, 256, 257, 511, 512, 513, 1024, 1025, 2500]
@@ -65,17 +66,20 @@ def make_case(seed):
     if sorted_cols:
         for u in range(m):
             colidx[rowptr[u]:rowptr[u + 1]].sort()
-    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511, 768, 1024, 1433]))
+    d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511, 768, 1024, 1433,
+                        1, 2, 3, 5, 7, 8, 16, 24, 40, 96, 264, 600]))
     share = rng.random() < 0.3 and m <= n
     ld = d + int(rng.choice([0, 0, 4, 12, 1, 3]))     # rows need no alignment beyond one float
     Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
     Xb = Yb[:m] if share else rng.uniform(-0.7, 0.7, (m, ld)).astype(np.float32)
     vals = rng.uniform(-1, 1, max(1, nnz)).astype(np.float32)[:nnz]
     fmt = str(rng.choice(["f32", "f32", "bf16", "f16"]))
-    if d not in (32, 64, 128, 256, 512) or ld % 8 != 0:
-        # 2-byte storage of Y exists for the five instance sizes and 16-byte aligned rows; elsewhere every third case
+    if d % 8 != 0 or d > 1024 or ld % 8 != 0:
+        # 2-byte storage of Y exists for multiples of 8 up to 1024 and 16-byte aligned rows; elsewhere every third case
         # that asked for it runs in double precision instead
         fmt = "f64" if fmt != "f32" and seed % 3 == 0 else "f32"
+    if fmt in ("f32", "f64") and rng.random() < 0.1:
+        opts["general_kernel_only"] = 1
     return m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts, fmt
 
 
@@ -89,7 +93,7 @@ def rounded(Y, fmt):
     return (keep.astype(np.uint32) << 16).view(np.float32)
 
 
-@pytest.mark.parametrize("seed", range(int(os.environ.get("FUSEDMM_RANDOM_CASES", "60"))))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FUSEDMM_RANDOM_CASES", "150"))))
 def test_random_case(B, seed):
     m, n, d, rowptr, colidx, vals, Xb, Yb, share, opts, fmt = make_case(1000 + seed)
     rng = np.random.default_rng(seed)
@@ -134,7 +138,9 @@ def test_random_case(B, seed):
     assert err <= (1e-12 if fmt == "f64" else TOL), f"{info}: max rel err {err:.3e} at {am}"
     assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
     counts = torch.zeros(max(1, len(colidx)), dtype=torch.int32, device="cuda")
-    plan.edge_visits(d, d <= 1024, counts)     # the indexing of the kernel that ran: the general one above 1024
+    # the indexing of the kernel that ran: 0 = the general one, 1 = the fp32 schedule, 2 = its double-precision instances
+    general = opts.get("general_kernel_only", 0) or d > (512 if fmt == "f64" else 1024)
+    plan.edge_visits(d, 0 if general else (2 if fmt == "f64" else 1), counts)
     torch.cuda.synchronize()
     if len(colidx):
         c = counts[:len(colidx)].cpu().numpy()
