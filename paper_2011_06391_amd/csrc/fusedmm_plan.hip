@@ -15,6 +15,7 @@
 
 #include <algorithm>
 #include <new>
+#include <system_error>
 #include <thread>
 #include <vector>
 
@@ -351,11 +352,19 @@ int build_work_lists(const std::vector<int64_t>& rp, int64_t m, const Settings& 
     tc[(size_t)t].cls_hist.assign(ncls * hw, 0);
     tc[(size_t)t].ti0 = (size_t)(std::lower_bound(tiles.rows.begin(), tiles.rows.end(), (int32_t)(m * t / T)) - tiles.rows.begin());
   }
+  // body(t) for every row range t: range 0 on the calling thread, the others on threads of their own; a range
+  // whose thread cannot be started (the process is at its limit) is walked by the calling thread as well.  The
+  // bodies allocate nothing and throw nothing.
   auto on_threads = [&](auto&& body) {
-    if (T == 1) { body(0); return; }
     std::vector<std::thread> workers;
     workers.reserve((size_t)T);
-    for (int t = 0; t < T; ++t) workers.emplace_back([&body, t]() { body(t); });
+    int started = 1;
+    try {
+      for (; started < T; ++started) workers.emplace_back([&body, t = started]() { body(t); });
+    } catch (const std::system_error&) {
+    }
+    body(0);
+    for (int t = started; t < T; ++t) body(t);
     for (auto& worker : workers) worker.join();
   };
 
