@@ -79,9 +79,29 @@ def build_microbench(verbose: bool = False) -> str:
     return MICROBENCH
 
 
+EXAMPLE_SRC = "example_c_abi.c"
+EXAMPLE = os.path.join(HERE, "example_c_abi")
+
+
+def build_example(verbose: bool = False) -> str:
+    """The plain-C user of the library (gcc, C99): links libfusedmm.so and the HIP runtime, nothing else."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-I", os.path.join(rocm, "include"), os.path.join(CSRC, EXAMPLE_SRC),
+           "-o", EXAMPLE, "-L", HERE, "-lfusedmm", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gcc failed for {EXAMPLE_SRC}:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {EXAMPLE}")
+    return EXAMPLE
+
+
 if __name__ == "__main__":
     if sys.argv[1:] == ["microbench"]:
         build_microbench(verbose=True)
+    elif sys.argv[1:] == ["example"]:
+        build_example(verbose=True)
     else:
         build(verbose=True)
     sys.exit(0)
