@@ -52,10 +52,9 @@ extern "C" {
 #define FUSEDMM_VERSION 100 /* 0.1.0 */
 
 /* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
- * paper's sweep, Table VI) and 1024 run the specialised kernels, every other
- * d up to 1024 the same schedule on the next larger of them, d = 2, 3, 4,
- * 8, 16 kernels of their own; d from 1025 to FUSEDMM_MAX_D runs the
- * general kernel (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
+ * paper's sweep, Table VI), 1024 and 2048 run the specialised kernels, every
+ * other d the same schedule on the next larger of them, d = 2, 3, 4, 8, 16
+ * kernels of their own (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
  * element: no alignment beyond that of a float is asked of the fp32 entry
  * points (aligned rows are read fastest: a row that straddles cache lines
  * costs up to a quarter more). */
@@ -102,14 +101,14 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
  * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
  * The five application patterns below, and the GCN pattern with MAX, MIN or MEAN pooling instead of
- * the sum, run kernels of their own when d is 32, 64, 128, 256, 512 or 1024, and masked forms of them
+ * the sum, run kernels of their own when d is 32, 64, 128, 256, 512, 1024 or 2048, and masked forms of them
  * (on the next larger size, skipping what lies beyond d) at the other multiples of 4; tuples with a
  * scalar message from a dot product or from the sum / difference of the operands run two families of
  * kernels with their vector loops fixed; every other tuple runs the same schedule with the ops read at
- * run time.  A d up to 1024 that is not a multiple of 4 runs the families, the GCN kernels or the
- * run-time-ops kernel in a form that masks down to the element.  d above 1024 runs the
- * general kernel (one wavefront per row or per 256-entry segment of a long row: a correctness path,
- * an order of magnitude slower). */
+ * run time.  A d that is not a multiple of 4 runs the families, the GCN kernels or the
+ * run-time-ops kernel in a form that masks down to the element.  A plan created with general_kernel_only
+ * runs the general kernel instead (one wavefront per row or per 256-entry segment of a long row: a
+ * correctness path, an order of magnitude slower), and so does double precision above d = 512. */
 typedef struct fusedmm_ops {
   int32_t vop, rop, sop, mop, aop;
   float alpha; /* used by FUSEDMM_SOP_SCAL only */

@@ -27,6 +27,7 @@ SOURCES = [
     "fusedmm_fast_d256.hip",
     "fusedmm_fast_d512.hip",
     "fusedmm_fast_d1024.hip",
+    "fusedmm_fast_d2048.hip",
     "fusedmm_fast_f64_d32.hip",
     "fusedmm_fast_f64_d64.hip",
     "fusedmm_fast_f64_d128.hip",

@@ -48,9 +48,12 @@ constexpr size_t kMaxProfiledCalls = 4096;
 
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
 // dimension up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in the last piece
-// when d is not a multiple of 4), else 0.  The largest size, 1024, does not exist in double precision.
-constexpr int32_t kMaxWideDim = 1024;
+// when d is not a multiple of 4), else 0.  The sizes go up to 2048 in fp32, to 1024 for Y stored in 2-byte elements,
+// to 512 in double precision.
+constexpr int32_t kMaxWideDim = 2048;
+constexpr int32_t kMaxWideDim2Byte = 1024;
 constexpr int32_t kMaxWideDimF64 = 512;
+static_assert(kMaxWideDim == FUSEDMM_MAX_D, "every accepted fp32 dimension has an instance to run on");
 int32_t instance_dim(int32_t d) {
   if (d < 1 || d > kMaxWideDim) return 0;
   int32_t D = 32;
@@ -64,7 +67,7 @@ int32_t instance_dim_f64(int32_t d) { return d > kMaxWideDimF64 ? 0 : instance_d
 // The same for Y stored in 2-byte elements: rows are read 16 bytes = 8 elements at a time, so d is a multiple
 // of 8, from 8 up to 1024.
 int32_t instance_dim_2byte(int32_t d) {
-  if (d < 8 || d % 8 != 0 || d > kMaxWideDim) return 0;
+  if (d < 8 || d % 8 != 0 || d > kMaxWideDim2Byte) return 0;
   return instance_dim(d);
 }
 

@@ -821,11 +821,14 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
         for (int i = 0; i < V; ++i) stage[wave][piece_index<GW, CW>(g, i)] = z[i];
       }
       __syncthreads();
-      if (threadIdx.x < (kMasked ? a.d_pieces : D / 4)) {
-        vec4 s = stage[0][threadIdx.x];
+      // a thread per 16-byte piece of the row (two passes at D = 2048, whose rows have 512 pieces)
+#pragma unroll
+      for (int pc = threadIdx.x; pc < D / 4; pc += kBlockThreads) {
+        if (kMasked && pc >= a.d_pieces) break;
+        vec4 s = stage[0][pc];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) {
-          const vec4 o = stage[w][threadIdx.x];
+          const vec4 o = stage[w][pc];
           if constexpr (P == PAT_RUNTIME) {
             s.x = aop_apply(a.aop, s.x, o.x); s.y = aop_apply(a.aop, s.y, o.y);
             s.z = aop_apply(a.aop, s.z, o.z); s.w = aop_apply(a.aop, s.w, o.w);
@@ -841,8 +844,8 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_fast_kernel(const Kerne
           if (a.mean && ch.part < 0) s *= (real)1 / (real)ch.e_count;  // the chunk is the whole row
         }
         real* dst = ch.part < 0 ? Z_of(a) + (int64_t)ch.row * a.ldz : partials_of(a) + (int64_t)ch.part * D;
-        if (kMask != kMaskRagged || (int)threadIdx.x < a.d_full) st4(dst + 4 * threadIdx.x, s);
-        else st_tail(dst + 4 * threadIdx.x, s, a.d_tail);
+        if (kMask != kMaskRagged || pc < a.d_full) st4(dst + 4 * pc, s);
+        else st_tail(dst + 4 * pc, s, a.d_tail);
       }
     }
   } else if (kind == kItemWave) {

@@ -14,8 +14,13 @@ constexpr bool kDouble = true;
 #define FMM_FN(name) FMM_CAT(FMM_CAT(name, _d), FMM_D)
 constexpr bool kDouble = false;
 #endif
-// double precision has no 2-byte storage of Y
-constexpr bool kNativeYOnly = kDouble;
+// sizes that exist for Y in the build's own element type only (no bfloat16 / half storage): double precision,
+// and the largest fp32 size
+#if defined(FMM_F64) || defined(FMM_NATIVE_Y_ONLY)
+constexpr bool kNativeYOnly = true;
+#else
+constexpr bool kNativeYOnly = false;
+#endif
 
 template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {

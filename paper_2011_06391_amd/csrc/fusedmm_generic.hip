@@ -275,10 +275,11 @@ __global__ __launch_bounds__(256) void fusedmm_merge_kernel(const MergeDesc* mer
   typedef E V4 __attribute__((ext_vector_type(4)));
   typedef E V4G __attribute__((ext_vector_type(4), aligned(sizeof(E))));
   const int cols = (d + 3) >> 2;
-  const int rows_per_block = 256 / cols;
-  const int r = threadIdx.x / cols, c = threadIdx.x - r * cols;
+  const int cols_here = cols < 256 ? cols : 256;  // rows of more than 256 columns take gridDim.y workgroups each
+  const int rows_per_block = 256 / cols_here;
+  const int r = threadIdx.x / cols_here, c = blockIdx.y * 256 + (threadIdx.x - r * cols_here);
   const int64_t mi = (int64_t)blockIdx.x * rows_per_block + r;
-  if (r >= rows_per_block || mi >= n_merges) return;
+  if (r >= rows_per_block || mi >= n_merges || c >= cols) return;
   const MergeDesc md = merges[mi];
   const E* src = partials + (int64_t)md.first_part * pstride + 4 * c;  // partial rows are pstride >= 4 * cols apart
   V4 s = {0, 0, 0, 0};
@@ -308,10 +309,11 @@ template <class E>
 static hipError_t launch_merge_t(const MergeDesc* merges, int32_t n_merges, const E* partials, int32_t d, int32_t pstride,
                                  int32_t aop, const int64_t* rowptr, E* Z, int64_t ldz, hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
-  const int rows_per_block = 256 / ((d + 3) >> 2);
+  const int cols = (d + 3) >> 2;
+  const int rows_per_block = 256 / (cols < 256 ? cols : 256);
   const int64_t blocks = ((int64_t)n_merges + rows_per_block - 1) / rows_per_block;
-  hipLaunchKernelGGL(fusedmm_merge_kernel<E>, dim3((unsigned)blocks), dim3(256), 0, stream, merges, n_merges, partials, d,
-                     pstride, aop, rowptr, Z, ldz);
+  hipLaunchKernelGGL(fusedmm_merge_kernel<E>, dim3((unsigned)blocks, (unsigned)((cols + 255) / 256)), dim3(256), 0, stream, merges,
+                     n_merges, partials, d, pstride, aop, rowptr, Z, ldz);
   return hipGetLastError();
 }
 hipError_t launch_merge(const MergeDesc* merges, int32_t n_merges, const float* partials, int32_t d, int32_t pstride,
@@ -421,7 +423,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 #define FMM_DECL(D)                                                                   \
   hipError_t launch_fast##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
   int packed_rows_per_block##D(int y_format);
-FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512) FMM_DECL(_d1024)
+FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512) FMM_DECL(_d1024) FMM_DECL(_d2048)
 FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256) FMM_DECL(_f64_d512)
 #undef FMM_DECL
 
@@ -443,6 +445,7 @@ int packed_rows_per_block(int d, int y_format) {
     case 256: return packed_rows_per_block_d256(y_format);
     case 512: return packed_rows_per_block_d512(y_format);
     case 1024: return packed_rows_per_block_d1024(y_format);
+    case 2048: return packed_rows_per_block_d2048(y_format);
     default: return 0;
   }
 }
@@ -465,6 +468,7 @@ hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hi
     case 256: return launch_fast_d256(pattern, y_format, a, stream);
     case 512: return launch_fast_d512(pattern, y_format, a, stream);
     case 1024: return launch_fast_d1024(pattern, y_format, a, stream);
+    case 2048: return launch_fast_d2048(pattern, y_format, a, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -373,7 +373,7 @@ def test_general_kernel_long_rows(B, case, d):
     plan.close()
 
 
-@pytest.mark.parametrize("d", (32, 128, 100, 50, 97, 127, 13, 301, 1024, 602, 1, 5, 7))
+@pytest.mark.parametrize("d", (32, 128, 100, 50, 97, 127, 13, 301, 1024, 602, 1, 5, 7, 1433, 2048))
 @pytest.mark.parametrize("case", SMALL_CASES, ids=[str(c[0]) + "-" + c[1] for c in SMALL_CASES])
 def test_element_aligned_rows_all_bins(B, case, d):
     """The wide kernels on rows that are only aligned to one float: views that start one column in, odd leading

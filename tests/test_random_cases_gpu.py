@@ -67,7 +67,7 @@ def make_case(seed):
         for u in range(m):
             colidx[rowptr[u]:rowptr[u + 1]].sort()
     d = int(rng.choice([32, 64, 128, 256, 512, 32, 64, 128, 256, 512, 4, 36, 100, 200, 300, 508, 13, 50, 97, 301, 511, 768, 1024, 1433,
-                        1, 2, 3, 5, 7, 8, 16, 24, 40, 96, 264, 600]))
+                        1, 2, 3, 5, 7, 8, 16, 24, 40, 96, 264, 600, 2048]))
     share = rng.random() < 0.3 and m <= n
     ld = d + int(rng.choice([0, 0, 4, 12, 1, 3]))     # rows need no alignment beyond one float
     Yb = rng.uniform(-0.7, 0.7, (n, ld)).astype(np.float32)
@@ -139,7 +139,7 @@ def test_random_case(B, seed):
     assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
     counts = torch.zeros(max(1, len(colidx)), dtype=torch.int32, device="cuda")
     # the indexing of the kernel that ran: 0 = the general one, 1 = the fp32 schedule, 2 = its double-precision instances
-    general = opts.get("general_kernel_only", 0) or d > (512 if fmt == "f64" else 1024)
+    general = opts.get("general_kernel_only", 0) or (fmt == "f64" and d > 512)
     plan.edge_visits(d, 0 if general else (2 if fmt == "f64" else 1), counts)
     torch.cuda.synchronize()
     if len(colidx):

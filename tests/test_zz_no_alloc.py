@@ -26,12 +26,12 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def one_case(B, scale, pairs, d, pattern, seed):
+def one_case(B, scale, pairs, d, pattern, seed, general=False):
     g = synth.rmat(scale, pairs, seed=seed)
     X = synth.fill_uniform((g.m, d), seed + 1, -0.5, 0.5)
     rp, ci, Xd = dev(g.rowptr), dev(g.colidx), dev(X)
     options = {"small_row_max": 8, "split_row_min": 64, "chunk_edges": 256, "column_classes": 8, "tile_row_min": 48,
-               "feature_dim_hint": 32}
+               "feature_dim_hint": 32, "general_kernel_only": int(general)}
     plan_ref = B.Plan(g.m, g.n, rp, ci, options)
     plan_ref.reserve(d)
     plan = B.Plan(g.m, g.n, rp, ci, options)      # never reserved beyond 32: only the static scratch can serve d
@@ -41,7 +41,7 @@ def one_case(B, scale, pairs, d, pattern, seed):
     Z_ref = torch.full((g.m, d), float("nan"), dtype=torch.float32, device="cuda")
     plan_ref.execute(ops, Xd, Xd, Z_ref)
     Z = torch.full((g.m, d), float("nan"), dtype=torch.float32, device="cuda")
-    if 32 < d <= 1024:
+    if d > 32 and not general:
         with pytest.raises(B.FusedMMError) as ei:   # the ordinary entry point refuses: nothing reserved for d
             plan.execute(ops, Xd, Xd, Z)
         assert ei.value.status == B.FUSEDMM_ERR_NOT_RESERVED
@@ -58,10 +58,12 @@ def test_two_calls_in_a_row_second_one_smaller(B):
     big = one_case(B, 13, (1 << 12) * 16, 128, "tdist", 601)
     small = one_case(B, 10, (1 << 9) * 16, 64, "one_minus_sigmoid", 602)
     assert small["partials"] < big["partials"]
-    # and once more through a ragged instance (d not a multiple of 4), through the general kernel (d above 1024),
-    # whose segments use the same array, and through the one-lane-per-entry kernels (partial rows 16 floats apart)
+    # and once more through a ragged instance (d not a multiple of 4), the largest instance (masked), the general
+    # kernel (a plan that asks for it), whose segments use the same array, and through the one-lane-per-entry
+    # kernels (partial rows 16 floats apart)
     one_case(B, 11, (1 << 10) * 16, 50, "fr", 603)
     one_case(B, 11, (1 << 10) * 16, 1100, "fr", 606)
+    one_case(B, 11, (1 << 10) * 16, 300, "fr", 607, general=True)
     one_case(B, 11, (1 << 10) * 16, 3, "fr", 604)
     one_case(B, 12, (1 << 11) * 16, 16, "sigmoid", 605)
 
