@@ -1,8 +1,8 @@
 """Every valid op tuple of the selector (4 VOP x 26 valid ROP/SOP pairs x 3 MOP x 4 AOP = 1248) against the
 oracle, on a small pattern that reaches every bin of the schedule, at dimensions with instances of their own
 (32, 128), between instance sizes on the masked instances (20; 6, 13, 27, 97, 301: rows that end inside a
-16-byte piece; 700 on the 1024 instance), two of the one-lane-per-entry kernels (2, 3), on the general kernel (1100, and 6, 27, 97, 128 with
-the plan told to use nothing else: its lane-group widths and register counts), with Y stored as bfloat16 / half
+16-byte piece; 700 on the 1024 instance, 1100 on the 2048 instance), two of the one-lane-per-entry kernels (2, 3), on the
+general kernel (6, 27, 97, 128 with the plan told to use nothing else: its lane-group widths and register counts), with Y stored as bfloat16 / half
 (narrow loads at 32, wide ones at 64 and 128), and in double precision on the specialised schedule (32, 256, and
 20 on the masked instance; bound 1e-12).  A dispatch slip -- a tuple
 recognised as a pattern it is not, a step skipped at run time -- cannot hide among hand-picked cases."""
@@ -53,7 +53,7 @@ def rounded(Y, fmt):
 @pytest.mark.parametrize("d,fmt", [(32, "f32"), (20, "f32"), (6, "f32"), (128, "f32"), (32, "bf16"), (64, "f16"),
                                    (128, "bf16"), (128, "f16"),
                                    # rows that end inside a 16-byte piece (ragged instances), the 1024 instance at 700,
-                                   # the general kernel at 1100
+                                   # the 2048 instance at 1100
                                    (2, "f32"), (3, "f32"), (13, "f32"), (27, "f32"), (97, "f32"), (301, "f32"),
                                    (700, "f32"), (1100, "f32"), (32, "f64"), (20, "f64"), (256, "f64"),
                                    # the general kernel at dimensions the wide kernels would take
