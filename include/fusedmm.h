@@ -108,7 +108,7 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * run time.  A d that is not a multiple of 4 runs the families, the GCN kernels or the
  * run-time-ops kernel in a form that masks down to the element.  A plan created with general_kernel_only
  * runs the general kernel instead (one wavefront per row or per 256-entry segment of a long row: a
- * correctness path, an order of magnitude slower), and so does double precision above d = 512. */
+ * correctness path, an order of magnitude slower). */
 typedef struct fusedmm_ops {
   int32_t vop, rop, sop, mop, aop;
   float alpha; /* used by FUSEDMM_SOP_SCAL only */
@@ -272,11 +272,11 @@ int fusedmm_to_f16(uint16_t* d_dst, const float* d_src, size_t count, void* stre
 
 /* Double precision (Section V: the method is not tied to single precision): X, Y, Z and the edge
  * values are fp64 and so is every step's arithmetic (the sigmoid's exponential, reciprocals and square
- * roots are the correctly rounded library ones, not the fp32 hardware approximations).  d up to 512
- * runs the specialised schedule of fusedmm_execute on double-precision instances (32, 64, 128, 256, 512; any
- * other dimension runs on the next larger one; rows may start at any element); d from 513 to
- * FUSEDMM_MAX_D runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op tuple either
- * way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan
+ * roots are the correctly rounded library ones, not the fp32 hardware approximations).  Every d
+ * runs the specialised schedule of fusedmm_execute on double-precision instances (32, 64, ... 2048; any
+ * other dimension runs on the next larger one; rows may start at any element); a plan created with
+ * general_kernel_only runs the general kernel (one wavefront per row or 256-entry segment).  Any valid op
+ * tuple either way.  Arguments, layout, ownership and errors as for fusedmm_execute; ops->alpha is widened.  A plan
  * with split rows needs fusedmm_plan_reserve_f64(plan, d) first (FUSEDMM_ERR_NOT_RESERVED otherwise):
  * fusedmm_plan_create reserves for fp32 rows only. */
 int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,

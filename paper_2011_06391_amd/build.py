@@ -33,6 +33,8 @@ SOURCES = [
     "fusedmm_fast_f64_d128.hip",
     "fusedmm_fast_f64_d256.hip",
     "fusedmm_fast_f64_d512.hip",
+    "fusedmm_fast_f64_d1024.hip",
+    "fusedmm_fast_f64_d2048.hip",
 ]
 
 # packed FP32 instructions are switched off for all device code

@@ -48,12 +48,11 @@ constexpr size_t kMaxProfiledCalls = 4096;
 
 // The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
 // dimension up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in the last piece
-// when d is not a multiple of 4), else 0.  The sizes go up to 2048 in fp32, to 1024 for Y stored in 2-byte elements,
-// to 512 in double precision.
+// when d is not a multiple of 4), else 0.  The sizes go up to 2048 in fp32 and double precision, to 1024 for Y
+// stored in 2-byte elements.
 constexpr int32_t kMaxWideDim = 2048;
 constexpr int32_t kMaxWideDim2Byte = 1024;
-constexpr int32_t kMaxWideDimF64 = 512;
-static_assert(kMaxWideDim == FUSEDMM_MAX_D, "every accepted fp32 dimension has an instance to run on");
+static_assert(kMaxWideDim == FUSEDMM_MAX_D, "every accepted dimension has an instance to run on");
 int32_t instance_dim(int32_t d) {
   if (d < 1 || d > kMaxWideDim) return 0;
   int32_t D = 32;
@@ -61,8 +60,8 @@ int32_t instance_dim(int32_t d) {
   return D;
 }
 
-// The same for double precision: the five sizes up to 512.
-int32_t instance_dim_f64(int32_t d) { return d > kMaxWideDimF64 ? 0 : instance_dim(d); }
+// The same sizes exist in double precision.
+int32_t instance_dim_f64(int32_t d) { return instance_dim(d); }
 
 // The same for Y stored in 2-byte elements: rows are read 16 bytes = 8 elements at a time, so d is a multiple
 // of 8, from 8 up to 1024.
@@ -77,7 +76,7 @@ int32_t partial_floats_f32(int32_t d) {
   return std::max<int32_t>(d >= kMaxWideDim ? kMaxWideDim : instance_dim(d), kSmallPartialStride);
 }
 // ... and in fp64 (two floats per element)
-int32_t partial_floats_f64(int32_t d) { return 2 * (d >= kMaxWideDimF64 ? kMaxWideDimF64 : instance_dim_f64(d)); }
+int32_t partial_floats_f64(int32_t d) { return 2 * (d >= kMaxWideDim ? kMaxWideDim : instance_dim_f64(d)); }
 
 bool ops_valid(const fusedmm_ops_t& o, bool allow_private = false) {
   if (allow_private && o.sop == kSopValueMinusSigmoid)  // scalar message from a reduction and the edge value

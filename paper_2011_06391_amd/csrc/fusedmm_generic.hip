@@ -425,6 +425,7 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
   int packed_rows_per_block##D(int y_format);
 FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512) FMM_DECL(_d1024) FMM_DECL(_d2048)
 FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256) FMM_DECL(_f64_d512)
+FMM_DECL(_f64_d1024) FMM_DECL(_f64_d2048)
 #undef FMM_DECL
 
 int packed_rows_per_block(int d, int y_format) {
@@ -435,6 +436,8 @@ int packed_rows_per_block(int d, int y_format) {
       case 128: return packed_rows_per_block_f64_d128(kYF32);
       case 256: return packed_rows_per_block_f64_d256(kYF32);
       case 512: return packed_rows_per_block_f64_d512(kYF32);
+      case 1024: return packed_rows_per_block_f64_d1024(kYF32);
+      case 2048: return packed_rows_per_block_f64_d2048(kYF32);
       default: return 0;
     }
   }
@@ -458,6 +461,8 @@ hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hi
       case 128: return launch_fast_f64_d128(pattern, kYF32, a, stream);
       case 256: return launch_fast_f64_d256(pattern, kYF32, a, stream);
       case 512: return launch_fast_f64_d512(pattern, kYF32, a, stream);
+      case 1024: return launch_fast_f64_d1024(pattern, kYF32, a, stream);
+      case 2048: return launch_fast_f64_d2048(pattern, kYF32, a, stream);
       default: return hipErrorInvalidValue;
     }
   }

@@ -43,7 +43,7 @@ CASES = [
 ]
 
 
-# every lane-group width and register count of the kernel
+# every lane-group width and register count of the general kernel, and whatever instance takes d by default
 @pytest.mark.parametrize("d", (2, 3, 5, 13, 27, 64, 128, 200, 301, 700))
 @pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
 def test_f64_matches_oracle(B, case, d):
@@ -61,24 +61,25 @@ def test_f64_matches_oracle(B, case, d):
     else:
         ops = B.make_ops(*gpu_ops, aop=gpu_aop)
     ops.alpha = alpha
-    plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx))
-    plan.reserve_f64(d)
     uses_x = ops.vop != B.VOP["SEL2ND"]
-    Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
-    plan.execute_f64(ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z,
-                     dev(vals.astype(np.float64)))
-    torch.cuda.synchronize()
-    Zg = Z.cpu().numpy()
-    scale = np.where(S > 0, S, 1.0)
-    err = np.abs(Zg - Zr_alpha) / scale
-    assert (Zg[S == 0] == 0).all()
-    assert err.max() <= TOL64, f"{case[0]} {gpu_aop} d={d}: {err.max():.3e}"
-    plan.close()
+    for options in (None, {"general_kernel_only": 1}):   # the kernel that takes d by default; the general kernel
+        plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx), options)
+        plan.reserve_f64(d)
+        Z = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+        plan.execute_f64(ops, dev(X.astype(np.float64)) if uses_x else None, dev(Y.astype(np.float64)), Z,
+                         dev(vals.astype(np.float64)))
+        torch.cuda.synchronize()
+        Zg = Z.cpu().numpy()
+        scale = np.where(S > 0, S, 1.0)
+        err = np.abs(Zg - Zr_alpha) / scale
+        assert (Zg[S == 0] == 0).all()
+        assert err.max() <= TOL64, f"{case[0]} {gpu_aop} d={d} {options}: {err.max():.3e}"
+        plan.close()
 
 
 # the specialised schedule's double-precision instances: instance sizes and dimensions between them, on a plan
 # whose options put rows into every bin (packed, wave, chunks, column-class tiles with partial rows)
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300, 13, 30, 97, 301, 1, 2, 6, 8, 16))
+@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 20, 100, 200, 300, 13, 30, 97, 301, 1, 2, 6, 8, 16, 700, 1024, 1500, 2048))
 @pytest.mark.parametrize("case", CASES, ids=[str(c[0]) + "-" + c[1] for c in CASES])
 def test_f64_specialised_schedule_all_bins(B, case, d):
     gpu_ops, gpu_aop, oracle_ops, oracle_aop = case
@@ -126,17 +127,20 @@ def test_f64_specialised_schedule_all_bins(B, case, d):
 
 
 def test_f64_specialised_schedule_is_the_one_that_runs(B):
-    """fusedmm_execute_f64 at d = 128 must be several times faster than at d = 520, which only the general kernel
-    takes, per element of work -- a silent fall-back of the instance sizes to the general kernel would show here.
+    """fusedmm_execute_f64 at d = 128 must be several times faster than the general kernel at the same d (a plan
+    that asks for it) -- a silent fall-back of the instance sizes to the general kernel would show here.
     Rows that start at an odd element run the same instances (the kernels read element-aligned vectors)."""
     g = synth.rmat(14, (1 << 14) * 32, seed=77)
     m = n = g.m
     rng = np.random.default_rng(3)
-    plan = B.Plan(m, n, dev(g.rowptr), dev(g.colidx))
-    plan.reserve_f64(520)
+    rp, ci = dev(g.rowptr), dev(g.colidx)
+    plan_fast = B.Plan(m, n, rp, ci)
+    plan_general = B.Plan(m, n, rp, ci, {"general_kernel_only": 1})
+    for p in (plan_fast, plan_general):
+        p.reserve_f64(128)
     ops = B.fusedmm_ops_preset("sigmoid")
 
-    def timed(d, off):
+    def timed(plan, d, off):
         Xw = torch.from_numpy(rng.uniform(-0.5, 0.5, (m, d + 4))).cuda()
         Zw = torch.empty((m, d + 4), dtype=torch.float64, device="cuda")
         X, Z = Xw[:, off:off + d], Zw[:, off:off + d]
@@ -151,9 +155,10 @@ def test_f64_specialised_schedule_is_the_one_that_runs(B):
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / 10 / d
 
-    t_fast, t_odd, t_gen = timed(128, 0), timed(128, 1), timed(520, 0)
+    t_fast, t_odd, t_gen = timed(plan_fast, 128, 0), timed(plan_fast, 128, 1), timed(plan_general, 128, 0)
     assert t_fast * 2 < t_gen and t_odd * 2 < t_gen, (t_fast, t_odd, t_gen)
-    plan.close()
+    plan_fast.close()
+    plan_general.close()
 
 
 def test_f64_reads_all_64_bits(B):

@@ -139,7 +139,7 @@ def test_random_case(B, seed):
     assert np.isnan(out[:, d:]).all(), info  # padding columns untouched
     counts = torch.zeros(max(1, len(colidx)), dtype=torch.int32, device="cuda")
     # the indexing of the kernel that ran: 0 = the general one, 1 = the fp32 schedule, 2 = its double-precision instances
-    general = opts.get("general_kernel_only", 0) or (fmt == "f64" and d > 512)
+    general = opts.get("general_kernel_only", 0)
     plan.edge_visits(d, 0 if general else (2 if fmt == "f64" else 1), counts)
     torch.cuda.synchronize()
     if len(colidx):
