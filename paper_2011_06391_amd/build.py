@@ -23,10 +23,15 @@ SOURCES = [
     "fusedmm_small.hip",
     "fusedmm_fast_d32.hip",
     "fusedmm_fast_d64.hip",
+    "fusedmm_fast_d96.hip",
     "fusedmm_fast_d128.hip",
+    "fusedmm_fast_d192.hip",
     "fusedmm_fast_d256.hip",
+    "fusedmm_fast_d384.hip",
     "fusedmm_fast_d512.hip",
+    "fusedmm_fast_d768.hip",
     "fusedmm_fast_d1024.hip",
+    "fusedmm_fast_d1536.hip",
     "fusedmm_fast_d2048.hip",
     "fusedmm_fast_f64_d32.hip",
     "fusedmm_fast_f64_d64.hip",

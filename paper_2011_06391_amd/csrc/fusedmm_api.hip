@@ -46,10 +46,11 @@ namespace {
 
 constexpr size_t kMaxProfiledCalls = 4096;
 
-// The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (any
-// dimension up to kMaxWideDim: the masked instances skip what lies beyond d, element by element in the last piece
-// when d is not a multiple of 4), else 0.  The sizes go up to 2048 in fp32 and double precision, to 1024 for Y
-// stored in 2-byte elements.
+// The instance size a dimension runs on: itself if it has instances of its own, else the next larger one (the
+// masked instances skip what lies beyond d, element by element in the last piece when d is not a multiple of 4),
+// else 0.  fp32: the powers of two from 32 to 2048 and the sizes halfway between them (96 ... 1536: a dimension
+// such as 300 or 768 would leave 40 % or 25 % of the lanes of the next power of two idle); Y stored in 2-byte
+// elements: the same sizes up to 1024; double precision: the powers of two.
 constexpr int32_t kMaxWideDim = 2048;
 constexpr int32_t kMaxWideDim2Byte = 1024;
 static_assert(kMaxWideDim == FUSEDMM_MAX_D, "every accepted dimension has an instance to run on");
@@ -57,14 +58,19 @@ int32_t instance_dim(int32_t d) {
   if (d < 1 || d > kMaxWideDim) return 0;
   int32_t D = 32;
   while (D < d) D *= 2;
+  return (D >= 128 && d <= D / 4 * 3) ? D / 4 * 3 : D;
+}
+
+// Double precision: the powers of two.
+int32_t instance_dim_f64(int32_t d) {
+  if (d < 1 || d > kMaxWideDim) return 0;
+  int32_t D = 32;
+  while (D < d) D *= 2;
   return D;
 }
 
-// The same sizes exist in double precision.
-int32_t instance_dim_f64(int32_t d) { return instance_dim(d); }
-
-// The same for Y stored in 2-byte elements: rows are read 16 bytes = 8 elements at a time, so d is a multiple
-// of 8, from 8 up to 1024.
+// Y stored in 2-byte elements: rows are read 16 bytes = 8 elements at a time, so d is a multiple of 8, from 8 up
+// to 1024.
 int32_t instance_dim_2byte(int32_t d) {
   if (d < 8 || d % 8 != 0 || d > kMaxWideDim2Byte) return 0;
   return instance_dim(d);
@@ -195,8 +201,9 @@ void fill_generic_segments(const fusedmm_plan* p, GenericArgsT<T>* g) {
   g->partials = static_cast<T*>(p->d_gen_partials);
 }
 
-// d: the instance size of a wide kernel, or the dimension itself for the kernels for very short feature vectors
-void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelArgs* a) {
+// d: the instance size of a wide kernel (pattern: the instance launch_fast will be given), or the dimension itself
+// for the kernels for very short feature vectors
+void fill_schedule_args(const fusedmm_plan* p, int pattern, int32_t d, int y_format, KernelArgs* a) {
   a->rowptr = p->d_rowptr;
   a->colidx = p->d_colidx;
   a->order = p->d_order;
@@ -213,7 +220,7 @@ void fill_schedule_args(const fusedmm_plan* p, int32_t d, int y_format, KernelAr
   a->nb_zero = (p->n_empty + kZeroRowsPerBlock - 1) / kZeroRowsPerBlock;
   a->nb_chunk = p->n_chunks;
   a->nb_wave = (p->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
-  const int rpb = (is_small_dim(d) && y_format != kYF64) ? small_packed_rows_per_block(d) : packed_rows_per_block(d, y_format);
+  const int rpb = (is_small_dim(d) && y_format != kYF64) ? small_packed_rows_per_block(d) : packed_rows_per_block(pattern, d, y_format);
   a->nb_packed = rpb > 0 ? (p->n_packed + rpb - 1) / rpb : 0;
 }
 
@@ -390,7 +397,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     }
     float* partials = static_scratch ? static_cast<float*>(static_scratch) : plan->d_partials;
     KernelArgs a;
-    fill_schedule_args(plan, d, kYF32, &a);
+    fill_schedule_args(plan, recognised, d, kYF32, &a);
     a.partials = partials;
     a.d_pieces = a.d_full = a.d_tail = 0;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
@@ -412,7 +419,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     }
     float* partials = static_scratch ? static_cast<float*>(static_scratch) : plan->d_partials;
     KernelArgs a;
-    fill_schedule_args(plan, D, y_format, &a);
+    fill_schedule_args(plan, pattern, D, y_format, &a);
     a.partials = partials;
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
@@ -531,7 +538,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     const int family = recognise_family(*ops);
     const int pattern = choose_pattern(recognised, family, d, D);
     KernelArgs a;
-    fill_schedule_args(plan, D, kYF64, &a);
+    fill_schedule_args(plan, pattern, D, kYF64, &a);
     fill_op_args(*ops, &a);
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
@@ -589,14 +596,16 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     const int fmt = fast_path == 2 ? kYF64 : kYF32;
     const int32_t D = fast_path == 2 ? instance_dim_f64(d)
                                      : (is_small_dim(d) ? 0 : instance_dim(d));  // 0: the kernels for very short feature vectors
-    fill_schedule_args(plan, D ? D : d, fmt, &a);
+    // a dimension that is not a multiple of 4 runs the ragged instances, which may have lane groups of their own
+    const int visit = (D != 0 && d % 4 != 0) ? (PAT_VISIT | kPatRagged) : PAT_VISIT;
+    fill_schedule_args(plan, visit, D ? D : d, fmt, &a);
     a.values = nullptr; a.X = nullptr; a.Y = nullptr; a.Z = nullptr;
     a.ldx = a.ldy = a.ldz = d;
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
     a.visit_counts = d_counts;
-    e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(PAT_VISIT, D, fmt, a, stream);
+    e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(visit, D, fmt, a, stream);
   } else {
     GenericArgs g = {};
     g.rowptr = plan->d_rowptr; g.colidx = plan->d_colidx;

@@ -22,18 +22,56 @@ constexpr bool kNativeYOnly = true;
 constexpr bool kNativeYOnly = false;
 #endif
 
+// Three sets of lane groups and unrolls per size (the last two default to the first):
+//   FMM_GW / UW / GP / UP           the application patterns at the size itself: the values a sweep found fastest
+//   FMM_GW_R / UW_R / GP_R / UP_R   every other instance -- masked and ragged forms, the tuple families, run-time
+//                                   ops.  They need more registers per lane or test a mask per register: at the
+//                                   large sizes the narrow lane groups that suit the plain patterns leave the
+//                                   ragged forms one wavefront per SIMD (d = 1433 on 32-lane groups: 3.4 ms
+//                                   against 1.6 ms on 64) and make the masked ones slower than the full size
+//   FMM_GW_2B / ...                 rows of 2-byte elements (the kernel halves the groups where that leaves 8
+//                                   lanes, to read 16 bytes per lane)
+#ifndef FMM_GW_R
+#define FMM_GW_R FMM_GW
+#define FMM_UW_R FMM_UW
+#define FMM_GP_R FMM_GP
+#define FMM_UP_R FMM_UP
+#endif
+#ifndef FMM_GW_2B
+#define FMM_GW_2B FMM_GW_R
+#define FMM_UW_2B FMM_UW_R
+#define FMM_GP_2B FMM_GP_R
+#define FMM_UP_2B FMM_UP_R
+#endif
+
+// whether an instance takes the second set
+constexpr bool register_heavy(int pm) {
+  const int p = pm & ~(kPatMasked | kPatRagged);
+  return (pm & (kPatRagged | kPatMasked)) != 0 || p == PAT_RUNTIME || p == PAT_DOT || p == PAT_DOT_MM || p == PAT_DIST || p == PAT_DIST_MM;
+}
+
 template <int P, int YF>
 static hipError_t launch_one(const KernelArgs& a, hipStream_t stream) {
   const int64_t blocks = (int64_t)a.nb_tiled + a.nb_chunk + a.nb_wave + a.nb_packed + a.nb_zero;
   if (blocks <= 0) return hipSuccess;
-  hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP, YF>), dim3((unsigned)blocks),
-                     dim3(kBlockThreads), 0, stream, a);
+  if constexpr (YF != kYF32) {
+    hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW_2B, FMM_UW_2B, FMM_GP_2B, FMM_UP_2B, YF>), dim3((unsigned)blocks),
+                       dim3(kBlockThreads), 0, stream, a);
+  } else if constexpr (register_heavy(P)) {
+    hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW_R, FMM_UW_R, FMM_GP_R, FMM_UP_R, YF>), dim3((unsigned)blocks),
+                       dim3(kBlockThreads), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((fusedmm_fast_kernel<P, FMM_D, FMM_GW, FMM_UW, FMM_GP, FMM_UP, YF>), dim3((unsigned)blocks),
+                       dim3(kBlockThreads), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
-// rows of 2-byte elements use lane groups half as wide where that leaves 8 lanes (see the kernel)
-int FMM_FN(packed_rows_per_block)(int y_format) {
-  const int gp = (y_format != kYF32 && FMM_GP >= 16) ? FMM_GP / 2 : FMM_GP;
+// rows per workgroup of the packed region: 4 wavefronts of 64 / GP rows, GP as launch_one chooses it
+int FMM_FN(packed_rows_per_block)(int pattern, int y_format) {
+  int gp = FMM_GP;
+  if (y_format != kYF32) gp = FMM_GP_2B >= 16 ? FMM_GP_2B / 2 : FMM_GP_2B;
+  else if (register_heavy(pattern)) gp = FMM_GP_R;
   return kWavesPerBlock * (64 / gp);
 }
 
@@ -57,6 +95,7 @@ static hipError_t launch_format(int pattern, const KernelArgs& a, hipStream_t st
         case PAT_GCN: return launch_one<PAT_GCN | kPatRagged, kYF32>(a, stream);
         case PAT_GCN_MAX: return launch_one<PAT_GCN_MAX | kPatRagged, kYF32>(a, stream);
         case PAT_GCN_MIN: return launch_one<PAT_GCN_MIN | kPatRagged, kYF32>(a, stream);
+        case PAT_VISIT: return launch_one<PAT_VISIT | kPatRagged, kYF32>(a, stream);  // the edge-visit hook on these lane groups
         default: return hipErrorInvalidValue;
       }
     }

@@ -422,33 +422,39 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
 // ---- dispatcher over the per-dimension translation units --------------------------------
 #define FMM_DECL(D)                                                                   \
   hipError_t launch_fast##D(int pattern, int y_format, const KernelArgs& a, hipStream_t stream); \
-  int packed_rows_per_block##D(int y_format);
+  int packed_rows_per_block##D(int pattern, int y_format);
 FMM_DECL(_d32) FMM_DECL(_d64) FMM_DECL(_d128) FMM_DECL(_d256) FMM_DECL(_d512) FMM_DECL(_d1024) FMM_DECL(_d2048)
+FMM_DECL(_d96) FMM_DECL(_d192) FMM_DECL(_d384) FMM_DECL(_d768) FMM_DECL(_d1536)
 FMM_DECL(_f64_d32) FMM_DECL(_f64_d64) FMM_DECL(_f64_d128) FMM_DECL(_f64_d256) FMM_DECL(_f64_d512)
 FMM_DECL(_f64_d1024) FMM_DECL(_f64_d2048)
 #undef FMM_DECL
 
-int packed_rows_per_block(int d, int y_format) {
+int packed_rows_per_block(int pattern, int d, int y_format) {
   if (y_format == kYF64) {
     switch (d) {
-      case 32: return packed_rows_per_block_f64_d32(kYF32);
-      case 64: return packed_rows_per_block_f64_d64(kYF32);
-      case 128: return packed_rows_per_block_f64_d128(kYF32);
-      case 256: return packed_rows_per_block_f64_d256(kYF32);
-      case 512: return packed_rows_per_block_f64_d512(kYF32);
-      case 1024: return packed_rows_per_block_f64_d1024(kYF32);
-      case 2048: return packed_rows_per_block_f64_d2048(kYF32);
+      case 32: return packed_rows_per_block_f64_d32(pattern, kYF32);
+      case 64: return packed_rows_per_block_f64_d64(pattern, kYF32);
+      case 128: return packed_rows_per_block_f64_d128(pattern, kYF32);
+      case 256: return packed_rows_per_block_f64_d256(pattern, kYF32);
+      case 512: return packed_rows_per_block_f64_d512(pattern, kYF32);
+      case 1024: return packed_rows_per_block_f64_d1024(pattern, kYF32);
+      case 2048: return packed_rows_per_block_f64_d2048(pattern, kYF32);
       default: return 0;
     }
   }
   switch (d) {
-    case 32: return packed_rows_per_block_d32(y_format);
-    case 64: return packed_rows_per_block_d64(y_format);
-    case 128: return packed_rows_per_block_d128(y_format);
-    case 256: return packed_rows_per_block_d256(y_format);
-    case 512: return packed_rows_per_block_d512(y_format);
-    case 1024: return packed_rows_per_block_d1024(y_format);
-    case 2048: return packed_rows_per_block_d2048(y_format);
+    case 32: return packed_rows_per_block_d32(pattern, y_format);
+    case 64: return packed_rows_per_block_d64(pattern, y_format);
+    case 128: return packed_rows_per_block_d128(pattern, y_format);
+    case 256: return packed_rows_per_block_d256(pattern, y_format);
+    case 512: return packed_rows_per_block_d512(pattern, y_format);
+    case 1024: return packed_rows_per_block_d1024(pattern, y_format);
+    case 2048: return packed_rows_per_block_d2048(pattern, y_format);
+    case 96: return packed_rows_per_block_d96(pattern, y_format);
+    case 192: return packed_rows_per_block_d192(pattern, y_format);
+    case 384: return packed_rows_per_block_d384(pattern, y_format);
+    case 768: return packed_rows_per_block_d768(pattern, y_format);
+    case 1536: return packed_rows_per_block_d1536(pattern, y_format);
     default: return 0;
   }
 }
@@ -474,6 +480,11 @@ hipError_t launch_fast(int pattern, int d, int y_format, const KernelArgs& a, hi
     case 512: return launch_fast_d512(pattern, y_format, a, stream);
     case 1024: return launch_fast_d1024(pattern, y_format, a, stream);
     case 2048: return launch_fast_d2048(pattern, y_format, a, stream);
+    case 96: return launch_fast_d96(pattern, y_format, a, stream);
+    case 192: return launch_fast_d192(pattern, y_format, a, stream);
+    case 384: return launch_fast_d384(pattern, y_format, a, stream);
+    case 768: return launch_fast_d768(pattern, y_format, a, stream);
+    case 1536: return launch_fast_d1536(pattern, y_format, a, stream);
     default: return hipErrorInvalidValue;
   }
 }

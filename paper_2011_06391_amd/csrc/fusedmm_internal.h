@@ -108,8 +108,9 @@ hipError_t launch_tile_bounds(const int64_t* rowptr, const int32_t* colidx, cons
                               const int64_t* out_off, int32_t n_rows, int32_t n_classes, const int32_t* class_start,
                               int32_t* bounds, int32_t* unsorted, hipStream_t stream);
 
-// Rows per workgroup in the packed range for dimension d and storage format of Y (host needs it for the grid).
-int packed_rows_per_block(int d, int y_format);
+// Rows per workgroup in the packed range for the instance (pattern id, size d, storage format of Y) that
+// launch_fast will run (the host needs it for the grid).
+int packed_rows_per_block(int pattern, int d, int y_format);
 
 // A scaling step outside the public selector, used by the minibatch layer (the paper's SOP is
 // user-definable, Section III-A): h = a_uv - sigmoid(s), which with a_uv = 1 on the stored entries of

@@ -16,7 +16,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
-FAST_DIMS = (32, 64, 128, 256, 512)
+FAST_DIMS = (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048)   # the sizes with instances of their own
 PATTERNS = ("sigmoid", "one_minus_sigmoid", "gcn", "tdist", "fr")
 ALPHA = 0.37
 

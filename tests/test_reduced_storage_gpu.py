@@ -79,7 +79,7 @@ def test_half_rounding_kernel_bit_exact(B):
     assert np.isnan(out.cpu().numpy().view(np.float16))[0]
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 1024, 16, 72, 136, 392, 600))
+@pytest.mark.parametrize("d", (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 16, 72, 136, 392, 600))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "general"))
 def test_half_storage_parity(B, pattern, d):
     rng = np.random.default_rng(41 + d)
@@ -127,7 +127,7 @@ def test_half_storage_parity(B, pattern, d):
         plan.close()
 
 
-@pytest.mark.parametrize("d", (32, 64, 128, 256, 512, 1024, 8, 16, 24, 40, 96, 200, 264, 504, 768))
+@pytest.mark.parametrize("d", (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 8, 16, 24, 40, 80, 200, 264, 504, 600))
 @pytest.mark.parametrize("pattern", ("one_minus_sigmoid", "gcn", "tdist", "fr", "general"))
 def test_bf16_storage_parity(B, pattern, d):
     rng = np.random.default_rng(31 + d)
