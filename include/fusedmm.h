@@ -52,9 +52,10 @@ extern "C" {
 #define FUSEDMM_VERSION 100 /* 0.1.0 */
 
 /* Largest feature dimension accepted.  d in {32, 64, 128, 256, 512} (the
- * paper's sweep, Table VI), 1024 and 2048 run the specialised kernels, every
- * other d the same schedule on the next larger of them, d = 2, 3, 4, 8, 16
- * kernels of their own (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
+ * paper's sweep, Table VI), 1024, 2048 and the sizes halfway between them
+ * (96, 192, ... 1536) run the specialised kernels, every other d the same
+ * schedule on the next larger of them, d = 2, 3, 4, 8, 16 kernels of their
+ * own (see fusedmm_ops_t below).  Rows of X, Y and Z may start at any
  * element: no alignment beyond that of a float is asked of the fp32 entry
  * points (aligned rows are read fastest: a row that straddles cache lines
  * costs up to a quarter more). */
@@ -101,7 +102,7 @@ typedef enum { FUSEDMM_AOP_SUM = 0, FUSEDMM_AOP_MAX = 1, FUSEDMM_AOP_MIN = 2, FU
  * SOP == EDGE_VALUE requires ROP == NOOP (the message is the stored edge value; nothing to reduce).
  * X is read iff VOP != SEL2ND; d_values is read iff SOP == EDGE_VALUE.
  * The five application patterns below, and the GCN pattern with MAX, MIN or MEAN pooling instead of
- * the sum, run kernels of their own when d is 32, 64, 128, 256, 512, 1024 or 2048, and masked forms of them
+ * the sum, run kernels of their own when d is 32, 64, 96, 128, 192, ... 1536 or 2048, and masked forms of them
  * (on the next larger size, skipping what lies beyond d) at the other multiples of 4; tuples with a
  * scalar message from a dot product or from the sum / difference of the operands run two families of
  * kernels with their vector loops fixed; every other tuple runs the same schedule with the ops read at
@@ -232,7 +233,7 @@ int fusedmm_execute(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d,
  * (FUSEDMM_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of the plan's scratch, so the
  * call works at any dimension whatever was reserved.  It calls no allocation routine of any kind.
  *   - Limit: partial rows x kernel size x 4 bytes (fusedmm_plan_stats gives the partial rows; the kernel size
- *     is d rounded up to 32/64/128/256/512; for the general kernel: 256-entry segments of long rows x d x 4)
+ *     is d rounded up to the next of 32, 64, 96, 128, 192, 256, ... 1536, 2048; for the general kernel: 256-entry segments of long rows x d x 4)
  *     must fit, else FUSEDMM_ERR_SCRATCH_LIMIT and nothing is launched.
  *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, or
  *     two plans) race on it.  Calls on one stream are ordered and safe.  Nothing in it has to start at
@@ -247,7 +248,7 @@ int fusedmm_execute_static_scratch(fusedmm_plan_t* plan, const fusedmm_ops_t* op
  * gathered rows are half as long, which is what bounds the kernel; x_u, every step's arithmetic,
  * the accumulation and Z stay fp32.  d_Y_bf16: device, n x d uint16 (ldy in elements, rows
  * 16-byte aligned: base aligned and ldy % 8 == 0; they are read 16 bytes = 8 elements per lane).  d is a
- * multiple of 8 from 8 to 1024 (32, 64, 128, 256, 512, 1024 on their own instances, the others on the next larger
+ * multiple of 8 from 8 to 1024 (32, 64, 96, 128, ... 768, 1024 on their own instances, the others on the next larger
  * one; FUSEDMM_ERR_UNSUPPORTED_DIM for any other d, FUSEDMM_ERR_INVALID_ARG for rows that are not
  * aligned).  Any valid op tuple.  The result is that of
  * fusedmm_execute on the fp32 matrix whose entries are the bfloat16 values widened back, up to the
