@@ -147,6 +147,19 @@ int choose_pattern(int recognised, int family, int32_t d, int32_t D) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// The ragged instances (d not a multiple of 4) gather the piece a row of Y ends in with one 4-element load, which
+// reads 4 - d % 4 elements beyond the row; from the row returned here on, that would reach beyond the last element
+// of the matrix, and the kernels move the load back to end with the row.  -1 when such a load of the first of those
+// rows would begin before the matrix (a matrix of fewer than four elements before that row's end): then the wide
+// kernels cannot take the call.
+int32_t first_back_row(int64_t n, int64_t ldy, int32_t d) {
+  if (d % 4 == 0 || n <= 0) return (int32_t)std::max<int64_t>(n, 0);
+  const int64_t beyond = 4 - d % 4;
+  const int64_t first = std::max<int64_t>(0, n - (beyond + ldy - 1) / ldy);
+  if (first * ldy + d - 4 < 0) return -1;
+  return (int32_t)first;
+}
+
 bool overlaps(const float* a, int64_t rows_a, int64_t ld_a, const float* b, int64_t rows_b, int64_t ld_b, int32_t d) {
   if (!a || !b || rows_a <= 0 || rows_b <= 0) return false;
   const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
@@ -366,9 +379,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
 
-  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; every other d up to 1024: the wide kernels, on the instance
-  // of d itself or the next larger one (choose_pattern says in which form); d above 1024, and every call of a plan
-  // that asks for it: the general kernel.  2-byte storage of Y exists on the wide kernels only (d = 8, 16, 24 ... 1024).
+  // d = 2, 3, 4, 8, 16: the one-lane-per-entry kernels; every other d: the wide kernels, on the instance of d
+  // itself or the next larger one (choose_pattern says in which form); every call of a plan that asks for it: the
+  // general kernel.  2-byte storage of Y exists on the wide kernels only (d = 8, 16, 24 ... 1024).
   const bool small = !y_bf16 && is_small_dim(d) && !plan->general_only;  // one lane per stored entry
   const int32_t D = y_bf16 ? instance_dim_2byte(d) : instance_dim(d);
   const int recognised = recognise(*ops);
@@ -378,7 +391,9 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
   // elements are read 16 bytes at a time and have to be aligned to that
   const bool y_ok = plan->nnz == 0 || !y_bf16 || (aligned16(d_Y) && ldy % 8 == 0);
   // the fast kernels address a row of Y by a 32-bit pitch in bytes
-  const bool fast = D != 0 && ldy < (int64_t(1) << 29) && y_ok && (y_bf16 || !plan->general_only);
+  // (and a ragged d needs four elements of Y before the end of the first row it reads backwards: see first_back_row)
+  const bool fast = D != 0 && ldy < (int64_t(1) << 29) && y_ok && (y_bf16 || !plan->general_only) &&
+                    (plan->nnz == 0 || first_back_row(plan->n, ldy, d) >= 0);
   if (y_bf16 && !fast) return D != 0 ? FUSEDMM_ERR_INVALID_ARG : FUSEDMM_ERR_UNSUPPORTED_DIM;
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
@@ -400,6 +415,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     fill_schedule_args(plan, recognised, d, kYF32, &a);
     a.partials = partials;
     a.d_pieces = a.d_full = a.d_tail = 0;
+    a.y_first_back_row = 0;
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     a.alpha = ops->alpha;
@@ -422,6 +438,7 @@ int execute_impl(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t d, cons
     fill_schedule_args(plan, pattern, D, y_format, &a);
     a.partials = partials;
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
+    a.y_first_back_row = first_back_row(plan->n, ldy, d);
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     fill_op_args(*ops, &a);
@@ -531,7 +548,8 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
   // the specialised schedule in double precision: the same dispatch as fp32 (a recognised pattern at an instance
   // size, else its tuple family, else the ops at run time) on row registers of four doubles
   const int32_t D = instance_dim_f64(d);
-  const bool fast = D != 0 && ldy < (int64_t(1) << 28) && !plan->general_only;
+  const bool fast = D != 0 && ldy < (int64_t(1) << 28) && !plan->general_only &&
+                    (plan->nnz == 0 || first_back_row(plan->n, ldy, d) >= 0);
   if (fast) {
     if (plan->n_parts > 0 && 2 * D > plan->partials_d) return FUSEDMM_ERR_NOT_RESERVED;
     const int recognised = recognise(*ops);
@@ -541,6 +559,7 @@ int fusedmm_execute_f64(fusedmm_plan_t* plan, const fusedmm_ops_t* ops, int32_t 
     fill_schedule_args(plan, pattern, D, kYF64, &a);
     fill_op_args(*ops, &a);
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
+    a.y_first_back_row = first_back_row(plan->n, ldy, d);
     a.values = d_values; a.X = d_X; a.Y = d_Y; a.Z = d_Z;
     a.ldx = ldx; a.ldy = ldy; a.ldz = ldz;
     hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr;
@@ -604,6 +623,7 @@ int fusedmm_debug_edge_visits(fusedmm_plan_t* plan, int32_t d, int32_t fast_path
     a.alpha = 0.f;
     a.vop = a.rop = a.sop = a.mop = a.aop = a.mean = 0;
     a.d_full = d / 4; a.d_tail = d % 4; a.d_pieces = (d + 3) / 4;
+    a.y_first_back_row = 0;  // no Y is read
     a.visit_counts = d_counts;
     e = D == 0 ? launch_small(PAT_VISIT, d, a, stream) : launch_fast(visit, D, fmt, a, stream);
   } else {

@@ -251,13 +251,19 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
   const char* row = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
   if constexpr (YF == kYF32) {
     static_assert(C == 1, "one 16-byte load per piece");
+    // Ragged rows: the piece the row ends in is fetched by the same 16-byte load instruction as the whole pieces.
+    // It then holds, beyond the row, the first elements of the next row of Y or padding -- inside the matrix either
+    // way -- except in the last row of Y (the last few when ldy < 3), after which the allocation may end: there the
+    // load is moved back so that it ends with the row.  trim_row puts the elements in place and zeros the rest later, once the loads of all
+    // rows in flight are issued (a use of the loaded value here would make the next row's loads wait for this one's).
+    const int back = (M == kMaskRagged && col >= a.y_first_back_row) ? 4 - a.d_tail : 0;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       const int piece = g + G * i;
-      if (M == kMaskNone || piece < (M == kMaskRagged ? a.d_full : a.d_pieces)) {
-        y[i] = *reinterpret_cast<const vec4g*>(row + (size_t)piece * sizeof(vec4));
-      } else if (M == kMaskRagged && piece < a.d_pieces) {  // the row ends inside this piece
-        y[i] = ld_tail(reinterpret_cast<const real*>(row) + 4 * piece, a.d_tail);
+      if (M == kMaskNone || piece < a.d_pieces) {
+        const real* p = reinterpret_cast<const real*>(row) + 4 * piece;
+        if constexpr (M == kMaskRagged) p -= piece == a.d_full ? back : 0;
+        y[i] = *reinterpret_cast<const vec4g*>(p);
       } else {
         y[i] = vec4{0.f, 0.f, 0.f, 0.f};
       }
@@ -285,6 +291,31 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
     for (int j = 0; j < V / 2; ++j) {
       y[2 * j] = widen4<YF>(v2u{raw[j].x, raw[j].y});
       y[2 * j + 1] = widen4<YF>(v2u{raw[j].z, raw[j].w});
+    }
+  }
+}
+
+// Ragged instances, fp32 / fp64 rows: the gathered piece the row ends in (piece d_full: register d_full / G of lane
+// d_full % G) holds d_tail elements of the row -- at its front, followed by whatever comes after the row, or, in the
+// last row of Y, at its back (see gather_row).  Move them to the front and zero the rest.  Selects, not products:
+// what lies beyond the row may be anything.
+template <int G, int V>
+__device__ __forceinline__ void trim_row(const KernelArgs& a, int g, int col, vec4 (&y)[V]) {
+  const int it = a.d_full / G;  // wave-uniform
+  const bool mine = g == a.d_full % G;
+  const bool moved = col >= a.y_first_back_row;
+  const int t = a.d_tail;
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    if (i == it) {
+      const vec4 v = y[i];
+      const real fx = moved ? (t == 1 ? v.w : (t == 2 ? v.z : v.y)) : v.x;
+      const real fy = t > 1 ? (moved ? (t == 2 ? v.w : v.z) : v.y) : (real)0;
+      const real fz = t > 2 ? (moved ? v.w : v.z) : (real)0;
+      y[i].x = mine ? fx : v.x;
+      y[i].y = mine ? fy : v.y;
+      y[i].z = mine ? fz : v.z;
+      y[i].w = mine ? (real)0 : v.w;
     }
   }
 }
@@ -627,7 +658,10 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
 #pragma unroll
           for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv, lane_tail);
+          for (int u = 0; u < U; ++u) {
+            if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
+            edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv, lane_tail);
+          }
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -650,7 +684,10 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
             if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
           }
 #pragma unroll
-          for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+          for (int u = 0; u < U; ++u) {
+            if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
+            edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+          }
         } else {
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -701,7 +738,10 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
           if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+        for (int u = 0; u < U; ++u) {
+          if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
+          edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+        }
       } else {
 #pragma unroll
         for (int u = 0; u < U; ++u)

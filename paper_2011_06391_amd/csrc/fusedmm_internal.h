@@ -86,6 +86,10 @@ struct KernelArgs {
   // instance size runs on it (pieces beyond are neither loaded nor stored); the first d_full of them are whole,
   // and when the dimension is not a multiple of 4 the last one holds d_tail (1..3) elements.
   int32_t d_pieces, d_full, d_tail;
+  // Ragged instances gather the piece a row of Y ends in with one 16-byte load, which reads up to three elements
+  // beyond the row: from this row of Y on that would leave the matrix (the last row, or the last few when ldy < 3),
+  // and the load is moved back to end with the row instead.
+  int32_t y_first_back_row;
   // schedule: blockIdx ranges, in this order: tiled items, chunks, one row per wavefront from
   // order[0 .. n_wave), packed rows from order[n_wave .. n_wave+n_packed), rows without entries
   // (zero fill only) from order[n_wave+n_packed .. n_wave+n_packed+n_empty).

@@ -419,6 +419,52 @@ def test_element_aligned_rows_all_bins(B, case, d):
         plan.close()
 
 
+@pytest.mark.parametrize("d", (1, 2, 3, 5, 6, 7, 9, 13, 34))
+def test_ragged_rows_at_the_end_of_y(B, d):
+    """Dimensions that are not a multiple of 4 gather the piece a row of Y ends in with one 4-element load: moved back
+    to end with the row where reading on would leave the matrix -- the last row; the last few rows when ld < 3; and
+    not possible at all in a matrix of fewer than 4 elements (the general kernel takes those).  Tiny Y (1 ... 5 rows,
+    every row gathered by every row of A), ld = d and d + 1, fp32 and fp64, X a different matrix."""
+    rng = np.random.default_rng(900 + d)
+    for n in (1, 2, 3, 5):
+        for ld in (d, d + 1):
+            m = 7
+            rowptr = np.arange(m + 1, dtype=np.int64) * n
+            colidx = np.tile(np.arange(n, dtype=np.int32), m)
+            Yw = rng.uniform(0.2, 0.9, (n, ld)).astype(np.float32)
+            Xw = rng.uniform(0.2, 0.9, (m, ld)).astype(np.float32)
+            if ld > d:
+                Yw[:, d:] = 1e30
+                Xw[:, d:] = 1e30
+            Y, X = np.ascontiguousarray(Yw[:, :d]), np.ascontiguousarray(Xw[:, :d])
+            rp, ci = dev(rowptr), dev(colidx)
+            for pattern in ("sigmoid", "gcn", "fr"):
+                vals = rng.uniform(0.5, 1.0, m * n).astype(np.float32)
+                Zr, S, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=ALPHA)
+                ops = B.fusedmm_ops_preset(pattern)
+                ops.alpha = ALPHA
+                plan = B.Plan(m, n, rp, ci, {"feature_dim_hint": d})
+                plan.reserve(d)
+                # Y exactly as long as its last row: a flat buffer of (n - 1) * ld + d elements
+                flat = torch.from_numpy(Yw.reshape(-1)[:(n - 1) * ld + d].copy()).cuda()
+                Yd = torch.as_strided(flat, (n, d), (ld, 1))
+                Xd = dev(Xw)[:, :d]
+                Z = torch.full((m, d), float("nan"), dtype=torch.float32, device="cuda")
+                plan.execute(ops, None if pattern == "gcn" else Xd, Yd, Z, dev(vals))
+                torch.cuda.synchronize()
+                check(Z.cpu().numpy(), Zr, S, f"{pattern} d={d} n={n} ld={ld}")
+                plan.reserve_f64(d)
+                Z64 = torch.full((m, d), float("nan"), dtype=torch.float64, device="cuda")
+                flat64 = flat.double()
+                plan.execute_f64(ops, None if pattern == "gcn" else Xd.double(), torch.as_strided(flat64, (n, d), (ld, 1)), Z64,
+                                 dev(vals).double())
+                torch.cuda.synchronize()
+                Zr64, S64, _ = oracle.unfused(rowptr, colidx, vals, X, Y, pattern, alpha=float(np.float32(ALPHA)))
+                e64 = np.abs(Z64.cpu().numpy() - Zr64) / np.where(S64 > 0, S64, 1.0)
+                assert e64.max() <= 1e-12, f"f64 {pattern} d={d} n={n} ld={ld}: {e64.max():.3e}"
+                plan.close()
+
+
 def test_leading_dimensions_and_rectangular(B):
     """ld > d for X, Y and Z; m != n; X distinct from Y; columns beyond d must stay untouched."""
     rng = np.random.default_rng(5)
