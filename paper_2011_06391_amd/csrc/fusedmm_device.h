@@ -235,7 +235,27 @@ __device__ __forceinline__ int piece_index(int g, int i) {
   if constexpr (C == 1) return g + G * i; else return 2 * (g + G * (i / 2)) + (i & 1);
 }
 
-// One lane's share of row `col` of Y, V registers in the layout of piece_index<G, C>: fp32 (fp64 in the
+// What a lane holds of a gathered row of Y between the loads and the arithmetic: the registers as loaded -- V 16-byte
+// pieces of fp32 (fp64) elements, or, for rows of 2-byte elements, V 8-byte loads (C = 1) or V / 2 16-byte loads (C = 2).
+// Nothing may use a loaded value while the loads of the other rows in flight are still to be issued (the use would
+// make them wait), so placing, trimming and widening are left to finish_row.
+template <bool Native, int V, int C>
+struct RowBuf;
+template <int V, int C>
+struct RowBuf<true, V, C> { vec4 r[V]; };
+template <int V>
+struct RowBuf<false, V, 1> { v2u r[V]; };
+template <int V>
+struct RowBuf<false, V, 2> { v4u r[V / 2]; };
+
+template <bool Native, int V, int C>
+__device__ __forceinline__ void clear(RowBuf<Native, V, C>& b) {
+  constexpr int N = sizeof(b.r) / sizeof(b.r[0]);
+#pragma unroll
+  for (int i = 0; i < N; ++i) b.r[i] = {};
+}
+
+// One lane's share of row `col` of Y as loaded, in the layout of piece_index<G, C>: fp32 (fp64 in the
 // double-precision build) rows by one 16-byte load per piece; rows of 2-byte elements by one 8-byte load per
 // piece (C = 1) or one 16-byte load per two pieces (C = 2: half as many load instructions per row, and it is
 // the number of load instructions that occupies the return path).
@@ -243,10 +263,8 @@ __device__ __forceinline__ int piece_index(int g, int i) {
 // pitch in bytes (below 2^32, checked by the host) plus the lane's own offset.
 // M = kMaskPieces: pieces at or beyond a.d_pieces read as zero (a dimension below the instance's own);
 // M = kMaskRagged: and the row may end inside its last piece (a dimension that is not a multiple of 4).
-// Rows of 2-byte elements are loaded first, all of them, and widened afterwards: a conversion next to its
-// load inside the mask's branch would make every load wait for the one before.
 template <int YF, int G, int V, int C, int M>
-__device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, vec4 (&y)[V]) {
+__device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, RowBuf<YF == kYF32, V, C>& b) {
   const uint32_t pitch = (uint32_t)a.ldy * (YF == kYF32 ? (uint32_t)sizeof(real) : 2u);
   const char* row = static_cast<const char*>(a.Y) + (uint64_t)(uint32_t)col * (uint64_t)pitch;
   if constexpr (YF == kYF32) {
@@ -254,8 +272,7 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
     // Ragged rows: the piece the row ends in is fetched by the same 16-byte load instruction as the whole pieces.
     // It then holds, beyond the row, the first elements of the next row of Y or padding -- inside the matrix either
     // way -- except in the last row of Y (the last few when ldy < 3), after which the allocation may end: there the
-    // load is moved back so that it ends with the row.  trim_row puts the elements in place and zeros the rest later, once the loads of all
-    // rows in flight are issued (a use of the loaded value here would make the next row's loads wait for this one's).
+    // load is moved back so that it ends with the row.  finish_row puts the elements in place and zeros the rest.
     const int back = (M == kMaskRagged && col >= a.y_first_back_row) ? 4 - a.d_tail : 0;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
@@ -263,59 +280,66 @@ __device__ __forceinline__ void gather_row(const KernelArgs& a, int col, int g, 
       if (M == kMaskNone || piece < a.d_pieces) {
         const real* p = reinterpret_cast<const real*>(row) + 4 * piece;
         if constexpr (M == kMaskRagged) p -= piece == a.d_full ? back : 0;
-        y[i] = *reinterpret_cast<const vec4g*>(p);
+        b.r[i] = *reinterpret_cast<const vec4g*>(p);
       } else {
-        y[i] = vec4{0.f, 0.f, 0.f, 0.f};
+        b.r[i] = vec4{0.f, 0.f, 0.f, 0.f};
       }
     }
   } else if constexpr (C == 1) {
-    v2u raw[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       const int piece = g + G * i;
-      if (M == kMaskNone || piece < a.d_pieces) raw[i] = *reinterpret_cast<const v2u*>(row + (size_t)piece * 8u);
-      else raw[i] = v2u{0u, 0u};
+      if (M == kMaskNone || piece < a.d_pieces) b.r[i] = *reinterpret_cast<const v2u*>(row + (size_t)piece * 8u);
+      else b.r[i] = v2u{0u, 0u};
     }
-#pragma unroll
-    for (int i = 0; i < V; ++i) y[i] = widen4<YF>(raw[i]);
   } else {
     static_assert(V % 2 == 0, "16-byte chunks of 2-byte elements");
-    v4u raw[V / 2];
 #pragma unroll
     for (int j = 0; j < V / 2; ++j) {
       const int chunk = g + G * j;
-      if (M == kMaskNone || 2 * chunk + 1 < a.d_pieces) raw[j] = *reinterpret_cast<const v4u*>(row + (size_t)chunk * 16u);
-      else raw[j] = v4u{0u, 0u, 0u, 0u};
-    }
-#pragma unroll
-    for (int j = 0; j < V / 2; ++j) {
-      y[2 * j] = widen4<YF>(v2u{raw[j].x, raw[j].y});
-      y[2 * j + 1] = widen4<YF>(v2u{raw[j].z, raw[j].w});
+      if (M == kMaskNone || 2 * chunk + 1 < a.d_pieces) b.r[j] = *reinterpret_cast<const v4u*>(row + (size_t)chunk * 16u);
+      else b.r[j] = v4u{0u, 0u, 0u, 0u};
     }
   }
 }
 
-// Ragged instances, fp32 / fp64 rows: the gathered piece the row ends in (piece d_full: register d_full / G of lane
-// d_full % G) holds d_tail elements of the row -- at its front, followed by whatever comes after the row, or, in the
-// last row of Y, at its back (see gather_row).  Move them to the front and zero the rest.  Selects, not products:
-// what lies beyond the row may be anything.
-template <int G, int V>
-__device__ __forceinline__ void trim_row(const KernelArgs& a, int g, int col, vec4 (&y)[V]) {
-  const int it = a.d_full / G;  // wave-uniform
-  const bool mine = g == a.d_full % G;
-  const bool moved = col >= a.y_first_back_row;
-  const int t = a.d_tail;
+// The row as the arithmetic wants it, V registers of four elements, from what gather_row loaded: rows of 2-byte
+// elements are widened; in the ragged instances the gathered piece the row ends in (piece d_full: register
+// d_full / G of lane d_full % G) holds d_tail elements of the row -- at its front, followed by whatever comes after
+// the row, or, from row y_first_back_row of Y on, at its back -- which are moved to the front and the rest zeroed
+// (selects, not products: what lies beyond the row may be anything).
+template <int YF, int G, int V, int C, int M>
+__device__ __forceinline__ void finish_row(const KernelArgs& a, int g, int col, const RowBuf<YF == kYF32, V, C>& b, vec4 (&y)[V]) {
+  if constexpr (YF == kYF32) {
 #pragma unroll
-  for (int i = 0; i < V; ++i) {
-    if (i == it) {
-      const vec4 v = y[i];
-      const real fx = moved ? (t == 1 ? v.w : (t == 2 ? v.z : v.y)) : v.x;
-      const real fy = t > 1 ? (moved ? (t == 2 ? v.w : v.z) : v.y) : (real)0;
-      const real fz = t > 2 ? (moved ? v.w : v.z) : (real)0;
-      y[i].x = mine ? fx : v.x;
-      y[i].y = mine ? fy : v.y;
-      y[i].z = mine ? fz : v.z;
-      y[i].w = mine ? (real)0 : v.w;
+    for (int i = 0; i < V; ++i) y[i] = b.r[i];
+    if constexpr (M == kMaskRagged) {
+      const int it = a.d_full / G;  // wave-uniform
+      const bool mine = g == a.d_full % G;
+      const bool moved = col >= a.y_first_back_row;
+      const int t = a.d_tail;
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        if (i == it) {
+          const vec4 v = y[i];
+          const real fx = moved ? (t == 1 ? v.w : (t == 2 ? v.z : v.y)) : v.x;
+          const real fy = t > 1 ? (moved ? (t == 2 ? v.w : v.z) : v.y) : (real)0;
+          const real fz = t > 2 ? (moved ? v.w : v.z) : (real)0;
+          y[i].x = mine ? fx : v.x;
+          y[i].y = mine ? fy : v.y;
+          y[i].z = mine ? fz : v.z;
+          y[i].w = mine ? (real)0 : v.w;
+        }
+      }
+    }
+  } else if constexpr (C == 1) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) y[i] = widen4<YF>(b.r[i]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < V / 2; ++j) {
+      y[2 * j] = widen4<YF>(v2u{b.r[j].x, b.r[j].y});
+      y[2 * j + 1] = widen4<YF>(v2u{b.r[j].z, b.r[j].w});
     }
   }
 }
@@ -645,7 +669,7 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
     for (int k0 = 0; k0 < cnt; k0 += S * U) {
       int c[U];
       real av[U];
-      vec4 y[U][V];
+      RowBuf<YF == kYF32, V, C> rows[U];
       if (k0 + S * U <= cnt) {
         // every lane group has a stored entry in each of the U steps
 #pragma unroll
@@ -656,11 +680,12 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         }
         if constexpr (T::loads_y) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
+          for (int u = 0; u < U; ++u) gather_row<YF, G, V, C, kMask>(a, c[u], g, rows[u]);
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
-            edge_update<P, G, V, false>(x, y[u], av[u], a, true, z, nv, lane_tail);
+            vec4 y[V];
+            finish_row<YF, G, V, C, kMask>(a, g, c[u], rows[u], y);
+            edge_update<P, G, V, false>(x, y, av[u], a, true, z, nv, lane_tail);
           }
         } else {
 #pragma unroll
@@ -679,14 +704,14 @@ __device__ __forceinline__ void wave_accumulate(const KernelArgs& a, int64_t e0,
         if constexpr (T::loads_y) {
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-            if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
+            clear(rows[u]);
+            if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, rows[u]);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
-            edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+            vec4 y[V];
+            finish_row<YF, G, V, C, kMask>(a, g, c[u], rows[u], y);
+            edge_update<P, G, V, true>(x, y, av[u], a, ok[u], z, nv, lane_tail);
           }
         } else {
 #pragma unroll
@@ -723,7 +748,7 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
       bool ok[U];
       int c[U];
       real av[U];
-      vec4 y[U][V];
+      RowBuf<YF == kYF32, V, C> rows[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         ok[u] = (bb + k + u) < deg;
@@ -733,14 +758,14 @@ __device__ __forceinline__ void group_accumulate(const KernelArgs& a, int64_t e0
       if constexpr (T::loads_y) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-#pragma unroll
-          for (int i = 0; i < V; ++i) y[u][i] = vec4{0.f, 0.f, 0.f, 0.f};
-          if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, y[u]);
+          clear(rows[u]);
+          if (ok[u]) gather_row<YF, G, V, C, kMask>(a, c[u], g, rows[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          if constexpr (kMask == kMaskRagged && YF == kYF32) trim_row<G, V>(a, g, c[u], y[u]);
-          edge_update<P, G, V, true>(x, y[u], av[u], a, ok[u], z, nv, lane_tail);
+          vec4 y[V];
+          finish_row<YF, G, V, C, kMask>(a, g, c[u], rows[u], y);
+          edge_update<P, G, V, true>(x, y, av[u], a, ok[u], z, nv, lane_tail);
         }
       } else {
 #pragma unroll
