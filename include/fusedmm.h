@@ -219,6 +219,9 @@ int fusedmm_plan_stats(const fusedmm_plan_t* plan, int64_t* n_packed_rows, int64
  *   d_values  device, nnz fp32 edge values a_uv; NULL unless SOP == EDGE_VALUE
  *   d_X       device, m x d (ldx); may be NULL when VOP == SEL2ND
  *   d_Y       device, n x d (ldy);  d_Z  device, m x d (ldz), overwritten
+ * Y is the (n - 1) * ldy + d elements from d_Y on: when d is not a multiple of 4 the kernels may read (never
+ * use, never write) up to three elements after the end of a row of Y inside that range -- the start of the
+ * next row, or the padding between rows -- and nothing outside it.
  * Does not synchronise and does not allocate.  FUSEDMM_ERR_NOT_RESERVED when the pattern has split
  * rows and d exceeds what fusedmm_plan_create / fusedmm_plan_reserve reserved.  Z must not overlap
  * X, Y or d_values (FUSEDMM_ERR_ALIAS). */
