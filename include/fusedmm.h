@@ -318,6 +318,14 @@ int fusedmm_plan_read_profile_samples(fusedmm_plan_t* plan, double* main_kernel_
  * known traffic (bytes read + bytes written). */
 int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 
+/* Test hook, host only (no GPU work): which kernel size a feature dimension runs on.  storage: 0 = fp32
+ * (fusedmm_execute), 1 = Y in 2-byte elements (fusedmm_execute_bf16y / _f16y), 2 = double precision
+ * (fusedmm_execute_f64).  Returns the instance size of the specialised schedule (32, 64, 96, ... 2048: the
+ * dimension itself or the next larger size), d itself for the one-lane-per-entry kernels (fp32, d = 2, 3, 4, 8,
+ * 16), or 0 when that storage form does not take the dimension.  Also the stride of the partial rows, which
+ * fusedmm_execute_static_scratch's limit is counted in. */
+int fusedmm_debug_kernel_size(int32_t d, int32_t storage);
+
 /* Free the plan and everything it owns. */
 int fusedmm_plan_destroy(fusedmm_plan_t* plan);
 

@@ -39,7 +39,7 @@ EXPORTS = (
     "fusedmm_plan_reserve", "fusedmm_plan_reserve_f64", "fusedmm_plan_workspace_bytes", "fusedmm_plan_stats", "fusedmm_execute",
     "fusedmm_execute_static_scratch", "fusedmm_debug_edge_visits", "fusedmm_plan_set_profiling", "fusedmm_plan_read_profile",
     "fusedmm_plan_read_profile_samples",
-    "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
+    "fusedmm_plan_destroy", "fusedmm_debug_copy", "fusedmm_debug_kernel_size", "fusedmm_plan_create_tuned", "fusedmm_execute_bf16y",
     "fusedmm_to_bf16", "fusedmm_execute_f16y", "fusedmm_to_f16", "fusedmm_execute_f64",
     "fusedmm_minibatch_create", "fusedmm_minibatch_reserve", "fusedmm_minibatch_epoch",
     "fusedmm_minibatch_info", "fusedmm_minibatch_destroy",
@@ -123,6 +123,8 @@ def load():
     lib.fusedmm_plan_read_profile_samples.restype = ctypes.c_int
     lib.fusedmm_plan_read_profile_samples.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                                       i64, ctypes.POINTER(i64)]
+    lib.fusedmm_debug_kernel_size.restype = ctypes.c_int
+    lib.fusedmm_debug_kernel_size.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.fusedmm_debug_copy.restype = ctypes.c_int
     lib.fusedmm_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.fusedmm_plan_destroy.restype = ctypes.c_int
@@ -297,6 +299,10 @@ def fusedmm_plan_read_profile_samples(plan, capacity: int = 4096):
     _check(load().fusedmm_plan_read_profile_samples(plan, ms, empty, capacity, ctypes.byref(calls)),
            "fusedmm_plan_read_profile_samples")
     return list(ms[:calls.value]), list(empty[:calls.value])
+
+
+def fusedmm_debug_kernel_size(d: int, storage: str = "f32") -> int:
+    return load().fusedmm_debug_kernel_size(d, {"f32": 0, "bf16": 1, "f16": 1, "f64": 2}[storage])
 
 
 def fusedmm_debug_copy(d_dst, d_src, nbytes: int, stream=None) -> None:

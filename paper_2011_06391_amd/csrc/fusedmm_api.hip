@@ -805,6 +805,16 @@ int fusedmm_plan_create_tuned(fusedmm_plan_t** out, int64_t m, int64_t n, int64_
   return FUSEDMM_OK;
 }
 
+int fusedmm_debug_kernel_size(int32_t d, int32_t storage) {
+  if (d < 1 || d > FUSEDMM_MAX_D) return 0;
+  switch (storage) {
+    case 0: return is_small_dim(d) ? d : instance_dim(d);
+    case 1: return instance_dim_2byte(d);
+    case 2: return instance_dim_f64(d);
+    default: return 0;
+  }
+}
+
 int fusedmm_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream_) {
   if (bytes == 0) return FUSEDMM_OK;
   if (!d_dst || !d_src || bytes % 16 != 0 || !aligned16(d_dst) || !aligned16(d_src)) return FUSEDMM_ERR_INVALID_ARG;

@@ -56,6 +56,23 @@ def test_host_only_calls(lib):
     assert lib.fusedmm_plan_destroy(None) == binding.FUSEDMM_OK
 
 
+def test_which_kernel_size_a_dimension_runs_on(lib):
+    """The dispatch over feature dimensions (host logic, no GPU): every fp32 and fp64 dimension has a size to run on,
+    the smallest one that holds it; 2-byte storage takes multiples of 8 up to 1024."""
+    sizes = (32, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048)
+    k = binding.fusedmm_debug_kernel_size
+    for d in range(1, binding.FUSEDMM_MAX_D + 1):
+        want = d if d in (2, 3, 4, 8, 16) else min(s for s in sizes if s >= d)
+        assert k(d, "f32") == want, d
+        want64 = min(s for s in sizes if s >= d and s & (s - 1) == 0)
+        assert k(d, "f64") == want64, d
+        want2 = min(s for s in sizes if s >= d) if d % 8 == 0 and d <= 1024 else 0
+        assert k(d, "bf16") == want2, d
+    assert k(0, "f32") == 0 and k(binding.FUSEDMM_MAX_D + 1, "f32") == 0 and k(-5, "f64") == 0
+    for d, size in ((100, 128), (300, 384), (602, 768), (768, 768), (1433, 1536)):
+        assert k(d, "f32") == size
+
+
 def test_enum_values_match_header():
     text = open(HEADER).read()
     for table, prefix in ((binding.VOP, "FUSEDMM_VOP_"), (binding.ROP, "FUSEDMM_ROP_"), (binding.SOP, "FUSEDMM_SOP_"),
